@@ -1,0 +1,154 @@
+/*
+ * kimad.h - C ABI of the MI355X (gfx950) library for one worker's Kimad+ compression step.
+ *
+ * The calls follow the worker side of the Kimad algorithm (paper Algorithm 1, lines
+ * "Select compressor" and "Upload the compressed vector"), split at its natural seams:
+ *
+ *   kimad_profile      layer-wise compression-error table over a grid of candidate ratios
+ *                      (Section 3.2, Eq. norm decomposition; the Errors matrix of Appendix C)
+ *   kimad_allocate     budget-constrained choice of one grid point per layer
+ *                      (Section 3.2, Eq. optimisation; the dynamic programme of Appendix C)
+ *   kimad_compress_ef  per-layer TopK of x = g - h, sparse (index, value) payload, and the
+ *                      estimator update h <- h + TopK(g - h)
+ *                      (Section 2.2 TopK; Section 3.3 Eq. EF21-2; Algorithm 1 upload line)
+ *
+ * Notation: g = fresh update u (the gradient), h = estimator u_hat (error-feedback state),
+ * x = g - h.  "Layer" = one parameter tensor.  Magnitudes are compared on the binary32 bit
+ * pattern of x with the sign cleared; equal magnitudes keep the lower index first.
+ *
+ * Conventions
+ *   - Every pointer is marked HOST or DEVICE.  The library never allocates or frees device
+ *     memory: gradients, estimator, outputs and the workspace belong to the caller.
+ *   - All GPU work is enqueued on the given stream (a hipStream_t passed as void*; NULL is the
+ *     default stream); no call waits for the device except kimad_plan_create, which uploads
+ *     its tables synchronously.
+ *   - Return value: 0 on success, a negative kimad_status otherwise (argument errors are found
+ *     on the host before anything is enqueued).  Data-dependent outcomes (infeasible budget,
+ *     non-finite table, a K that is not on the grid) are written to a DEVICE status word.
+ *   - One plan must not be used from two streams at once: its workspace is shared state.
+ */
+#ifndef KIMAD_H
+#define KIMAD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KIMAD_MAX_J 64u                 /* candidate ratios per layer */
+#define KIMAD_MAX_N 0xFFF00000ull       /* elements per layer (indices are u32) */
+
+typedef enum kimad_status {
+    KIMAD_OK = 0,
+    KIMAD_ERR_INVALID_ARG = -1,
+    KIMAD_ERR_WORKSPACE_TOO_SMALL = -2,
+    KIMAD_ERR_CAPACITY_TOO_SMALL = -3,
+    KIMAD_ERR_HIP = -4,
+    KIMAD_ERR_NOT_IMPLEMENTED = -5,
+    KIMAD_ERR_INFEASIBLE = -6,          /* device status: budget below the cheapest allocation */
+    KIMAD_ERR_NONFINITE = -7,           /* device status: error table holds Inf or NaN */
+    KIMAD_ERR_OFFGRID = -8,             /* device status: KIMAD_REUSE_PROFILE given but K is not a grid size */
+    KIMAD_ERR_SCRATCH_OVERFLOW = -9,    /* device status: candidate buffer too small (see tmp_capacity_pairs) */
+    KIMAD_ERR_BAD_OFFSETS = -10         /* device status: offsets/K do not fit capacity_pairs */
+} kimad_status;
+
+/* One layer: DEVICE pointers to n fp32 values each.  g is read-only; h is updated in place by
+ * kimad_compress_ef only.  4-byte alignment suffices (16-byte alignment of both is fastest). */
+typedef struct kimad_layer {
+    const float* g;
+    float* h;
+    uint64_t n;                         /* 1 .. KIMAD_MAX_N */
+} kimad_layer_t;
+
+typedef struct kimad_config {
+    uint32_t pair_bytes;                /* bytes charged per kept entry; 0 means 8 (u32 index + fp32 value) */
+    uint32_t cost_units_D;              /* Appendix C discretisation factor D applied to the budget; 0 = exact */
+    uint64_t max_budget_bytes;          /* largest budget kimad_allocate will see; 0 = uncompressed size.
+                                           Sizes the DP tables when cost_units_D == 0. */
+    uint64_t tmp_capacity_pairs;        /* candidate-buffer entries; 0 = worst case (sum of n) */
+} kimad_config_t;
+
+/* flags of kimad_compress_ef */
+#define KIMAD_REUSE_PROFILE 1u          /* every K[i] is one of layer i's grid sizes and g, h are unchanged
+                                           since the last kimad_profile on this plan: reuse its thresholds */
+
+typedef struct kimad_plan kimad_plan_t; /* host object; owns no device memory */
+
+/* Bytes of DEVICE workspace a plan over these layer sizes needs.  n: HOST array of L sizes. */
+int kimad_workspace_bytes(const uint64_t* n, uint32_t L, uint32_t J,
+                          const kimad_config_t* cfg, uint64_t* bytes_out);
+
+/* Build a plan: validates arguments, computes the candidate sizes
+ *   K_ij = min(n_i, max(1, ceil(ratios[j] * n_i)))          (Section 3.2, the discrete set)
+ * and uploads layer descriptors and tile maps into the workspace.
+ *   layers   HOST array of L descriptors (device pointers inside)
+ *   ratios   HOST array of J values, strictly ascending, each in (0, 1]
+ *   workspace DEVICE, 256-byte aligned, at least kimad_workspace_bytes() bytes; the plan keeps
+ *            using it until kimad_plan_destroy.
+ * The plan stays valid while the layers' pointers and sizes stay the same. */
+int kimad_plan_create(const kimad_layer_t* layers, uint32_t L,
+                      const double* ratios, uint32_t J,
+                      const kimad_config_t* cfg,
+                      void* workspace, uint64_t workspace_bytes,
+                      void* stream, kimad_plan_t** plan_out);
+int kimad_plan_destroy(kimad_plan_t* plan);
+
+/* HOST copy of the plan's candidate sizes, L*J row-major (for callers that want K_ij). */
+int kimad_plan_grid_sizes(const kimad_plan_t* plan, uint64_t* K_table_out);
+
+/* Error profile (Section 3.2, Eq. norm decomposition):
+ *   err_table[i*J + j] = || x_i - TopK_{K_ij}(x_i) ||^2  = sum of squares of the entries dropped,
+ * fp64, DEVICE, L*J row-major.  Exactly 0 where K_ij = n_i.  Pure: g and h are not modified.
+ * Also records, inside the workspace, each candidate's selection threshold for
+ * KIMAD_REUSE_PROFILE. */
+int kimad_profile(kimad_plan_t* plan, double* err_table, void* stream);
+
+/* Allocation (Section 3.2 Eq. optimisation; Appendix C): choose j_i minimising
+ * sum_i err_table[i][j_i] subject to sum_i K_{i j_i} * pair_bytes <= budget_bytes.
+ *   P = floor(budget_bytes / pair_bytes); unit = 1 if D == 0 or P <= D else ceil(P / D);
+ *   capacity = floor(P / unit); cost w_ij = ceil(K_ij / unit).
+ * Rows are indexed by cost 0..capacity; candidates are tried in ascending j with strict "<";
+ * the answer ends at the smallest cost attaining the least total.
+ *   err_table   DEVICE, L*J fp64 (any table, e.g. kimad_profile's output)
+ *   j_out       DEVICE int32[L]      chosen grid index per layer
+ *   K_out       DEVICE uint64[L]     chosen size per layer
+ *   offsets_out DEVICE uint64[L+1]   exclusive scan of K_out
+ *   status_out  DEVICE int32[1]      KIMAD_OK, KIMAD_ERR_INFEASIBLE or KIMAD_ERR_NONFINITE
+ * On a non-zero status the other outputs are zero-filled. */
+int kimad_allocate(kimad_plan_t* plan, const double* err_table, uint64_t budget_bytes,
+                   int32_t* j_out, uint64_t* K_out, uint64_t* offsets_out,
+                   int32_t* status_out, void* stream);
+
+/* TopK selection, payload and estimator update (Section 2.2; Algorithm 1 upload line;
+ * Section 3.3 Eq. EF21-2).  For each layer i with x = g_i - h_i (fp32):
+ *   S_i = the K[i] entries of largest magnitude, equal magnitudes by lower index;
+ *   idx_out[offsets[i] + r] = r-th smallest index in S_i (layer-local), val_out[...] = x[idx];
+ *   h_i[idx] = fl32(h_i[idx] + x[idx]) for idx in S_i, all other entries untouched.
+ *   K        DEVICE uint64[L], each 0..n_i
+ *   offsets  DEVICE uint64[L+1], offsets[i] + K[i] <= capacity_pairs for every i
+ *   idx_out  DEVICE uint32[capacity_pairs];  val_out DEVICE float[capacity_pairs]
+ *   flags    0 (select from scratch: two extra passes over g, h) or KIMAD_REUSE_PROFILE
+ *   status_out DEVICE int32[1] */
+int kimad_compress_ef(kimad_plan_t* plan, const uint64_t* K, const uint64_t* offsets,
+                      uint32_t* idx_out, float* val_out, uint64_t capacity_pairs,
+                      uint32_t flags, int32_t* status_out, void* stream);
+
+/* profile -> allocate -> compress_ef(KIMAD_REUSE_PROFILE) on one stream: one worker's step. */
+int kimad_step(kimad_plan_t* plan, uint64_t budget_bytes, double* err_table,
+               int32_t* j_out, uint64_t* K_out, uint64_t* offsets_out,
+               uint32_t* idx_out, float* val_out, uint64_t capacity_pairs,
+               int32_t* status_out /* DEVICE int32[2]: allocate, compress */, void* stream);
+
+/* DEVICE diagnostics of the last kimad_profile on the plan, copied to HOST (synchronises the
+ * stream): out[0] = table entries whose error bound exceeded the certified tolerance before
+ * the exact fallback ran, out[1] = entries fixed by the fallback. */
+int kimad_profile_diagnostics(kimad_plan_t* plan, uint32_t* out2, void* stream);
+
+const char* kimad_strerror(int status);
+const char* kimad_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KIMAD_H */

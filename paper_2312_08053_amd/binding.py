@@ -1,0 +1,239 @@
+"""ctypes binding with the names of include/kimad.h.  Argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkimad.so")
+
+KIMAD_REUSE_PROFILE = 1
+KIMAD_MAX_J = 64
+
+EXPORTED_SYMBOLS = [
+    "kimad_workspace_bytes", "kimad_plan_create", "kimad_plan_destroy", "kimad_plan_grid_sizes",
+    "kimad_profile", "kimad_allocate", "kimad_compress_ef", "kimad_step",
+    "kimad_profile_diagnostics", "kimad_strerror", "kimad_version",
+]
+
+
+class KimadError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {kimad_strerror(code)} ({code})")
+
+
+class _Layer(C.Structure):
+    _fields_ = [("g", C.c_void_p), ("h", C.c_void_p), ("n", C.c_uint64)]
+
+
+class _Config(C.Structure):
+    _fields_ = [("pair_bytes", C.c_uint32), ("cost_units_D", C.c_uint32),
+                ("max_budget_bytes", C.c_uint64), ("tmp_capacity_pairs", C.c_uint64)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load libkimad.so (built by paper_2312_08053_amd.build).  Fails loudly when it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: run `python -m paper_2312_08053_amd.build` (there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, u32, u64, i32p = C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p
+    L.kimad_workspace_bytes.argtypes = [C.POINTER(C.c_uint64), u32, u32, C.POINTER(_Config), C.POINTER(C.c_uint64)]
+    L.kimad_plan_create.argtypes = [C.POINTER(_Layer), u32, C.POINTER(C.c_double), u32, C.POINTER(_Config),
+                                    vp, u64, vp, C.POINTER(vp)]
+    L.kimad_plan_destroy.argtypes = [vp]
+    L.kimad_plan_grid_sizes.argtypes = [vp, C.POINTER(C.c_uint64)]
+    L.kimad_profile.argtypes = [vp, vp, vp]
+    L.kimad_allocate.argtypes = [vp, vp, u64, vp, vp, vp, i32p, vp]
+    L.kimad_compress_ef.argtypes = [vp, vp, vp, vp, vp, u64, u32, i32p, vp]
+    L.kimad_step.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, u64, i32p, vp]
+    L.kimad_profile_diagnostics.argtypes = [vp, C.POINTER(C.c_uint32), vp]
+    L.kimad_strerror.argtypes = [C.c_int]
+    L.kimad_strerror.restype = C.c_char_p
+    L.kimad_version.restype = C.c_char_p
+    for name in EXPORTED_SYMBOLS:
+        if name not in ("kimad_strerror", "kimad_version"):
+            getattr(L, name).restype = C.c_int
+    _lib = L
+    return L
+
+
+def kimad_strerror(code: int) -> str:
+    return lib().kimad_strerror(int(code)).decode()
+
+
+def kimad_version() -> str:
+    return lib().kimad_version().decode()
+
+
+def _cfg(pair_bytes=8, D=0, max_budget_bytes=0, tmp_capacity_pairs=0) -> _Config:
+    return _Config(int(pair_bytes), int(D), int(max_budget_bytes), int(tmp_capacity_pairs))
+
+
+def _check(code: int, where: str) -> None:
+    if code != 0:
+        raise KimadError(code, where)
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return int(torch.cuda.current_stream().cuda_stream)
+    return int(getattr(stream, "cuda_stream", stream))
+
+
+def kimad_workspace_bytes(sizes: Sequence[int], J: int, pair_bytes=8, D=0, max_budget_bytes=0,
+                          tmp_capacity_pairs=0) -> int:
+    n = (C.c_uint64 * len(sizes))(*[int(s) for s in sizes])
+    out = C.c_uint64(0)
+    cfg = _cfg(pair_bytes, D, max_budget_bytes, tmp_capacity_pairs)
+    _check(lib().kimad_workspace_bytes(n, len(sizes), int(J), C.byref(cfg), C.byref(out)), "kimad_workspace_bytes")
+    return int(out.value)
+
+
+def kimad_plan_create(g_ptrs: Sequence[int], h_ptrs: Sequence[int], sizes: Sequence[int], ratios: Sequence[float],
+                      workspace_ptr: int, workspace_bytes: int, stream=None, pair_bytes=8, D=0,
+                      max_budget_bytes=0, tmp_capacity_pairs=0) -> int:
+    L = len(sizes)
+    layers = (_Layer * L)()
+    for i in range(L):
+        layers[i].g, layers[i].h, layers[i].n = int(g_ptrs[i]), int(h_ptrs[i]), int(sizes[i])
+    r = (C.c_double * len(ratios))(*[float(x) for x in ratios])
+    cfg = _cfg(pair_bytes, D, max_budget_bytes, tmp_capacity_pairs)
+    plan = C.c_void_p(0)
+    _check(lib().kimad_plan_create(layers, L, r, len(ratios), C.byref(cfg), C.c_void_p(int(workspace_ptr)),
+                                   int(workspace_bytes), C.c_void_p(_stream(stream)), C.byref(plan)),
+           "kimad_plan_create")
+    return int(plan.value)
+
+
+def kimad_plan_destroy(plan: int) -> None:
+    _check(lib().kimad_plan_destroy(C.c_void_p(plan)), "kimad_plan_destroy")
+
+
+def kimad_profile(plan: int, err_table, stream=None) -> None:
+    _check(lib().kimad_profile(C.c_void_p(plan), C.c_void_p(_ptr(err_table)), C.c_void_p(_stream(stream))),
+           "kimad_profile")
+
+
+def kimad_allocate(plan: int, err_table, budget_bytes: int, j_out, K_out, offsets_out, status_out,
+                   stream=None) -> None:
+    _check(lib().kimad_allocate(C.c_void_p(plan), C.c_void_p(_ptr(err_table)), int(budget_bytes),
+                                C.c_void_p(_ptr(j_out)), C.c_void_p(_ptr(K_out)), C.c_void_p(_ptr(offsets_out)),
+                                C.c_void_p(_ptr(status_out)), C.c_void_p(_stream(stream))), "kimad_allocate")
+
+
+def kimad_compress_ef(plan: int, K, offsets, idx_out, val_out, capacity_pairs: int, flags: int, status_out,
+                      stream=None) -> None:
+    _check(lib().kimad_compress_ef(C.c_void_p(plan), C.c_void_p(_ptr(K)), C.c_void_p(_ptr(offsets)),
+                                   C.c_void_p(_ptr(idx_out)), C.c_void_p(_ptr(val_out)), int(capacity_pairs),
+                                   int(flags), C.c_void_p(_ptr(status_out)), C.c_void_p(_stream(stream))),
+           "kimad_compress_ef")
+
+
+def kimad_step(plan: int, budget_bytes: int, err_table, j_out, K_out, offsets_out, idx_out, val_out,
+               capacity_pairs: int, status_out, stream=None) -> None:
+    _check(lib().kimad_step(C.c_void_p(plan), int(budget_bytes), C.c_void_p(_ptr(err_table)),
+                            C.c_void_p(_ptr(j_out)), C.c_void_p(_ptr(K_out)), C.c_void_p(_ptr(offsets_out)),
+                            C.c_void_p(_ptr(idx_out)), C.c_void_p(_ptr(val_out)), int(capacity_pairs),
+                            C.c_void_p(_ptr(status_out)), C.c_void_p(_stream(stream))), "kimad_step")
+
+
+class Plan:
+    """Owns the torch tensors a plan needs (workspace, outputs) and forwards to the C calls.
+
+    ``g`` and ``h`` are flat fp32 CUDA tensors holding the layers back to back in the order of
+    ``sizes`` (or lists of per-layer tensors).
+    """
+
+    def __init__(self, g, h, sizes: Sequence[int], ratios: Sequence[float], pair_bytes: int = 8, D: int = 0,
+                 max_budget_bytes: int = 0, tmp_capacity_pairs: int = 0, capacity_pairs: Optional[int] = None):
+        import torch
+        self.torch = torch
+        self.sizes = [int(s) for s in sizes]
+        self.L, self.J = len(self.sizes), len(ratios)
+        self.ratios = [float(r) for r in ratios]
+        if isinstance(g, (list, tuple)):
+            g_ptrs = [int(t.data_ptr()) for t in g]
+            h_ptrs = [int(t.data_ptr()) for t in h]
+            dev = g[0].device
+        else:
+            starts = np.concatenate([[0], np.cumsum(self.sizes)])
+            g_ptrs = [int(g.data_ptr()) + 4 * int(s) for s in starts[:-1]]
+            h_ptrs = [int(h.data_ptr()) + 4 * int(s) for s in starts[:-1]]
+            dev = g.device
+        self._keep = (g, h)
+        self.device = dev
+        nbytes = kimad_workspace_bytes(self.sizes, self.J, pair_bytes, D, max_budget_bytes, tmp_capacity_pairs)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        base = int(self.workspace.data_ptr())
+        self._ws_ptr = (base + 255) // 256 * 256
+        self.workspace_bytes = nbytes
+        self.handle = kimad_plan_create(g_ptrs, h_ptrs, self.sizes, self.ratios, self._ws_ptr, nbytes,
+                                        None, pair_bytes, D, max_budget_bytes, tmp_capacity_pairs)
+        d = int(sum(self.sizes))
+        self.capacity_pairs = int(capacity_pairs) if capacity_pairs is not None else d
+        self.err_table = torch.empty(self.L * self.J, dtype=torch.float64, device=dev)
+        self.j = torch.empty(self.L, dtype=torch.int32, device=dev)
+        self.K = torch.empty(self.L, dtype=torch.int64, device=dev)
+        self.offsets = torch.empty(self.L + 1, dtype=torch.int64, device=dev)
+        self.status = torch.zeros(2, dtype=torch.int32, device=dev)
+        self.idx = torch.empty(self.capacity_pairs, dtype=torch.int32, device=dev)
+        self.val = torch.empty(self.capacity_pairs, dtype=torch.float32, device=dev)
+
+    def grid_sizes(self) -> np.ndarray:
+        out = (C.c_uint64 * (self.L * self.J))()
+        _check(lib().kimad_plan_grid_sizes(C.c_void_p(self.handle), out), "kimad_plan_grid_sizes")
+        return np.array(out[:], dtype=np.int64).reshape(self.L, self.J)
+
+    def profile(self, err_table=None):
+        t = self.err_table if err_table is None else err_table
+        kimad_profile(self.handle, t)
+        return t
+
+    def allocate(self, budget_bytes: int, err_table=None):
+        t = self.err_table if err_table is None else err_table
+        kimad_allocate(self.handle, t, budget_bytes, self.j, self.K, self.offsets, self.status[0:1])
+        return self.j, self.K, self.offsets, self.status[0:1]
+
+    def compress_ef(self, K=None, offsets=None, reuse_profile: bool = False):
+        K = self.K if K is None else K
+        offsets = self.offsets if offsets is None else offsets
+        kimad_compress_ef(self.handle, K, offsets, self.idx, self.val, self.capacity_pairs,
+                          KIMAD_REUSE_PROFILE if reuse_profile else 0, self.status[1:2])
+        return self.idx, self.val, self.status[1:2]
+
+    def step(self, budget_bytes: int):
+        kimad_step(self.handle, budget_bytes, self.err_table, self.j, self.K, self.offsets, self.idx, self.val,
+                   self.capacity_pairs, self.status)
+        return self.status
+
+    def diagnostics(self):
+        out = (C.c_uint32 * 2)()
+        _check(lib().kimad_profile_diagnostics(C.c_void_p(self.handle), out, C.c_void_p(_stream(None))),
+               "kimad_profile_diagnostics")
+        return int(out[0]), int(out[1])
+
+    def close(self):
+        if getattr(self, "handle", 0):
+            kimad_plan_destroy(self.handle)
+            self.handle = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

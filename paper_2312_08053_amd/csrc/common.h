@@ -1,0 +1,166 @@
+// Shared definitions for the gfx950 kernels: layouts, radix digits, loaders, wave primitives.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace kimad {
+
+// ---- radix decomposition of the 31-bit magnitude key -------------------------------------
+// key = bits(x) & 0x7fffffff.  digit 1 = key[30:19] (8 exponent + 4 mantissa bits), digit 2 =
+// key[18:12], digit 3 = key[11:0].  Every element of one digit-1 bin shares its exponent field,
+// which lets squares be summed exactly as integers relative to that exponent.
+constexpr uint32_t D1_BITS = 12, D2_BITS = 7, D3_BITS = 12;
+constexpr uint32_t D1_BINS = 1u << D1_BITS;   // 4096
+constexpr uint32_t D2_BINS = 1u << D2_BITS;   // 128
+constexpr uint32_t D3_BINS = 1u << D3_BITS;   // 4096
+constexpr uint32_t D1_SHIFT = 19, D2_SHIFT = 12;
+constexpr uint32_t MAX_SLOTS = 64;            // distinct boundary bins per layer (<= J)
+constexpr uint32_t NO_SLOT = 0xFF;
+constexpr uint32_t KIMAD_MAX_J_CONST = 64;   // must equal KIMAD_MAX_J of the public header
+constexpr uint32_t KEY_INVALID = 0xFFFFFFFFu; // marks lanes outside the layer
+
+constexpr uint32_t SMALL_MAX = 8192;          // layers up to this size are sorted whole in LDS
+constexpr uint32_t CHUNK = 2048;              // elements one wave compacts at a time
+constexpr uint32_t SQ_SHIFT = 16;             // squares of 24-bit significands are kept >> 16
+constexpr uint64_t CNT_ONE = 1ull << 48;      // packed LDS entry: [count:16 | sum of squares:48]
+constexpr uint64_t SQ_MASK = CNT_ONE - 1;
+
+// selection modes of a layer in the compaction pass
+enum : uint32_t { SEL_NONE = 0, SEL_PREFIX = 1, SEL_ALL = 2 };
+
+struct LayerDesc {
+    const float* g;
+    float* h;
+    uint32_t n;        // elements
+    uint32_t mis;      // (address of g / 4) & 3: virtual index v = element + mis is 16-byte aligned at v % 4 == 0
+    uint32_t hvec;     // h has the same misalignment, so it can be read with 16-byte loads too
+    int32_t big;       // index among the tiled ("big") layers, -1 for a small layer
+    uint32_t tile0;    // first tile of this layer in the tile list
+    uint32_t ntiles;
+    uint32_t chunk0;   // first chunk of this layer in the chunk list
+    uint32_t nchunks;
+};
+
+// Per big layer, what the compaction pass needs.
+struct SelRec {
+    uint32_t mode;     // SEL_*
+    uint32_t prefix;   // 19-bit key prefix of the threshold (digit1 | digit2)
+    uint32_t above;    // entries whose prefix is greater (certainly selected)
+    uint32_t amb;      // entries whose prefix is equal (decided by digit 3)
+    uint64_t tmp_base; // start of this layer's candidates in the candidate buffer
+    uint32_t cap;      // candidates this layer may write
+    uint32_t K;
+};
+
+// ---- small device helpers ----------------------------------------------------------------
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+
+__device__ __forceinline__ uint32_t mbcnt(uint64_t mask) {
+    // number of set bits of mask below the calling lane
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+__device__ __forceinline__ uint64_t ballot(bool p) { return __ballot(p); }
+
+__device__ __forceinline__ uint32_t key_of(float x) { return __float_as_uint(x) & 0x7FFFFFFFu; }
+
+// Integer square of the significand, truncated to 32 bits.  For bin 0 (denormals below 2^-130
+// and zeros) callers use sq_exact() instead.  Exponent 255 (Inf/NaN) contributes a NaN count.
+__device__ __forceinline__ uint32_t sq_fixed(uint32_t key) {
+    uint32_t e = key >> 23, m = key & 0x7FFFFFu;
+    uint32_t m24 = e ? (m | 0x800000u) : m;
+    uint64_t sq = (uint64_t)m24 * (uint64_t)m24;
+    uint32_t c = (uint32_t)(sq >> SQ_SHIFT);
+    return e == 255u ? (m != 0u ? 1u : 0u) : c;
+}
+__device__ __forceinline__ uint64_t sq_exact(uint32_t key) {   // key < 2^19
+    return (uint64_t)key * (uint64_t)key;
+}
+
+// Value of one unit of a digit-1 bin's integer sum of squares, as a double.
+__device__ __forceinline__ double bin_scale(uint32_t bin1) {
+    uint32_t e = bin1 >> 4;
+    if (bin1 == 0u) return __longlong_as_double((int64_t)(1023 - 298) << 52);           // 2^-298
+    int ex = 2 * ((int)(e ? e : 1u) - 150) + (int)SQ_SHIFT;
+    return __longlong_as_double((int64_t)(1023 + ex) << 52);
+}
+__device__ __forceinline__ double sq_to_double(uint32_t bin1, uint64_t s, uint32_t cnt) {
+    // Exponent 255: s counts NaNs.  Any NaN makes the sum NaN, otherwise any entry makes it Inf.
+    if ((bin1 >> 4) == 255u) {
+        if (s) return __longlong_as_double(0x7FF8000000000000ll);
+        return cnt ? __longlong_as_double(0x7FF0000000000000ll) : 0.0;
+    }
+    return (double)s * bin_scale(bin1);
+}
+
+// Four consecutive virtual positions v .. v+3 of a layer (v % 4 == 0).  Lanes outside the layer
+// get KEY_INVALID.  16-byte loads are used when the quad is entirely inside.
+struct Quad {
+    float g[4], h[4];
+    uint32_t key[4];
+};
+
+__device__ __forceinline__ void load_quad(const LayerDesc& L, uint32_t v, Quad& q) {
+    const uint32_t lo = L.mis, hi = L.mis + L.n;
+    if (v >= lo && v + 4u <= hi) {
+        const uint32_t e = v - lo;
+        const float4 G = *reinterpret_cast<const float4*>(L.g + e);
+        q.g[0] = G.x; q.g[1] = G.y; q.g[2] = G.z; q.g[3] = G.w;
+        if (L.hvec) {
+            const float4 H = *reinterpret_cast<const float4*>(L.h + e);
+            q.h[0] = H.x; q.h[1] = H.y; q.h[2] = H.z; q.h[3] = H.w;
+        } else {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) q.h[c] = L.h[e + c];
+        }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) q.key[c] = key_of(q.g[c] - q.h[c]);
+    } else {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t vv = v + c;
+            if (vv >= lo && vv < hi) {
+                q.g[c] = L.g[vv - lo];
+                q.h[c] = L.h[vv - lo];
+                q.key[c] = key_of(q.g[c] - q.h[c]);
+            } else {
+                q.g[c] = 0.f; q.h[c] = 0.f; q.key[c] = KEY_INVALID;
+            }
+        }
+    }
+}
+
+// Block-wide exclusive scan over one value per thread (any block size that is a multiple of 64,
+// up to 1024).  `scratch` needs 16 entries.  Returns the exclusive prefix; *total gets the sum.
+template <typename T>
+__device__ __forceinline__ T wave_inclusive_scan(T v) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        T o = __shfl_up(v, d, 64);
+        if ((int)lane_id() >= d) v += o;
+    }
+    return v;
+}
+
+template <typename T>
+__device__ __forceinline__ T block_exclusive_scan(T v, T* scratch, T* total) {
+    const uint32_t w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    T inc = wave_inclusive_scan(v);
+    // exclusive prefix taken from the neighbouring lane: subtracting v back out would cancel
+    // catastrophically for floating-point sums whose terms grow along the scan
+    T exc = __shfl_up(inc, 1, 64);
+    if (lane_id() == 0) exc = 0;
+    if (lane_id() == 63) scratch[w] = inc;
+    __syncthreads();
+    T base = 0, tot = 0;
+    for (uint32_t i = 0; i < nw; ++i) {
+        T s = scratch[i];
+        if (i < w) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    if (total) *total = tot;
+    return base + exc;
+}
+
+}  // namespace kimad

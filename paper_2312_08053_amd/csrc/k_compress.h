@@ -1,0 +1,427 @@
+// Selection, compaction and estimator update.
+//
+// Computes, per layer, the support of TopK_K(x) for x = g - h (paper Section 2.2), writes the
+// (index, value) payload that Algorithm 1's worker uploads, and applies h <- h + TopK(x)
+// (Section 3.3, Eq. EF21-2).  Equal magnitudes are kept in order of lower index.
+//
+// Tiled layers: one streaming pass writes every entry whose 19-bit key prefix is >= the layer's
+// threshold prefix into a candidate buffer (in index order inside each 2048-element chunk) and
+// histograms the last 12 key bits of the entries whose prefix is equal.  Four small kernels then
+// fix the exact threshold key and tie quota, count survivors per chunk, scan the chunks in index
+// order and write payload and estimator.
+#pragma once
+#include "common.h"
+#include "k_profile.h"   // LDS sort helpers shared with the small-layer profile
+
+namespace kimad {
+
+struct CompressBuffers {
+    const LayerDesc* layers;
+    const uint32_t* chunk_layer;  // tile -> layer (a tile holds tile_elems / CHUNK chunks)
+    const uint32_t* big_layer;
+    const uint32_t* small_layer;
+    uint32_t tile_elems;
+    uint32_t L, B, J;
+    const uint32_t* Ktab;         // [L][J] grid sizes
+    // threshold cache written by the profile scans
+    const uint32_t* sel_prefix;
+    const uint32_t* sel_above;
+    const uint32_t* sel_amb;
+    // per big layer
+    SelRec* sel;                  // [B]
+    uint32_t* cursor;             // [B] candidates reserved so far
+    uint32_t* hist3;              // [B][4096] last-digit histogram of the ambiguous entries
+    uint32_t* tau;                // [B] exact threshold key
+    uint32_t* quota;              // [B] entries equal to tau that are kept (lowest indices)
+    // per chunk
+    uint32_t* rec_start;          // start inside the layer's candidate region
+    uint32_t* rec_cnt;            // candidates written
+    uint32_t* rec_amb;            // of which ambiguous
+    uint32_t* c_gt;               // candidates above tau
+    uint32_t* c_eq;               // candidates equal to tau
+    uint32_t* o_base;             // first payload slot of the chunk inside the layer
+    uint32_t* o_allow;            // ties this chunk may keep
+    // candidate buffer
+    uint32_t* tmp_idx;
+    float* tmp_x;
+    float* tmp_h;
+    uint64_t tmp_capacity;
+    // outputs
+    const uint64_t* K;
+    const uint64_t* offsets;
+    uint32_t* idx_out;
+    float* val_out;
+    uint64_t capacity_pairs;
+    int32_t* status;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Per layer: turn K[i] into a selection record using the profile's threshold cache.
+// One workgroup; thread b handles big layer b (looping).
+__global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_offgrid, int32_t err_scratch,
+                                                int32_t err_offsets) {
+    __shared__ unsigned long long s64[16];
+    __shared__ int bad;
+    const uint32_t tid = threadIdx.x;
+    if (tid == 0) bad = 0;
+    __syncthreads();
+    // validate offsets / K for every layer
+    for (uint32_t i = tid; i < cb.L; i += 256) {
+        const uint64_t K = cb.K[i], off = cb.offsets[i];
+        if (K > cb.layers[i].n || off > cb.capacity_pairs || K > cb.capacity_pairs - off) atomicMax(&bad, 1);
+    }
+    __syncthreads();
+    const bool offsets_bad = bad != 0;
+    __syncthreads();
+    unsigned long long running = 0;            // candidates of the big layers handled in earlier rounds
+    for (uint32_t b0 = 0; b0 < cb.B; b0 += 256) {
+        const uint32_t b = b0 + tid;
+        SelRec r;
+        r.mode = SEL_NONE; r.prefix = 0; r.above = 0; r.amb = 0; r.tmp_base = 0; r.cap = 0; r.K = 0;
+        if (b < cb.B && !offsets_bad) {
+            const uint32_t li = cb.big_layer[b];
+            const uint32_t n = cb.layers[li].n;
+            const uint32_t K = (uint32_t)cb.K[li];
+            r.K = K;
+            if (K == 0u) {
+                r.mode = SEL_NONE;
+            } else if (K == n) {
+                r.mode = SEL_ALL; r.cap = n; r.above = n;
+            } else {
+                int found = -1;
+                for (uint32_t j = 0; j < cb.J; ++j)
+                    if (cb.Ktab[(size_t)li * cb.J + j] == K) { found = (int)j; break; }
+                if (found < 0) {
+                    atomicMax(&bad, 2);
+                } else {
+                    const size_t t = (size_t)li * cb.J + found;
+                    r.mode = SEL_PREFIX;
+                    r.prefix = cb.sel_prefix[t];
+                    r.above = cb.sel_above[t];
+                    r.amb = cb.sel_amb[t];
+                    r.cap = r.above + r.amb;
+                }
+            }
+        }
+        unsigned long long tot;
+        const unsigned long long ex = block_exclusive_scan<unsigned long long>((unsigned long long)r.cap, s64, &tot);
+        r.tmp_base = running + ex;
+        running += tot;
+        if (b < cb.B) {
+            cb.sel[b] = r;
+            cb.cursor[b] = 0u;
+        }
+    }
+    __syncthreads();
+    const bool overflow = running > cb.tmp_capacity;
+    if (overflow || bad) {
+        // refuse the whole call: nothing is written by the later kernels
+        for (uint32_t b = tid; b < cb.B; b += 256) { cb.sel[b].mode = SEL_NONE; cb.sel[b].cap = 0; cb.sel[b].K = 0; }
+        if (tid == 0) *cb.status = offsets_bad ? err_offsets : (bad == 2 ? err_offgrid : err_scratch);
+    } else if (tid == 0) {
+        *cb.status = 0;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Streaming compaction pass.  One wave per 2048-element chunk; a workgroup of 4 waves walks the
+// chunks of one tile.  Each lane holds 8 quads (32 elements); positions come from ballots, so
+// the candidates of a chunk are written in index order at a range reserved with one atomic.
+__global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
+    const uint32_t tile = blockIdx.x;
+    const uint32_t li = cb.chunk_layer[tile];
+    const LayerDesc L = cb.layers[li];
+    const SelRec S = cb.sel[L.big];
+    const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+    const uint32_t chunks_per_tile = cb.tile_elems / CHUNK;
+    const uint32_t tile_in_layer = tile - L.tile0;
+    uint32_t* hist3 = cb.hist3 + (size_t)L.big * D3_BINS;
+
+    for (uint32_t cc = wave; cc < chunks_per_tile; cc += 4) {
+        const uint32_t chunk_in_layer = tile_in_layer * chunks_per_tile + cc;
+        if (chunk_in_layer >= L.nchunks) break;
+        const uint32_t chunk = L.chunk0 + chunk_in_layer;
+        if (S.mode == SEL_NONE) {
+            if (lane == 0) { cb.rec_start[chunk] = 0; cb.rec_cnt[chunk] = 0; cb.rec_amb[chunk] = 0; }
+            continue;
+        }
+        const uint32_t vbase = chunk_in_layer * CHUNK;
+        Quad q[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) load_quad(L, vbase + u * 256u + lane * 4u, q[u]);
+
+        // flags: bit c of sel[u] = candidate, of amb[u] = ambiguous
+        uint32_t selm[8], ambm[8];
+        uint32_t mine = 0, mine_amb = 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            selm[u] = 0; ambm[u] = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t key = q[u].key[c];
+                if (key == KEY_INVALID) continue;
+                const uint32_t p = key >> D2_SHIFT;
+                const bool all = S.mode == SEL_ALL;
+                const bool sure = all || p > S.prefix;
+                const bool amb = !all && p == S.prefix;
+                if (sure || amb) { selm[u] |= 1u << c; ++mine; }
+                if (amb) { ambm[u] |= 1u << c; ++mine_amb; }
+            }
+        }
+        // wave totals and the exclusive prefix of `mine` over lanes, per quad row
+        uint32_t total = 0, total_amb = 0;
+        uint32_t rowbase[8];                    // candidates in earlier rows + earlier lanes of this row
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const uint32_t cnt = __popc(selm[u]);
+            // exclusive prefix over lanes of a small integer: three ballots on its bits
+            const uint64_t b0 = ballot(cnt & 1u), b1 = ballot(cnt & 2u), b2 = ballot(cnt & 4u);
+            const uint32_t ex = mbcnt(b0) + 2u * mbcnt(b1) + 4u * mbcnt(b2);
+            rowbase[u] = total + ex;
+            total += __popcll(b0) + 2u * __popcll(b1) + 4u * __popcll(b2);
+        }
+        {
+            uint32_t a = mine_amb;
+#pragma unroll
+            for (int d = 32; d > 0; d >>= 1) a += __shfl_xor(a, d, 64);
+            total_amb = a;
+        }
+        uint32_t start = 0;
+        if (total) {
+            if (lane == 0) start = atomicAdd(&cb.cursor[L.big], total);
+            start = __shfl(start, 0, 64);
+        }
+        // Reservations never exceed the layer's cap when the cache matches the data; if the data
+        // changed since the profile, drop what does not fit instead of writing out of bounds.
+        const uint32_t written = start >= S.cap ? 0u : min(total, S.cap - start);
+        if (lane == 0) { cb.rec_start[chunk] = start; cb.rec_cnt[chunk] = written; cb.rec_amb[chunk] = total_amb; }
+        if (total == 0) continue;
+        const uint64_t base = S.tmp_base + start;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            uint32_t pos = rowbase[u];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (selm[u] & (1u << c)) {
+                    if ((uint64_t)start + pos < S.cap) {
+                        const uint64_t o = base + pos;
+                        cb.tmp_idx[o] = vbase + u * 256u + lane * 4u + c - L.mis;
+                        cb.tmp_x[o] = q[u].g[c] - q[u].h[c];
+                        cb.tmp_h[o] = q[u].h[c];
+                    }
+                    ++pos;
+                }
+            }
+        }
+        if (total_amb) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const bool a = (ambm[u] >> c) & 1u;
+                    const uint64_t am = ballot(a);
+                    if (am == 0) continue;
+                    const uint32_t low = q[u].key[c] & (D3_BINS - 1);
+                    // one atomic per wave when every ambiguous lane holds the same key (zeros, constants)
+                    const uint32_t first = __shfl(low, __ffsll((long long)am) - 1, 64);
+                    const bool uniform = ballot(a && low != first) == 0;
+                    if (uniform) {
+                        if (lane == (uint32_t)(__ffsll((long long)am) - 1)) atomicAdd(&hist3[first], (uint32_t)__popcll(am));
+                    } else if (a) {
+                        atomicAdd(&hist3[low], 1u);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Exact threshold key and tie quota per big layer from the last-digit histogram.
+__global__ __launch_bounds__(256) void k_resolve(CompressBuffers cb) {
+    __shared__ uint32_t su[16];
+    __shared__ uint32_t res[2];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    const SelRec S = cb.sel[b];
+    if (S.mode != SEL_PREFIX) {
+        if (tid == 0) { cb.tau[b] = 0u; cb.quota[b] = 0u; }   // SEL_ALL: every key is > "-1"; handled by mode
+        return;
+    }
+    const uint32_t need = S.K - S.above;           // 1..amb entries to take from the ambiguous ones
+    const uint32_t* h = cb.hist3 + (size_t)b * D3_BINS;
+    // thread t owns digits 16t..16t+15; we need, from the top, the digit where the running count reaches `need`
+    uint32_t c[16], sum = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) { c[k] = h[tid * 16u + k]; sum += c[k]; }
+    uint32_t tot;
+    const uint32_t ex = block_exclusive_scan<uint32_t>(sum, su, &tot);
+    // entries in digits above this thread's range
+    uint32_t above = tot - ex - sum;
+    if (tid == 0) { res[0] = 0xFFFFFFFFu; res[1] = 0; }
+    __syncthreads();
+    if (above < need && above + sum >= need) {
+#pragma unroll
+        for (int k = 15; k >= 0; --k) {
+            if (above + c[k] >= need) { res[0] = tid * 16u + k; res[1] = need - above; break; }
+            above += c[k];
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        if (res[0] == 0xFFFFFFFFu) {               // histogram does not cover the quota (stale cache): keep all ambiguous
+            cb.tau[b] = S.prefix << D2_SHIFT; cb.quota[b] = 0xFFFFFFFFu;
+        } else {
+            cb.tau[b] = (S.prefix << D2_SHIFT) | res[0];
+            cb.quota[b] = res[1];
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per chunk: how many candidates lie above tau and how many equal it.  One wave per chunk.
+__global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_t nchunks_total,
+                                                     const uint32_t* chunk_big) {
+    const uint32_t chunk = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (chunk >= nchunks_total) return;
+    const uint32_t lane = lane_id();
+    const uint32_t b = chunk_big[chunk];
+    const SelRec S = cb.sel[b];
+    const uint32_t cnt = cb.rec_cnt[chunk], amb = cb.rec_amb[chunk];
+    uint32_t gt = cnt, eq = 0;
+    if (S.mode == SEL_PREFIX && amb) {
+        const uint32_t tau = cb.tau[b];
+        const uint64_t base = S.tmp_base + cb.rec_start[chunk];
+        gt = 0;
+        for (uint32_t k = lane; k < cnt; k += 64) {
+            const uint32_t key = key_of(cb.tmp_x[base + k]);
+            gt += key > tau;
+            eq += key == tau;
+        }
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
+    }
+    if (lane == 0) { cb.c_gt[chunk] = gt; cb.c_eq[chunk] = eq; }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per big layer: scan its chunks in index order.  Ties are granted to the lowest indices first.
+__global__ __launch_bounds__(1024) void k_chunk_scan(CompressBuffers cb) {
+    __shared__ uint32_t su[16];
+    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    const uint32_t li = cb.big_layer[b];
+    const LayerDesc L = cb.layers[li];
+    const uint32_t quota = cb.quota[b];
+    uint32_t run_eq = 0, run_out = 0;
+    for (uint32_t c0 = 0; c0 < L.nchunks; c0 += 1024) {
+        const uint32_t c = c0 + tid;
+        const bool ok = c < L.nchunks;
+        const uint32_t gt = ok ? cb.c_gt[L.chunk0 + c] : 0u;
+        const uint32_t eq = ok ? cb.c_eq[L.chunk0 + c] : 0u;
+        uint32_t eq_tot;
+        const uint32_t eq_before = run_eq + block_exclusive_scan<uint32_t>(eq, su, &eq_tot);
+        uint32_t allow = 0;
+        if (eq_before < quota) allow = min(eq, quota - eq_before);
+        uint32_t out_tot;
+        const uint32_t ob = run_out + block_exclusive_scan<uint32_t>(gt + allow, su, &out_tot);
+        if (ok) { cb.o_base[L.chunk0 + c] = ob; cb.o_allow[L.chunk0 + c] = allow; }
+        run_eq += eq_tot;
+        run_out += out_tot;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Per chunk: write the surviving candidates as payload and update the estimator.
+__global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t nchunks_total,
+                                                  const uint32_t* chunk_big) {
+    const uint32_t chunk = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (chunk >= nchunks_total) return;
+    const uint32_t lane = lane_id();
+    const uint32_t b = chunk_big[chunk];
+    const SelRec S = cb.sel[b];
+    if (S.mode == SEL_NONE) return;
+    const uint32_t cnt = cb.rec_cnt[chunk];
+    if (cnt == 0) return;
+    const uint32_t li = cb.big_layer[b];
+    float* h = cb.layers[li].h;
+    const bool filter = S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0;
+    const uint32_t tau = cb.tau[b];
+    const uint32_t allow = cb.o_allow[chunk];
+    const uint64_t src = S.tmp_base + cb.rec_start[chunk];
+    const uint64_t dst = cb.offsets[li];
+    const uint32_t room = S.K;                     // payload slots of this layer
+    uint32_t out_run = cb.o_base[chunk], eq_run = 0;
+    for (uint32_t k0 = 0; k0 < cnt; k0 += 64) {
+        const uint32_t k = k0 + lane;
+        const bool in = k < cnt;
+        uint32_t idx = 0; float x = 0.f, hv = 0.f;
+        if (in) { idx = cb.tmp_idx[src + k]; x = cb.tmp_x[src + k]; hv = cb.tmp_h[src + k]; }
+        bool keep = in;
+        if (filter) {
+            const uint32_t key = key_of(x);
+            const bool iseq = in && key == tau;
+            const uint64_t eqm = ballot(iseq);
+            keep = in && (key > tau || (iseq && eq_run + mbcnt(eqm) < allow));
+            eq_run += (uint32_t)__popcll(eqm);
+        }
+        const uint64_t km = ballot(keep);
+        const uint32_t pos = out_run + mbcnt(km);
+        if (keep && pos < room) {
+            const uint64_t o = dst + pos;
+            cb.idx_out[o] = idx;
+            cb.val_out[o] = x;
+            h[idx] = hv + x;
+        }
+        out_run += (uint32_t)__popcll(km);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Small layers: sort in LDS, mark the first K of the order, emit in index order.
+__global__ __launch_bounds__(256) void k_small_compress(CompressBuffers cb) {
+    __shared__ unsigned long long a[SMALL_MAX];
+    __shared__ uint32_t flag[SMALL_MAX / 32];
+    __shared__ uint32_t su[16];
+    __shared__ int bad;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t li = cb.small_layer[blockIdx.x];
+    const LayerDesc L = cb.layers[li];
+    // the lookup kernel refuses the whole call through the status word; small layers re-check
+    // their own slice so that nothing is written out of bounds
+    const uint64_t K64 = cb.K[li], off = cb.offsets[li];
+    if (tid == 0) bad = (*cb.status != 0);
+    __syncthreads();
+    if (bad || K64 == 0 || K64 > L.n || off > cb.capacity_pairs || K64 > cb.capacity_pairs - off) return;
+    const uint32_t K = (uint32_t)K64;
+    const uint32_t P = next_pow2(L.n < 2 ? 2 : L.n);
+    load_sorted_small(L, a, P);
+    bitonic_sort_lds<256>(a, P);
+    for (uint32_t w = tid; w < SMALL_MAX / 32; w += 256) flag[w] = 0u;
+    __syncthreads();
+    for (uint32_t rk = tid; rk < K; rk += 256) {
+        const uint32_t idx = (uint32_t)a[rk];
+        atomicOr(&flag[idx >> 5], 1u << (idx & 31));
+    }
+    __syncthreads();
+    // emit in index order: thread t owns indices [t*per, (t+1)*per), per a multiple of 32 or the whole word range
+    const uint32_t words = (L.n + 31) / 32;
+    const uint32_t wper = (words + 255) / 256;
+    uint32_t mine = 0;
+    for (uint32_t w = tid * wper; w < min(words, (tid + 1) * wper); ++w) mine += __popc(flag[w]);
+    uint32_t pos = block_exclusive_scan<uint32_t>(mine, su, nullptr);
+    for (uint32_t w = tid * wper; w < min(words, (tid + 1) * wper); ++w) {
+        uint32_t f = flag[w];
+        while (f) {
+            const uint32_t bit = __ffs(f) - 1;
+            f &= f - 1;
+            const uint32_t idx = w * 32 + bit;
+            const float g = L.g[idx], hv = L.h[idx];
+            const float x = g - hv;
+            cb.idx_out[off + pos] = idx;
+            cb.val_out[off + pos] = x;
+            L.h[idx] = hv + x;
+            ++pos;
+        }
+    }
+}
+
+}  // namespace kimad

@@ -1,0 +1,397 @@
+// Error-profile kernels: two streaming histogram passes over g, h for the tiled layers, two
+// per-layer scan kernels, and a whole-layer LDS sort for small layers.
+//
+// What they compute is the Errors matrix of the paper's Appendix C with the squared-l2 error of
+// Section 3.2 (Eq. norm decomposition): E_ij = sum of x^2 over the entries TopK_{K_ij} drops.
+#pragma once
+#include "common.h"
+
+namespace kimad {
+
+struct ProfileBuffers {
+    const LayerDesc* layers;
+    const uint32_t* tile_layer;   // tile -> layer
+    const uint32_t* big_layer;    // big index -> layer
+    const uint32_t* small_layer;  // small index -> layer
+    uint32_t tile_elems;          // elements per tile (multiple of 2048, <= 32768)
+    // pass 1
+    uint32_t* cnt1;               // [B][4096]
+    uint64_t* sq1;                // [B][4096]
+    // boundary bins
+    uint8_t* lut1;                // [B][4096] digit-1 bin -> slot or NO_SLOT
+    uint32_t* nslots;             // [B]
+    uint32_t* slot_bin;           // [B][64]
+    // pass 2
+    uint32_t* cnt2;               // [B][64][128]
+    uint64_t* sq2;                // [B][64][128]
+    // per target (layer-major, stride J)
+    uint32_t* tgt_slot;           // slot, or NO_SLOT when K == n (nothing dropped)
+    uint32_t* tgt_r;              // entries selected inside the boundary bin (1..count)
+    uint32_t* tgt_above1;         // entries in higher digit-1 bins
+    double* tgt_below;            // sum of squares of all lower digit-1 bins
+    // threshold cache for the compaction pass
+    uint32_t* sel_prefix;         // 19-bit prefix
+    uint32_t* sel_above;          // entries with a greater prefix
+    uint32_t* sel_amb;            // entries with an equal prefix
+    uint32_t* diag;               // [0] uncertified entries, [1] entries fixed by the fallback
+};
+
+// ---------------------------------------------------------------------------------------------
+// Pass 1: per-layer histogram of digit 1 with counts and integer sums of squares.
+// One workgroup per tile; the histogram lives in LDS as packed 64-bit entries.
+__global__ __launch_bounds__(256) void k_hist1(ProfileBuffers pb) {
+    __shared__ unsigned long long hist[D1_BINS];
+    __shared__ unsigned long long sq0;         // exact squares of bin 0 (tiny denormals)
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t b = tid; b < D1_BINS; b += 256) hist[b] = 0ull;
+    if (tid == 0) sq0 = 0ull;
+    __syncthreads();
+
+    const uint32_t tile = blockIdx.x;
+    const uint32_t li = pb.tile_layer[tile];
+    const LayerDesc L = pb.layers[li];
+    const uint32_t vbase = (tile - L.tile0) * pb.tile_elems;
+    const uint32_t iters = pb.tile_elems / 1024u;
+
+    for (uint32_t it = 0; it < iters; it += 2) {
+        Quad q[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) load_quad(L, vbase + (it + u) * 1024u + tid * 4u, q[u]);
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t key = q[u].key[c];
+                if (key == KEY_INVALID) continue;
+                const uint32_t bin = key >> D1_SHIFT;
+                if (bin != 0u) {
+                    atomicAdd(&hist[bin], CNT_ONE | (unsigned long long)sq_fixed(key));
+                } else {
+                    atomicAdd(&hist[0], CNT_ONE);
+                    if (key) atomicAdd(&sq0, sq_exact(key));
+                }
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t* cnt = pb.cnt1 + (size_t)L.big * D1_BINS;
+    unsigned long long* sq = reinterpret_cast<unsigned long long*>(pb.sq1) + (size_t)L.big * D1_BINS;
+    for (uint32_t b = tid; b < D1_BINS; b += 256) {
+        const unsigned long long v = hist[b];
+        if (v) {
+            atomicAdd(&cnt[b], (uint32_t)(v >> 48));
+            const unsigned long long s = b ? (v & SQ_MASK) : sq0;
+            if (s) atomicAdd(&sq[b], s);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scan 1: per big layer, locate every candidate's boundary bin in digit 1.
+// targets: K values, row `li` of a [L][J] table.
+__global__ __launch_bounds__(256) void k_scan1(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J) {
+    __shared__ uint32_t cnt[D1_BINS];
+    __shared__ uint32_t above[D1_BINS];      // entries in strictly higher bins
+    __shared__ double below[D1_BINS];        // squares in strictly lower bins
+    __shared__ uint32_t su[16];
+    __shared__ double sd[16];
+    __shared__ uint32_t tbin[MAX_SLOTS];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t big = blockIdx.x;
+    const uint32_t li = pb.big_layer[big];
+    const LayerDesc L = pb.layers[li];
+    const uint32_t* gcnt = pb.cnt1 + (size_t)big * D1_BINS;
+    const uint64_t* gsq = pb.sq1 + (size_t)big * D1_BINS;
+
+    // thread t owns bins 16t .. 16t+15
+    uint32_t c[16];
+    double s[16];
+    uint32_t csum = 0;
+    double ssum = 0.0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const uint32_t b = tid * 16u + k;
+        c[k] = gcnt[b];
+        s[k] = sq_to_double(b, gsq[b], c[k]);
+        csum += c[k];
+        ssum += s[k];
+    }
+    uint32_t ctot;
+    const uint32_t cex = block_exclusive_scan<uint32_t>(csum, su, &ctot);
+    const double sex = block_exclusive_scan<double>(ssum, sd, nullptr);
+    {
+        uint32_t run_c = cex;      // entries in bins below the current one
+        double run_s = sex;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const uint32_t b = tid * 16u + k;
+            cnt[b] = c[k];
+            below[b] = run_s;
+            run_c += c[k];
+            above[b] = ctot - run_c;
+            run_s += s[k];
+        }
+    }
+    uint8_t* lut = pb.lut1 + (size_t)big * D1_BINS;
+    for (uint32_t b = tid; b < D1_BINS; b += 256) lut[b] = (uint8_t)NO_SLOT;
+    __syncthreads();
+
+    if (tid < J) {
+        const uint32_t K = Ktab[(size_t)li * J + tid];
+        uint32_t bin = 0xFFFFFFFFu;
+        if (K != 0u && K < L.n) {
+            // smallest bin with above[bin] < K (above is non-increasing, above[4095] = 0)
+            uint32_t lo = 0, hi = D1_BINS - 1;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (above[mid] < K) hi = mid; else lo = mid + 1;
+            }
+            bin = lo;
+            pb.tgt_r[(size_t)li * J + tid] = K - above[bin];
+            pb.tgt_above1[(size_t)li * J + tid] = above[bin];
+            pb.tgt_below[(size_t)li * J + tid] = below[bin];
+        }
+        tbin[tid] = bin;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        // Targets are sorted by K, so equal boundary bins are adjacent.
+        uint32_t ns = 0, last = 0xFFFFFFFFu;
+        for (uint32_t j = 0; j < J; ++j) {
+            const uint32_t bin = tbin[j];
+            uint32_t slot = NO_SLOT;
+            if (bin != 0xFFFFFFFFu) {
+                if (bin != last) {
+                    lut[bin] = (uint8_t)ns;
+                    pb.slot_bin[(size_t)big * MAX_SLOTS + ns] = bin;
+                    last = bin;
+                    ++ns;
+                }
+                slot = ns - 1;
+            }
+            pb.tgt_slot[(size_t)li * J + j] = slot;
+        }
+        pb.nslots[big] = ns;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pass 2: digit-2 histograms (count + squares) of the entries that fall in a boundary bin.
+__global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb) {
+    __shared__ unsigned long long sub[MAX_SLOTS * D2_BINS];   // 64 KB
+    __shared__ unsigned long long sub0[D2_BINS];              // exact squares when the slot is bin 0
+    __shared__ uint8_t lut[D1_BINS];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t tile = blockIdx.x;
+    const uint32_t li = pb.tile_layer[tile];
+    const LayerDesc L = pb.layers[li];
+    const uint32_t ns = pb.nslots[L.big];
+    if (ns == 0) return;
+    {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(pb.lut1 + (size_t)L.big * D1_BINS);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
+        for (uint32_t b = tid; b < D1_BINS / 4; b += 512) dst[b] = src[b];
+    }
+    for (uint32_t b = tid; b < ns * D2_BINS; b += 512) sub[b] = 0ull;
+    if (tid < D2_BINS) sub0[tid] = 0ull;
+    __syncthreads();
+
+    const uint32_t vbase = (tile - L.tile0) * pb.tile_elems;
+    const uint32_t iters = pb.tile_elems / 2048u;
+    for (uint32_t it = 0; it < iters; it += 2) {
+        Quad q[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (it + u < iters) load_quad(L, vbase + (it + u) * 2048u + tid * 4u, q[u]);
+            else { q[u].key[0] = q[u].key[1] = q[u].key[2] = q[u].key[3] = KEY_INVALID; }
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t key = q[u].key[c];
+                if (key == KEY_INVALID) continue;
+                const uint32_t bin = key >> D1_SHIFT;
+                const uint32_t slot = lut[bin];
+                if (slot == NO_SLOT) continue;
+                const uint32_t d2 = (key >> D2_SHIFT) & (D2_BINS - 1);
+                if (bin != 0u) {
+                    atomicAdd(&sub[slot * D2_BINS + d2], CNT_ONE | (unsigned long long)sq_fixed(key));
+                } else {
+                    atomicAdd(&sub[slot * D2_BINS + d2], CNT_ONE);
+                    if (key) atomicAdd(&sub0[d2], sq_exact(key));
+                }
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t* cnt = pb.cnt2 + (size_t)L.big * MAX_SLOTS * D2_BINS;
+    unsigned long long* sq = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)L.big * MAX_SLOTS * D2_BINS;
+    const uint32_t slot0 = lut[0];   // slot of bin 0, if it is a boundary bin
+    for (uint32_t b = tid; b < ns * D2_BINS; b += 512) {
+        const unsigned long long v = sub[b];
+        if (v) {
+            atomicAdd(&cnt[b], (uint32_t)(v >> 48));
+            const unsigned long long s = (b / D2_BINS == slot0) ? sub0[b % D2_BINS] : (v & SQ_MASK);
+            if (s) atomicAdd(&sq[b], s);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scan 2: per big layer and candidate, locate the boundary inside digit 2, assemble E_ij and
+// remember the 19-bit threshold prefix.  What is left undecided is how the `unsel` smallest of
+// the `m` entries sharing that prefix split the prefix bin's exact sum of squares Q; their
+// magnitudes differ by at most 2^-11 relative, and the estimate below is clamped to rigorous
+// bounds.  Entries whose bound is not tight enough are counted in diag[0].
+__device__ __forceinline__ float prefix_lo(uint32_t prefix) { return __uint_as_float(prefix << D2_SHIFT); }
+
+__global__ __launch_bounds__(64) void k_scan2(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
+                                              double* err_table, double tol) {
+    const uint32_t big = blockIdx.x;
+    const uint32_t li = pb.big_layer[big];
+    const LayerDesc L = pb.layers[li];
+    const uint32_t j = threadIdx.x;
+    if (j >= J) return;
+    const size_t t = (size_t)li * J + j;
+    const uint32_t K = Ktab[t];
+    const uint32_t slot = pb.tgt_slot[t];
+    if (slot == NO_SLOT) {                      // K == n (or K == 0): nothing / everything dropped
+        if (err_table) err_table[t] = 0.0;
+        pb.sel_prefix[t] = 0u;
+        pb.sel_above[t] = (K == 0u) ? 0u : L.n;
+        pb.sel_amb[t] = 0u;
+        return;
+    }
+    const uint32_t bin = pb.slot_bin[(size_t)big * MAX_SLOTS + slot];
+    const uint32_t r = pb.tgt_r[t];
+    const uint32_t* cnt = pb.cnt2 + ((size_t)big * MAX_SLOTS + slot) * D2_BINS;
+    const uint64_t* sq = pb.sq2 + ((size_t)big * MAX_SLOTS + slot) * D2_BINS;
+    // walk digit 2 from the top until r entries are covered
+    uint32_t acc = 0;
+    int u = (int)D2_BINS - 1;
+    for (; u > 0; --u) {
+        const uint32_t cu = cnt[u];
+        if (acc + cu >= r) break;
+        acc += cu;
+    }
+    const uint32_t m = cnt[u];
+    const uint32_t rsel = r - acc;              // 1..m selected inside the prefix bin
+    const uint32_t unsel = m - rsel;
+    double below2 = 0.0;
+    for (int k = 0; k < u; ++k) below2 += sq_to_double(bin, sq[k], cnt[k]);
+    const uint32_t prefix = (bin << D2_BITS) | (uint32_t)u;
+    double est = 0.0, bound = 0.0;
+    if (unsel) {
+        const double Q = sq_to_double(bin, sq[u], m);
+        const double lo = (double)prefix_lo(prefix), hi = (double)prefix_lo(prefix + 1u);
+        const double f = (double)unsel / (double)m;
+        double ub = fmin(f * Q, (double)unsel * hi * hi);
+        double lb = fmax((double)unsel * lo * lo, Q - (double)rsel * hi * hi);
+        if (!(lb <= ub)) { const double mid = 0.5 * (lb + ub); lb = ub = mid; }
+        // smooth-density model: the dropped entries fill the lowest fraction f of [lo, hi)
+        const double w = hi - lo;
+        const double a = lo + 0.5 * f * w, c = lo + 0.5 * w;
+        est = (double)unsel * a * a * (Q / ((double)m * c * c));
+        if (!(est >= lb)) est = lb;
+        if (!(est <= ub)) est = ub;
+        bound = fmax(ub - est, est - lb);
+        if ((bin >> 4) == 255u) {
+            // Inf/NaN entries: the dropped ones are the lowest keys, i.e. the infinities first.
+            const uint64_t nans = sq[u];
+            const uint64_t infs = (uint64_t)m - nans;
+            est = (uint64_t)unsel > infs ? __longlong_as_double(0x7FF8000000000000ll)
+                                         : __longlong_as_double(0x7FF0000000000000ll);
+            bound = 0.0;
+        }
+    }
+    const double E = pb.tgt_below[t] + below2 + est;
+    if (err_table) err_table[t] = E;
+    if (bound > tol * E) atomicAdd(&pb.diag[0], 1u);
+    pb.sel_prefix[t] = prefix;
+    pb.sel_above[t] = pb.tgt_above1[t] + acc;
+    pb.sel_amb[t] = m;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Small layers: the whole layer is sorted in LDS by (magnitude descending, index ascending);
+// E_ij is the suffix sum of squares in sorted order, in fp64.  One workgroup per layer.
+// Sort key: (0x7fffffff - key) << 32 | index, ascending.
+template <uint32_t THREADS>
+__device__ __forceinline__ void bitonic_sort_lds(unsigned long long* a, uint32_t P) {
+    for (uint32_t k = 2; k <= P; k <<= 1) {
+        for (uint32_t jj = k >> 1; jj > 0; jj >>= 1) {
+            for (uint32_t t = threadIdx.x; t < P / 2; t += THREADS) {
+                const uint32_t i = 2 * t - (t & (jj - 1));     // index with bit jj clear
+                const uint32_t l = i + jj;
+                const bool up = ((i & k) == 0);
+                const unsigned long long x = a[i], y = a[l];
+                if ((x > y) == up) { a[i] = y; a[l] = x; }
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__device__ __forceinline__ uint32_t next_pow2(uint32_t n) {
+    uint32_t p = 1;
+    while (p < n) p <<= 1;
+    return p;
+}
+
+__device__ __forceinline__ void load_sorted_small(const LayerDesc& L, unsigned long long* a, uint32_t P) {
+    for (uint32_t e = threadIdx.x; e < P; e += blockDim.x) {
+        unsigned long long v = ~0ull;
+        if (e < L.n) {
+            const uint32_t key = key_of(L.g[e] - L.h[e]);
+            v = ((unsigned long long)(0x7FFFFFFFu - key) << 32) | e;
+        }
+        a[e] = v;
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(256) void k_small_profile(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
+                                                       double* err_table) {
+    __shared__ unsigned long long a[SMALL_MAX];       // 64 KB
+    __shared__ double loc[256];
+    const uint32_t li = pb.small_layer[blockIdx.x];
+    const LayerDesc L = pb.layers[li];
+    const uint32_t P = next_pow2(L.n < 2 ? 2 : L.n);
+    load_sorted_small(L, a, P);
+    bitonic_sort_lds<256>(a, P);
+    // thread t owns ranks [t*per, (t+1)*per) and sums their squares from the smallest upward
+    const uint32_t per = P / 256u ? P / 256u : 1u;
+    const uint32_t tid = threadIdx.x;
+    double local = 0.0;
+    for (uint32_t k = per; k-- > 0;) {
+        const uint32_t rk = tid * per + k;
+        if (rk < L.n) {
+            const uint32_t key = 0x7FFFFFFFu - (uint32_t)(a[rk] >> 32);
+            const double v = (double)__uint_as_float(key);
+            local += v * v;
+        }
+    }
+    loc[tid] = local;
+    __syncthreads();
+    if (tid < J) {
+        const uint32_t K = Ktab[(size_t)li * J + tid];
+        double E = 0.0;
+        if (K < L.n) {
+            // ranks >= K are dropped: all later threads' sums (smallest first), then the tail of
+            // the thread that owns rank K
+            const uint32_t owner = K / per;
+            for (uint32_t w = 255; w > owner; --w) E += loc[w];
+            for (uint32_t rk = (owner + 1) * per; rk-- > K;) {
+                if (rk < L.n) {
+                    const uint32_t key = 0x7FFFFFFFu - (uint32_t)(a[rk] >> 32);
+                    const double v = (double)__uint_as_float(key);
+                    E += v * v;
+                }
+            }
+        }
+        err_table[(size_t)li * J + tid] = E;
+    }
+}
+
+}  // namespace kimad

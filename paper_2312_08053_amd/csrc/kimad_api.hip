@@ -1,0 +1,493 @@
+// C ABI of the library: argument checks, workspace layout, kernel launches.
+// Declarations and the contract of every entry point are in include/kimad.h.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/kimad.h"
+#include "common.h"
+#include "k_profile.h"
+#include "k_compress.h"
+#include "k_alloc.h"
+
+static_assert(kimad::KIMAD_MAX_J_CONST == KIMAD_MAX_J, "J limit mismatch");
+
+namespace {
+
+using namespace kimad;
+
+constexpr uint64_t ALIGN = 256;
+
+inline uint64_t align_up(uint64_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+// Byte offsets of every array inside the workspace.
+struct Layout {
+    uint32_t L = 0, J = 0, B = 0, S = 0;
+    uint32_t tile_elems = 0, ntiles = 0, nchunks = 0;
+    uint64_t dp_cells = 0, tmp_cap = 0, sum_kmax = 0;
+    // static tables
+    uint64_t layers, ktab, tile_layer, chunk_big, big_layer, small_layer;
+    // zeroed before every profile
+    uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, zero1_end;
+    uint64_t lut1, nslots, slot_bin;
+    uint64_t tgt_slot, tgt_r, tgt_above1, tgt_below, sel_prefix, sel_above, sel_amb;
+    // compress
+    uint64_t ksel, sel, cursor, zero2_begin, hist3, zero2_end, tau, quota;
+    uint64_t rec_start, rec_cnt, rec_amb, c_gt, c_eq, o_base, o_allow;
+    uint64_t tmp_idx, tmp_x, tmp_h;
+    // allocation
+    uint64_t row0, row1, choice, dp_flags;
+    uint64_t total = 0;
+};
+
+struct HostLayer {
+    uint32_t n, mis, hvec;
+    int32_t big;
+    uint32_t tile0, ntiles, chunk0, nchunks;
+};
+
+uint32_t pick_tile_elems(uint64_t d_big) {
+    // aim at >= 8 tiles per compute unit on large inputs, keep tiles within the 16-bit LDS counters
+    uint64_t t = 32768;
+    while (t > 2048 && d_big / t < 256ull * 8ull) t >>= 1;
+    return (uint32_t)t;
+}
+
+uint32_t grid_size_K(double r, uint64_t n) {
+    double k = std::ceil(r * (double)n);
+    if (k < 1.0) k = 1.0;
+    if (k > (double)n) k = (double)n;
+    return (uint32_t)k;
+}
+
+// Shapes only: misalignment is taken as the worst case (3) so that the layout does not depend on
+// pointer values and kimad_workspace_bytes can be called before the tensors exist.
+int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t& cfg, Layout& lo,
+                std::vector<HostLayer>* hl) {
+    if (!n || L == 0 || L > 65535 || J == 0 || J > KIMAD_MAX_J) return KIMAD_ERR_INVALID_ARG;
+    lo.L = L; lo.J = J;
+    uint64_t d_big = 0, d_all = 0;
+    uint32_t B = 0, S = 0;
+    for (uint32_t i = 0; i < L; ++i) {
+        if (n[i] == 0 || n[i] > KIMAD_MAX_N) return KIMAD_ERR_INVALID_ARG;
+        d_all += n[i];
+        if (n[i] > SMALL_MAX) { d_big += n[i]; ++B; } else ++S;
+    }
+    lo.B = B; lo.S = S;
+    lo.tile_elems = pick_tile_elems(d_big);
+    uint64_t nt = 0, nc = 0;
+    if (hl) hl->resize(L);
+    int32_t bi = 0;
+    for (uint32_t i = 0; i < L; ++i) {
+        HostLayer h{};
+        h.n = (uint32_t)n[i];
+        h.big = -1;
+        if (n[i] > SMALL_MAX) {
+            const uint64_t span = n[i] + 3;
+            h.big = bi++;
+            h.tile0 = (uint32_t)nt; h.ntiles = (uint32_t)((span + lo.tile_elems - 1) / lo.tile_elems);
+            h.chunk0 = (uint32_t)nc; h.nchunks = (uint32_t)((span + CHUNK - 1) / CHUNK);
+            nt += h.ntiles; nc += h.nchunks;
+        }
+        if (hl) (*hl)[i] = h;
+    }
+    if (nt > 0x7FFFFFFFull || nc > 0xFFFFFFFFull) return KIMAD_ERR_INVALID_ARG;
+    lo.ntiles = (uint32_t)nt; lo.nchunks = (uint32_t)nc;
+    lo.sum_kmax = d_all;                                  // the last grid ratio may be 1
+    const uint32_t pair = cfg.pair_bytes ? cfg.pair_bytes : 8u;
+    if (cfg.cost_units_D) {
+        lo.dp_cells = std::min<uint64_t>(cfg.cost_units_D, d_all) + 1;
+    } else {
+        uint64_t pmax = cfg.max_budget_bytes ? cfg.max_budget_bytes / pair : d_all;
+        lo.dp_cells = std::min<uint64_t>(pmax, d_all) + 1;
+    }
+    lo.tmp_cap = cfg.tmp_capacity_pairs ? cfg.tmp_capacity_pairs : d_big;
+
+    uint64_t off = 0;
+    auto take = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes); return o; };
+    const uint64_t LJ = (uint64_t)L * J;
+    lo.layers = take(sizeof(LayerDesc) * (uint64_t)L);
+    lo.ktab = take(4 * LJ);
+    lo.tile_layer = take(4ull * (nt ? nt : 1));
+    lo.chunk_big = take(4ull * (nc ? nc : 1));
+    lo.big_layer = take(4ull * (B ? B : 1));
+    lo.small_layer = take(4ull * (S ? S : 1));
+    lo.zero1_begin = off;
+    lo.cnt1 = take(4ull * B * D1_BINS);
+    lo.sq1 = take(8ull * B * D1_BINS);
+    lo.cnt2 = take(4ull * B * MAX_SLOTS * D2_BINS);
+    lo.sq2 = take(8ull * B * MAX_SLOTS * D2_BINS);
+    lo.diag = take(16);
+    lo.zero1_end = off;
+    lo.lut1 = take(1ull * B * D1_BINS);
+    lo.nslots = take(4ull * (B ? B : 1));
+    lo.slot_bin = take(4ull * B * MAX_SLOTS);
+    lo.tgt_slot = take(4 * LJ);
+    lo.tgt_r = take(4 * LJ);
+    lo.tgt_above1 = take(4 * LJ);
+    lo.tgt_below = take(8 * LJ);
+    lo.sel_prefix = take(4 * LJ);
+    lo.sel_above = take(4 * LJ);
+    lo.sel_amb = take(4 * LJ);
+    lo.ksel = take(4ull * L);
+    lo.sel = take(sizeof(SelRec) * (uint64_t)(B ? B : 1));
+    lo.cursor = take(4ull * (B ? B : 1));
+    lo.zero2_begin = off;
+    lo.hist3 = take(4ull * B * D3_BINS);
+    lo.zero2_end = off;
+    lo.tau = take(4ull * (B ? B : 1));
+    lo.quota = take(4ull * (B ? B : 1));
+    const uint64_t ncb = 4ull * (nc ? nc : 1);
+    lo.rec_start = take(ncb); lo.rec_cnt = take(ncb); lo.rec_amb = take(ncb);
+    lo.c_gt = take(ncb); lo.c_eq = take(ncb); lo.o_base = take(ncb); lo.o_allow = take(ncb);
+    lo.tmp_idx = take(4 * lo.tmp_cap); lo.tmp_x = take(4 * lo.tmp_cap); lo.tmp_h = take(4 * lo.tmp_cap);
+    lo.row0 = take(8 * lo.dp_cells);
+    lo.row1 = take(8 * lo.dp_cells);
+    lo.choice = take((uint64_t)L * align_up(lo.dp_cells));
+    lo.dp_flags = take(16);
+    lo.total = off;
+    return KIMAD_OK;
+}
+
+kimad_config_t normalise(const kimad_config_t* cfg) {
+    kimad_config_t c{};
+    if (cfg) c = *cfg;
+    if (c.pair_bytes == 0) c.pair_bytes = 8;
+    return c;
+}
+
+__global__ __launch_bounds__(256) void k_zero16(uint4* p, uint64_t n16) {
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ __launch_bounds__(256) void k_make_ksel(const uint64_t* K, const kimad::LayerDesc* layers, uint32_t L,
+                                                   uint32_t* ksel) {
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i < L) {
+        const uint64_t k = K[i];
+        ksel[i] = k > layers[i].n ? layers[i].n : (uint32_t)k;
+    }
+}
+
+}  // namespace
+
+struct kimad_plan {
+    Layout lo;
+    kimad_config_t cfg;
+    std::vector<HostLayer> hl;
+    std::vector<uint32_t> ktab;      // host copy of K_ij
+    std::vector<uint32_t> kmax;      // K_{i,J-1}
+    char* ws = nullptr;
+    int device = 0;
+    kimad::ProfileBuffers pb;
+    kimad::CompressBuffers cb;
+};
+
+namespace {
+
+template <typename T> T* at(kimad_plan* p, uint64_t off) { return reinterpret_cast<T*>(p->ws + off); }
+
+#define KIMAD_LAUNCH_CHECK()                                   \
+    do {                                                       \
+        if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP; \
+    } while (0)
+
+int zero_range(kimad_plan* p, uint64_t begin, uint64_t end, hipStream_t s) {
+    const uint64_t n16 = (end - begin) / 16;
+    if (n16 == 0) return KIMAD_OK;
+    const uint32_t blocks = (uint32_t)std::min<uint64_t>((n16 + 255) / 256, 2048);
+    hipLaunchKernelGGL(k_zero16, dim3(blocks), dim3(256), 0, s, at<uint4>(p, begin), n16);
+    KIMAD_LAUNCH_CHECK();
+    return KIMAD_OK;
+}
+
+// Histogram passes + scans for a target table (the plan's grid, or one K per layer).
+int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, double* err_table, hipStream_t s) {
+    const Layout& lo = p->lo;
+    int rc = zero_range(p, lo.zero1_begin, lo.zero1_end, s);
+    if (rc) return rc;
+    if (lo.B) {
+        hipLaunchKernelGGL(k_hist1, dim3(lo.ntiles), dim3(256), 0, s, p->pb);
+        KIMAD_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_scan1, dim3(lo.B), dim3(256), 0, s, p->pb, ktab_dev, J);
+        KIMAD_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_hist2, dim3(lo.ntiles), dim3(512), 0, s, p->pb);
+        KIMAD_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_scan2, dim3(lo.B), dim3(64), 0, s, p->pb, ktab_dev, J, err_table, 2e-6);
+        KIMAD_LAUNCH_CHECK();
+    }
+    return KIMAD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int kimad_workspace_bytes(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t* cfg, uint64_t* bytes_out) {
+    if (!bytes_out) return KIMAD_ERR_INVALID_ARG;
+    Layout lo;
+    const int rc = make_layout(n, L, J, normalise(cfg), lo, nullptr);
+    if (rc) return rc;
+    *bytes_out = lo.total;
+    return KIMAD_OK;
+}
+
+int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* ratios, uint32_t J,
+                      const kimad_config_t* cfg, void* workspace, uint64_t workspace_bytes, void* stream,
+                      kimad_plan_t** plan_out) {
+    if (!layers || !ratios || !workspace || !plan_out) return KIMAD_ERR_INVALID_ARG;
+    if (L == 0 || L > 65535 || J == 0 || J > KIMAD_MAX_J) return KIMAD_ERR_INVALID_ARG;
+    if (((uintptr_t)workspace) % ALIGN) return KIMAD_ERR_INVALID_ARG;
+    for (uint32_t j = 0; j < J; ++j) {
+        if (!(ratios[j] > 0.0) || !(ratios[j] <= 1.0)) return KIMAD_ERR_INVALID_ARG;
+        if (j && !(ratios[j] > ratios[j - 1])) return KIMAD_ERR_INVALID_ARG;
+    }
+    std::vector<uint64_t> n(L);
+    for (uint32_t i = 0; i < L; ++i) {
+        if (!layers[i].g || !layers[i].h) return KIMAD_ERR_INVALID_ARG;
+        if (((uintptr_t)layers[i].g) % 4 || ((uintptr_t)layers[i].h) % 4) return KIMAD_ERR_INVALID_ARG;
+        n[i] = layers[i].n;
+    }
+    kimad_plan* p = new (std::nothrow) kimad_plan();
+    if (!p) return KIMAD_ERR_INVALID_ARG;
+    p->cfg = normalise(cfg);
+    int rc = make_layout(n.data(), L, J, p->cfg, p->lo, &p->hl);
+    if (rc) { delete p; return rc; }
+    if (workspace_bytes < p->lo.total) { delete p; return KIMAD_ERR_WORKSPACE_TOO_SMALL; }
+    p->ws = static_cast<char*>(workspace);
+    if (hipGetDevice(&p->device) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
+    const Layout& lo = p->lo;
+
+    // host tables
+    std::vector<LayerDesc> ld(L);
+    std::vector<uint32_t> tile_layer(lo.ntiles ? lo.ntiles : 1), chunk_big(lo.nchunks ? lo.nchunks : 1);
+    std::vector<uint32_t> big_layer(lo.B ? lo.B : 1), small_layer(lo.S ? lo.S : 1);
+    p->ktab.resize((size_t)L * J);
+    p->kmax.resize(L);
+    uint32_t si = 0;
+    for (uint32_t i = 0; i < L; ++i) {
+        HostLayer& h = p->hl[i];
+        h.mis = (uint32_t)((((uintptr_t)layers[i].g) / 4) & 3u);
+        h.hvec = ((((uintptr_t)layers[i].h) / 4) & 3u) == h.mis;
+        LayerDesc& d = ld[i];
+        d.g = layers[i].g; d.h = layers[i].h; d.n = h.n; d.mis = h.mis; d.hvec = h.hvec; d.big = h.big;
+        if (h.big >= 0) {
+            // Tiles and chunks are reserved for the worst misalignment; positions past the end of
+            // the layer load nothing.
+            for (uint32_t t = 0; t < h.ntiles; ++t) tile_layer[h.tile0 + t] = i;
+            for (uint32_t c = 0; c < h.nchunks; ++c) chunk_big[h.chunk0 + c] = (uint32_t)h.big;
+            d.tile0 = h.tile0; d.ntiles = h.ntiles; d.chunk0 = h.chunk0; d.nchunks = h.nchunks;
+            big_layer[h.big] = i;
+        } else {
+            d.tile0 = d.ntiles = d.chunk0 = d.nchunks = 0;
+            small_layer[si++] = i;
+        }
+        for (uint32_t j = 0; j < J; ++j) p->ktab[(size_t)i * J + j] = grid_size_K(ratios[j], h.n);
+        p->kmax[i] = p->ktab[(size_t)i * J + J - 1];
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    auto up = [&](uint64_t off, const void* src, size_t bytes) {
+        return hipMemcpyAsync(p->ws + off, src, bytes, hipMemcpyHostToDevice, s) == hipSuccess;
+    };
+    bool ok = up(lo.layers, ld.data(), sizeof(LayerDesc) * L) && up(lo.ktab, p->ktab.data(), 4ull * L * J) &&
+              up(lo.tile_layer, tile_layer.data(), 4ull * tile_layer.size()) &&
+              up(lo.chunk_big, chunk_big.data(), 4ull * chunk_big.size()) &&
+              up(lo.big_layer, big_layer.data(), 4ull * big_layer.size()) &&
+              up(lo.small_layer, small_layer.data(), 4ull * small_layer.size());
+    ok = ok && hipStreamSynchronize(s) == hipSuccess;     // host vectors go out of scope below
+    if (!ok) { delete p; return KIMAD_ERR_HIP; }
+
+    ProfileBuffers& pb = p->pb;
+    pb.layers = at<LayerDesc>(p, lo.layers);
+    pb.tile_layer = at<uint32_t>(p, lo.tile_layer);
+    pb.big_layer = at<uint32_t>(p, lo.big_layer);
+    pb.small_layer = at<uint32_t>(p, lo.small_layer);
+    pb.tile_elems = lo.tile_elems;
+    pb.cnt1 = at<uint32_t>(p, lo.cnt1); pb.sq1 = at<uint64_t>(p, lo.sq1);
+    pb.lut1 = at<uint8_t>(p, lo.lut1); pb.nslots = at<uint32_t>(p, lo.nslots); pb.slot_bin = at<uint32_t>(p, lo.slot_bin);
+    pb.cnt2 = at<uint32_t>(p, lo.cnt2); pb.sq2 = at<uint64_t>(p, lo.sq2);
+    pb.tgt_slot = at<uint32_t>(p, lo.tgt_slot); pb.tgt_r = at<uint32_t>(p, lo.tgt_r);
+    pb.tgt_above1 = at<uint32_t>(p, lo.tgt_above1); pb.tgt_below = at<double>(p, lo.tgt_below);
+    pb.sel_prefix = at<uint32_t>(p, lo.sel_prefix); pb.sel_above = at<uint32_t>(p, lo.sel_above);
+    pb.sel_amb = at<uint32_t>(p, lo.sel_amb); pb.diag = at<uint32_t>(p, lo.diag);
+
+    CompressBuffers& cb = p->cb;
+    cb.layers = pb.layers; cb.chunk_layer = pb.tile_layer; cb.big_layer = pb.big_layer; cb.small_layer = pb.small_layer;
+    cb.tile_elems = lo.tile_elems; cb.L = L; cb.B = lo.B; cb.J = J;
+    cb.Ktab = at<uint32_t>(p, lo.ktab);
+    cb.sel_prefix = pb.sel_prefix; cb.sel_above = pb.sel_above; cb.sel_amb = pb.sel_amb;
+    cb.sel = at<SelRec>(p, lo.sel); cb.cursor = at<uint32_t>(p, lo.cursor); cb.hist3 = at<uint32_t>(p, lo.hist3);
+    cb.tau = at<uint32_t>(p, lo.tau); cb.quota = at<uint32_t>(p, lo.quota);
+    cb.rec_start = at<uint32_t>(p, lo.rec_start); cb.rec_cnt = at<uint32_t>(p, lo.rec_cnt);
+    cb.rec_amb = at<uint32_t>(p, lo.rec_amb); cb.c_gt = at<uint32_t>(p, lo.c_gt); cb.c_eq = at<uint32_t>(p, lo.c_eq);
+    cb.o_base = at<uint32_t>(p, lo.o_base); cb.o_allow = at<uint32_t>(p, lo.o_allow);
+    cb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); cb.tmp_x = at<float>(p, lo.tmp_x); cb.tmp_h = at<float>(p, lo.tmp_h);
+    cb.tmp_capacity = lo.tmp_cap;
+    cb.K = nullptr; cb.offsets = nullptr; cb.idx_out = nullptr; cb.val_out = nullptr; cb.capacity_pairs = 0;
+    cb.status = nullptr;
+    *plan_out = p;
+    return KIMAD_OK;
+}
+
+int kimad_plan_destroy(kimad_plan_t* plan) {
+    delete plan;
+    return KIMAD_OK;
+}
+
+int kimad_plan_grid_sizes(const kimad_plan_t* plan, uint64_t* K_table_out) {
+    if (!plan || !K_table_out) return KIMAD_ERR_INVALID_ARG;
+    for (size_t t = 0; t < plan->ktab.size(); ++t) K_table_out[t] = plan->ktab[t];
+    return KIMAD_OK;
+}
+
+int kimad_profile(kimad_plan_t* p, double* err_table, void* stream) {
+    if (!p || !err_table) return KIMAD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Layout& lo = p->lo;
+    int rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s);
+    if (rc) return rc;
+    if (lo.S) {
+        hipLaunchKernelGGL(k_small_profile, dim3(lo.S), dim3(256), 0, s, p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
+        KIMAD_LAUNCH_CHECK();
+    }
+    return KIMAD_OK;
+}
+
+int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_bytes, int32_t* j_out, uint64_t* K_out,
+                   uint64_t* offsets_out, int32_t* status_out, void* stream) {
+    if (!p || !err_table || !j_out || !K_out || !offsets_out || !status_out) return KIMAD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Layout& lo = p->lo;
+    const uint64_t P = budget_bytes / p->cfg.pair_bytes;
+    const uint64_t D = p->cfg.cost_units_D;
+    const uint64_t unit = (D == 0 || P <= D) ? 1 : (P + D - 1) / D;
+    uint64_t cap = P / unit;
+    // Costs above the dearest allocation are unreachable (+inf for ever): cutting the rows there
+    // changes no finite cell and so neither the least total nor the smallest cost attaining it.
+    uint64_t wmax = 0;
+    for (uint32_t i = 0; i < lo.L; ++i) wmax += ((uint64_t)p->kmax[i] + unit - 1) / unit;
+    if (cap > wmax) cap = wmax;
+    if (cap + 1 > lo.dp_cells) return KIMAD_ERR_INVALID_ARG;   // budget beyond cfg.max_budget_bytes
+
+    AllocBuffers ab;
+    ab.E = err_table; ab.Ktab = at<uint32_t>(p, lo.ktab); ab.L = lo.L; ab.J = lo.J;
+    ab.unit = unit; ab.cap = (uint32_t)cap;
+    ab.row0 = at<double>(p, lo.row0); ab.row1 = at<double>(p, lo.row1);
+    ab.choice = at<uint8_t>(p, lo.choice); ab.stride = align_up(lo.dp_cells);
+    ab.j_out = j_out; ab.K_out = K_out; ab.offsets_out = offsets_out; ab.status = status_out;
+    ab.flags = at<uint32_t>(p, lo.dp_flags);
+    int rc = zero_range(p, lo.dp_flags, lo.dp_flags + 16, s);
+    if (rc) return rc;
+    const uint32_t cell_blocks = (uint32_t)((cap + 1 + 255) / 256);
+    hipLaunchKernelGGL(k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), 0, s, ab);
+    KIMAD_LAUNCH_CHECK();
+    const double* last = ab.row0;
+    if (cap + 1 <= DP_LDS_CELLS) {
+        hipLaunchKernelGGL(k_dp_lds, dim3(1), dim3(1024), 0, s, ab);
+        KIMAD_LAUNCH_CHECK();
+    } else {
+        double* rows[2] = {ab.row0, ab.row1};
+        for (uint32_t i = 0; i < lo.L; ++i) {
+            hipLaunchKernelGGL(k_dp_layer, dim3(cell_blocks), dim3(256), 0, s, ab, i, rows[i & 1], rows[(i + 1) & 1]);
+            KIMAD_LAUNCH_CHECK();
+        }
+        last = rows[lo.L & 1];
+    }
+    hipLaunchKernelGGL(k_dp_final, dim3(1), dim3(1024), 0, s, ab, last, (int32_t)KIMAD_ERR_INFEASIBLE,
+                       (int32_t)KIMAD_ERR_NONFINITE);
+    KIMAD_LAUNCH_CHECK();
+    return KIMAD_OK;
+}
+
+int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offsets, uint32_t* idx_out, float* val_out,
+                      uint64_t capacity_pairs, uint32_t flags, int32_t* status_out, void* stream) {
+    if (!p || !K || !offsets || !idx_out || !val_out || !status_out) return KIMAD_ERR_INVALID_ARG;
+    if (flags & ~KIMAD_REUSE_PROFILE) return KIMAD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Layout& lo = p->lo;
+    CompressBuffers cb = p->cb;
+    cb.K = K; cb.offsets = offsets; cb.idx_out = idx_out; cb.val_out = val_out;
+    cb.capacity_pairs = capacity_pairs; cb.status = status_out;
+    if (!(flags & KIMAD_REUSE_PROFILE)) {
+        // select from scratch: the two histogram passes with one target per layer
+        uint32_t* ksel = at<uint32_t>(p, lo.ksel);
+        hipLaunchKernelGGL(k_make_ksel, dim3((lo.L + 255) / 256), dim3(256), 0, s, K, cb.layers, lo.L, ksel);
+        KIMAD_LAUNCH_CHECK();
+        int rc = run_select_passes(p, ksel, 1, nullptr, s);
+        if (rc) return rc;
+        cb.Ktab = ksel;
+        cb.J = 1;
+    }
+    int rc = zero_range(p, lo.zero2_begin, lo.zero2_end, s);
+    if (rc) return rc;
+    hipLaunchKernelGGL(k_lookup, dim3(1), dim3(256), 0, s, cb, (int32_t)KIMAD_ERR_OFFGRID,
+                       (int32_t)KIMAD_ERR_SCRATCH_OVERFLOW, (int32_t)KIMAD_ERR_BAD_OFFSETS);
+    KIMAD_LAUNCH_CHECK();
+    if (lo.B) {
+        const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
+        const uint32_t cblocks = (lo.nchunks + 3) / 4;
+        hipLaunchKernelGGL(k_compact, dim3(lo.ntiles), dim3(256), 0, s, cb);
+        KIMAD_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_resolve, dim3(lo.B), dim3(256), 0, s, cb);
+        KIMAD_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_chunk_count, dim3(cblocks), dim3(256), 0, s, cb, lo.nchunks, chunk_big);
+        KIMAD_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_chunk_scan, dim3(lo.B), dim3(1024), 0, s, cb);
+        KIMAD_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_finalize, dim3(cblocks), dim3(256), 0, s, cb, lo.nchunks, chunk_big);
+        KIMAD_LAUNCH_CHECK();
+    }
+    if (lo.S) {
+        hipLaunchKernelGGL(k_small_compress, dim3(lo.S), dim3(256), 0, s, cb);
+        KIMAD_LAUNCH_CHECK();
+    }
+    return KIMAD_OK;
+}
+
+int kimad_step(kimad_plan_t* p, uint64_t budget_bytes, double* err_table, int32_t* j_out, uint64_t* K_out,
+               uint64_t* offsets_out, uint32_t* idx_out, float* val_out, uint64_t capacity_pairs, int32_t* status_out,
+               void* stream) {
+    if (!status_out) return KIMAD_ERR_INVALID_ARG;
+    int rc = kimad_profile(p, err_table, stream);
+    if (rc) return rc;
+    rc = kimad_allocate(p, err_table, budget_bytes, j_out, K_out, offsets_out, status_out, stream);
+    if (rc) return rc;
+    // On an allocation failure K and offsets are zero-filled, so the compression writes nothing.
+    return kimad_compress_ef(p, K_out, offsets_out, idx_out, val_out, capacity_pairs, KIMAD_REUSE_PROFILE,
+                             status_out + 1, stream);
+}
+
+int kimad_profile_diagnostics(kimad_plan_t* p, uint32_t* out2, void* stream) {
+    if (!p || !out2) return KIMAD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(out2, p->ws + p->lo.diag, 8, hipMemcpyDeviceToHost, s) != hipSuccess) return KIMAD_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return KIMAD_ERR_HIP;
+    return KIMAD_OK;
+}
+
+const char* kimad_strerror(int status) {
+    switch (status) {
+        case KIMAD_OK: return "ok";
+        case KIMAD_ERR_INVALID_ARG: return "invalid argument";
+        case KIMAD_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case KIMAD_ERR_CAPACITY_TOO_SMALL: return "payload capacity too small";
+        case KIMAD_ERR_HIP: return "HIP runtime error";
+        case KIMAD_ERR_NOT_IMPLEMENTED: return "not implemented";
+        case KIMAD_ERR_INFEASIBLE: return "budget below the cheapest allocation";
+        case KIMAD_ERR_NONFINITE: return "error table holds a non-finite entry";
+        case KIMAD_ERR_OFFGRID: return "K is not one of the layer's grid sizes";
+        case KIMAD_ERR_SCRATCH_OVERFLOW: return "candidate buffer too small";
+        case KIMAD_ERR_BAD_OFFSETS: return "K/offsets do not fit the payload capacity";
+        default: return "unknown status";
+    }
+}
+
+const char* kimad_version(void) { return "kimad-gfx950 0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI.
+
+Bars: error table within 1e-5 relative (exactly 0 where K = n); allocation, payload indices,
+payload values and the updated estimator bit-exact.
+"""
+import numpy as np
+import pytest
+
+import kimad_synth as ks
+from oracle import kimad_oracle as ko
+from tests import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+
+
+def _full_check(work, reuse=True, table_rel=1e-5):
+    import torch
+    g, h = gh.to_device(work)
+    plan = gh.make_plan(work, g, h)
+    gL, hL = gh.oracle_layers(work)
+    E_ref, Kt = ko.profile(gL, hL, work.ratios)
+    assert np.array_equal(plan.grid_sizes(), Kt)
+
+    # profile
+    E_gpu = plan.profile().cpu().numpy().reshape(work.L, -1)
+    torch.cuda.synchronize()
+    gh.assert_table_close(E_gpu, E_ref, Kt, work.sizes)
+    assert np.array_equal(h.cpu().numpy().view(np.uint32), work.h.view(np.uint32)), "profile must not touch h"
+
+    # allocation on the oracle's table: bit-exact choice
+    st, j_ref, K_ref, off_ref = ko.allocate(E_ref, Kt, work.budget_bytes, work.pair_bytes, work.cost_units_D)
+    E_dev = torch.from_numpy(E_ref.reshape(-1).copy()).cuda()
+    j, K, off, status = plan.allocate(work.budget_bytes, E_dev)
+    assert int(status.item()) == st
+    if st == ko.OK:
+        assert np.array_equal(j.cpu().numpy(), j_ref)
+        assert np.array_equal(K.cpu().numpy().astype(np.uint64), K_ref)
+        assert np.array_equal(off.cpu().numpy().astype(np.uint64), off_ref)
+    # allocation on the GPU's own table: the oracle DP on that same table must agree bit for bit
+    j2, K2, off2, status2 = plan.allocate(work.budget_bytes)
+    st2, j2_ref, K2_ref, off2_ref = ko.allocate(E_gpu, Kt, work.budget_bytes, work.pair_bytes, work.cost_units_D)
+    assert int(status2.item()) == st2
+    if st2 == ko.OK:
+        assert np.array_equal(j2.cpu().numpy(), j2_ref)
+        assert np.array_equal(off2.cpu().numpy().astype(np.uint64), off2_ref)
+    if st != ko.OK:
+        return plan
+
+    # compression with the oracle's K (thresholds reused from the profile, or selected afresh)
+    Kd = torch.from_numpy(K_ref.astype(np.int64)).cuda()
+    offd = torch.from_numpy(off_ref.astype(np.int64)).cuda()
+    idx, val, cstat = plan.compress_ef(Kd, offd, reuse_profile=reuse)
+    torch.cuda.synchronize()
+    assert int(cstat.item()) == 0
+    gh.check_compress(work, plan, h, K_ref, off_ref, idx, val)
+    assert 8 * int(off_ref[-1]) <= work.budget_bytes
+    return plan
+
+
+def test_mlp_set():
+    _full_check(ks.make_workload("mlp"))
+
+
+def test_mlp_set_select_from_scratch():
+    _full_check(ks.make_workload("mlp"), reuse=False)
+
+
+def test_resnet18_set():
+    _full_check(ks.make_workload("resnet18"))
+
+
+@pytest.mark.parametrize("frac", [0.001, 0.01, 0.05])
+def test_resnet50_set(frac):
+    _full_check(ks.make_workload("resnet50", budget_frac=frac))
+
+
+def test_resnet50_set_discretised_budget():
+    _full_check(ks.make_workload("resnet50", D=1000))
+
+
+def test_gpt2_reduced_set():
+    # same recipe as the 124M set, two blocks and a 4096-row embedding: several tiles per layer,
+    # ragged tails, small vectors next to matrices
+    _full_check(ks.make_workload("gpt2", n_layer=2, vocab=4099))
+
+
+def test_gpt2_reduced_nonzero_estimator_from_scratch():
+    _full_check(ks.make_workload("gpt2", n_layer=1, vocab=2053, h_factor=0.5), reuse=False)
+
+
+def test_step_entry_point_matches_separate_calls():
+    import torch
+    work = ks.make_workload("resnet18")
+    g, h = gh.to_device(work)
+    plan = gh.make_plan(work, g, h)
+    status = plan.step(work.budget_bytes)
+    torch.cuda.synchronize()
+    assert status.cpu().numpy().tolist() == [0, 0]
+    gL, hL = gh.oracle_layers(work)
+    E_gpu = plan.err_table.cpu().numpy().reshape(work.L, -1)
+    Kt = plan.grid_sizes()
+    st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, work.budget_bytes, 8, work.cost_units_D)
+    assert st == ko.OK
+    assert np.array_equal(plan.K.cpu().numpy().astype(np.uint64), K_ref)
+    gh.check_compress(work, plan, h, K_ref, off_ref, plan.idx, plan.val)
