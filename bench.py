@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Benchmark of one worker's Kimad+ compression step on one MI355X.
+
+A "step" is one pass of the whole hot path over one synthetic gradient set that is already
+resident in HBM: kimad_profile -> kimad_allocate -> kimad_compress_ef (thresholds reused).
+Prints ONE JSON line.  The metric is gradient GB/s = 4 * d / t_step.
+
+The estimator h is restored from a device copy before every step, outside the timed
+intervals: every step then compresses the same x = g - h, as the first round of training
+would.  Each step is timed with a pair of events on the stream the library launches on;
+`ms_per_step` is the mean of those intervals, `wall_ms_per_step` the host clock around all
+K steps including the restores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
+
+STREAMING_KERNELS = ("k_hist1", "k_hist2", "k_compact")
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="gpt2", choices=["mlp", "resnet18", "resnet50", "gpt2"])
+    ap.add_argument("--D", type=int, default=None, help="cost discretisation factor (default: the workload's)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-blocks", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build measures one worker on one GPU; --gpus must be 1 "
+              "(the path has no exchange between workers, see DESIGN.md)", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import kimad_synth as ks
+    import paper_2312_08053_amd as kimad
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    kimad.lib()   # fails loudly when the HIP library is missing
+
+    t0 = time.time()
+    kw = {} if args.D is None else {"D": args.D}
+    work = ks.make_workload(args.workload, **kw)
+    t_gen = time.time() - t0
+    d, L, J = work.d, work.L, len(work.ratios)
+    g = torch.from_numpy(work.g).cuda()
+    h = torch.from_numpy(work.h).cuda()
+    h0 = h.clone()
+    plan = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes,
+                      D=work.cost_units_D, max_budget_bytes=work.budget_bytes,
+                      capacity_pairs=work.budget_bytes // work.pair_bytes + 1)
+    stream = torch.cuda.current_stream()
+
+    def one_step():
+        plan.step(work.budget_bytes)
+
+    for _ in range(args.warmup):
+        h.copy_(h0)
+        one_step()
+    torch.cuda.synchronize()
+    status = plan.status.cpu().tolist()
+    if status != [0, 0]:
+        print(f"bench.py: step failed with device status {status}", file=sys.stderr)
+        return 4
+    sumK = int(plan.offsets[-1].item())
+
+    # ---- timed region: K steps, each bracketed by events; h restored between the intervals
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    ends = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    for k in range(args.steps):
+        h.copy_(h0)
+        starts[k].record(stream)
+        one_step()
+        ends[k].record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - w0) * 1e3 / args.steps
+    per_step = [starts[k].elapsed_time(ends[k]) for k in range(args.steps)]
+    ms = float(np.mean(per_step))
+
+    # ---- the same steps again with an event after every kernel: per-kernel durations
+    plan.set_timing(True)
+    agg: dict = {}
+    order = []
+    for k in range(args.steps):
+        h.copy_(h0)
+        one_step()
+        for name, t in plan.get_timings():
+            if name not in agg:
+                agg[name] = []
+                order.append(name)
+            agg[name].append(t)
+    plan.set_timing(False)
+    kern = {n: {"launches_per_step": len(v) / args.steps, "avg_ms": float(np.mean(v)),
+                "ms_per_step": float(np.sum(v)) / args.steps} for n, v in agg.items()}
+    stage_ms = {"profile": 0.0, "allocate": 0.0, "compress": 0.0}
+    for n, v in kern.items():
+        if n.startswith("k_dp"):
+            stage_ms["allocate"] += v["ms_per_step"]
+        elif n in ("k_hist1", "k_scan1", "k_hist2", "k_scan2", "k_small_profile"):
+            stage_ms["profile"] += v["ms_per_step"]
+        elif n != "k_zero16":
+            stage_ms["compress"] += v["ms_per_step"]
+
+    d_big = int(sum(int(n) for n in work.sizes if int(n) > 8192))
+    alg_bytes = {"k_hist1": 8 * d_big, "k_hist2": 8 * d_big, "k_compact": 8 * d_big + 12 * sumK}
+    dom = max((n for n in STREAMING_KERNELS if n in kern), key=lambda n: kern[n]["avg_ms"])
+    ach = alg_bytes[dom] / (kern[dom]["avg_ms"] * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "algorithmic_bytes_per_launch": alg_bytes[dom],
+                "avg_launch_ms": round(kern[dom]["avg_ms"], 5)}
+
+    bytes_min = 8 * d + (work.pair_bytes + 4) * sumK + 8 * L * J + 8 * (L + 1)
+    value = 4.0 * d / (ms * 1e-3) / 1e9
+    t_no_alloc = ms - stage_ms["allocate"]
+    out = {
+        "metric": "gradient GB/s compressed per step (profile+select+EF)",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{work.name}-shaped gradient set ({L} tensors, {d} elements)",
+                   "ratios": J, "budget_bytes": work.budget_bytes, "cost_units_D": work.cost_units_D,
+                   "payload_pairs": sumK, "estimator": "zero" if not work.h.any() else "nonzero",
+                   "tile_elems": None},
+        "wall_ms_per_step": round(wall_ms, 4),
+        "min_ms_per_step": round(float(np.min(per_step)), 4),
+        "path_roofline": {"bytes_min": bytes_min, "frac_of_hbm_peak": round(bytes_min / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                          "frac_without_allocate": round(bytes_min / (t_no_alloc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                          "gradient_GBs_without_allocate": round(4.0 * d / (t_no_alloc * 1e-3) / 1e9, 2)},
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "kernels": {n: {k: round(v, 5) for k, v in kern[n].items()} for n in order},
+        "roofline": roofline,
+        "input_generation_s": round(t_gen, 1),
+    }
+
+    # ---- the CPU oracle on a bounded sample of the same workload (rank 0, reported baseline)
+    if not args.no_cpu_baseline:
+        from oracle import kimad_oracle as ko
+        gL, hL = work.layer_views(work.g), work.layer_views(work.h)
+        if work.name == "gpt2":
+            # tensors of the first transformer blocks (12 per block, after wte and wpe)
+            sel = list(range(2, 2 + 12 * args.cpu_sample_blocks))
+            what = f"first {args.cpu_sample_blocks} transformer blocks"
+        else:
+            sel = list(range(L))
+            what = "all tensors"
+        gs, hs = [gL[i] for i in sel], [hL[i].copy() for i in sel]
+        ds = int(sum(len(x) for x in gs))
+        budget_s = int(work.budget_bytes * ds / d)
+        c0 = time.perf_counter()
+        res = ko.step(gs, hs, work.ratios, budget_s, work.pair_bytes, work.cost_units_D)
+        cpu_s = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": round(4.0 * ds / cpu_s / 1e9, 5), "unit": "GB/s", "cores": 1,
+                               "kind": "oracle", "seconds": round(cpu_s, 2),
+                               "sample": f"{what}: {len(sel)} tensors, {ds} elements, budget scaled to {budget_s} B; "
+                                         f"status {res['status']}"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

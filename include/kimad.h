@@ -145,6 +145,16 @@ int kimad_step(kimad_plan_t* plan, uint64_t budget_bytes, double* err_table,
  * the exact fallback ran, out[1] = entries fixed by the fallback. */
 int kimad_profile_diagnostics(kimad_plan_t* plan, uint32_t* out2, void* stream);
 
+/* Per-kernel timing (tracing aid for benchmarks).  With timing enabled the library records a
+ * HIP event on the stream after every kernel it launches.  kimad_plan_get_timings waits for the
+ * last recorded event, then writes one entry per launch since the last call: the kernel names,
+ * newline-separated, into `names` (HOST, names_bytes long) and the durations in milliseconds
+ * into `ms` (HOST, max_entries floats); *count_out = entries written.  At most 1024 launches are
+ * kept between two calls. */
+int kimad_plan_set_timing(kimad_plan_t* plan, int enable);
+int kimad_plan_get_timings(kimad_plan_t* plan, char* names, uint32_t names_bytes, float* ms,
+                           uint32_t max_entries, uint32_t* count_out);
+
 const char* kimad_strerror(int status);
 const char* kimad_version(void);
 

@@ -15,7 +15,8 @@ KIMAD_MAX_J = 64
 EXPORTED_SYMBOLS = [
     "kimad_workspace_bytes", "kimad_plan_create", "kimad_plan_destroy", "kimad_plan_grid_sizes",
     "kimad_profile", "kimad_allocate", "kimad_compress_ef", "kimad_step",
-    "kimad_profile_diagnostics", "kimad_strerror", "kimad_version",
+    "kimad_profile_diagnostics", "kimad_plan_set_timing", "kimad_plan_get_timings",
+    "kimad_strerror", "kimad_version",
 ]
 
 
@@ -57,6 +58,8 @@ def lib() -> C.CDLL:
     L.kimad_compress_ef.argtypes = [vp, vp, vp, vp, vp, u64, u32, i32p, vp]
     L.kimad_step.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, u64, i32p, vp]
     L.kimad_profile_diagnostics.argtypes = [vp, C.POINTER(C.c_uint32), vp]
+    L.kimad_plan_set_timing.argtypes = [vp, C.c_int]
+    L.kimad_plan_get_timings.argtypes = [vp, C.c_char_p, u32, C.POINTER(C.c_float), u32, C.POINTER(C.c_uint32)]
     L.kimad_strerror.argtypes = [C.c_int]
     L.kimad_strerror.restype = C.c_char_p
     L.kimad_version.restype = C.c_char_p
@@ -226,6 +229,19 @@ class Plan:
         _check(lib().kimad_profile_diagnostics(C.c_void_p(self.handle), out, C.c_void_p(_stream(None))),
                "kimad_profile_diagnostics")
         return int(out[0]), int(out[1])
+
+    def set_timing(self, enable: bool) -> None:
+        _check(lib().kimad_plan_set_timing(C.c_void_p(self.handle), int(bool(enable))), "kimad_plan_set_timing")
+
+    def get_timings(self):
+        """[(kernel name, milliseconds)] for every launch since the last call (timing must be on)."""
+        names = C.create_string_buffer(65536)
+        ms = (C.c_float * 1024)()
+        cnt = C.c_uint32(0)
+        _check(lib().kimad_plan_get_timings(C.c_void_p(self.handle), names, 65536, ms, 1024, C.byref(cnt)),
+               "kimad_plan_get_timings")
+        nm = names.value.decode().split("\n")[:cnt.value]
+        return [(nm[k], float(ms[k])) for k in range(cnt.value)]
 
     def close(self):
         if getattr(self, "handle", 0):

@@ -187,23 +187,39 @@ struct kimad_plan {
     int device = 0;
     kimad::ProfileBuffers pb;
     kimad::CompressBuffers cb;
+    // optional per-kernel timing (events recorded after every launch)
+    bool timing = false;
+    std::vector<hipEvent_t> ev;
+    std::vector<const char*> ev_name;
+    uint32_t ev_n = 0;
+    ~kimad_plan() { for (hipEvent_t e : ev) (void)hipEventDestroy(e); }
 };
 
 namespace {
 
 template <typename T> T* at(kimad_plan* p, uint64_t off) { return reinterpret_cast<T*>(p->ws + off); }
 
-#define KIMAD_LAUNCH_CHECK()                                   \
-    do {                                                       \
-        if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP; \
+constexpr uint32_t MAX_EVENTS = 1024;
+
+// With timing on, an event follows every launch; the interval between consecutive events is
+// that kernel's duration on the stream.
+void mark(kimad_plan* p, hipStream_t s, const char* name) {
+    if (!p->timing || p->ev_n >= MAX_EVENTS) return;
+    if (hipEventRecord(p->ev[p->ev_n], s) == hipSuccess) p->ev_name[p->ev_n++] = name;
+}
+
+#define KLAUNCH(p, s, name, kern, grid, block, ...)                    \
+    do {                                                               \
+        hipLaunchKernelGGL(kern, grid, block, 0, s, __VA_ARGS__);      \
+        if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP;     \
+        mark(p, s, name);                                              \
     } while (0)
 
 int zero_range(kimad_plan* p, uint64_t begin, uint64_t end, hipStream_t s) {
     const uint64_t n16 = (end - begin) / 16;
     if (n16 == 0) return KIMAD_OK;
     const uint32_t blocks = (uint32_t)std::min<uint64_t>((n16 + 255) / 256, 2048);
-    hipLaunchKernelGGL(k_zero16, dim3(blocks), dim3(256), 0, s, at<uint4>(p, begin), n16);
-    KIMAD_LAUNCH_CHECK();
+    KLAUNCH(p, s, "k_zero16", k_zero16, dim3(blocks), dim3(256), at<uint4>(p, begin), n16);
     return KIMAD_OK;
 }
 
@@ -213,14 +229,10 @@ int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, doubl
     int rc = zero_range(p, lo.zero1_begin, lo.zero1_end, s);
     if (rc) return rc;
     if (lo.B) {
-        hipLaunchKernelGGL(k_hist1, dim3(lo.ntiles), dim3(256), 0, s, p->pb);
-        KIMAD_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_scan1, dim3(lo.B), dim3(256), 0, s, p->pb, ktab_dev, J);
-        KIMAD_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_hist2, dim3(lo.ntiles), dim3(512), 0, s, p->pb);
-        KIMAD_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_scan2, dim3(lo.B), dim3(64), 0, s, p->pb, ktab_dev, J, err_table, 2e-6);
-        KIMAD_LAUNCH_CHECK();
+        KLAUNCH(p, s, "k_hist1", k_hist1, dim3(lo.ntiles), dim3(256), p->pb);
+        KLAUNCH(p, s, "k_scan1", k_scan1, dim3(lo.B), dim3(256), p->pb, ktab_dev, J);
+        KLAUNCH(p, s, "k_hist2", k_hist2, dim3(lo.ntiles), dim3(512), p->pb);
+        KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(64), p->pb, ktab_dev, J, err_table, 2e-6);
     }
     return KIMAD_OK;
 }
@@ -350,11 +362,11 @@ int kimad_profile(kimad_plan_t* p, double* err_table, void* stream) {
     if (!p || !err_table) return KIMAD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Layout& lo = p->lo;
+    mark(p, s, "begin");
     int rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s);
     if (rc) return rc;
     if (lo.S) {
-        hipLaunchKernelGGL(k_small_profile, dim3(lo.S), dim3(256), 0, s, p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
-        KIMAD_LAUNCH_CHECK();
+        KLAUNCH(p, s, "k_small_profile", k_small_profile, dim3(lo.S), dim3(256), p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
     }
     return KIMAD_OK;
 }
@@ -382,26 +394,23 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     ab.choice = at<uint8_t>(p, lo.choice); ab.stride = align_up(lo.dp_cells);
     ab.j_out = j_out; ab.K_out = K_out; ab.offsets_out = offsets_out; ab.status = status_out;
     ab.flags = at<uint32_t>(p, lo.dp_flags);
+    mark(p, s, "begin");
     int rc = zero_range(p, lo.dp_flags, lo.dp_flags + 16, s);
     if (rc) return rc;
     const uint32_t cell_blocks = (uint32_t)((cap + 1 + 255) / 256);
-    hipLaunchKernelGGL(k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), 0, s, ab);
-    KIMAD_LAUNCH_CHECK();
+    KLAUNCH(p, s, "k_dp_init", k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), ab);
     const double* last = ab.row0;
     if (cap + 1 <= DP_LDS_CELLS) {
-        hipLaunchKernelGGL(k_dp_lds, dim3(1), dim3(1024), 0, s, ab);
-        KIMAD_LAUNCH_CHECK();
+        KLAUNCH(p, s, "k_dp_lds", k_dp_lds, dim3(1), dim3(1024), ab);
     } else {
         double* rows[2] = {ab.row0, ab.row1};
         for (uint32_t i = 0; i < lo.L; ++i) {
-            hipLaunchKernelGGL(k_dp_layer, dim3(cell_blocks), dim3(256), 0, s, ab, i, rows[i & 1], rows[(i + 1) & 1]);
-            KIMAD_LAUNCH_CHECK();
+            KLAUNCH(p, s, "k_dp_layer", k_dp_layer, dim3(cell_blocks), dim3(256), ab, i, rows[i & 1], rows[(i + 1) & 1]);
         }
         last = rows[lo.L & 1];
     }
-    hipLaunchKernelGGL(k_dp_final, dim3(1), dim3(1024), 0, s, ab, last, (int32_t)KIMAD_ERR_INFEASIBLE,
+    KLAUNCH(p, s, "k_dp_final", k_dp_final, dim3(1), dim3(1024), ab, last, (int32_t)KIMAD_ERR_INFEASIBLE,
                        (int32_t)KIMAD_ERR_NONFINITE);
-    KIMAD_LAUNCH_CHECK();
     return KIMAD_OK;
 }
 
@@ -414,11 +423,11 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
     CompressBuffers cb = p->cb;
     cb.K = K; cb.offsets = offsets; cb.idx_out = idx_out; cb.val_out = val_out;
     cb.capacity_pairs = capacity_pairs; cb.status = status_out;
+    mark(p, s, "begin");
     if (!(flags & KIMAD_REUSE_PROFILE)) {
         // select from scratch: the two histogram passes with one target per layer
         uint32_t* ksel = at<uint32_t>(p, lo.ksel);
-        hipLaunchKernelGGL(k_make_ksel, dim3((lo.L + 255) / 256), dim3(256), 0, s, K, cb.layers, lo.L, ksel);
-        KIMAD_LAUNCH_CHECK();
+        KLAUNCH(p, s, "k_make_ksel", k_make_ksel, dim3((lo.L + 255) / 256), dim3(256), K, cb.layers, lo.L, ksel);
         int rc = run_select_passes(p, ksel, 1, nullptr, s);
         if (rc) return rc;
         cb.Ktab = ksel;
@@ -426,26 +435,19 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
     }
     int rc = zero_range(p, lo.zero2_begin, lo.zero2_end, s);
     if (rc) return rc;
-    hipLaunchKernelGGL(k_lookup, dim3(1), dim3(256), 0, s, cb, (int32_t)KIMAD_ERR_OFFGRID,
+    KLAUNCH(p, s, "k_lookup", k_lookup, dim3(1), dim3(256), cb, (int32_t)KIMAD_ERR_OFFGRID,
                        (int32_t)KIMAD_ERR_SCRATCH_OVERFLOW, (int32_t)KIMAD_ERR_BAD_OFFSETS);
-    KIMAD_LAUNCH_CHECK();
     if (lo.B) {
         const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
         const uint32_t cblocks = (lo.nchunks + 3) / 4;
-        hipLaunchKernelGGL(k_compact, dim3(lo.ntiles), dim3(256), 0, s, cb);
-        KIMAD_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_resolve, dim3(lo.B), dim3(256), 0, s, cb);
-        KIMAD_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_chunk_count, dim3(cblocks), dim3(256), 0, s, cb, lo.nchunks, chunk_big);
-        KIMAD_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_chunk_scan, dim3(lo.B), dim3(1024), 0, s, cb);
-        KIMAD_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_finalize, dim3(cblocks), dim3(256), 0, s, cb, lo.nchunks, chunk_big);
-        KIMAD_LAUNCH_CHECK();
+        KLAUNCH(p, s, "k_compact", k_compact, dim3(lo.ntiles), dim3(256), cb);
+        KLAUNCH(p, s, "k_resolve", k_resolve, dim3(lo.B), dim3(256), cb);
+        KLAUNCH(p, s, "k_chunk_count", k_chunk_count, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
+        KLAUNCH(p, s, "k_chunk_scan", k_chunk_scan, dim3(lo.B), dim3(1024), cb);
+        KLAUNCH(p, s, "k_finalize", k_finalize, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
     }
     if (lo.S) {
-        hipLaunchKernelGGL(k_small_compress, dim3(lo.S), dim3(256), 0, s, cb);
-        KIMAD_LAUNCH_CHECK();
+        KLAUNCH(p, s, "k_small_compress", k_small_compress, dim3(lo.S), dim3(256), cb);
     }
     return KIMAD_OK;
 }
@@ -468,6 +470,44 @@ int kimad_profile_diagnostics(kimad_plan_t* p, uint32_t* out2, void* stream) {
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (hipMemcpyAsync(out2, p->ws + p->lo.diag, 8, hipMemcpyDeviceToHost, s) != hipSuccess) return KIMAD_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return KIMAD_ERR_HIP;
+    return KIMAD_OK;
+}
+
+int kimad_plan_set_timing(kimad_plan_t* p, int enable) {
+    if (!p) return KIMAD_ERR_INVALID_ARG;
+    if (enable && p->ev.empty()) {
+        p->ev.resize(MAX_EVENTS);
+        p->ev_name.assign(MAX_EVENTS, "");
+        for (uint32_t k = 0; k < MAX_EVENTS; ++k)
+            if (hipEventCreate(&p->ev[k]) != hipSuccess) { p->ev.resize(k); p->timing = false; return KIMAD_ERR_HIP; }
+    }
+    p->timing = enable != 0;
+    p->ev_n = 0;
+    return KIMAD_OK;
+}
+
+int kimad_plan_get_timings(kimad_plan_t* p, char* names, uint32_t names_bytes, float* ms, uint32_t max_entries,
+                           uint32_t* count_out) {
+    if (!p || !names || !ms || !count_out) return KIMAD_ERR_INVALID_ARG;
+    uint32_t n = 0;
+    size_t pos = 0;
+    if (p->ev_n) {
+        if (hipEventSynchronize(p->ev[p->ev_n - 1]) != hipSuccess) return KIMAD_ERR_HIP;
+        for (uint32_t k = 1; k < p->ev_n && n < max_entries; ++k) {
+            if (std::strcmp(p->ev_name[k], "begin") == 0) continue;   // gap between two calls
+            float t = 0.f;
+            if (hipEventElapsedTime(&t, p->ev[k - 1], p->ev[k]) != hipSuccess) return KIMAD_ERR_HIP;
+            const size_t len = std::strlen(p->ev_name[k]);
+            if (pos + len + 2 > names_bytes) break;
+            std::memcpy(names + pos, p->ev_name[k], len);
+            pos += len;
+            names[pos++] = '\n';
+            ms[n++] = t;
+        }
+    }
+    if (names_bytes) names[pos < names_bytes ? pos : names_bytes - 1] = 0;
+    *count_out = n;
+    p->ev_n = 0;
     return KIMAD_OK;
 }
 
