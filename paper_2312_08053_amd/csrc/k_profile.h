@@ -33,8 +33,21 @@ struct ProfileBuffers {
     uint32_t* sel_prefix;         // 19-bit prefix
     uint32_t* sel_above;          // entries with a greater prefix
     uint32_t* sel_amb;            // entries with an equal prefix
-    uint32_t* diag;               // [0] uncertified entries, [1] entries fixed by the fallback
+    uint32_t* diag;               // [0] uncertified entries, [1] entries fixed by the exact fallback,
+                                  // [2] pool entries handed out
+    // exact fallback for entries whose bound is not tight: last-digit histograms of their prefix bins
+    uint32_t* layer_flag;         // [B] layer has at least one pool entry
+    uint32_t* pool_prefix;        // [POOL_MAX]
+    uint32_t* pool_big;           // [POOL_MAX]
+    uint32_t* pool_t0;            // [POOL_MAX] first target (li * J + j) of the run sharing the prefix
+    uint32_t* pool_cnt;           // [POOL_MAX] targets in that run
+    uint32_t* pool_hist;          // [POOL_MAX][4096]
+    uint32_t* tgt_unsel;          // dropped entries inside the prefix bin
+    double* tgt_base;             // E without the prefix bin's share
 };
+
+constexpr uint32_t POOL_MAX = 256;
+constexpr uint32_t POOL_NONE = 0xFFFFu;
 
 // ---------------------------------------------------------------------------------------------
 // Pass 1: per-layer histogram of digit 1 with counts and integer sums of squares.
@@ -246,13 +259,10 @@ __global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb) {
 // bounds.  Entries whose bound is not tight enough are counted in diag[0].
 __device__ __forceinline__ float prefix_lo(uint32_t prefix) { return __uint_as_float(prefix << D2_SHIFT); }
 
-__global__ __launch_bounds__(64) void k_scan2(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
-                                              double* err_table, double tol) {
-    const uint32_t big = blockIdx.x;
-    const uint32_t li = pb.big_layer[big];
+__device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uint32_t* Ktab, uint32_t J,
+                                             double* err_table, double tol, uint32_t big, uint32_t li,
+                                             uint32_t j, bool* flagged, uint32_t* prefix_out) {
     const LayerDesc L = pb.layers[li];
-    const uint32_t j = threadIdx.x;
-    if (j >= J) return;
     const size_t t = (size_t)li * J + j;
     const uint32_t K = Ktab[t];
     const uint32_t slot = pb.tgt_slot[t];
@@ -261,6 +271,8 @@ __global__ __launch_bounds__(64) void k_scan2(ProfileBuffers pb, const uint32_t*
         pb.sel_prefix[t] = 0u;
         pb.sel_above[t] = (K == 0u) ? 0u : L.n;
         pb.sel_amb[t] = 0u;
+        pb.tgt_unsel[t] = 0u;
+        pb.tgt_base[t] = 0.0;
         return;
     }
     const uint32_t bin = pb.slot_bin[(size_t)big * MAX_SLOTS + slot];
@@ -281,36 +293,179 @@ __global__ __launch_bounds__(64) void k_scan2(ProfileBuffers pb, const uint32_t*
     double below2 = 0.0;
     for (int k = 0; k < u; ++k) below2 += sq_to_double(bin, sq[k], cnt[k]);
     const uint32_t prefix = (bin << D2_BITS) | (uint32_t)u;
-    double est = 0.0, bound = 0.0;
+    double est = 0.0, half_gap = 0.0;
     if (unsel) {
         const double Q = sq_to_double(bin, sq[u], m);
-        const double lo = (double)prefix_lo(prefix), hi = (double)prefix_lo(prefix + 1u);
-        const double f = (double)unsel / (double)m;
-        double ub = fmin(f * Q, (double)unsel * hi * hi);
-        double lb = fmax((double)unsel * lo * lo, Q - (double)rsel * hi * hi);
-        if (!(lb <= ub)) { const double mid = 0.5 * (lb + ub); lb = ub = mid; }
-        // smooth-density model: the dropped entries fill the lowest fraction f of [lo, hi)
-        const double w = hi - lo;
-        const double a = lo + 0.5 * f * w, c = lo + 0.5 * w;
-        est = (double)unsel * a * a * (Q / ((double)m * c * c));
-        if (!(est >= lb)) est = lb;
-        if (!(est <= ub)) est = ub;
-        bound = fmax(ub - est, est - lb);
         if ((bin >> 4) == 255u) {
             // Inf/NaN entries: the dropped ones are the lowest keys, i.e. the infinities first.
             const uint64_t nans = sq[u];
             const uint64_t infs = (uint64_t)m - nans;
             est = (uint64_t)unsel > infs ? __longlong_as_double(0x7FF8000000000000ll)
                                          : __longlong_as_double(0x7FF0000000000000ll);
-            bound = 0.0;
+        } else {
+            // The dropped entries are the `unsel` smallest of m values in [lo, hi) whose squares sum
+            // to Q: at least unsel*lo^2 and Q - rsel*hi^2, at most their mean share and unsel*hi^2.
+            const double lo = (double)prefix_lo(prefix), hi = (double)prefix_lo(prefix + 1u);
+            const double ub = fmin(((double)unsel / (double)m) * Q, (double)unsel * hi * hi);
+            const double lb = fmin(ub, fmax((double)unsel * lo * lo, Q - (double)rsel * hi * hi));
+            est = 0.5 * (lb + ub);
+            half_gap = 0.5 * (ub - lb);
         }
     }
-    const double E = pb.tgt_below[t] + below2 + est;
+    const double base = pb.tgt_below[t] + below2;
+    const double E = base + est;
     if (err_table) err_table[t] = E;
-    if (bound > tol * E) atomicAdd(&pb.diag[0], 1u);
     pb.sel_prefix[t] = prefix;
     pb.sel_above[t] = pb.tgt_above1[t] + acc;
     pb.sel_amb[t] = m;
+    pb.tgt_unsel[t] = unsel;
+    pb.tgt_base[t] = base;
+    *flagged = err_table != nullptr && half_gap > tol * E;
+    *prefix_out = prefix;
+}
+
+// One wave per big layer: thread j handles candidate j.  Candidates whose error bound is too
+// wide are grouped by prefix (equal prefixes are adjacent because K ascends) and each group gets
+// one pool entry for the exact last-digit pass.
+__global__ __launch_bounds__(64) void k_scan2(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
+                                              double* err_table, double tol) {
+    const uint32_t big = blockIdx.x;
+    const uint32_t li = pb.big_layer[big];
+    const uint32_t j = threadIdx.x;
+    bool flagged = false;
+    uint32_t prefix = 0xFFFFFFFFu - j;          // distinct dummy for idle lanes and K == n
+    if (j < J) scan2_target(pb, Ktab, J, err_table, tol, big, li, j, &flagged, &prefix);
+    const uint32_t prev = __shfl_up(prefix, 1, 64);
+    const bool head = j == 0 || prev != prefix;
+    const uint64_t heads = ballot(head), flags = ballot(flagged);
+    if (flags == 0) return;
+    // run of this lane: from its head (highest head bit at or below j) to the lane before the next head
+    const uint64_t below_or_eq = heads & (~0ull >> (63 - j));
+    const uint32_t h0 = 63u - (uint32_t)__clzll((long long)below_or_eq);
+    const uint64_t after = heads & ~((2ull << j) - 1ull);
+    const uint32_t h1 = after ? (uint32_t)__ffsll((long long)after) - 1u : 64u;   // exclusive end
+    const uint64_t run_mask = (h1 >= 64 ? ~0ull : ((1ull << h1) - 1ull)) & ~((1ull << h0) - 1ull);
+    const bool run_flagged = (flags & run_mask) != 0;
+    if (flagged) atomicAdd(&pb.diag[0], 1u);
+    if (head && run_flagged && j < J) {
+        const uint32_t f = atomicAdd(&pb.diag[2], 1u);
+        if (f < POOL_MAX) {
+            pb.pool_prefix[f] = prefix;
+            pb.pool_big[f] = big;
+            pb.pool_t0[f] = li * J + j;
+            pb.pool_cnt[f] = h1 - h0;
+            pb.layer_flag[big] = 1u;
+        }
+    }
+}
+
+// Exact fallback, pass: last-digit histogram of every pooled prefix bin.  One workgroup per tile;
+// tiles of layers without pool entries return at once.
+__global__ __launch_bounds__(256) void k_hist3p(ProfileBuffers pb) {
+    __shared__ uint32_t pfx[POOL_MAX];
+    __shared__ uint32_t pid[POOL_MAX];
+    __shared__ uint32_t npool;
+    const uint32_t tile = blockIdx.x, tid = threadIdx.x;
+    const uint32_t li = pb.tile_layer[tile];
+    const LayerDesc L = pb.layers[li];
+    if (!pb.layer_flag[L.big]) return;
+    if (tid == 0) npool = 0;
+    __syncthreads();
+    const uint32_t total = min(pb.diag[2], POOL_MAX);
+    for (uint32_t f = tid; f < total; f += 256) {
+        if (pb.pool_big[f] == (uint32_t)L.big) {
+            const uint32_t k = atomicAdd(&npool, 1u);
+            pfx[k] = pb.pool_prefix[f];
+            pid[k] = f;
+        }
+    }
+    __syncthreads();
+    const uint32_t np = npool;
+    const uint32_t vbase = (tile - L.tile0) * pb.tile_elems;
+    const uint32_t iters = pb.tile_elems / 1024u;
+    for (uint32_t it = 0; it < iters; ++it) {
+        Quad q;
+        load_quad(L, vbase + it * 1024u + tid * 4u, q);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t key = q.key[c];
+            uint32_t f = POOL_NONE;
+            if (key != KEY_INVALID) {
+                const uint32_t p = key >> D2_SHIFT;
+                for (uint32_t k = 0; k < np; ++k) if (pfx[k] == p) f = pid[k];
+            }
+            const bool a = f != POOL_NONE;
+            const uint64_t am = ballot(a);
+            if (am == 0) continue;
+            // one atomic per wave when all matching lanes hold the same key (constants, zeros)
+            const uint32_t first_lane = (uint32_t)__ffsll((long long)am) - 1u;
+            const uint32_t k0 = __shfl(key, first_lane, 64);
+            if (ballot(a && key != k0) == 0) {
+                if (lane_id() == first_lane) atomicAdd(&pb.pool_hist[(size_t)f * D3_BINS + (key & (D3_BINS - 1))], (uint32_t)__popcll(am));
+            } else if (a) {
+                atomicAdd(&pb.pool_hist[(size_t)f * D3_BINS + (key & (D3_BINS - 1))], 1u);
+            }
+        }
+    }
+}
+
+// Exact fallback, scan: one workgroup per pool entry.  With the full key known, the squares of the
+// `unsel` smallest entries of the prefix bin are summed exactly in fp64, smallest first.
+__global__ __launch_bounds__(256) void k_scan3p(ProfileBuffers pb, double* err_table) {
+    __shared__ uint32_t su[16];
+    __shared__ double sd[16];
+    __shared__ uint32_t cum[D3_BINS];      // entries in lower digits
+    __shared__ double sumsq[D3_BINS];      // their squares
+    const uint32_t f = blockIdx.x, tid = threadIdx.x;
+    if (f >= min(pb.diag[2], POOL_MAX)) return;
+    const uint32_t prefix = pb.pool_prefix[f];
+    const uint32_t* h = pb.pool_hist + (size_t)f * D3_BINS;
+    uint32_t c[16];
+    double s[16];
+    uint32_t csum = 0;
+    double ssum = 0.0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const uint32_t d3 = tid * 16u + k;
+        c[k] = h[d3];
+        pb.pool_hist[(size_t)f * D3_BINS + d3] = 0u;       // leave the pool clean for the next call
+        const double v = (double)__uint_as_float((prefix << D2_SHIFT) | d3);
+        s[k] = (double)c[k] * v * v;
+        csum += c[k];
+        ssum += s[k];
+    }
+    const uint32_t cex = block_exclusive_scan<uint32_t>(csum, su, nullptr);
+    const double sex = block_exclusive_scan<double>(ssum, sd, nullptr);
+    {
+        uint32_t rc = cex;
+        double rs = sex;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            cum[tid * 16u + k] = rc;
+            sumsq[tid * 16u + k] = rs;
+            rc += c[k];
+            rs += s[k];
+        }
+    }
+    __syncthreads();
+    const uint32_t t0 = pb.pool_t0[f], cnt = pb.pool_cnt[f];
+    for (uint32_t k = tid; k < cnt; k += 256) {
+        const uint32_t t = t0 + k;
+        const uint32_t unsel = pb.tgt_unsel[t];
+        double U = 0.0;
+        if (unsel) {
+            // largest digit d with cum[d] < unsel: digits below d are dropped whole
+            uint32_t lo = 0, hi = D3_BINS - 1;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi + 1) >> 1;
+                if (cum[mid] < unsel) lo = mid; else hi = mid - 1;
+            }
+            const double v = (double)__uint_as_float((prefix << D2_SHIFT) | lo);
+            U = sumsq[lo] + (double)(unsel - cum[lo]) * v * v;
+        }
+        err_table[t] = pb.tgt_base[t] + U;
+        atomicAdd(&pb.diag[1], 1u);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------

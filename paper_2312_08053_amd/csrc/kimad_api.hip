@@ -22,6 +22,9 @@ namespace {
 using namespace kimad;
 
 constexpr uint64_t ALIGN = 256;
+// A table entry is accepted from the two histogram levels when its rigorous error bound is
+// below this fraction of the entry; otherwise the exact last-digit pass recomputes it.
+constexpr double CERT_TOL = 4e-6;
 
 inline uint64_t align_up(uint64_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
@@ -33,7 +36,8 @@ struct Layout {
     // static tables
     uint64_t layers, ktab, tile_layer, chunk_big, big_layer, small_layer;
     // zeroed before every profile
-    uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, zero1_end;
+    uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, zero1_end;
+    uint64_t pool_prefix, pool_big, pool_t0, pool_cnt, pool_hist, tgt_unsel, tgt_base;
     uint64_t lut1, nslots, slot_bin;
     uint64_t tgt_slot, tgt_r, tgt_above1, tgt_below, sel_prefix, sel_above, sel_amb;
     // compress
@@ -123,7 +127,15 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.cnt2 = take(4ull * B * MAX_SLOTS * D2_BINS);
     lo.sq2 = take(8ull * B * MAX_SLOTS * D2_BINS);
     lo.diag = take(16);
+    lo.layer_flag = take(4ull * (B ? B : 1));
     lo.zero1_end = off;
+    lo.pool_prefix = take(4ull * POOL_MAX);
+    lo.pool_big = take(4ull * POOL_MAX);
+    lo.pool_t0 = take(4ull * POOL_MAX);
+    lo.pool_cnt = take(4ull * POOL_MAX);
+    lo.pool_hist = take(4ull * POOL_MAX * D3_BINS);      // zero between calls: cleared by its reader
+    lo.tgt_unsel = take(4 * LJ);
+    lo.tgt_base = take(8 * LJ);
     lo.lut1 = take(1ull * B * D1_BINS);
     lo.nslots = take(4ull * (B ? B : 1));
     lo.slot_bin = take(4ull * B * MAX_SLOTS);
@@ -232,7 +244,12 @@ int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, doubl
         KLAUNCH(p, s, "k_hist1", k_hist1, dim3(lo.ntiles), dim3(256), p->pb);
         KLAUNCH(p, s, "k_scan1", k_scan1, dim3(lo.B), dim3(256), p->pb, ktab_dev, J);
         KLAUNCH(p, s, "k_hist2", k_hist2, dim3(lo.ntiles), dim3(512), p->pb);
-        KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(64), p->pb, ktab_dev, J, err_table, 2e-6);
+        KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(64), p->pb, ktab_dev, J, err_table, CERT_TOL);
+        if (err_table) {
+            // exact last-digit pass for the entries scan 2 could not certify (usually none)
+            KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(lo.ntiles), dim3(256), p->pb);
+            KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(POOL_MAX), dim3(256), p->pb, err_table);
+        }
     }
     return KIMAD_OK;
 }
@@ -328,6 +345,14 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.tgt_above1 = at<uint32_t>(p, lo.tgt_above1); pb.tgt_below = at<double>(p, lo.tgt_below);
     pb.sel_prefix = at<uint32_t>(p, lo.sel_prefix); pb.sel_above = at<uint32_t>(p, lo.sel_above);
     pb.sel_amb = at<uint32_t>(p, lo.sel_amb); pb.diag = at<uint32_t>(p, lo.diag);
+    pb.layer_flag = at<uint32_t>(p, lo.layer_flag);
+    pb.pool_prefix = at<uint32_t>(p, lo.pool_prefix); pb.pool_big = at<uint32_t>(p, lo.pool_big);
+    pb.pool_t0 = at<uint32_t>(p, lo.pool_t0); pb.pool_cnt = at<uint32_t>(p, lo.pool_cnt);
+    pb.pool_hist = at<uint32_t>(p, lo.pool_hist);
+    pb.tgt_unsel = at<uint32_t>(p, lo.tgt_unsel); pb.tgt_base = at<double>(p, lo.tgt_base);
+    // the pool histograms must start at zero; afterwards k_scan3p clears what it has read
+    if (hipMemsetAsync(p->ws + lo.pool_hist, 0, 4ull * POOL_MAX * D3_BINS, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
 
     CompressBuffers& cb = p->cb;
     cb.layers = pb.layers; cb.chunk_layer = pb.tile_layer; cb.big_layer = pb.big_layer; cb.small_layer = pb.small_layer;

@@ -25,6 +25,8 @@ def _full_check(work, reuse=True, table_rel=1e-5):
     E_gpu = plan.profile().cpu().numpy().reshape(work.L, -1)
     torch.cuda.synchronize()
     gh.assert_table_close(E_gpu, E_ref, Kt, work.sizes)
+    uncertified, fixed = plan.diagnostics()
+    assert uncertified == fixed, "every entry with a loose bound must have been recomputed exactly"
     assert np.array_equal(h.cpu().numpy().view(np.uint32), work.h.view(np.uint32)), "profile must not touch h"
 
     # allocation on the oracle's table: bit-exact choice
