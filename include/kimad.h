@@ -49,7 +49,6 @@ typedef enum kimad_status {
     KIMAD_ERR_INFEASIBLE = -6,          /* device status: budget below the cheapest allocation */
     KIMAD_ERR_NONFINITE = -7,           /* device status: error table holds Inf or NaN */
     KIMAD_ERR_OFFGRID = -8,             /* device status: KIMAD_REUSE_PROFILE given but K is not a grid size */
-    KIMAD_ERR_SCRATCH_OVERFLOW = -9,    /* device status: candidate buffer too small (see tmp_capacity_pairs) */
     KIMAD_ERR_BAD_OFFSETS = -10         /* device status: offsets/K do not fit capacity_pairs */
 } kimad_status;
 
@@ -66,8 +65,11 @@ typedef struct kimad_config {
     uint32_t cost_units_D;              /* Appendix C discretisation factor D applied to the budget; 0 = exact */
     uint64_t max_budget_bytes;          /* largest budget kimad_allocate will see; 0 = uncompressed size.
                                            Sizes the DP tables when cost_units_D == 0. */
-    uint64_t tmp_capacity_pairs;        /* candidate-buffer entries; 0 = worst case (sum of n) */
+    uint64_t flags;                     /* KIMAD_CFG_* */
 } kimad_config_t;
+
+#define KIMAD_CFG_CLASSIC_PROFILE 1ull  /* profile with two full passes over g, h instead of the sampled
+                                           single pass (same results; for comparison and testing) */
 
 /* flags of kimad_compress_ef */
 #define KIMAD_REUSE_PROFILE 1u          /* every K[i] is one of layer i's grid sizes and g, h are unchanged
@@ -100,9 +102,12 @@ int kimad_plan_grid_sizes(const kimad_plan_t* plan, uint64_t* K_table_out);
 /* Error profile (Section 3.2, Eq. norm decomposition):
  *   err_table[i*J + j] = || x_i - TopK_{K_ij}(x_i) ||^2  = sum of squares of the entries dropped,
  * fp64, DEVICE, L*J row-major.  Exactly 0 where K_ij = n_i.  Pure: g and h are not modified.
- * Also records, inside the workspace, each candidate's selection threshold for
- * KIMAD_REUSE_PROFILE. */
-int kimad_profile(kimad_plan_t* plan, double* err_table, void* stream);
+ * Also records, inside the workspace, each candidate's selection threshold and the layer's
+ * largest entries (index, x, h) for KIMAD_REUSE_PROFILE.
+ *   budget_hint_bytes  the budget the following kimad_allocate will get, or 0 if unknown.  It only
+ *                      sizes how many of the largest entries are kept for the compression; no
+ *                      result depends on it. */
+int kimad_profile(kimad_plan_t* plan, double* err_table, uint64_t budget_hint_bytes, void* stream);
 
 /* Allocation (Section 3.2 Eq. optimisation; Appendix C): choose j_i minimising
  * sum_i err_table[i][j_i] subject to sum_i K_{i j_i} * pair_bytes <= budget_bytes.
@@ -141,9 +146,19 @@ int kimad_step(kimad_plan_t* plan, uint64_t budget_bytes, double* err_table,
                int32_t* status_out /* DEVICE int32[2]: allocate, compress */, void* stream);
 
 /* DEVICE diagnostics of the last kimad_profile on the plan, copied to HOST (synchronises the
- * stream): out[0] = table entries whose error bound exceeded the certified tolerance before
- * the exact fallback ran, out[1] = entries fixed by the fallback. */
-int kimad_profile_diagnostics(kimad_plan_t* plan, uint32_t* out2, void* stream);
+ * stream): out[0] = table entries whose error bound exceeded the certified tolerance before the
+ * exact last-digit pass ran, out[1] = entries that pass recomputed, out[2] = histograms it used,
+ * out[3] = layers whose sampled prediction missed and were recounted by a full pass. */
+int kimad_profile_diagnostics(kimad_plan_t* plan, uint32_t* out4, void* stream);
+
+/* Per-layer state of the last profile / compression, for benchmarks and tests (synchronises the
+ * stream).  For each layer larger than 8192 entries, 8 words are written to `out` (HOST):
+ * layer index, spill bin (entries at or above this digit-1 bin were kept as candidates; 4096 = none),
+ * slots fixed before the pass, slots filled from the candidates, redo flag, candidates kept,
+ * candidates valid, selection mode of the last kimad_compress_ef (0 none, 1 read g and h,
+ * 2 all entries, 3 from the candidates). */
+int kimad_plan_layer_states(kimad_plan_t* plan, uint32_t* out, uint32_t max_layers, uint32_t* count_out,
+                            void* stream);
 
 /* Per-kernel timing (tracing aid for benchmarks).  With timing enabled the library records a
  * HIP event on the stream after every kernel it launches.  kimad_plan_get_timings waits for the

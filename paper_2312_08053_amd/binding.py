@@ -10,12 +10,13 @@ import numpy as np
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkimad.so")
 
 KIMAD_REUSE_PROFILE = 1
+KIMAD_CFG_CLASSIC_PROFILE = 1
 KIMAD_MAX_J = 64
 
 EXPORTED_SYMBOLS = [
     "kimad_workspace_bytes", "kimad_plan_create", "kimad_plan_destroy", "kimad_plan_grid_sizes",
     "kimad_profile", "kimad_allocate", "kimad_compress_ef", "kimad_step",
-    "kimad_profile_diagnostics", "kimad_plan_set_timing", "kimad_plan_get_timings",
+    "kimad_profile_diagnostics", "kimad_plan_layer_states", "kimad_plan_set_timing", "kimad_plan_get_timings",
     "kimad_strerror", "kimad_version",
 ]
 
@@ -32,7 +33,7 @@ class _Layer(C.Structure):
 
 class _Config(C.Structure):
     _fields_ = [("pair_bytes", C.c_uint32), ("cost_units_D", C.c_uint32),
-                ("max_budget_bytes", C.c_uint64), ("tmp_capacity_pairs", C.c_uint64)]
+                ("max_budget_bytes", C.c_uint64), ("flags", C.c_uint64)]
 
 
 _lib = None
@@ -53,11 +54,12 @@ def lib() -> C.CDLL:
                                     vp, u64, vp, C.POINTER(vp)]
     L.kimad_plan_destroy.argtypes = [vp]
     L.kimad_plan_grid_sizes.argtypes = [vp, C.POINTER(C.c_uint64)]
-    L.kimad_profile.argtypes = [vp, vp, vp]
+    L.kimad_profile.argtypes = [vp, vp, u64, vp]
     L.kimad_allocate.argtypes = [vp, vp, u64, vp, vp, vp, i32p, vp]
     L.kimad_compress_ef.argtypes = [vp, vp, vp, vp, vp, u64, u32, i32p, vp]
     L.kimad_step.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, u64, i32p, vp]
     L.kimad_profile_diagnostics.argtypes = [vp, C.POINTER(C.c_uint32), vp]
+    L.kimad_plan_layer_states.argtypes = [vp, C.POINTER(C.c_uint32), u32, C.POINTER(C.c_uint32), vp]
     L.kimad_plan_set_timing.argtypes = [vp, C.c_int]
     L.kimad_plan_get_timings.argtypes = [vp, C.c_char_p, u32, C.POINTER(C.c_float), u32, C.POINTER(C.c_uint32)]
     L.kimad_strerror.argtypes = [C.c_int]
@@ -78,8 +80,8 @@ def kimad_version() -> str:
     return lib().kimad_version().decode()
 
 
-def _cfg(pair_bytes=8, D=0, max_budget_bytes=0, tmp_capacity_pairs=0) -> _Config:
-    return _Config(int(pair_bytes), int(D), int(max_budget_bytes), int(tmp_capacity_pairs))
+def _cfg(pair_bytes=8, D=0, max_budget_bytes=0, cfg_flags=0) -> _Config:
+    return _Config(int(pair_bytes), int(D), int(max_budget_bytes), int(cfg_flags))
 
 
 def _check(code: int, where: str) -> None:
@@ -99,23 +101,23 @@ def _stream(stream) -> int:
 
 
 def kimad_workspace_bytes(sizes: Sequence[int], J: int, pair_bytes=8, D=0, max_budget_bytes=0,
-                          tmp_capacity_pairs=0) -> int:
+                          cfg_flags=0) -> int:
     n = (C.c_uint64 * len(sizes))(*[int(s) for s in sizes])
     out = C.c_uint64(0)
-    cfg = _cfg(pair_bytes, D, max_budget_bytes, tmp_capacity_pairs)
+    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags)
     _check(lib().kimad_workspace_bytes(n, len(sizes), int(J), C.byref(cfg), C.byref(out)), "kimad_workspace_bytes")
     return int(out.value)
 
 
 def kimad_plan_create(g_ptrs: Sequence[int], h_ptrs: Sequence[int], sizes: Sequence[int], ratios: Sequence[float],
                       workspace_ptr: int, workspace_bytes: int, stream=None, pair_bytes=8, D=0,
-                      max_budget_bytes=0, tmp_capacity_pairs=0) -> int:
+                      max_budget_bytes=0, cfg_flags=0) -> int:
     L = len(sizes)
     layers = (_Layer * L)()
     for i in range(L):
         layers[i].g, layers[i].h, layers[i].n = int(g_ptrs[i]), int(h_ptrs[i]), int(sizes[i])
     r = (C.c_double * len(ratios))(*[float(x) for x in ratios])
-    cfg = _cfg(pair_bytes, D, max_budget_bytes, tmp_capacity_pairs)
+    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags)
     plan = C.c_void_p(0)
     _check(lib().kimad_plan_create(layers, L, r, len(ratios), C.byref(cfg), C.c_void_p(int(workspace_ptr)),
                                    int(workspace_bytes), C.c_void_p(_stream(stream)), C.byref(plan)),
@@ -127,9 +129,9 @@ def kimad_plan_destroy(plan: int) -> None:
     _check(lib().kimad_plan_destroy(C.c_void_p(plan)), "kimad_plan_destroy")
 
 
-def kimad_profile(plan: int, err_table, stream=None) -> None:
-    _check(lib().kimad_profile(C.c_void_p(plan), C.c_void_p(_ptr(err_table)), C.c_void_p(_stream(stream))),
-           "kimad_profile")
+def kimad_profile(plan: int, err_table, budget_hint_bytes: int = 0, stream=None) -> None:
+    _check(lib().kimad_profile(C.c_void_p(plan), C.c_void_p(_ptr(err_table)), int(budget_hint_bytes),
+                               C.c_void_p(_stream(stream))), "kimad_profile")
 
 
 def kimad_allocate(plan: int, err_table, budget_bytes: int, j_out, K_out, offsets_out, status_out,
@@ -163,7 +165,7 @@ class Plan:
     """
 
     def __init__(self, g, h, sizes: Sequence[int], ratios: Sequence[float], pair_bytes: int = 8, D: int = 0,
-                 max_budget_bytes: int = 0, tmp_capacity_pairs: int = 0, capacity_pairs: Optional[int] = None):
+                 max_budget_bytes: int = 0, cfg_flags: int = 0, capacity_pairs: Optional[int] = None):
         import torch
         self.torch = torch
         self.sizes = [int(s) for s in sizes]
@@ -180,13 +182,13 @@ class Plan:
             dev = g.device
         self._keep = (g, h)
         self.device = dev
-        nbytes = kimad_workspace_bytes(self.sizes, self.J, pair_bytes, D, max_budget_bytes, tmp_capacity_pairs)
+        nbytes = kimad_workspace_bytes(self.sizes, self.J, pair_bytes, D, max_budget_bytes, cfg_flags)
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
         base = int(self.workspace.data_ptr())
         self._ws_ptr = (base + 255) // 256 * 256
         self.workspace_bytes = nbytes
         self.handle = kimad_plan_create(g_ptrs, h_ptrs, self.sizes, self.ratios, self._ws_ptr, nbytes,
-                                        None, pair_bytes, D, max_budget_bytes, tmp_capacity_pairs)
+                                        None, pair_bytes, D, max_budget_bytes, cfg_flags)
         d = int(sum(self.sizes))
         self.capacity_pairs = int(capacity_pairs) if capacity_pairs is not None else d
         self.err_table = torch.empty(self.L * self.J, dtype=torch.float64, device=dev)
@@ -202,9 +204,9 @@ class Plan:
         _check(lib().kimad_plan_grid_sizes(C.c_void_p(self.handle), out), "kimad_plan_grid_sizes")
         return np.array(out[:], dtype=np.int64).reshape(self.L, self.J)
 
-    def profile(self, err_table=None):
+    def profile(self, err_table=None, budget_hint_bytes: int = 0):
         t = self.err_table if err_table is None else err_table
-        kimad_profile(self.handle, t)
+        kimad_profile(self.handle, t, budget_hint_bytes)
         return t
 
     def allocate(self, budget_bytes: int, err_table=None):
@@ -225,10 +227,20 @@ class Plan:
         return self.status
 
     def diagnostics(self):
-        out = (C.c_uint32 * 2)()
+        out = (C.c_uint32 * 4)()
         _check(lib().kimad_profile_diagnostics(C.c_void_p(self.handle), out, C.c_void_p(_stream(None))),
                "kimad_profile_diagnostics")
-        return int(out[0]), int(out[1])
+        return dict(uncertified=int(out[0]), recomputed=int(out[1]), pool_entries=int(out[2]),
+                    redo_layers=int(out[3]))
+
+    def layer_states(self):
+        """Per tiled layer: dict(layer, spill_bin, slots_pre, slots_cand, redo, spill_cnt, spill_valid, mode)."""
+        out = (C.c_uint32 * (8 * self.L))()
+        cnt = C.c_uint32(0)
+        _check(lib().kimad_plan_layer_states(C.c_void_p(self.handle), out, self.L, C.byref(cnt),
+                                             C.c_void_p(_stream(None))), "kimad_plan_layer_states")
+        names = ("layer", "spill_bin", "slots_pre", "slots_cand", "redo", "spill_cnt", "spill_valid", "mode")
+        return [dict(zip(names, out[8 * b:8 * b + 8])) for b in range(cnt.value)]
 
     def set_timing(self, enable: bool) -> None:
         _check(lib().kimad_plan_set_timing(C.c_void_p(self.handle), int(bool(enable))), "kimad_plan_set_timing")

@@ -20,13 +20,22 @@ constexpr uint32_t KIMAD_MAX_J_CONST = 64;   // must equal KIMAD_MAX_J of the pu
 constexpr uint32_t KEY_INVALID = 0xFFFFFFFFu; // marks lanes outside the layer
 
 constexpr uint32_t SMALL_MAX = 8192;          // layers up to this size are sorted whole in LDS
-constexpr uint32_t CHUNK = 2048;              // elements one wave compacts at a time
+constexpr uint32_t CHUNK = 1024;              // elements one wave compacts at a time (4 quads per lane)
+constexpr uint32_t NQ = CHUNK / 256;          // quads per lane and chunk
+constexpr uint32_t PRE_SLOTS = 96;            // digit-2 slots the single-pass profile can hold in LDS
+constexpr uint32_t SLOT_STRIDE = PRE_SLOTS + 64;  // slots per layer in the global digit-2 tables: 0..95 fixed
+                                              // before a pass, 96..159 found after it (filled from candidates)
+// LDS entry of a slot in the single-pass profile: [count:20 | sum of (significand^2 >> 24):44]
+constexpr uint32_t PK_SHIFT = 24;
+constexpr uint64_t PK_ONE = 1ull << 44;
+constexpr uint64_t PK_MASK = PK_ONE - 1;
+constexpr uint32_t PK_MAX_CHUNKS = 1023;      // 1023 * 1024 entries < 2^20: the count field cannot overflow
 constexpr uint32_t SQ_SHIFT = 16;             // squares of 24-bit significands are kept >> 16
 constexpr uint64_t CNT_ONE = 1ull << 48;      // packed LDS entry: [count:16 | sum of squares:48]
 constexpr uint64_t SQ_MASK = CNT_ONE - 1;
 
 // selection modes of a layer in the compaction pass
-enum : uint32_t { SEL_NONE = 0, SEL_PREFIX = 1, SEL_ALL = 2 };
+enum : uint32_t { SEL_NONE = 0, SEL_PREFIX = 1, SEL_ALL = 2, SEL_CAND = 3 };
 
 struct LayerDesc {
     const float* g;
@@ -39,6 +48,20 @@ struct LayerDesc {
     uint32_t ntiles;
     uint32_t chunk0;   // first chunk of this layer in the chunk list
     uint32_t nchunks;
+    uint32_t sstride;  // the sampling pre-pass reads one chunk out of every sstride
+    uint32_t pad;
+    uint64_t tmp0;     // start of this layer's region (n entries) in the candidate buffer
+};
+
+// Per big layer, state of the fused single-pass profile.
+struct LayerState {
+    uint32_t spill_bin;    // entries whose digit-1 bin is >= spill_bin were written to the candidate buffer
+    uint32_t nslots_d;     // boundary-bin slots fixed before the pass (predicted, or exact after a redo)
+    uint32_t nslots_t;     // slots 64.. assigned after the pass and filled from the candidates
+    uint32_t redo;         // prediction missed: digit 2 is recounted by a full pass over this layer
+    uint32_t spill_cnt;    // entries in the candidate region
+    uint32_t spill_valid;  // the region holds exactly the entries with bin >= spill_bin, in index order per chunk
+    uint32_t pad[2];
 };
 
 // Per big layer, what the compaction pass needs.
@@ -47,7 +70,7 @@ struct SelRec {
     uint32_t prefix;   // 19-bit key prefix of the threshold (digit1 | digit2)
     uint32_t above;    // entries whose prefix is greater (certainly selected)
     uint32_t amb;      // entries whose prefix is equal (decided by digit 3)
-    uint64_t tmp_base; // start of this layer's candidates in the candidate buffer
+    uint64_t tmp_base; // start of this layer's region in the candidate buffer
     uint32_t cap;      // candidates this layer may write
     uint32_t K;
 };

@@ -45,7 +45,7 @@ struct CompressBuffers {
     uint32_t* tmp_idx;
     float* tmp_x;
     float* tmp_h;
-    uint64_t tmp_capacity;
+    const LayerState* state;      // fused-profile state (spill range) per big layer
     // outputs
     const uint64_t* K;
     const uint64_t* offsets;
@@ -58,9 +58,8 @@ struct CompressBuffers {
 // ---------------------------------------------------------------------------------------------
 // Per layer: turn K[i] into a selection record using the profile's threshold cache.
 // One workgroup; thread b handles big layer b (looping).
-__global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_offgrid, int32_t err_scratch,
-                                                int32_t err_offsets) {
-    __shared__ unsigned long long s64[16];
+__global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_offgrid, int32_t err_offsets,
+                                                uint32_t use_candidates) {
     __shared__ int bad;
     const uint32_t tid = threadIdx.x;
     if (tid == 0) bad = 0;
@@ -73,14 +72,13 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
     __syncthreads();
     const bool offsets_bad = bad != 0;
     __syncthreads();
-    unsigned long long running = 0;            // candidates of the big layers handled in earlier rounds
-    for (uint32_t b0 = 0; b0 < cb.B; b0 += 256) {
-        const uint32_t b = b0 + tid;
+    for (uint32_t b = tid; b < cb.B; b += 256) {
         SelRec r;
-        r.mode = SEL_NONE; r.prefix = 0; r.above = 0; r.amb = 0; r.tmp_base = 0; r.cap = 0; r.K = 0;
-        if (b < cb.B && !offsets_bad) {
-            const uint32_t li = cb.big_layer[b];
-            const uint32_t n = cb.layers[li].n;
+        r.mode = SEL_NONE; r.prefix = 0; r.above = 0; r.amb = 0; r.cap = 0; r.K = 0;
+        const uint32_t li = cb.big_layer[b];
+        const uint32_t n = cb.layers[li].n;
+        r.tmp_base = cb.layers[li].tmp0;
+        if (!offsets_bad) {
             const uint32_t K = (uint32_t)cb.K[li];
             r.K = K;
             if (K == 0u) {
@@ -95,37 +93,36 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
                     atomicMax(&bad, 2);
                 } else {
                     const size_t t = (size_t)li * cb.J + found;
-                    r.mode = SEL_PREFIX;
                     r.prefix = cb.sel_prefix[t];
                     r.above = cb.sel_above[t];
                     r.amb = cb.sel_amb[t];
-                    r.cap = r.above + r.amb;
+                    r.cap = n;
+                    const LayerState st = cb.state[b];
+                    // every entry at or above the threshold prefix already sits in the candidate buffer
+                    const bool in_spill = use_candidates && st.spill_valid && st.spill_bin < D1_BINS &&
+                                          r.prefix >= (st.spill_bin << D2_BITS);
+                    r.mode = in_spill ? SEL_CAND : SEL_PREFIX;
                 }
             }
         }
-        unsigned long long tot;
-        const unsigned long long ex = block_exclusive_scan<unsigned long long>((unsigned long long)r.cap, s64, &tot);
-        r.tmp_base = running + ex;
-        running += tot;
-        if (b < cb.B) {
-            cb.sel[b] = r;
-            cb.cursor[b] = 0u;
-        }
+        cb.sel[b] = r;
+        // the classic pass reserves its candidates from zero; the spilled ones keep their records
+        if (r.mode != SEL_CAND) cb.cursor[b] = 0u;
     }
     __syncthreads();
-    const bool overflow = running > cb.tmp_capacity;
-    if (overflow || bad) {
+    if (bad) {
         // refuse the whole call: nothing is written by the later kernels
         for (uint32_t b = tid; b < cb.B; b += 256) { cb.sel[b].mode = SEL_NONE; cb.sel[b].cap = 0; cb.sel[b].K = 0; }
-        if (tid == 0) *cb.status = offsets_bad ? err_offsets : (bad == 2 ? err_offgrid : err_scratch);
+        if (tid == 0) *cb.status = offsets_bad ? err_offsets : err_offgrid;
     } else if (tid == 0) {
         *cb.status = 0;
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Streaming compaction pass.  One wave per 2048-element chunk; a workgroup of 4 waves walks the
-// chunks of one tile.  Each lane holds 8 quads (32 elements); positions come from ballots, so
+// Streaming compaction pass (layers whose threshold lies below the spilled range, or all layers
+// when no fused profile preceded).  One wave per chunk; a workgroup of 4 waves walks the chunks
+// of one tile.  Each lane holds 4 quads (16 elements); positions come from ballots, so
 // the candidates of a chunk are written in index order at a range reserved with one atomic.
 __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
     const uint32_t tile = blockIdx.x;
@@ -136,25 +133,23 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
     const uint32_t chunks_per_tile = cb.tile_elems / CHUNK;
     const uint32_t tile_in_layer = tile - L.tile0;
     uint32_t* hist3 = cb.hist3 + (size_t)L.big * D3_BINS;
+    // layers served from the spilled candidates (or with K = 0) need no pass over g, h
+    if (S.mode == SEL_NONE || S.mode == SEL_CAND) return;
 
     for (uint32_t cc = wave; cc < chunks_per_tile; cc += 4) {
         const uint32_t chunk_in_layer = tile_in_layer * chunks_per_tile + cc;
         if (chunk_in_layer >= L.nchunks) break;
         const uint32_t chunk = L.chunk0 + chunk_in_layer;
-        if (S.mode == SEL_NONE) {
-            if (lane == 0) { cb.rec_start[chunk] = 0; cb.rec_cnt[chunk] = 0; cb.rec_amb[chunk] = 0; }
-            continue;
-        }
         const uint32_t vbase = chunk_in_layer * CHUNK;
-        Quad q[8];
+        Quad q[NQ];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) load_quad(L, vbase + u * 256u + lane * 4u, q[u]);
+        for (int u = 0; u < (int)NQ; ++u) load_quad(L, vbase + u * 256u + lane * 4u, q[u]);
 
         // flags: bit c of sel[u] = candidate, of amb[u] = ambiguous
-        uint32_t selm[8], ambm[8];
+        uint32_t selm[NQ], ambm[NQ];
         uint32_t mine = 0, mine_amb = 0;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < (int)NQ; ++u) {
             selm[u] = 0; ambm[u] = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -170,9 +165,9 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
         }
         // wave totals and the exclusive prefix of `mine` over lanes, per quad row
         uint32_t total = 0, total_amb = 0;
-        uint32_t rowbase[8];                    // candidates in earlier rows + earlier lanes of this row
+        uint32_t rowbase[NQ];                   // candidates in earlier rows + earlier lanes of this row
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < (int)NQ; ++u) {
             const uint32_t cnt = __popc(selm[u]);
             // exclusive prefix over lanes of a small integer: three ballots on its bits
             const uint64_t b0 = ballot(cnt & 1u), b1 = ballot(cnt & 2u), b2 = ballot(cnt & 4u);
@@ -198,7 +193,7 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
         if (total == 0) continue;
         const uint64_t base = S.tmp_base + start;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
+        for (int u = 0; u < (int)NQ; ++u) {
             uint32_t pos = rowbase[u];
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -215,7 +210,7 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
         }
         if (total_amb) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
+            for (int u = 0; u < (int)NQ; ++u) {
 #pragma unroll
                 for (int c = 0; c < 4; ++c) {
                     const bool a = (ambm[u] >> c) & 1u;
@@ -237,14 +232,48 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Last-digit histogram of the spilled candidates that share the threshold prefix (layers in
+// SEL_CAND mode).  One wave per chunk.
+__global__ __launch_bounds__(256) void k_hist3c(CompressBuffers cb, uint32_t nchunks_total, const uint32_t* chunk_big) {
+    const uint32_t chunk = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (chunk >= nchunks_total) return;
+    const uint32_t b = chunk_big[chunk];
+    const SelRec S = cb.sel[b];
+    if (S.mode != SEL_CAND) return;
+    const uint32_t cnt = cb.rec_cnt[chunk];
+    if (cnt == 0u) return;
+    const uint64_t base = S.tmp_base + cb.rec_start[chunk];
+    uint32_t* hist3 = cb.hist3 + (size_t)b * D3_BINS;
+    const uint32_t lane = lane_id();
+    for (uint32_t k0 = 0; k0 < cnt; k0 += 64) {
+        const uint32_t k = k0 + lane;
+        uint32_t key = 0;
+        bool a = false;
+        if (k < cnt) {
+            key = key_of(cb.tmp_x[base + k]);
+            a = (key >> D2_SHIFT) == S.prefix;
+        }
+        const uint64_t am = ballot(a);
+        if (am == 0) continue;
+        const uint32_t first_lane = (uint32_t)__ffsll((long long)am) - 1u;
+        const uint32_t k0v = __shfl(key, first_lane, 64);
+        if (ballot(a && key != k0v) == 0) {
+            if (lane == first_lane) atomicAdd(&hist3[key & (D3_BINS - 1)], (uint32_t)__popcll(am));
+        } else if (a) {
+            atomicAdd(&hist3[key & (D3_BINS - 1)], 1u);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Exact threshold key and tie quota per big layer from the last-digit histogram.
 __global__ __launch_bounds__(256) void k_resolve(CompressBuffers cb) {
     __shared__ uint32_t su[16];
     __shared__ uint32_t res[2];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
     const SelRec S = cb.sel[b];
-    if (S.mode != SEL_PREFIX) {
-        if (tid == 0) { cb.tau[b] = 0u; cb.quota[b] = 0u; }   // SEL_ALL: every key is > "-1"; handled by mode
+    if (S.mode != SEL_PREFIX && S.mode != SEL_CAND) {
+        if (tid == 0) { cb.tau[b] = 0u; cb.quota[b] = 0u; }   // SEL_ALL / SEL_NONE: decided by the mode alone
         return;
     }
     const uint32_t need = S.K - S.above;           // 1..amb entries to take from the ambiguous ones
@@ -286,9 +315,11 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
     const uint32_t lane = lane_id();
     const uint32_t b = chunk_big[chunk];
     const SelRec S = cb.sel[b];
-    const uint32_t cnt = cb.rec_cnt[chunk], amb = cb.rec_amb[chunk];
+    const uint32_t cnt = cb.rec_cnt[chunk];
     uint32_t gt = cnt, eq = 0;
-    if (S.mode == SEL_PREFIX && amb) {
+    // spilled candidates reach below the threshold and are always filtered; the classic pass wrote
+    // only entries at or above the threshold prefix, so chunks without ambiguous ones pass whole
+    if (S.mode == SEL_CAND || (S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0u)) {
         const uint32_t tau = cb.tau[b];
         const uint64_t base = S.tmp_base + cb.rec_start[chunk];
         gt = 0;
@@ -343,7 +374,7 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
     if (cnt == 0) return;
     const uint32_t li = cb.big_layer[b];
     float* h = cb.layers[li].h;
-    const bool filter = S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0;
+    const bool filter = S.mode == SEL_CAND || (S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0u);
     const uint32_t tau = cb.tau[b];
     const uint32_t allow = cb.o_allow[chunk];
     const uint64_t src = S.tmp_base + cb.rec_start[chunk];

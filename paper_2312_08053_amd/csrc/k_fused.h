@@ -1,0 +1,496 @@
+// Single-pass error profile.
+//
+// The classic profile (k_profile.h) reads g and h twice: once to find every candidate's boundary
+// bin in digit 1, once to histogram digit 2 inside those bins.  Here a sampling pre-pass over
+// ~1/16 of each layer predicts, per layer,
+//   * which digit-1 bins can hold the boundary of a "dense" candidate (K beyond the top few
+//     percent): those bins get digit-2 slots before the pass, and
+//   * a spill bin: every entry at or above it (the top few percent, sized from the budget hint)
+//     is written to the candidate buffer as (index, x, h), in index order inside each chunk.
+// One streaming pass then builds the exact digit-1 histogram, the digit-2 histograms of the
+// predicted bins and the candidate buffer.  Candidates whose boundary lies in the spilled range
+// get their digit-2 histograms from the candidate buffer (a few percent of the data), and the
+// compaction later selects from the candidates instead of reading g and h again.
+//
+// Nothing in the result depends on the prediction: a boundary that falls outside what was
+// predicted marks the layer for a recount by the classic full pass (LayerState::redo), and a
+// chosen K beyond the spilled range makes the compaction read g and h for that layer.
+//
+// Computes the same quantities as k_profile.h: the Errors matrix of the paper's Appendix C with
+// the squared-l2 error of Section 3.2.
+#pragma once
+#include "common.h"
+#include "k_profile.h"
+
+namespace kimad {
+
+constexpr uint32_t SAMPLE_GROUPS_PER_WG = 16;   // sampled chunks one sampling workgroup reads
+constexpr uint32_t FUSED_THREADS = 1024;
+constexpr uint32_t FUSED_WAVES = FUSED_THREADS / 64;
+
+__device__ __forceinline__ uint32_t hash32(uint32_t a) {
+    a ^= a >> 16; a *= 0x7feb352du; a ^= a >> 15; a *= 0x846ca68bu; a ^= a >> 16;
+    return a;
+}
+
+// Chunk of the layer read by sampled group `gidx`: one per `stride` chunks, at a hashed phase.
+__device__ __forceinline__ uint32_t sampled_chunk(uint32_t gidx, uint32_t stride) {
+    return gidx * stride + (stride > 1 ? hash32(gidx * 2654435761u + 12345u) % stride : 0u);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sampling pre-pass: digit-1 counts of the sampled chunks.
+__global__ __launch_bounds__(256) void k_sample(ProfileBuffers pb) {
+    __shared__ uint32_t hist[D1_BINS];
+    const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    for (uint32_t b = tid; b < D1_BINS; b += 256) hist[b] = 0u;
+    __syncthreads();
+    const uint32_t li = pb.swg_layer[blockIdx.x];
+    const LayerDesc L = pb.layers[li];
+    const uint32_t first = pb.swg_first[blockIdx.x];
+    for (uint32_t k = wave; k < SAMPLE_GROUPS_PER_WG; k += 4) {
+        const uint32_t chunk = sampled_chunk(first + k, L.sstride);
+        if (chunk >= L.nchunks) continue;
+        const uint32_t vbase = chunk * CHUNK;
+        Quad q[NQ];
+#pragma unroll
+        for (int u = 0; u < (int)NQ; ++u) load_quad(L, vbase + u * 256u + lane * 4u, q[u]);
+#pragma unroll
+        for (int u = 0; u < (int)NQ; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                if (q[u].key[c] != KEY_INVALID) atomicAdd(&hist[q[u].key[c] >> D1_SHIFT], 1u);
+    }
+    __syncthreads();
+    uint32_t* sh = pb.shist + (size_t)L.big * D1_BINS;
+    for (uint32_t b = tid; b < D1_BINS; b += 256) {
+        const uint32_t v = hist[b];
+        if (v) {
+            atomicAdd(&sh[b], v);
+            atomicAdd(&pb.ghist[b], (unsigned long long)v * L.sstride);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Prediction: per big layer, the spill bin and the digit-1 bins that get a slot.
+// `budget_pairs` = expected budget of the following allocation in pairs (0 = unknown).
+__global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
+                                                 unsigned long long budget_pairs) {
+    __shared__ uint32_t above[D1_BINS];        // sample entries in strictly higher bins
+    __shared__ uint32_t bitmap[D1_BINS / 32];
+    __shared__ uint32_t su[16];
+    __shared__ unsigned long long s64[16];
+    __shared__ uint32_t sh_gbin, sh_spill, sh_ns;
+    const uint32_t tid = threadIdx.x, big = blockIdx.x;
+    const uint32_t li = pb.big_layer[big];
+    const LayerDesc L = pb.layers[li];
+
+    // (1) global threshold bin: the highest bin b with (entries of all layers in bins >= b) >= 2.5 x budget
+    {
+        unsigned long long c[16], sum = 0;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { c[k] = pb.ghist[tid * 16u + k]; sum += c[k]; }
+        unsigned long long tot;
+        const unsigned long long ex = block_exclusive_scan<unsigned long long>(sum, s64, &tot);
+        unsigned long long ab = tot - ex - sum;            // entries above this thread's bins
+        const unsigned long long want = budget_pairs * 5ull / 2ull;
+        if (tid == 0) sh_gbin = 0u;                        // budget beyond everything: bin 0
+        __syncthreads();
+        if (budget_pairs && ab < want && ab + sum >= want) {
+#pragma unroll
+            for (int k = 15; k >= 0; --k) {
+                if (ab + c[k] >= want) { sh_gbin = tid * 16u + k; break; }
+                ab += c[k];
+            }
+        }
+        __syncthreads();
+    }
+    // (2) this layer's sample: suffix counts
+    uint32_t c[16], csum = 0;
+    const uint32_t* sh = pb.shist + (size_t)big * D1_BINS;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) { c[k] = sh[tid * 16u + k]; csum += c[k]; }
+    uint32_t ns_total;
+    const uint32_t cex = block_exclusive_scan<uint32_t>(csum, su, &ns_total);
+    {
+        uint32_t run = cex;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) { run += c[k]; above[tid * 16u + k] = ns_total - run; }
+    }
+    if (tid < D1_BINS / 32) bitmap[tid] = 0u;
+    __syncthreads();
+    const double scale = (double)L.n / (double)(ns_total ? ns_total : 1u);   // population per sample entry
+    // smallest bin with above[bin] < k, i.e. the bin holding the sample entry of rank k (k >= 1)
+    auto find_bin = [&](uint32_t k) {
+        uint32_t lo = 0, hi = D1_BINS - 1;
+        while (lo < hi) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (above[mid] < k) hi = mid; else lo = mid + 1;
+        }
+        return lo;
+    };
+    if (tid == 0) {
+        // Spill everything down to the global threshold bin; at least the top 2 % (the sparse upper
+        // tail would otherwise need a slot per candidate) and twice the smallest grid size (plus
+        // 3 sigma of the sample count); at most ~12 % of the layer.
+        const uint32_t K0 = Ktab[(size_t)li * J];
+        const double k0s = 2.0 * (double)K0 / scale;
+        uint32_t floor_rank = (uint32_t)fmin((double)ns_total, ceil(k0s + 3.0 * sqrt(k0s) + 2.0));
+        floor_rank = max(floor_rank, max(1u, ns_total / 50u));
+        uint32_t b = find_bin(floor_rank);
+        if (budget_pairs) b = min(b, sh_gbin);
+        const uint32_t bc = find_bin(max(1u, ns_total / 8u));      // never below the top 12.5 %
+        sh_spill = max(b, bc);
+    }
+    __syncthreads();
+    const uint32_t spill_bin = sh_spill;
+    // (3) bins that may hold the boundary of a candidate outside the spilled range
+    if (tid < J) {
+        const uint32_t K = Ktab[(size_t)li * J + tid];
+        if (K < L.n) {
+            const double ks = (double)K / scale;
+            const double sg = sqrt(fmax(0.0, ks * (1.0 - ks / (double)ns_total)));
+            const double klo = floor(ks - 5.0 * sg) - 2.0, khi = ceil(ks + 5.0 * sg) + 2.0;
+            const uint32_t rlo = (uint32_t)fmin((double)ns_total, fmax(1.0, klo));
+            const uint32_t rhi = (uint32_t)fmin((double)ns_total, fmax(1.0, khi));
+            const uint32_t btop = find_bin(rlo), bbot = khi > (double)ns_total ? 0u : find_bin(rhi);
+            // bin 0 (zeros and the tiniest denormals) never gets a slot here: its squares need the
+            // exact accumulators of the full recount
+            for (uint32_t b = max(bbot, 1u); b <= btop; ++b)
+                if (b < spill_bin) atomicOr(&bitmap[b >> 5], 1u << (b & 31));
+        }
+    }
+    __syncthreads();
+    // (4) slots for the marked bins, highest bins first, at most PRE_SLOTS
+    uint8_t* lut = pb.lut1 + (size_t)big * D1_BINS;
+    for (uint32_t b = tid; b < D1_BINS; b += 256) lut[b] = (uint8_t)NO_SLOT;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t ns = 0;
+        for (int w = (int)(D1_BINS / 32) - 1; w >= 0 && ns < PRE_SLOTS; --w) {
+            uint32_t m = bitmap[w];
+            while (m && ns < PRE_SLOTS) {
+                const uint32_t bit = 31u - (uint32_t)__clz((int)m);
+                m &= ~(1u << bit);
+                const uint32_t b = (uint32_t)w * 32u + bit;
+                lut[b] = (uint8_t)ns;
+                pb.slot_bin[(size_t)big * SLOT_STRIDE + ns] = b;
+                ++ns;
+            }
+        }
+        LayerState st;
+        st.spill_bin = spill_bin; st.nslots_d = ns; st.nslots_t = 0; st.redo = 0;
+        st.spill_cnt = 0; st.spill_valid = 0; st.pad[0] = st.pad[1] = 0;
+        pb.state[big] = st;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The streaming pass.  Persistent grid: workgroup w owns a contiguous range of chunks, walks it
+// layer by layer, and keeps that layer's histograms in LDS: 4096 digit-1 bins (u32 counts, u64
+// integer sums of squares) and up to 96 slots x 128 digit-2 bins packed as [count:20 | sum:44] of
+// (significand^2 >> 24).  Entries whose bin has a slot are counted only there.  One wave handles
+// one chunk at a time: 4 quads per lane, histogram updates from registers, then ballot-ranked
+// spilling of the entries at or above the layer's spill bin at a range reserved with one atomic.
+//
+// The packed sums drop the low 24 bits of each square: the true sum of (square >> 16) lies in
+// [256 S, 256 S + 256 count); the flush stores the midpoint and the scans widen their bounds by
+// half that interval (2^-23 relative).
+__global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint32_t chunks_per_wg) {
+    __shared__ uint32_t cnt[D1_BINS];                             // 16 KB
+    __shared__ unsigned long long sq[D1_BINS];                    // 32 KB
+    __shared__ unsigned long long pk[PRE_SLOTS * D2_BINS];        // 96 KB
+    __shared__ uint8_t lut[D1_BINS];                              // 4 KB
+    const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    const uint32_t c_begin = blockIdx.x * chunks_per_wg;
+    const uint32_t c_end = min(pb.nchunks_total, c_begin + chunks_per_wg);
+    uint32_t cur = c_begin;
+    while (cur < c_end) {
+        const uint32_t big = pb.chunk_big[cur];
+        const uint32_t li = pb.big_layer[big];
+        const LayerDesc L = pb.layers[li];
+        const LayerState st = pb.state[big];
+        const uint32_t seg_end = min(min(c_end, L.chunk0 + L.nchunks), cur + PK_MAX_CHUNKS);
+        const uint32_t nsub = st.nslots_d * D2_BINS;
+        for (uint32_t b = tid; b < D1_BINS; b += FUSED_THREADS) { cnt[b] = 0u; sq[b] = 0ull; }
+        for (uint32_t b = tid; b < nsub; b += FUSED_THREADS) pk[b] = 0ull;
+        {
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(pb.lut1 + (size_t)big * D1_BINS);
+            uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
+            for (uint32_t b = tid; b < D1_BINS / 4; b += FUSED_THREADS) dst[b] = src[b];
+        }
+        __syncthreads();
+        const uint32_t spill_key = st.spill_bin >= D1_BINS ? 0x80000000u : (st.spill_bin << D1_SHIFT);
+        const uint64_t tmp0 = L.tmp0;
+
+        for (uint32_t chunk = cur + wave; chunk < seg_end; chunk += FUSED_WAVES) {
+            const uint32_t vbase = (chunk - L.chunk0) * CHUNK;
+            Quad q[NQ];
+#pragma unroll
+            for (int u = 0; u < (int)NQ; ++u) load_quad(L, vbase + u * 256u + lane * 4u, q[u]);
+            uint32_t selm[NQ];
+#pragma unroll
+            for (int u = 0; u < (int)NQ; ++u) {
+                selm[u] = 0;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const uint32_t key = q[u].key[c];
+                    if (key == KEY_INVALID) continue;
+                    const uint32_t bin = key >> D1_SHIFT;
+                    const uint32_t slot = lut[bin];
+                    if (slot != NO_SLOT) {
+                        // slot bins are never bin 0, so the significand square is at least 2^38
+                        const uint32_t m = key & 0x7FFFFFu, e = key >> 23;
+                        const uint32_t m24 = e ? (m | 0x800000u) : m;
+                        const unsigned long long t = e == 255u ? (unsigned long long)(m != 0u)
+                                                               : ((unsigned long long)m24 * m24) >> PK_SHIFT;
+                        atomicAdd(&pk[slot * D2_BINS + ((key >> D2_SHIFT) & (D2_BINS - 1))], PK_ONE | t);
+                    } else {
+                        const unsigned long long s2 = bin ? (unsigned long long)sq_fixed(key) : sq_exact(key);
+                        atomicAdd(&cnt[bin], 1u);
+                        if (s2) atomicAdd(&sq[bin], s2);
+                    }
+                    if (key >= spill_key) selm[u] |= 1u << c;
+                }
+            }
+            uint32_t total = 0, rowbase[NQ];
+#pragma unroll
+            for (int u = 0; u < (int)NQ; ++u) {
+                const uint32_t n1 = __popc(selm[u]);
+                const uint64_t b0 = ballot(n1 & 1u), b1 = ballot(n1 & 2u), b2 = ballot(n1 & 4u);
+                rowbase[u] = total + mbcnt(b0) + 2u * mbcnt(b1) + 4u * mbcnt(b2);
+                total += (uint32_t)__popcll(b0) + 2u * (uint32_t)__popcll(b1) + 4u * (uint32_t)__popcll(b2);
+            }
+            uint32_t start = 0;
+            if (total) {
+                if (lane == 0) start = atomicAdd(&pb.cursor[big], total);
+                start = __shfl(start, 0, 64);
+            }
+            if (lane == 0) { pb.rec_start[chunk] = start; pb.rec_cnt[chunk] = total; }
+            if (total) {
+                const uint64_t base = tmp0 + start;          // start + total <= n: an entry is spilled once
+#pragma unroll
+                for (int u = 0; u < (int)NQ; ++u) {
+                    uint32_t pos = rowbase[u];
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        if (selm[u] & (1u << c)) {
+                            const uint64_t o = base + pos;
+                            pb.tmp_idx[o] = vbase + u * 256u + lane * 4u + c - L.mis;
+                            pb.tmp_x[o] = q[u].g[c] - q[u].h[c];
+                            pb.tmp_h[o] = q[u].h[c];
+                            ++pos;
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // flush this layer's share
+        uint32_t* gc1 = pb.cnt1 + (size_t)big * D1_BINS;
+        unsigned long long* gs1 = reinterpret_cast<unsigned long long*>(pb.sq1) + (size_t)big * D1_BINS;
+        uint32_t* gc2 = pb.cnt2 + (size_t)big * SLOT_STRIDE * D2_BINS;
+        unsigned long long* gs2 = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)big * SLOT_STRIDE * D2_BINS;
+        for (uint32_t b = tid; b < D1_BINS; b += FUSED_THREADS) {
+            const uint32_t v = cnt[b];
+            if (v) {
+                atomicAdd(&gc1[b], v);
+                const unsigned long long s2 = sq[b];
+                if (s2) atomicAdd(&gs1[b], s2);
+            }
+        }
+        for (uint32_t b = tid; b < nsub; b += FUSED_THREADS) {
+            const unsigned long long v = pk[b];
+            if (v) {
+                const uint32_t n1 = (uint32_t)(v >> 44);
+                const unsigned long long t = v & PK_MASK;
+                const uint32_t bin = pb.slot_bin[(size_t)big * SLOT_STRIDE + b / D2_BINS];
+                atomicAdd(&gc2[b], n1);
+                // exponent 255: t counts NaNs and is kept as it is; otherwise the midpoint in units of 2^16
+                const unsigned long long s2 = (bin >> 4) == 255u ? t : (t << 8) + ((unsigned long long)n1 << 7);
+                if (s2) atomicAdd(&gs2[b], s2);
+            }
+        }
+        __syncthreads();
+        cur = seg_end;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// After the pass: exact digit-1 histogram (slot bins contribute the totals of their digit-2
+// bins), boundary bin per candidate, and what each boundary needs:
+//   - its bin already has a slot                          -> nothing
+//   - its bin is in the spilled range                     -> a slot 96.. filled from the candidates
+//   - neither (prediction missed), or slots run out       -> redo: exact slots, full recount
+__global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J) {
+    __shared__ uint32_t cnt[D1_BINS];
+    __shared__ uint32_t above[D1_BINS];
+    __shared__ double below[D1_BINS];
+    __shared__ uint32_t su[16];
+    __shared__ double sd[16];
+    __shared__ uint32_t tbin[MAX_SLOTS];
+    __shared__ uint8_t lut[D1_BINS];
+    __shared__ uint32_t sh_redo;
+    const uint32_t tid = threadIdx.x, big = blockIdx.x;
+    const uint32_t li = pb.big_layer[big];
+    const LayerDesc L = pb.layers[li];
+    LayerState st = pb.state[big];
+    const uint32_t* gcnt = pb.cnt1 + (size_t)big * D1_BINS;
+    const uint64_t* gsq = pb.sq1 + (size_t)big * D1_BINS;
+    uint8_t* glut = pb.lut1 + (size_t)big * D1_BINS;
+    uint8_t* glutc = pb.lutc + (size_t)big * D1_BINS;
+    {
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(glut);
+        uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
+        for (uint32_t b = tid; b < D1_BINS / 4; b += 256) dst[b] = src[b];
+    }
+    if (tid == 0) sh_redo = 0u;
+    __syncthreads();
+
+    uint32_t c[16];
+    double s[16];
+    uint32_t csum = 0;
+    double ssum = 0.0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const uint32_t b = tid * 16u + k;
+        const uint32_t slot = lut[b];
+        uint32_t cc = gcnt[b];
+        unsigned long long ss = gsq[b];
+        if (slot != NO_SLOT) {
+            const uint32_t* c2 = pb.cnt2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
+            const uint64_t* s2 = pb.sq2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
+            for (uint32_t d = 0; d < D2_BINS; ++d) { cc += c2[d]; ss += s2[d]; }
+        }
+        c[k] = cc;
+        s[k] = sq_to_double(b, ss, cc);
+        csum += cc;
+        ssum += s[k];
+    }
+    uint32_t ctot;
+    const uint32_t cex = block_exclusive_scan<uint32_t>(csum, su, &ctot);
+    const double sex = block_exclusive_scan<double>(ssum, sd, nullptr);
+    {
+        uint32_t run_c = cex;
+        double run_s = sex;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            const uint32_t b = tid * 16u + k;
+            cnt[b] = c[k];
+            below[b] = run_s;
+            run_c += c[k];
+            above[b] = ctot - run_c;
+            run_s += s[k];
+        }
+    }
+    for (uint32_t b = tid; b < D1_BINS; b += 256) glutc[b] = (uint8_t)NO_SLOT;
+    __syncthreads();
+
+    const uint32_t spill_cnt = st.spill_bin >= D1_BINS ? 0u
+                             : (st.spill_bin == 0u ? ctot : above[st.spill_bin - 1u]);
+    const bool spill_valid = pb.cursor[big] == spill_cnt;
+    if (tid < J) {
+        const uint32_t K = Ktab[(size_t)li * J + tid];
+        uint32_t bin = 0xFFFFFFFFu;
+        if (K != 0u && K < L.n) {
+            uint32_t lo = 0, hi = D1_BINS - 1;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi) >> 1;
+                if (above[mid] < K) hi = mid; else lo = mid + 1;
+            }
+            bin = lo;
+            pb.tgt_r[(size_t)li * J + tid] = K - above[bin];
+            pb.tgt_above1[(size_t)li * J + tid] = above[bin];
+            pb.tgt_below[(size_t)li * J + tid] = below[bin];
+            if (lut[bin] == NO_SLOT && !(spill_valid && bin >= st.spill_bin)) atomicOr(&sh_redo, 1u);
+        }
+        tbin[tid] = bin;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        // candidates ascend in K, so equal boundary bins are adjacent
+        uint32_t nt = 0, last = 0xFFFFFFFFu;
+        bool redo = sh_redo != 0u;
+        if (!redo) {
+            for (uint32_t j = 0; j < J; ++j) {
+                const uint32_t bin = tbin[j];
+                if (bin != 0xFFFFFFFFu && lut[bin] == NO_SLOT && bin != last) { last = bin; ++nt; }
+            }
+            if (nt > SLOT_STRIDE - PRE_SLOTS) redo = true;
+        }
+        sh_redo = redo ? 1u : 0u;
+    }
+    __syncthreads();
+    const bool redo = sh_redo != 0u;
+    if (redo) {
+        // exact slots for every boundary bin; their digit-2 counts are recounted by a full pass
+        for (uint32_t b = tid; b < D1_BINS; b += 256) glut[b] = (uint8_t)NO_SLOT;
+        uint32_t* c2 = pb.cnt2 + (size_t)big * SLOT_STRIDE * D2_BINS;
+        unsigned long long* s2 = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)big * SLOT_STRIDE * D2_BINS;
+        for (uint32_t e = tid; e < PRE_SLOTS * D2_BINS; e += 256) { c2[e] = 0u; s2[e] = 0ull; }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        uint32_t nd = redo ? 0u : st.nslots_d, nt = 0, last = 0xFFFFFFFFu, last_slot = NO_SLOT;
+        for (uint32_t j = 0; j < J; ++j) {
+            const uint32_t bin = tbin[j];
+            uint32_t slot = NO_SLOT;
+            if (bin != 0xFFFFFFFFu) {
+                if (redo) {
+                    if (bin != last) {
+                        glut[bin] = (uint8_t)nd;
+                        pb.slot_bin[(size_t)big * SLOT_STRIDE + nd] = bin;
+                        last = bin; last_slot = nd; ++nd;
+                    }
+                    slot = last_slot;
+                } else if (lut[bin] != NO_SLOT) {
+                    slot = lut[bin];
+                } else {
+                    if (bin != last) {
+                        const uint32_t sl = PRE_SLOTS + nt;
+                        glutc[bin] = (uint8_t)sl;
+                        pb.slot_bin[(size_t)big * SLOT_STRIDE + sl] = bin;
+                        last = bin; last_slot = sl; ++nt;
+                    }
+                    slot = last_slot;
+                }
+            }
+            pb.tgt_slot[(size_t)li * J + j] = slot;
+        }
+        if (redo) atomicAdd(&pb.diag[3], 1u);
+        st.nslots_d = nd; st.nslots_t = nt; st.redo = redo ? 1u : 0u;
+        st.spill_cnt = spill_cnt; st.spill_valid = spill_valid ? 1u : 0u;
+        pb.state[big] = st;
+        pb.nslots[big] = nd;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Digit-2 histograms of the slots 96.. from the candidate buffer.  One wave per chunk.
+__global__ __launch_bounds__(256) void k_hist2c(ProfileBuffers pb) {
+    const uint32_t chunk = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (chunk >= pb.nchunks_total) return;
+    const uint32_t big = pb.chunk_big[chunk];
+    const LayerState st = pb.state[big];
+    if (st.redo || st.nslots_t == 0u) return;
+    const uint32_t cnt = pb.rec_cnt[chunk];
+    if (cnt == 0u) return;
+    const uint32_t li = pb.big_layer[big];
+    const uint64_t base = pb.layers[li].tmp0 + pb.rec_start[chunk];
+    const uint8_t* lutc = pb.lutc + (size_t)big * D1_BINS;
+    uint32_t* c2 = pb.cnt2 + (size_t)big * SLOT_STRIDE * D2_BINS;
+    unsigned long long* s2 = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)big * SLOT_STRIDE * D2_BINS;
+    for (uint32_t k = lane_id(); k < cnt; k += 64) {
+        const uint32_t key = key_of(pb.tmp_x[base + k]);
+        const uint32_t bin = key >> D1_SHIFT;
+        const uint32_t slot = lutc[bin];
+        if (slot == NO_SLOT) continue;
+        const uint32_t e = slot * D2_BINS + ((key >> D2_SHIFT) & (D2_BINS - 1));
+        const unsigned long long s = bin ? (unsigned long long)sq_fixed(key) : sq_exact(key);
+        atomicAdd(&c2[e], 1u);
+        if (s) atomicAdd(&s2[e], s);
+    }
+}
+
+}  // namespace kimad

@@ -22,8 +22,8 @@ struct ProfileBuffers {
     uint32_t* nslots;             // [B]
     uint32_t* slot_bin;           // [B][64]
     // pass 2
-    uint32_t* cnt2;               // [B][64][128]
-    uint64_t* sq2;                // [B][64][128]
+    uint32_t* cnt2;               // [B][SLOT_STRIDE][128]
+    uint64_t* sq2;                // [B][SLOT_STRIDE][128]
     // per target (layer-major, stride J)
     uint32_t* tgt_slot;           // slot, or NO_SLOT when K == n (nothing dropped)
     uint32_t* tgt_r;              // entries selected inside the boundary bin (1..count)
@@ -44,6 +44,21 @@ struct ProfileBuffers {
     uint32_t* pool_hist;          // [POOL_MAX][4096]
     uint32_t* tgt_unsel;          // dropped entries inside the prefix bin
     double* tgt_base;             // E without the prefix bin's share
+    // fused single-pass profile
+    LayerState* state;            // [B]
+    const uint32_t* chunk_big;    // chunk -> big index
+    uint32_t nchunks_total;
+    const uint32_t* swg_layer;    // sampling workgroup -> layer
+    const uint32_t* swg_first;    // sampling workgroup -> its first sampled group in that layer
+    uint32_t* shist;              // [B][4096] digit-1 counts of the sample
+    unsigned long long* ghist;    // [4096] sample counts of all layers, scaled by the sampling stride
+    uint8_t* lutc;                // [B][4096] digit-1 bin -> slot 64.. filled from the candidates
+    uint32_t* cursor;             // [B] candidates reserved so far
+    uint32_t* rec_start;          // per chunk: start inside the layer's candidate region
+    uint32_t* rec_cnt;            // per chunk: candidates written
+    uint32_t* tmp_idx;
+    float* tmp_x;
+    float* tmp_h;
 };
 
 constexpr uint32_t POOL_MAX = 256;
@@ -176,7 +191,7 @@ __global__ __launch_bounds__(256) void k_scan1(ProfileBuffers pb, const uint32_t
             if (bin != 0xFFFFFFFFu) {
                 if (bin != last) {
                     lut[bin] = (uint8_t)ns;
-                    pb.slot_bin[(size_t)big * MAX_SLOTS + ns] = bin;
+                    pb.slot_bin[(size_t)big * SLOT_STRIDE + ns] = bin;
                     last = bin;
                     ++ns;
                 }
@@ -185,6 +200,10 @@ __global__ __launch_bounds__(256) void k_scan1(ProfileBuffers pb, const uint32_t
             pb.tgt_slot[(size_t)li * J + j] = slot;
         }
         pb.nslots[big] = ns;
+        LayerState st;
+        st.spill_bin = D1_BINS; st.nslots_d = ns; st.nslots_t = 0; st.redo = 1;
+        st.spill_cnt = 0; st.spill_valid = 0; st.pad[0] = st.pad[1] = 0;
+        pb.state[big] = st;
     }
 }
 
@@ -198,8 +217,9 @@ __global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb) {
     const uint32_t tile = blockIdx.x;
     const uint32_t li = pb.tile_layer[tile];
     const LayerDesc L = pb.layers[li];
-    const uint32_t ns = pb.nslots[L.big];
-    if (ns == 0) return;
+    const LayerState st = pb.state[L.big];
+    const uint32_t ns = st.nslots_d;
+    if (!st.redo || ns == 0) return;
     {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(pb.lut1 + (size_t)L.big * D1_BINS);
         uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
@@ -238,8 +258,8 @@ __global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb) {
         }
     }
     __syncthreads();
-    uint32_t* cnt = pb.cnt2 + (size_t)L.big * MAX_SLOTS * D2_BINS;
-    unsigned long long* sq = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)L.big * MAX_SLOTS * D2_BINS;
+    uint32_t* cnt = pb.cnt2 + (size_t)L.big * SLOT_STRIDE * D2_BINS;
+    unsigned long long* sq = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)L.big * SLOT_STRIDE * D2_BINS;
     const uint32_t slot0 = lut[0];   // slot of bin 0, if it is a boundary bin
     for (uint32_t b = tid; b < ns * D2_BINS; b += 512) {
         const unsigned long long v = sub[b];
@@ -275,10 +295,10 @@ __device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uin
         pb.tgt_base[t] = 0.0;
         return;
     }
-    const uint32_t bin = pb.slot_bin[(size_t)big * MAX_SLOTS + slot];
+    const uint32_t bin = pb.slot_bin[(size_t)big * SLOT_STRIDE + slot];
     const uint32_t r = pb.tgt_r[t];
-    const uint32_t* cnt = pb.cnt2 + ((size_t)big * MAX_SLOTS + slot) * D2_BINS;
-    const uint64_t* sq = pb.sq2 + ((size_t)big * MAX_SLOTS + slot) * D2_BINS;
+    const uint32_t* cnt = pb.cnt2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
+    const uint64_t* sq = pb.sq2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
     // walk digit 2 from the top until r entries are covered
     uint32_t acc = 0;
     int u = (int)D2_BINS - 1;
@@ -314,6 +334,8 @@ __device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uin
     }
     const double base = pb.tgt_below[t] + below2;
     const double E = base + est;
+    // single-pass slots hold midpoints of intervals 2^-23 wide (relative): part of the bound
+    if (!pb.state[big].redo) half_gap += E * 1.2e-7;
     if (err_table) err_table[t] = E;
     pb.sel_prefix[t] = prefix;
     pb.sel_above[t] = pb.tgt_above1[t] + acc;

@@ -12,6 +12,7 @@
 #include "../../include/kimad.h"
 #include "common.h"
 #include "k_profile.h"
+#include "k_fused.h"
 #include "k_compress.h"
 #include "k_alloc.h"
 
@@ -31,17 +32,18 @@ inline uint64_t align_up(uint64_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 // Byte offsets of every array inside the workspace.
 struct Layout {
     uint32_t L = 0, J = 0, B = 0, S = 0;
-    uint32_t tile_elems = 0, ntiles = 0, nchunks = 0;
+    uint32_t tile_elems = 0, ntiles = 0, nchunks = 0, nswg = 0;
     uint64_t dp_cells = 0, tmp_cap = 0, sum_kmax = 0;
     // static tables
     uint64_t layers, ktab, tile_layer, chunk_big, big_layer, small_layer;
     // zeroed before every profile
-    uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, zero1_end;
+    uint64_t swg_layer, swg_first, state, lutc;
+    uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, shist, ghist, cursor, zero1_end;
     uint64_t pool_prefix, pool_big, pool_t0, pool_cnt, pool_hist, tgt_unsel, tgt_base;
     uint64_t lut1, nslots, slot_bin;
     uint64_t tgt_slot, tgt_r, tgt_above1, tgt_below, sel_prefix, sel_above, sel_amb;
     // compress
-    uint64_t ksel, sel, cursor, zero2_begin, hist3, zero2_end, tau, quota;
+    uint64_t ksel, sel, zero2_begin, hist3, zero2_end, tau, quota;
     uint64_t rec_start, rec_cnt, rec_amb, c_gt, c_eq, o_base, o_allow;
     uint64_t tmp_idx, tmp_x, tmp_h;
     // allocation
@@ -53,6 +55,8 @@ struct HostLayer {
     uint32_t n, mis, hvec;
     int32_t big;
     uint32_t tile0, ntiles, chunk0, nchunks;
+    uint32_t sstride, sgroups, swg0, nswg;   // sampling: stride in chunks, sampled groups, workgroups
+    uint64_t tmp0;                           // region start in the candidate buffer
 };
 
 uint32_t pick_tile_elems(uint64_t d_big) {
@@ -84,7 +88,8 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     }
     lo.B = B; lo.S = S;
     lo.tile_elems = pick_tile_elems(d_big);
-    uint64_t nt = 0, nc = 0;
+    uint64_t nt = 0, nc = 0, tmp_run = 0;
+    uint32_t nsw = 0;
     if (hl) hl->resize(L);
     int32_t bi = 0;
     for (uint32_t i = 0; i < L; ++i) {
@@ -97,9 +102,16 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
             h.tile0 = (uint32_t)nt; h.ntiles = (uint32_t)((span + lo.tile_elems - 1) / lo.tile_elems);
             h.chunk0 = (uint32_t)nc; h.nchunks = (uint32_t)((span + CHUNK - 1) / CHUNK);
             nt += h.ntiles; nc += h.nchunks;
+            // sample one chunk in every `sstride`, keeping at least ~64 sampled chunks per layer
+            h.sstride = std::max<uint32_t>(1, std::min<uint32_t>(16, h.nchunks / 64));
+            h.sgroups = (h.nchunks + h.sstride - 1) / h.sstride;
+            h.swg0 = nsw; h.nswg = (h.sgroups + SAMPLE_GROUPS_PER_WG - 1) / SAMPLE_GROUPS_PER_WG;
+            nsw += h.nswg;
+            h.tmp0 = tmp_run; tmp_run += n[i];
         }
         if (hl) (*hl)[i] = h;
     }
+    lo.nswg = nsw;
     if (nt > 0x7FFFFFFFull || nc > 0xFFFFFFFFull) return KIMAD_ERR_INVALID_ARG;
     lo.ntiles = (uint32_t)nt; lo.nchunks = (uint32_t)nc;
     lo.sum_kmax = d_all;                                  // the last grid ratio may be 1
@@ -110,7 +122,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
         uint64_t pmax = cfg.max_budget_bytes ? cfg.max_budget_bytes / pair : d_all;
         lo.dp_cells = std::min<uint64_t>(pmax, d_all) + 1;
     }
-    lo.tmp_cap = cfg.tmp_capacity_pairs ? cfg.tmp_capacity_pairs : d_big;
+    lo.tmp_cap = d_big;                                   // one region of n entries per tiled layer
 
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes); return o; };
@@ -121,13 +133,20 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.chunk_big = take(4ull * (nc ? nc : 1));
     lo.big_layer = take(4ull * (B ? B : 1));
     lo.small_layer = take(4ull * (S ? S : 1));
+    lo.swg_layer = take(4ull * (nsw ? nsw : 1));
+    lo.swg_first = take(4ull * (nsw ? nsw : 1));
+    lo.state = take(sizeof(LayerState) * (uint64_t)(B ? B : 1));
+    lo.lutc = take(1ull * B * D1_BINS);
     lo.zero1_begin = off;
     lo.cnt1 = take(4ull * B * D1_BINS);
     lo.sq1 = take(8ull * B * D1_BINS);
-    lo.cnt2 = take(4ull * B * MAX_SLOTS * D2_BINS);
-    lo.sq2 = take(8ull * B * MAX_SLOTS * D2_BINS);
+    lo.cnt2 = take(4ull * B * SLOT_STRIDE * D2_BINS);
+    lo.sq2 = take(8ull * B * SLOT_STRIDE * D2_BINS);
     lo.diag = take(16);
     lo.layer_flag = take(4ull * (B ? B : 1));
+    lo.shist = take(4ull * B * D1_BINS);
+    lo.ghist = take(8ull * D1_BINS);
+    lo.cursor = take(4ull * (B ? B : 1));
     lo.zero1_end = off;
     lo.pool_prefix = take(4ull * POOL_MAX);
     lo.pool_big = take(4ull * POOL_MAX);
@@ -138,7 +157,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.tgt_base = take(8 * LJ);
     lo.lut1 = take(1ull * B * D1_BINS);
     lo.nslots = take(4ull * (B ? B : 1));
-    lo.slot_bin = take(4ull * B * MAX_SLOTS);
+    lo.slot_bin = take(4ull * B * SLOT_STRIDE);
     lo.tgt_slot = take(4 * LJ);
     lo.tgt_r = take(4 * LJ);
     lo.tgt_above1 = take(4 * LJ);
@@ -148,7 +167,6 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.sel_amb = take(4 * LJ);
     lo.ksel = take(4ull * L);
     lo.sel = take(sizeof(SelRec) * (uint64_t)(B ? B : 1));
-    lo.cursor = take(4ull * (B ? B : 1));
     lo.zero2_begin = off;
     lo.hist3 = take(4ull * B * D3_BINS);
     lo.zero2_end = off;
@@ -197,6 +215,8 @@ struct kimad_plan {
     std::vector<uint32_t> kmax;      // K_{i,J-1}
     char* ws = nullptr;
     int device = 0;
+    uint32_t main_wgs = 256;         // persistent workgroups of the fused pass (one per compute unit)
+    uint32_t chunks_per_wg = 0;
     kimad::ProfileBuffers pb;
     kimad::CompressBuffers cb;
     // optional per-kernel timing (events recorded after every launch)
@@ -254,6 +274,26 @@ int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, doubl
     return KIMAD_OK;
 }
 
+// Single-pass profile: sample, predict, one streaming pass, candidate-fed digit-2 slots, and the
+// classic recount only for layers whose prediction missed.
+int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, hipStream_t s) {
+    const Layout& lo = p->lo;
+    const uint32_t* ktab = at<uint32_t>(p, lo.ktab);
+    int rc = zero_range(p, lo.zero1_begin, lo.zero1_end, s);
+    if (rc) return rc;
+    if (!lo.B) return KIMAD_OK;
+    KLAUNCH(p, s, "k_sample", k_sample, dim3(lo.nswg), dim3(256), p->pb);
+    KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs);
+    KLAUNCH(p, s, "k_main", k_main, dim3(p->main_wgs), dim3(FUSED_THREADS), p->pb, p->chunks_per_wg);
+    KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J);
+    KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + 3) / 4), dim3(256), p->pb);
+    KLAUNCH(p, s, "k_hist2", k_hist2, dim3(lo.ntiles), dim3(512), p->pb);          // layers marked redo only
+    KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(64), p->pb, ktab, lo.J, err_table, CERT_TOL);
+    KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(lo.ntiles), dim3(256), p->pb);
+    KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(POOL_MAX), dim3(256), p->pb, err_table);
+    return KIMAD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -297,6 +337,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     std::vector<LayerDesc> ld(L);
     std::vector<uint32_t> tile_layer(lo.ntiles ? lo.ntiles : 1), chunk_big(lo.nchunks ? lo.nchunks : 1);
     std::vector<uint32_t> big_layer(lo.B ? lo.B : 1), small_layer(lo.S ? lo.S : 1);
+    std::vector<uint32_t> swg_layer(lo.nswg ? lo.nswg : 1), swg_first(lo.nswg ? lo.nswg : 1);
     p->ktab.resize((size_t)L * J);
     p->kmax.resize(L);
     uint32_t si = 0;
@@ -312,9 +353,15 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
             for (uint32_t t = 0; t < h.ntiles; ++t) tile_layer[h.tile0 + t] = i;
             for (uint32_t c = 0; c < h.nchunks; ++c) chunk_big[h.chunk0 + c] = (uint32_t)h.big;
             d.tile0 = h.tile0; d.ntiles = h.ntiles; d.chunk0 = h.chunk0; d.nchunks = h.nchunks;
+            d.sstride = h.sstride; d.pad = 0; d.tmp0 = h.tmp0;
+            for (uint32_t w = 0; w < h.nswg; ++w) {
+                swg_layer[h.swg0 + w] = i;
+                swg_first[h.swg0 + w] = w * SAMPLE_GROUPS_PER_WG;
+            }
             big_layer[h.big] = i;
         } else {
             d.tile0 = d.ntiles = d.chunk0 = d.nchunks = 0;
+            d.sstride = 1; d.pad = 0; d.tmp0 = 0;
             small_layer[si++] = i;
         }
         for (uint32_t j = 0; j < J; ++j) p->ktab[(size_t)i * J + j] = grid_size_K(ratios[j], h.n);
@@ -328,7 +375,9 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
               up(lo.tile_layer, tile_layer.data(), 4ull * tile_layer.size()) &&
               up(lo.chunk_big, chunk_big.data(), 4ull * chunk_big.size()) &&
               up(lo.big_layer, big_layer.data(), 4ull * big_layer.size()) &&
-              up(lo.small_layer, small_layer.data(), 4ull * small_layer.size());
+              up(lo.small_layer, small_layer.data(), 4ull * small_layer.size()) &&
+              up(lo.swg_layer, swg_layer.data(), 4ull * swg_layer.size()) &&
+              up(lo.swg_first, swg_first.data(), 4ull * swg_first.size());
     ok = ok && hipStreamSynchronize(s) == hipSuccess;     // host vectors go out of scope below
     if (!ok) { delete p; return KIMAD_ERR_HIP; }
 
@@ -350,8 +399,24 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.pool_t0 = at<uint32_t>(p, lo.pool_t0); pb.pool_cnt = at<uint32_t>(p, lo.pool_cnt);
     pb.pool_hist = at<uint32_t>(p, lo.pool_hist);
     pb.tgt_unsel = at<uint32_t>(p, lo.tgt_unsel); pb.tgt_base = at<double>(p, lo.tgt_base);
-    // the pool histograms must start at zero; afterwards k_scan3p clears what it has read
-    if (hipMemsetAsync(p->ws + lo.pool_hist, 0, 4ull * POOL_MAX * D3_BINS, s) != hipSuccess ||
+    pb.state = at<LayerState>(p, lo.state);
+    pb.chunk_big = at<uint32_t>(p, lo.chunk_big); pb.nchunks_total = lo.nchunks;
+    pb.swg_layer = at<uint32_t>(p, lo.swg_layer); pb.swg_first = at<uint32_t>(p, lo.swg_first);
+    pb.shist = at<uint32_t>(p, lo.shist); pb.ghist = at<unsigned long long>(p, lo.ghist);
+    pb.lutc = at<uint8_t>(p, lo.lutc); pb.cursor = at<uint32_t>(p, lo.cursor);
+    pb.rec_start = at<uint32_t>(p, lo.rec_start); pb.rec_cnt = at<uint32_t>(p, lo.rec_cnt);
+    pb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); pb.tmp_x = at<float>(p, lo.tmp_x); pb.tmp_h = at<float>(p, lo.tmp_h);
+    {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device) != hipSuccess || cus <= 0) cus = 256;
+        p->main_wgs = (uint32_t)cus;
+        p->chunks_per_wg = (lo.nchunks + p->main_wgs - 1) / p->main_wgs;
+        if (p->chunks_per_wg == 0) p->chunks_per_wg = 1;
+    }
+    // the pool histograms must start at zero; afterwards k_scan3p clears what it has read.
+    // Layer states start as "nothing spilled, nothing cached".
+    if (hipMemsetAsync(p->ws + lo.state, 0, sizeof(LayerState) * (uint64_t)(lo.B ? lo.B : 1), s) != hipSuccess ||
+        hipMemsetAsync(p->ws + lo.pool_hist, 0, 4ull * POOL_MAX * D3_BINS, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
 
     CompressBuffers& cb = p->cb;
@@ -359,13 +424,13 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     cb.tile_elems = lo.tile_elems; cb.L = L; cb.B = lo.B; cb.J = J;
     cb.Ktab = at<uint32_t>(p, lo.ktab);
     cb.sel_prefix = pb.sel_prefix; cb.sel_above = pb.sel_above; cb.sel_amb = pb.sel_amb;
-    cb.sel = at<SelRec>(p, lo.sel); cb.cursor = at<uint32_t>(p, lo.cursor); cb.hist3 = at<uint32_t>(p, lo.hist3);
+    cb.sel = at<SelRec>(p, lo.sel); cb.cursor = pb.cursor; cb.hist3 = at<uint32_t>(p, lo.hist3);
     cb.tau = at<uint32_t>(p, lo.tau); cb.quota = at<uint32_t>(p, lo.quota);
     cb.rec_start = at<uint32_t>(p, lo.rec_start); cb.rec_cnt = at<uint32_t>(p, lo.rec_cnt);
     cb.rec_amb = at<uint32_t>(p, lo.rec_amb); cb.c_gt = at<uint32_t>(p, lo.c_gt); cb.c_eq = at<uint32_t>(p, lo.c_eq);
     cb.o_base = at<uint32_t>(p, lo.o_base); cb.o_allow = at<uint32_t>(p, lo.o_allow);
     cb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); cb.tmp_x = at<float>(p, lo.tmp_x); cb.tmp_h = at<float>(p, lo.tmp_h);
-    cb.tmp_capacity = lo.tmp_cap;
+    cb.state = pb.state;
     cb.K = nullptr; cb.offsets = nullptr; cb.idx_out = nullptr; cb.val_out = nullptr; cb.capacity_pairs = 0;
     cb.status = nullptr;
     *plan_out = p;
@@ -383,12 +448,16 @@ int kimad_plan_grid_sizes(const kimad_plan_t* plan, uint64_t* K_table_out) {
     return KIMAD_OK;
 }
 
-int kimad_profile(kimad_plan_t* p, double* err_table, void* stream) {
+int kimad_profile(kimad_plan_t* p, double* err_table, uint64_t budget_hint_bytes, void* stream) {
     if (!p || !err_table) return KIMAD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Layout& lo = p->lo;
     mark(p, s, "begin");
-    int rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s);
+    int rc;
+    if (p->cfg.flags & KIMAD_CFG_CLASSIC_PROFILE)
+        rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s);
+    else
+        rc = run_fused_profile(p, err_table, budget_hint_bytes / p->cfg.pair_bytes, s);
     if (rc) return rc;
     if (lo.S) {
         KLAUNCH(p, s, "k_small_profile", k_small_profile, dim3(lo.S), dim3(256), p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
@@ -461,11 +530,12 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
     int rc = zero_range(p, lo.zero2_begin, lo.zero2_end, s);
     if (rc) return rc;
     KLAUNCH(p, s, "k_lookup", k_lookup, dim3(1), dim3(256), cb, (int32_t)KIMAD_ERR_OFFGRID,
-                       (int32_t)KIMAD_ERR_SCRATCH_OVERFLOW, (int32_t)KIMAD_ERR_BAD_OFFSETS);
+            (int32_t)KIMAD_ERR_BAD_OFFSETS, (uint32_t)((flags & KIMAD_REUSE_PROFILE) ? 1u : 0u));
     if (lo.B) {
         const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
         const uint32_t cblocks = (lo.nchunks + 3) / 4;
         KLAUNCH(p, s, "k_compact", k_compact, dim3(lo.ntiles), dim3(256), cb);
+        KLAUNCH(p, s, "k_hist3c", k_hist3c, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
         KLAUNCH(p, s, "k_resolve", k_resolve, dim3(lo.B), dim3(256), cb);
         KLAUNCH(p, s, "k_chunk_count", k_chunk_count, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
         KLAUNCH(p, s, "k_chunk_scan", k_chunk_scan, dim3(lo.B), dim3(1024), cb);
@@ -481,7 +551,7 @@ int kimad_step(kimad_plan_t* p, uint64_t budget_bytes, double* err_table, int32_
                uint64_t* offsets_out, uint32_t* idx_out, float* val_out, uint64_t capacity_pairs, int32_t* status_out,
                void* stream) {
     if (!status_out) return KIMAD_ERR_INVALID_ARG;
-    int rc = kimad_profile(p, err_table, stream);
+    int rc = kimad_profile(p, err_table, budget_bytes, stream);
     if (rc) return rc;
     rc = kimad_allocate(p, err_table, budget_bytes, j_out, K_out, offsets_out, status_out, stream);
     if (rc) return rc;
@@ -490,10 +560,10 @@ int kimad_step(kimad_plan_t* p, uint64_t budget_bytes, double* err_table, int32_
                              status_out + 1, stream);
 }
 
-int kimad_profile_diagnostics(kimad_plan_t* p, uint32_t* out2, void* stream) {
-    if (!p || !out2) return KIMAD_ERR_INVALID_ARG;
+int kimad_profile_diagnostics(kimad_plan_t* p, uint32_t* out4, void* stream) {
+    if (!p || !out4) return KIMAD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (hipMemcpyAsync(out2, p->ws + p->lo.diag, 8, hipMemcpyDeviceToHost, s) != hipSuccess) return KIMAD_ERR_HIP;
+    if (hipMemcpyAsync(out4, p->ws + p->lo.diag, 16, hipMemcpyDeviceToHost, s) != hipSuccess) return KIMAD_ERR_HIP;
     if (hipStreamSynchronize(s) != hipSuccess) return KIMAD_ERR_HIP;
     return KIMAD_OK;
 }
@@ -536,6 +606,29 @@ int kimad_plan_get_timings(kimad_plan_t* p, char* names, uint32_t names_bytes, f
     return KIMAD_OK;
 }
 
+int kimad_plan_layer_states(kimad_plan_t* p, uint32_t* out, uint32_t max_layers, uint32_t* count_out, void* stream) {
+    if (!p || !out || !count_out) return KIMAD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const uint32_t B = std::min<uint32_t>(p->lo.B, max_layers);
+    std::vector<LayerState> st(B ? B : 1);
+    std::vector<SelRec> sel(B ? B : 1);
+    if (B) {
+        if (hipMemcpyAsync(st.data(), p->ws + p->lo.state, sizeof(LayerState) * B, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipMemcpyAsync(sel.data(), p->ws + p->lo.sel, sizeof(SelRec) * B, hipMemcpyDeviceToHost, s) != hipSuccess ||
+            hipStreamSynchronize(s) != hipSuccess) return KIMAD_ERR_HIP;
+    }
+    uint32_t b = 0;
+    for (uint32_t i = 0; i < p->lo.L && b < B; ++i) {
+        if (p->hl[i].big < 0) continue;
+        uint32_t* o = out + 8 * (size_t)b;
+        o[0] = i; o[1] = st[b].spill_bin; o[2] = st[b].nslots_d; o[3] = st[b].nslots_t;
+        o[4] = st[b].redo; o[5] = st[b].spill_cnt; o[6] = st[b].spill_valid; o[7] = sel[b].mode;
+        ++b;
+    }
+    *count_out = b;
+    return KIMAD_OK;
+}
+
 const char* kimad_strerror(int status) {
     switch (status) {
         case KIMAD_OK: return "ok";
@@ -547,7 +640,6 @@ const char* kimad_strerror(int status) {
         case KIMAD_ERR_INFEASIBLE: return "budget below the cheapest allocation";
         case KIMAD_ERR_NONFINITE: return "error table holds a non-finite entry";
         case KIMAD_ERR_OFFGRID: return "K is not one of the layer's grid sizes";
-        case KIMAD_ERR_SCRATCH_OVERFLOW: return "candidate buffer too small";
         case KIMAD_ERR_BAD_OFFSETS: return "K/offsets do not fit the payload capacity";
         default: return "unknown status";
     }

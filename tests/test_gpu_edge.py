@@ -209,6 +209,32 @@ def test_device_side_refusals_leave_h_untouched():
     gh.check_compress(work, plan, h, Kt[:, 3], off.cpu().numpy(), plan.idx, plan.val)
 
 
+def _hash32(a):
+    a &= 0xFFFFFFFF
+    a ^= a >> 16; a = (a * 0x7feb352d) & 0xFFFFFFFF
+    a ^= a >> 15; a = (a * 0x846ca68b) & 0xFFFFFFFF
+    a ^= a >> 16
+    return a
+
+
+def test_sample_that_misleads_the_prediction_is_recounted():
+    # The single-pass profile reads one 1024-entry chunk in every `stride` first.  Make exactly those
+    # chunks huge and the rest ordinary: the bins predicted for the dense candidates are all wrong,
+    # and the layer must be recounted by the full pass with the same exact results.
+    rng = np.random.default_rng(10)
+    n = 1024 * 1024
+    nchunks = n // 1024
+    stride = max(1, min(16, nchunks // 64))
+    x = rng.standard_normal(n).astype(np.float32)
+    for grp in range((nchunks + stride - 1) // stride):
+        c = grp * stride + _hash32((grp * 2654435761 + 12345) & 0xFFFFFFFF) % stride
+        if c < nchunks:
+            x[c * 1024:(c + 1) * 1024] *= 1e6
+    # 16-byte aligned start, so that chunks of the layer are chunks of the buffer
+    w = _work([x], [np.zeros(n, np.float32)], GRID, budget_frac=0.02)
+    _full_check(w, expect_redo=1)
+
+
 def test_results_are_reproducible_and_profile_is_pure():
     import torch
     work = ks.make_workload("resnet18")

@@ -13,20 +13,27 @@ from tests import gpu_harness as gh
 pytestmark = pytest.mark.gpu
 
 
-def _full_check(work, reuse=True, table_rel=1e-5):
+def _full_check(work, reuse=True, classic=False, hint=True, expect_redo=None):
+    """profile / allocate / compress_ef against the oracle.
+
+    classic: two-pass profile instead of the sampled single pass; hint: pass the budget to the
+    profile (sizes the spilled range); expect_redo: assert on the number of layers whose sampled
+    prediction missed."""
     import torch
     g, h = gh.to_device(work)
-    plan = gh.make_plan(work, g, h)
+    plan = gh.make_plan(work, g, h, cfg_flags=1 if classic else 0)
     gL, hL = gh.oracle_layers(work)
     E_ref, Kt = ko.profile(gL, hL, work.ratios)
     assert np.array_equal(plan.grid_sizes(), Kt)
 
     # profile
-    E_gpu = plan.profile().cpu().numpy().reshape(work.L, -1)
+    E_gpu = plan.profile(budget_hint_bytes=work.budget_bytes if hint else 0).cpu().numpy().reshape(work.L, -1)
     torch.cuda.synchronize()
     gh.assert_table_close(E_gpu, E_ref, Kt, work.sizes)
-    uncertified, fixed = plan.diagnostics()
-    assert uncertified == fixed, "every entry with a loose bound must have been recomputed exactly"
+    diag = plan.diagnostics()
+    assert diag["uncertified"] == diag["recomputed"], "every entry with a loose bound must be recomputed exactly"
+    if expect_redo is not None:
+        assert diag["redo_layers"] == expect_redo, diag
     assert np.array_equal(h.cpu().numpy().view(np.uint32), work.h.view(np.uint32)), "profile must not touch h"
 
     # allocation on the oracle's table: bit-exact choice
@@ -63,12 +70,24 @@ def test_mlp_set():
     _full_check(ks.make_workload("mlp"))
 
 
+def test_mlp_set_classic_two_pass_profile():
+    _full_check(ks.make_workload("mlp"), classic=True)
+
+
+def test_mlp_set_without_budget_hint():
+    _full_check(ks.make_workload("mlp"), hint=False)
+
+
 def test_mlp_set_select_from_scratch():
     _full_check(ks.make_workload("mlp"), reuse=False)
 
 
 def test_resnet18_set():
     _full_check(ks.make_workload("resnet18"))
+
+
+def test_resnet18_set_classic_two_pass_profile():
+    _full_check(ks.make_workload("resnet18"), classic=True)
 
 
 @pytest.mark.parametrize("frac", [0.001, 0.01, 0.05])
@@ -83,7 +102,26 @@ def test_resnet50_set_discretised_budget():
 def test_gpt2_reduced_set():
     # same recipe as the 124M set, two blocks and a 4096-row embedding: several tiles per layer,
     # ragged tails, small vectors next to matrices
-    _full_check(ks.make_workload("gpt2", n_layer=2, vocab=4099))
+    _full_check(ks.make_workload("gpt2", n_layer=2, vocab=4099), expect_redo=0)
+
+
+def test_budget_larger_than_hinted_falls_back_to_reading_g_and_h():
+    # the profile keeps the top few percent for a 1 % budget; the allocation then gets 30 %
+    import torch
+    work = ks.make_workload("gpt2", n_layer=1, vocab=4099)
+    g, h = gh.to_device(work)
+    plan = gh.make_plan(work, g, h, max_budget_bytes=30 * work.budget_bytes)
+    plan.profile(budget_hint_bytes=work.budget_bytes)
+    plan.allocate(30 * work.budget_bytes)
+    plan.compress_ef(reuse_profile=True)
+    torch.cuda.synchronize()
+    assert plan.status.cpu().tolist() == [0, 0]
+    E = plan.err_table.cpu().numpy().reshape(work.L, -1)
+    st, j, K, off = ko.allocate(E, plan.grid_sizes(), 30 * work.budget_bytes, 8, work.cost_units_D)
+    assert st == 0 and np.array_equal(plan.K.cpu().numpy().astype(np.uint64), K)
+    modes = [st["mode"] for st in plan.layer_states()]
+    assert 1 in modes and 3 in modes, modes          # some layers re-read g and h, others use the candidates
+    gh.check_compress(work, plan, h, K, off, plan.idx, plan.val)
 
 
 def test_gpt2_reduced_nonzero_estimator_from_scratch():
