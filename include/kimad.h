@@ -49,6 +49,7 @@ typedef enum kimad_status {
     KIMAD_ERR_INFEASIBLE = -6,          /* device status: budget below the cheapest allocation */
     KIMAD_ERR_NONFINITE = -7,           /* device status: error table holds Inf or NaN */
     KIMAD_ERR_OFFGRID = -8,             /* device status: KIMAD_REUSE_PROFILE given but K is not a grid size */
+    KIMAD_ERR_INTERNAL = -9,            /* device status: an internal capacity bound was violated (a bug) */
     KIMAD_ERR_BAD_OFFSETS = -10         /* device status: offsets/K do not fit capacity_pairs */
 } kimad_status;
 

@@ -60,7 +60,7 @@ struct LayerState {
     uint32_t nslots_t;     // slots 64.. assigned after the pass and filled from the candidates
     uint32_t redo;         // prediction missed: digit 2 is recounted by a full pass over this layer
     uint32_t spill_cnt;    // entries in the candidate region
-    uint32_t spill_valid;  // the region holds exactly the entries with bin >= spill_bin, in index order per chunk
+    uint32_t spill_valid;  // the region holds every entry with bin >= spill_bin, in index order per chunk
     uint32_t pad[2];
 };
 
@@ -151,6 +151,28 @@ __device__ __forceinline__ void load_quad(const LayerDesc& L, uint32_t v, Quad& 
             }
         }
     }
+}
+
+// Space for a wave's candidates.  Waves take blocks of SPILL_BLOCK entries (or exactly what a
+// chunk needs, if more) from the layer's cursor with one returning atomic per block, instead of
+// one per chunk: thousands of waves adding to the same address serialise.  Unused tails of blocks
+// are never referenced: chunk records delimit what is valid.
+constexpr uint32_t SPILL_BLOCK = 512;
+constexpr uint32_t REGION_SLACK = 2048;       // a layer's region holds n + REGION_SLACK entries
+struct WaveAlloc { uint32_t base, left; };
+
+__device__ __forceinline__ uint32_t wave_reserve(WaveAlloc& wa, uint32_t total, uint32_t* cursor) {
+    if (total > wa.left) {
+        const uint32_t want = total > SPILL_BLOCK ? total : SPILL_BLOCK;
+        uint32_t b = 0;
+        if (lane_id() == 0) b = atomicAdd(cursor, want);
+        wa.base = __shfl(b, 0, 64);
+        wa.left = want;
+    }
+    const uint32_t start = wa.base;
+    wa.base += total;
+    wa.left -= total;
+    return start;
 }
 
 // Block-wide exclusive scan over one value per thread (any block size that is a multiple of 64,

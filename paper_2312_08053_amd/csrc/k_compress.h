@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
             if (K == 0u) {
                 r.mode = SEL_NONE;
             } else if (K == n) {
-                r.mode = SEL_ALL; r.cap = n; r.above = n;
+                r.mode = SEL_ALL; r.cap = n + REGION_SLACK; r.above = n;
             } else {
                 int found = -1;
                 for (uint32_t j = 0; j < cb.J; ++j)
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
                     r.prefix = cb.sel_prefix[t];
                     r.above = cb.sel_above[t];
                     r.amb = cb.sel_amb[t];
-                    r.cap = n;
+                    r.cap = n + REGION_SLACK;
                     const LayerState st = cb.state[b];
                     // every entry at or above the threshold prefix already sits in the candidate buffer
                     const bool in_spill = use_candidates && st.spill_valid && st.spill_bin < D1_BINS &&
@@ -124,7 +124,7 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
 // when no fused profile preceded).  One wave per chunk; a workgroup of 4 waves walks the chunks
 // of one tile.  Each lane holds 4 quads (16 elements); positions come from ballots, so
 // the candidates of a chunk are written in index order at a range reserved with one atomic.
-__global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
+__global__ __launch_bounds__(256) void k_compact(CompressBuffers cb, int32_t err_internal) {
     const uint32_t tile = blockIdx.x;
     const uint32_t li = cb.chunk_layer[tile];
     const LayerDesc L = cb.layers[li];
@@ -135,6 +135,7 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
     uint32_t* hist3 = cb.hist3 + (size_t)L.big * D3_BINS;
     // layers served from the spilled candidates (or with K = 0) need no pass over g, h
     if (S.mode == SEL_NONE || S.mode == SEL_CAND) return;
+    WaveAlloc wa{0u, 0u};
 
     for (uint32_t cc = wave; cc < chunks_per_tile; cc += 4) {
         const uint32_t chunk_in_layer = tile_in_layer * chunks_per_tile + cc;
@@ -182,13 +183,11 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb) {
             total_amb = a;
         }
         uint32_t start = 0;
-        if (total) {
-            if (lane == 0) start = atomicAdd(&cb.cursor[L.big], total);
-            start = __shfl(start, 0, 64);
-        }
-        // Reservations never exceed the layer's cap when the cache matches the data; if the data
-        // changed since the profile, drop what does not fit instead of writing out of bounds.
+        if (total) start = wave_reserve(wa, total, &cb.cursor[L.big]);
+        // A region of n + REGION_SLACK entries holds every chunk's block; should a reservation still
+        // not fit, drop it, never write out of bounds, and report it.
         const uint32_t written = start >= S.cap ? 0u : min(total, S.cap - start);
+        if (written != total && lane == 0) atomicMin(cb.status, err_internal);
         if (lane == 0) { cb.rec_start[chunk] = start; cb.rec_cnt[chunk] = written; cb.rec_amb[chunk] = total_amb; }
         if (total == 0) continue;
         const uint64_t base = S.tmp_base + start;

@@ -223,6 +223,8 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         __syncthreads();
         const uint32_t spill_key = st.spill_bin >= D1_BINS ? 0x80000000u : (st.spill_bin << D1_SHIFT);
         const uint64_t tmp0 = L.tmp0;
+        const uint32_t region = L.n + REGION_SLACK;
+        WaveAlloc wa{0u, 0u};
 
         for (uint32_t chunk = cur + wave; chunk < seg_end; chunk += FUSED_WAVES) {
             const uint32_t vbase = (chunk - L.chunk0) * CHUNK;
@@ -264,12 +266,15 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
             }
             uint32_t start = 0;
             if (total) {
-                if (lane == 0) start = atomicAdd(&pb.cursor[big], total);
-                start = __shfl(start, 0, 64);
+                start = wave_reserve(wa, total, &pb.cursor[big]);
+                if (start + total > region) {                // cannot happen for sane spill ranges; never write past the region
+                    if (lane == 0) atomicOr(&pb.spill_over[big], 1u);
+                    total = 0;
+                }
             }
             if (lane == 0) { pb.rec_start[chunk] = start; pb.rec_cnt[chunk] = total; }
             if (total) {
-                const uint64_t base = tmp0 + start;          // start + total <= n: an entry is spilled once
+                const uint64_t base = tmp0 + start;
 #pragma unroll
                 for (int u = 0; u < (int)NQ; ++u) {
                     uint32_t pos = rowbase[u];
@@ -389,7 +394,7 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
 
     const uint32_t spill_cnt = st.spill_bin >= D1_BINS ? 0u
                              : (st.spill_bin == 0u ? ctot : above[st.spill_bin - 1u]);
-    const bool spill_valid = pb.cursor[big] == spill_cnt;
+    const bool spill_valid = pb.spill_over[big] == 0u;
     if (tid < J) {
         const uint32_t K = Ktab[(size_t)li * J + tid];
         uint32_t bin = 0xFFFFFFFFu;

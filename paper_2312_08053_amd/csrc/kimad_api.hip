@@ -38,7 +38,7 @@ struct Layout {
     uint64_t layers, ktab, tile_layer, chunk_big, big_layer, small_layer;
     // zeroed before every profile
     uint64_t swg_layer, swg_first, state, lutc;
-    uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, shist, ghist, cursor, zero1_end;
+    uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, shist, ghist, cursor, spill_over, zero1_end;
     uint64_t pool_prefix, pool_big, pool_t0, pool_cnt, pool_hist, tgt_unsel, tgt_base;
     uint64_t lut1, nslots, slot_bin;
     uint64_t tgt_slot, tgt_r, tgt_above1, tgt_below, sel_prefix, sel_above, sel_amb;
@@ -107,7 +107,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
             h.sgroups = (h.nchunks + h.sstride - 1) / h.sstride;
             h.swg0 = nsw; h.nswg = (h.sgroups + SAMPLE_GROUPS_PER_WG - 1) / SAMPLE_GROUPS_PER_WG;
             nsw += h.nswg;
-            h.tmp0 = tmp_run; tmp_run += n[i];
+            h.tmp0 = tmp_run; tmp_run += n[i] + REGION_SLACK;
         }
         if (hl) (*hl)[i] = h;
     }
@@ -122,7 +122,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
         uint64_t pmax = cfg.max_budget_bytes ? cfg.max_budget_bytes / pair : d_all;
         lo.dp_cells = std::min<uint64_t>(pmax, d_all) + 1;
     }
-    lo.tmp_cap = d_big;                                   // one region of n entries per tiled layer
+    lo.tmp_cap = tmp_run;                                 // one region of n + REGION_SLACK entries per tiled layer
 
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes); return o; };
@@ -147,6 +147,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.shist = take(4ull * B * D1_BINS);
     lo.ghist = take(8ull * D1_BINS);
     lo.cursor = take(4ull * (B ? B : 1));
+    lo.spill_over = take(4ull * (B ? B : 1));
     lo.zero1_end = off;
     lo.pool_prefix = take(4ull * POOL_MAX);
     lo.pool_big = take(4ull * POOL_MAX);
@@ -404,6 +405,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.swg_layer = at<uint32_t>(p, lo.swg_layer); pb.swg_first = at<uint32_t>(p, lo.swg_first);
     pb.shist = at<uint32_t>(p, lo.shist); pb.ghist = at<unsigned long long>(p, lo.ghist);
     pb.lutc = at<uint8_t>(p, lo.lutc); pb.cursor = at<uint32_t>(p, lo.cursor);
+    pb.spill_over = at<uint32_t>(p, lo.spill_over);
     pb.rec_start = at<uint32_t>(p, lo.rec_start); pb.rec_cnt = at<uint32_t>(p, lo.rec_cnt);
     pb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); pb.tmp_x = at<float>(p, lo.tmp_x); pb.tmp_h = at<float>(p, lo.tmp_h);
     {
@@ -534,7 +536,7 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
     if (lo.B) {
         const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
         const uint32_t cblocks = (lo.nchunks + 3) / 4;
-        KLAUNCH(p, s, "k_compact", k_compact, dim3(lo.ntiles), dim3(256), cb);
+        KLAUNCH(p, s, "k_compact", k_compact, dim3(lo.ntiles), dim3(256), cb, (int32_t)KIMAD_ERR_INTERNAL);
         KLAUNCH(p, s, "k_hist3c", k_hist3c, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
         KLAUNCH(p, s, "k_resolve", k_resolve, dim3(lo.B), dim3(256), cb);
         KLAUNCH(p, s, "k_chunk_count", k_chunk_count, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
@@ -640,6 +642,7 @@ const char* kimad_strerror(int status) {
         case KIMAD_ERR_INFEASIBLE: return "budget below the cheapest allocation";
         case KIMAD_ERR_NONFINITE: return "error table holds a non-finite entry";
         case KIMAD_ERR_OFFGRID: return "K is not one of the layer's grid sizes";
+        case KIMAD_ERR_INTERNAL: return "internal error: candidate region overflow";
         case KIMAD_ERR_BAD_OFFSETS: return "K/offsets do not fit the payload capacity";
         default: return "unknown status";
     }
