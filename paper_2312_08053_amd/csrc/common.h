@@ -153,6 +153,41 @@ __device__ __forceinline__ void load_quad(const LayerDesc& L, uint32_t v, Quad& 
     }
 }
 
+// All quads of one chunk for one wave: lane l gets positions vbase + u*256 + 4l .. +3 as raw g, h
+// values; bit 4u+c of `valid` tells whether position c of quad u lies inside the layer.  Interior
+// chunks of layers whose h shares g's alignment take straight 16-byte loads with no per-lane checks.
+struct QuadGH {
+    float g[4], h[4];
+};
+
+template <int N>
+__device__ __forceinline__ void load_chunk(const LayerDesc& L, uint32_t vbase, QuadGH (&q)[N], uint32_t& valid) {
+    const uint32_t lane = lane_id();
+    if (L.hvec && vbase >= L.mis && vbase + (uint32_t)N * 256u <= L.mis + L.n) {
+        const float4* gp = reinterpret_cast<const float4*>(L.g + (vbase - L.mis)) + lane;
+        const float4* hp = reinterpret_cast<const float4*>(L.h + (vbase - L.mis)) + lane;
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            const float4 G = gp[u * 64], H = hp[u * 64];
+            q[u].g[0] = G.x; q[u].g[1] = G.y; q[u].g[2] = G.z; q[u].g[3] = G.w;
+            q[u].h[0] = H.x; q[u].h[1] = H.y; q[u].h[2] = H.z; q[u].h[3] = H.w;
+        }
+        valid = (N >= 8) ? 0xFFFFFFFFu : ((1u << (4 * N)) - 1u);
+    } else {
+        valid = 0u;
+#pragma unroll
+        for (int u = 0; u < N; ++u) {
+            Quad t;
+            load_quad(L, vbase + u * 256u + lane * 4u, t);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                q[u].g[c] = t.g[c]; q[u].h[c] = t.h[c];
+                if (t.key[c] != KEY_INVALID) valid |= 1u << (4 * u + c);
+            }
+        }
+    }
+}
+
 // Space for a wave's candidates.  Waves take blocks of SPILL_BLOCK entries (or exactly what a
 // chunk needs, if more) from the layer's cursor with one returning atomic per block, instead of
 // one per chunk: thousands of waves adding to the same address serialise.  Unused tails of blocks

@@ -145,7 +145,9 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
     }
     __syncthreads();
     const uint32_t spill_bin = sh_spill;
-    // (3) bins that may hold the boundary of a candidate outside the spilled range
+    // (3) bins that may hold a candidate's boundary: +-5 sigma of the sample rank, every bin in between.
+    // Bin 0 (zeros and the tiniest denormals) never gets a slot here: its squares need the exact
+    // accumulators of the full recount.
     if (tid < J) {
         const uint32_t K = Ktab[(size_t)li * J + tid];
         if (K < L.n) {
@@ -155,25 +157,28 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
             const uint32_t rlo = (uint32_t)fmin((double)ns_total, fmax(1.0, klo));
             const uint32_t rhi = (uint32_t)fmin((double)ns_total, fmax(1.0, khi));
             const uint32_t btop = find_bin(rlo), bbot = khi > (double)ns_total ? 0u : find_bin(rhi);
-            // bin 0 (zeros and the tiniest denormals) never gets a slot here: its squares need the
-            // exact accumulators of the full recount
-            for (uint32_t b = max(bbot, 1u); b <= btop; ++b)
-                if (b < spill_bin) atomicOr(&bitmap[b >> 5], 1u << (b & 31));
+            // A boundary in the spilled range can also be resolved from the candidates, which is
+            // cheap only where few entries lie above it: skip the prediction for the sparse top
+            // (fewer than 64 sample entries above), where it would cost many bins.
+            const bool sparse_top = ks < 64.0 && bbot >= spill_bin;
+            if (!sparse_top)
+                for (uint32_t b = max(bbot, 1u); b <= btop; ++b) atomicOr(&bitmap[b >> 5], 1u << (b & 31));
         }
     }
     __syncthreads();
-    // (4) slots for the marked bins, highest bins first, at most PRE_SLOTS
+    // (4) slots for the marked bins, lowest bins first (they hold the most entries), at most PRE_SLOTS;
+    // what is cut off lies in the spilled range or makes the layer a redo
     uint8_t* lut = pb.lut1 + (size_t)big * D1_BINS;
     for (uint32_t b = tid; b < D1_BINS; b += 256) lut[b] = (uint8_t)NO_SLOT;
     __syncthreads();
     if (tid == 0) {
         uint32_t ns = 0;
-        for (int w = (int)(D1_BINS / 32) - 1; w >= 0 && ns < PRE_SLOTS; --w) {
+        for (uint32_t w = 0; w < D1_BINS / 32 && ns < PRE_SLOTS; ++w) {
             uint32_t m = bitmap[w];
             while (m && ns < PRE_SLOTS) {
-                const uint32_t bit = 31u - (uint32_t)__clz((int)m);
-                m &= ~(1u << bit);
-                const uint32_t b = (uint32_t)w * 32u + bit;
+                const uint32_t bit = (uint32_t)__ffs((int)m) - 1u;
+                m &= m - 1u;
+                const uint32_t b = w * 32u + bit;
                 lut[b] = (uint8_t)ns;
                 pb.slot_bin[(size_t)big * SLOT_STRIDE + ns] = b;
                 ++ns;
@@ -188,19 +193,58 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
 
 // ---------------------------------------------------------------------------------------------
 // The streaming pass.  Persistent grid: workgroup w owns a contiguous range of chunks, walks it
-// layer by layer, and keeps that layer's histograms in LDS: 4096 digit-1 bins (u32 counts, u64
-// integer sums of squares) and up to 96 slots x 128 digit-2 bins packed as [count:20 | sum:44] of
-// (significand^2 >> 24).  Entries whose bin has a slot are counted only there.  One wave handles
-// one chunk at a time: 4 quads per lane, histogram updates from registers, then ballot-ranked
-// spilling of the entries at or above the layer's spill bin at a range reserved with one atomic.
+// layer by layer, and keeps that layer's histograms in LDS as one array of packed entries
+// [count:20 | sum:44] of (significand^2 >> 24): 4096 digit-1 bins, then up to 96 slots x 128 digit-2
+// bins.  Entries whose bin has a slot are counted only there.  Bin 0 (zeros, tiniest denormals)
+// keeps exact squares in a separate accumulator.  One wave handles one chunk at a time: 4 quads per
+// lane (the next chunk's loads are issued before the current one is processed), one LDS atomic
+// per entry, then ballot-ranked spilling of the entries at or above the layer's spill bin.
 //
 // The packed sums drop the low 24 bits of each square: the true sum of (square >> 16) lies in
 // [256 S, 256 S + 256 count); the flush stores the midpoint and the scans widen their bounds by
 // half that interval (2^-23 relative).
+constexpr uint32_t PK_ENTRIES = D1_BINS + PRE_SLOTS * D2_BINS;     // 16384 entries, 128 KB
+
+__device__ __forceinline__ unsigned long long pk_term(uint32_t key) {
+    const uint32_t m = key & 0x7FFFFFu, e = key >> 23;
+    const uint32_t m24 = e ? (m | 0x800000u) : m;
+    return e == 255u ? (unsigned long long)(m != 0u) : ((unsigned long long)m24 * m24) >> PK_SHIFT;
+}
+
+struct MainCtx {
+    unsigned long long* pk;
+    unsigned long long* sq0;
+    const uint8_t* lut;
+    uint32_t spill_key;
+};
+
+// histogram updates and spill flags of one chunk
+__device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[NQ], uint32_t valid,
+                                           uint32_t (&selm)[NQ]) {
+#pragma unroll
+    for (int u = 0; u < (int)NQ; ++u) {
+        selm[u] = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (!(valid & (1u << (4 * u + c)))) continue;
+            const uint32_t key = key_of(q[u].g[c] - q[u].h[c]);
+            const uint32_t bin = key >> D1_SHIFT;
+            const uint32_t slot = cx.lut[bin];
+            const uint32_t e = slot == NO_SLOT ? bin : D1_BINS + slot * D2_BINS + ((key >> D2_SHIFT) & (D2_BINS - 1));
+            if (bin != 0u) {
+                atomicAdd(&cx.pk[e], PK_ONE | pk_term(key));
+            } else {
+                atomicAdd(&cx.pk[0], PK_ONE);
+                if (key) atomicAdd(cx.sq0, sq_exact(key));
+            }
+            if (key >= cx.spill_key) selm[u] |= 1u << c;
+        }
+    }
+}
+
 __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint32_t chunks_per_wg) {
-    __shared__ uint32_t cnt[D1_BINS];                             // 16 KB
-    __shared__ unsigned long long sq[D1_BINS];                    // 32 KB
-    __shared__ unsigned long long pk[PRE_SLOTS * D2_BINS];        // 96 KB
+    __shared__ unsigned long long pk[PK_ENTRIES];                 // 128 KB
+    __shared__ unsigned long long sq0;
     __shared__ uint8_t lut[D1_BINS];                              // 4 KB
     const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
     const uint32_t c_begin = blockIdx.x * chunks_per_wg;
@@ -212,50 +256,32 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         const LayerDesc L = pb.layers[li];
         const LayerState st = pb.state[big];
         const uint32_t seg_end = min(min(c_end, L.chunk0 + L.nchunks), cur + PK_MAX_CHUNKS);
-        const uint32_t nsub = st.nslots_d * D2_BINS;
-        for (uint32_t b = tid; b < D1_BINS; b += FUSED_THREADS) { cnt[b] = 0u; sq[b] = 0ull; }
-        for (uint32_t b = tid; b < nsub; b += FUSED_THREADS) pk[b] = 0ull;
+        const uint32_t used = D1_BINS + st.nslots_d * D2_BINS;
+        for (uint32_t b = tid; b < used; b += FUSED_THREADS) pk[b] = 0ull;
+        if (tid == 0) sq0 = 0ull;
         {
             const uint32_t* src = reinterpret_cast<const uint32_t*>(pb.lut1 + (size_t)big * D1_BINS);
             uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
             for (uint32_t b = tid; b < D1_BINS / 4; b += FUSED_THREADS) dst[b] = src[b];
         }
         __syncthreads();
-        const uint32_t spill_key = st.spill_bin >= D1_BINS ? 0x80000000u : (st.spill_bin << D1_SHIFT);
+        MainCtx cx;
+        cx.pk = pk; cx.sq0 = &sq0; cx.lut = lut;
+        cx.spill_key = st.spill_bin >= D1_BINS ? 0x80000000u : (st.spill_bin << D1_SHIFT);
         const uint64_t tmp0 = L.tmp0;
         const uint32_t region = L.n + REGION_SLACK;
         WaveAlloc wa{0u, 0u};
 
-        for (uint32_t chunk = cur + wave; chunk < seg_end; chunk += FUSED_WAVES) {
+        uint32_t chunk = cur + wave;
+        QuadGH q[NQ], qn[NQ];
+        uint32_t valid = 0, valid_n = 0;
+        if (chunk < seg_end) load_chunk<NQ>(L, (chunk - L.chunk0) * CHUNK, q, valid);
+        while (chunk < seg_end) {
+            const uint32_t next = chunk + FUSED_WAVES;
+            if (next < seg_end) load_chunk<NQ>(L, (next - L.chunk0) * CHUNK, qn, valid_n);   // in flight during the work below
             const uint32_t vbase = (chunk - L.chunk0) * CHUNK;
-            Quad q[NQ];
-#pragma unroll
-            for (int u = 0; u < (int)NQ; ++u) load_quad(L, vbase + u * 256u + lane * 4u, q[u]);
             uint32_t selm[NQ];
-#pragma unroll
-            for (int u = 0; u < (int)NQ; ++u) {
-                selm[u] = 0;
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const uint32_t key = q[u].key[c];
-                    if (key == KEY_INVALID) continue;
-                    const uint32_t bin = key >> D1_SHIFT;
-                    const uint32_t slot = lut[bin];
-                    if (slot != NO_SLOT) {
-                        // slot bins are never bin 0, so the significand square is at least 2^38
-                        const uint32_t m = key & 0x7FFFFFu, e = key >> 23;
-                        const uint32_t m24 = e ? (m | 0x800000u) : m;
-                        const unsigned long long t = e == 255u ? (unsigned long long)(m != 0u)
-                                                               : ((unsigned long long)m24 * m24) >> PK_SHIFT;
-                        atomicAdd(&pk[slot * D2_BINS + ((key >> D2_SHIFT) & (D2_BINS - 1))], PK_ONE | t);
-                    } else {
-                        const unsigned long long s2 = bin ? (unsigned long long)sq_fixed(key) : sq_exact(key);
-                        atomicAdd(&cnt[bin], 1u);
-                        if (s2) atomicAdd(&sq[bin], s2);
-                    }
-                    if (key >= spill_key) selm[u] |= 1u << c;
-                }
-            }
+            main_count(cx, q, valid, selm);
             uint32_t total = 0, rowbase[NQ];
 #pragma unroll
             for (int u = 0; u < (int)NQ; ++u) {
@@ -290,31 +316,28 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
                     }
                 }
             }
+#pragma unroll
+            for (int u = 0; u < (int)NQ; ++u) q[u] = qn[u];
+            valid = valid_n;
+            chunk = next;
         }
         __syncthreads();
-        // flush this layer's share
+        // flush this layer's share: counts as they are, sums as midpoints in units of 2^16
         uint32_t* gc1 = pb.cnt1 + (size_t)big * D1_BINS;
         unsigned long long* gs1 = reinterpret_cast<unsigned long long*>(pb.sq1) + (size_t)big * D1_BINS;
         uint32_t* gc2 = pb.cnt2 + (size_t)big * SLOT_STRIDE * D2_BINS;
         unsigned long long* gs2 = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)big * SLOT_STRIDE * D2_BINS;
-        for (uint32_t b = tid; b < D1_BINS; b += FUSED_THREADS) {
-            const uint32_t v = cnt[b];
-            if (v) {
-                atomicAdd(&gc1[b], v);
-                const unsigned long long s2 = sq[b];
-                if (s2) atomicAdd(&gs1[b], s2);
-            }
-        }
-        for (uint32_t b = tid; b < nsub; b += FUSED_THREADS) {
+        for (uint32_t b = tid; b < used; b += FUSED_THREADS) {
             const unsigned long long v = pk[b];
             if (v) {
                 const uint32_t n1 = (uint32_t)(v >> 44);
                 const unsigned long long t = v & PK_MASK;
-                const uint32_t bin = pb.slot_bin[(size_t)big * SLOT_STRIDE + b / D2_BINS];
-                atomicAdd(&gc2[b], n1);
-                // exponent 255: t counts NaNs and is kept as it is; otherwise the midpoint in units of 2^16
-                const unsigned long long s2 = (bin >> 4) == 255u ? t : (t << 8) + ((unsigned long long)n1 << 7);
-                if (s2) atomicAdd(&gs2[b], s2);
+                const uint32_t bin = b < D1_BINS ? b : pb.slot_bin[(size_t)big * SLOT_STRIDE + (b - D1_BINS) / D2_BINS];
+                // exponent 255: t counts NaNs and is kept; bin 0: exact squares from sq0
+                const unsigned long long s2 = (bin >> 4) == 255u ? t
+                                            : (b == 0u ? sq0 : (t << 8) + ((unsigned long long)n1 << 7));
+                if (b < D1_BINS) { atomicAdd(&gc1[b], n1); if (s2) atomicAdd(&gs1[b], s2); }
+                else { atomicAdd(&gc2[b - D1_BINS], n1); if (s2) atomicAdd(&gs2[b - D1_BINS], s2); }
             }
         }
         __syncthreads();
