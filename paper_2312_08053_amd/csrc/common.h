@@ -75,6 +75,22 @@ struct SelRec {
     uint32_t K;
 };
 
+// ---- global-memory accessors ----------------------------------------------------------------
+// Layer pointers come out of a table in memory, so the compiler only knows them as generic
+// ("flat") pointers; flat accesses count against the LDS counter as well and serialise with the
+// LDS atomics.  They always point to device memory: say so.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(1))) const float gc_float;
+typedef __attribute__((address_space(1))) float g_float;
+typedef __attribute__((address_space(1))) const f32x4 gc_f32x4;
+
+__device__ __forceinline__ float gload(const float* p) { return *reinterpret_cast<gc_float*>((uintptr_t)p); }
+__device__ __forceinline__ float4 gload4(const float* p) {
+    const f32x4 v = *reinterpret_cast<gc_f32x4*>((uintptr_t)p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void gstore(float* p, float v) { *reinterpret_cast<g_float*>((uintptr_t)p) = v; }
+
 // ---- small device helpers ----------------------------------------------------------------
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 
@@ -127,14 +143,14 @@ __device__ __forceinline__ void load_quad(const LayerDesc& L, uint32_t v, Quad& 
     const uint32_t lo = L.mis, hi = L.mis + L.n;
     if (v >= lo && v + 4u <= hi) {
         const uint32_t e = v - lo;
-        const float4 G = *reinterpret_cast<const float4*>(L.g + e);
+        const float4 G = gload4(L.g + e);
         q.g[0] = G.x; q.g[1] = G.y; q.g[2] = G.z; q.g[3] = G.w;
         if (L.hvec) {
-            const float4 H = *reinterpret_cast<const float4*>(L.h + e);
+            const float4 H = gload4(L.h + e);
             q.h[0] = H.x; q.h[1] = H.y; q.h[2] = H.z; q.h[3] = H.w;
         } else {
 #pragma unroll
-            for (int c = 0; c < 4; ++c) q.h[c] = L.h[e + c];
+            for (int c = 0; c < 4; ++c) q.h[c] = gload(L.h + e + c);
         }
 #pragma unroll
         for (int c = 0; c < 4; ++c) q.key[c] = key_of(q.g[c] - q.h[c]);
@@ -143,8 +159,8 @@ __device__ __forceinline__ void load_quad(const LayerDesc& L, uint32_t v, Quad& 
         for (int c = 0; c < 4; ++c) {
             const uint32_t vv = v + c;
             if (vv >= lo && vv < hi) {
-                q.g[c] = L.g[vv - lo];
-                q.h[c] = L.h[vv - lo];
+                q.g[c] = gload(L.g + (vv - lo));
+                q.h[c] = gload(L.h + (vv - lo));
                 q.key[c] = key_of(q.g[c] - q.h[c]);
             } else {
                 q.g[c] = 0.f; q.h[c] = 0.f; q.key[c] = KEY_INVALID;
@@ -164,11 +180,11 @@ template <int N>
 __device__ __forceinline__ void load_chunk(const LayerDesc& L, uint32_t vbase, QuadGH (&q)[N], uint32_t& valid) {
     const uint32_t lane = lane_id();
     if (L.hvec && vbase >= L.mis && vbase + (uint32_t)N * 256u <= L.mis + L.n) {
-        const float4* gp = reinterpret_cast<const float4*>(L.g + (vbase - L.mis)) + lane;
-        const float4* hp = reinterpret_cast<const float4*>(L.h + (vbase - L.mis)) + lane;
+        const float* gp = L.g + (vbase - L.mis) + 4u * lane;
+        const float* hp = L.h + (vbase - L.mis) + 4u * lane;
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-            const float4 G = gp[u * 64], H = hp[u * 64];
+            const float4 G = gload4(gp + u * 256), H = gload4(hp + u * 256);
             q[u].g[0] = G.x; q[u].g[1] = G.y; q[u].g[2] = G.z; q[u].g[3] = G.w;
             q[u].h[0] = H.x; q[u].h[1] = H.y; q[u].h[2] = H.z; q[u].h[3] = H.w;
         }

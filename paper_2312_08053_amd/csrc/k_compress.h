@@ -399,7 +399,7 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
             const uint64_t o = dst + pos;
             cb.idx_out[o] = idx;
             cb.val_out[o] = x;
-            h[idx] = hv + x;
+            gstore(h + idx, hv + x);
         }
         out_run += (uint32_t)__popcll(km);
     }
@@ -444,11 +444,11 @@ __global__ __launch_bounds__(256) void k_small_compress(CompressBuffers cb) {
             const uint32_t bit = __ffs(f) - 1;
             f &= f - 1;
             const uint32_t idx = w * 32 + bit;
-            const float g = L.g[idx], hv = L.h[idx];
+            const float g = gload(L.g + idx), hv = gload(L.h + idx);
             const float x = g - hv;
             cb.idx_out[off + pos] = idx;
             cb.val_out[off + pos] = x;
-            L.h[idx] = hv + x;
+            gstore(L.h + idx, hv + x);
             ++pos;
         }
     }

@@ -197,13 +197,14 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
 // [count:20 | sum:44] of (significand^2 >> 24): 4096 digit-1 bins, then up to 96 slots x 128 digit-2
 // bins.  Entries whose bin has a slot are counted only there.  Bin 0 (zeros, tiniest denormals)
 // keeps exact squares in a separate accumulator.  One wave handles one chunk at a time: 4 quads per
-// lane (the next chunk's loads are issued before the current one is processed), one LDS atomic
-// per entry, then ballot-ranked spilling of the entries at or above the layer's spill bin.
+// lane, one LDS atomic per entry, then ballot-ranked spilling of the entries at or above the layer's
+// spill bin, staged through LDS so that the candidate writes are coalesced.
 //
 // The packed sums drop the low 24 bits of each square: the true sum of (square >> 16) lies in
 // [256 S, 256 S + 256 count); the flush stores the midpoint and the scans widen their bounds by
 // half that interval (2^-23 relative).
 constexpr uint32_t PK_ENTRIES = D1_BINS + PRE_SLOTS * D2_BINS;     // 16384 entries, 128 KB
+constexpr uint32_t STAGE = 128;                                    // candidates a wave stages per round
 
 __device__ __forceinline__ unsigned long long pk_term(uint32_t key) {
     const uint32_t m = key & 0x7FFFFFu, e = key >> 23;
@@ -218,27 +219,182 @@ struct MainCtx {
     uint32_t spill_key;
 };
 
-// histogram updates and spill flags of one chunk
+// histogram updates and spill flags of one chunk.  Keys, then all 16 table look-ups, then all 16
+// atomics: written in phases so that the LDS reads are issued together and waited for once.
 __device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[NQ], uint32_t valid,
                                            uint32_t (&selm)[NQ]) {
+    uint32_t slots[NQ];                        // four table bytes per quad, packed
+#pragma unroll
+    for (int u = 0; u < (int)NQ; ++u) {
+        uint32_t p = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            p |= (uint32_t)cx.lut[key_of(q[u].g[c] - q[u].h[c]) >> D1_SHIFT] << (8 * c);
+        slots[u] = p;
+    }
 #pragma unroll
     for (int u = 0; u < (int)NQ; ++u) {
         selm[u] = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             if (!(valid & (1u << (4 * u + c)))) continue;
-            const uint32_t key = key_of(q[u].g[c] - q[u].h[c]);
-            const uint32_t bin = key >> D1_SHIFT;
-            const uint32_t slot = cx.lut[bin];
-            const uint32_t e = slot == NO_SLOT ? bin : D1_BINS + slot * D2_BINS + ((key >> D2_SHIFT) & (D2_BINS - 1));
+            const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
+            const uint32_t bin = k >> D1_SHIFT;
+            const uint32_t slot = (slots[u] >> (8 * c)) & 0xFFu;
+            const uint32_t e = slot == NO_SLOT ? bin : D1_BINS + slot * D2_BINS + ((k >> D2_SHIFT) & (D2_BINS - 1));
             if (bin != 0u) {
-                atomicAdd(&cx.pk[e], PK_ONE | pk_term(key));
+                atomicAdd(&cx.pk[e], PK_ONE | pk_term(k));
             } else {
                 atomicAdd(&cx.pk[0], PK_ONE);
-                if (key) atomicAdd(cx.sq0, sq_exact(key));
+                if (k) atomicAdd(cx.sq0, sq_exact(k));
             }
-            if (key >= cx.spill_key) selm[u] |= 1u << c;
+            if (k >= cx.spill_key) selm[u] |= 1u << c;
         }
+    }
+}
+
+// Spilling without global stores in the steady state.  A store in the loop would make every wait
+// for the next chunk's loads a wait for the store acknowledgements as well, and a returning global
+// atomic per reservation serialises thousands of waves on one address.  So:
+//   * the workgroup owns the slice of the layer's candidate region that corresponds to its chunks
+//     (one entry of space per element: it can never overflow), cut into blocks of 128 entries;
+//   * a wave takes blocks from an LDS cursor, fills its current block in an LDS window, and writes
+//     the window out with coalesced stores only when the next chunk does not fit;
+//   * chunk records wait in LDS until that flush.  A chunk's candidates are always contiguous.
+constexpr uint32_t PEND = 16;                   // chunk records a wave holds back
+
+struct WaveSpill {
+    uint32_t* win_i;      // LDS window of the current block: indices
+    float* win_x;
+    float* win_h;
+    uint32_t* pend;       // LDS: PEND x (chunk, start, count)
+    uint32_t* lds_cursor; // blocks handed out in this workgroup's slice
+    uint64_t slice0;      // first entry of the slice in the candidate buffer
+    uint32_t slice_rel;   // the same, relative to the layer's region (chunk records are region-relative)
+    uint32_t blk;         // region-relative start of the current block (valid if have_blk)
+    uint32_t fill;        // entries in the window
+    uint32_t flushed;     // of which already written
+    uint32_t npend;
+    bool have_blk;
+};
+
+__device__ __forceinline__ void wave_sync_lds() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+__device__ __forceinline__ void spill_flush(const ProfileBuffers& pb, WaveSpill& ws, uint64_t tmp0) {
+    const uint32_t lane = lane_id();
+    wave_sync_lds();
+    if (ws.have_blk) {
+        for (uint32_t k = ws.flushed + lane; k < ws.fill; k += 64) {
+            const uint64_t o = tmp0 + ws.blk + k;
+            pb.tmp_idx[o] = ws.win_i[k];
+            pb.tmp_x[o] = ws.win_x[k];
+            pb.tmp_h[o] = ws.win_h[k];
+        }
+        ws.flushed = ws.fill;
+    }
+    if (lane < ws.npend) {
+        const uint32_t chunk = ws.pend[3 * lane];
+        pb.rec_start[chunk] = ws.pend[3 * lane + 1];
+        pb.rec_cnt[chunk] = ws.pend[3 * lane + 2];
+    }
+    ws.npend = 0;
+    wave_sync_lds();
+}
+
+// take `nb` consecutive blocks of the slice; returns the region-relative entry index of the first
+__device__ __forceinline__ uint32_t spill_take_blocks(WaveSpill& ws, uint32_t nb) {
+    uint32_t b = 0;
+    if (lane_id() == 0) b = atomicAdd(ws.lds_cursor, nb);
+    b = __builtin_amdgcn_readfirstlane(b);
+    return ws.slice_rel + b * STAGE;
+}
+
+// One chunk of the streaming pass for one wave: histogram updates, ranks of the entries to spill,
+// space for them, window writes, chunk record.
+__device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainCtx& cx, const LayerDesc& L, WaveSpill& ws,
+                                           uint32_t chunk, const QuadGH (&q)[NQ], uint32_t valid) {
+    const uint32_t lane = lane_id();
+    const uint32_t vbase = (chunk - L.chunk0) * CHUNK;
+    uint32_t selm[NQ];
+    main_count(cx, q, valid, selm);
+    uint32_t total = 0, rowbase[NQ];
+#pragma unroll
+    for (int u = 0; u < (int)NQ; ++u) {
+        const uint32_t n1 = __popc(selm[u]);
+        const uint64_t b0 = ballot(n1 & 1u), b1 = ballot(n1 & 2u), b2 = ballot(n1 & 4u);
+        rowbase[u] = total + mbcnt(b0) + 2u * mbcnt(b1) + 4u * mbcnt(b2);
+        total += (uint32_t)__popcll(b0) + 2u * (uint32_t)__popcll(b1) + 4u * (uint32_t)__popcll(b2);
+    }
+    if (total == 0) return;                      // records start out as "nothing spilled"
+    if (total <= STAGE) {
+        if (!ws.have_blk || ws.fill + total > STAGE || ws.npend == PEND) {
+            spill_flush(pb, ws, L.tmp0);
+            if (!ws.have_blk || ws.fill + total > STAGE) {
+                ws.blk = spill_take_blocks(ws, 1u);
+                ws.fill = 0; ws.flushed = 0; ws.have_blk = true;
+            }
+        }
+        const uint32_t at = ws.fill;
+#pragma unroll
+        for (int u = 0; u < (int)NQ; ++u) {
+            uint32_t pos = at + rowbase[u];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if (selm[u] & (1u << c)) {
+                    ws.win_i[pos] = vbase + u * 256u + lane * 4u + c - L.mis;
+                    ws.win_x[pos] = q[u].g[c] - q[u].h[c];
+                    ws.win_h[pos] = q[u].h[c];
+                    ++pos;
+                }
+            }
+        }
+        if (lane == 0) {
+            ws.pend[3 * ws.npend] = chunk;
+            ws.pend[3 * ws.npend + 1] = ws.blk + at;
+            ws.pend[3 * ws.npend + 2] = total;
+        }
+        ws.fill += total;
+        ws.npend += 1;
+    } else {
+        // a dense chunk: its own run of blocks, written through the window in rounds
+        spill_flush(pb, ws, L.tmp0);
+        ws.have_blk = false;
+        const uint32_t start = spill_take_blocks(ws, (total + STAGE - 1) / STAGE);
+        const uint64_t base = L.tmp0 + start;
+        for (uint32_t r0 = 0; r0 < total; r0 += STAGE) {
+#pragma unroll
+            for (int u = 0; u < (int)NQ; ++u) {
+                uint32_t pos = rowbase[u];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    if (selm[u] & (1u << c)) {
+                        const uint32_t k = pos - r0;
+                        if (k < STAGE) {
+                            ws.win_i[k] = vbase + u * 256u + lane * 4u + c - L.mis;
+                            ws.win_x[k] = q[u].g[c] - q[u].h[c];
+                            ws.win_h[k] = q[u].h[c];
+                        }
+                        ++pos;
+                    }
+                }
+            }
+            wave_sync_lds();
+#pragma unroll
+            for (uint32_t k = lane; k < STAGE; k += 64) {
+                if (r0 + k < total) {
+                    const uint64_t o = base + r0 + k;
+                    pb.tmp_idx[o] = ws.win_i[k];
+                    pb.tmp_x[o] = ws.win_x[k];
+                    pb.tmp_h[o] = ws.win_h[k];
+                }
+            }
+            wave_sync_lds();
+        }
+        if (lane == 0) { pb.rec_start[chunk] = start; pb.rec_cnt[chunk] = total; }
     }
 }
 
@@ -246,7 +402,12 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
     __shared__ unsigned long long pk[PK_ENTRIES];                 // 128 KB
     __shared__ unsigned long long sq0;
     __shared__ uint8_t lut[D1_BINS];                              // 4 KB
-    const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
+    __shared__ uint32_t stage_i[FUSED_WAVES * STAGE];             // 3 x 8 KB: per-wave block windows
+    __shared__ float stage_x[FUSED_WAVES * STAGE];
+    __shared__ float stage_h[FUSED_WAVES * STAGE];
+    __shared__ uint32_t pend[FUSED_WAVES * PEND * 3];             // 3 KB
+    __shared__ uint32_t lds_cursor;
+    const uint32_t tid = threadIdx.x, wave = tid >> 6;
     const uint32_t c_begin = blockIdx.x * chunks_per_wg;
     const uint32_t c_end = min(pb.nchunks_total, c_begin + chunks_per_wg);
     uint32_t cur = c_begin;
@@ -258,7 +419,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         const uint32_t seg_end = min(min(c_end, L.chunk0 + L.nchunks), cur + PK_MAX_CHUNKS);
         const uint32_t used = D1_BINS + st.nslots_d * D2_BINS;
         for (uint32_t b = tid; b < used; b += FUSED_THREADS) pk[b] = 0ull;
-        if (tid == 0) sq0 = 0ull;
+        if (tid == 0) { sq0 = 0ull; lds_cursor = 0u; }
         {
             const uint32_t* src = reinterpret_cast<const uint32_t*>(pb.lut1 + (size_t)big * D1_BINS);
             uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
@@ -268,59 +429,19 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         MainCtx cx;
         cx.pk = pk; cx.sq0 = &sq0; cx.lut = lut;
         cx.spill_key = st.spill_bin >= D1_BINS ? 0x80000000u : (st.spill_bin << D1_SHIFT);
-        const uint64_t tmp0 = L.tmp0;
-        const uint32_t region = L.n + REGION_SLACK;
-        WaveAlloc wa{0u, 0u};
+        WaveSpill ws;
+        ws.win_i = stage_i + wave * STAGE; ws.win_x = stage_x + wave * STAGE; ws.win_h = stage_h + wave * STAGE;
+        ws.pend = pend + wave * PEND * 3; ws.lds_cursor = &lds_cursor;
+        ws.slice_rel = (cur - L.chunk0) * CHUNK; ws.slice0 = L.tmp0 + ws.slice_rel;
+        ws.blk = 0; ws.fill = 0; ws.flushed = 0; ws.npend = 0; ws.have_blk = false;
 
-        uint32_t chunk = cur + wave;
-        QuadGH q[NQ], qn[NQ];
-        uint32_t valid = 0, valid_n = 0;
-        if (chunk < seg_end) load_chunk<NQ>(L, (chunk - L.chunk0) * CHUNK, q, valid);
-        while (chunk < seg_end) {
-            const uint32_t next = chunk + FUSED_WAVES;
-            if (next < seg_end) load_chunk<NQ>(L, (next - L.chunk0) * CHUNK, qn, valid_n);   // in flight during the work below
-            const uint32_t vbase = (chunk - L.chunk0) * CHUNK;
-            uint32_t selm[NQ];
-            main_count(cx, q, valid, selm);
-            uint32_t total = 0, rowbase[NQ];
-#pragma unroll
-            for (int u = 0; u < (int)NQ; ++u) {
-                const uint32_t n1 = __popc(selm[u]);
-                const uint64_t b0 = ballot(n1 & 1u), b1 = ballot(n1 & 2u), b2 = ballot(n1 & 4u);
-                rowbase[u] = total + mbcnt(b0) + 2u * mbcnt(b1) + 4u * mbcnt(b2);
-                total += (uint32_t)__popcll(b0) + 2u * (uint32_t)__popcll(b1) + 4u * (uint32_t)__popcll(b2);
-            }
-            uint32_t start = 0;
-            if (total) {
-                start = wave_reserve(wa, total, &pb.cursor[big]);
-                if (start + total > region) {                // cannot happen for sane spill ranges; never write past the region
-                    if (lane == 0) atomicOr(&pb.spill_over[big], 1u);
-                    total = 0;
-                }
-            }
-            if (lane == 0) { pb.rec_start[chunk] = start; pb.rec_cnt[chunk] = total; }
-            if (total) {
-                const uint64_t base = tmp0 + start;
-#pragma unroll
-                for (int u = 0; u < (int)NQ; ++u) {
-                    uint32_t pos = rowbase[u];
-#pragma unroll
-                    for (int c = 0; c < 4; ++c) {
-                        if (selm[u] & (1u << c)) {
-                            const uint64_t o = base + pos;
-                            pb.tmp_idx[o] = vbase + u * 256u + lane * 4u + c - L.mis;
-                            pb.tmp_x[o] = q[u].g[c] - q[u].h[c];
-                            pb.tmp_h[o] = q[u].h[c];
-                            ++pos;
-                        }
-                    }
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < (int)NQ; ++u) q[u] = qn[u];
-            valid = valid_n;
-            chunk = next;
+        for (uint32_t chunk = cur + wave; chunk < seg_end; chunk += FUSED_WAVES) {
+            QuadGH q[NQ];
+            uint32_t valid = 0;
+            load_chunk<NQ>(L, (chunk - L.chunk0) * CHUNK, q, valid);
+            main_chunk(pb, cx, L, ws, chunk, q, valid);
         }
+        spill_flush(pb, ws, L.tmp0);
         __syncthreads();
         // flush this layer's share: counts as they are, sums as midpoints in units of 2^16
         uint32_t* gc1 = pb.cnt1 + (size_t)big * D1_BINS;

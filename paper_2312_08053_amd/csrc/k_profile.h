@@ -521,7 +521,7 @@ __device__ __forceinline__ void load_sorted_small(const LayerDesc& L, unsigned l
     for (uint32_t e = threadIdx.x; e < P; e += blockDim.x) {
         unsigned long long v = ~0ull;
         if (e < L.n) {
-            const uint32_t key = key_of(L.g[e] - L.h[e]);
+            const uint32_t key = key_of(gload(L.g + e) - gload(L.h + e));
             v = ((unsigned long long)(0x7FFFFFFFu - key) << 32) | e;
         }
         a[e] = v;

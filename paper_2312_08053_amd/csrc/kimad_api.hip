@@ -148,6 +148,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.ghist = take(8ull * D1_BINS);
     lo.cursor = take(4ull * (B ? B : 1));
     lo.spill_over = take(4ull * (B ? B : 1));
+    lo.rec_cnt = take(4ull * (nc ? nc : 1));              // chunk records start out as "nothing spilled"
     lo.zero1_end = off;
     lo.pool_prefix = take(4ull * POOL_MAX);
     lo.pool_big = take(4ull * POOL_MAX);
@@ -174,7 +175,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.tau = take(4ull * (B ? B : 1));
     lo.quota = take(4ull * (B ? B : 1));
     const uint64_t ncb = 4ull * (nc ? nc : 1);
-    lo.rec_start = take(ncb); lo.rec_cnt = take(ncb); lo.rec_amb = take(ncb);
+    lo.rec_start = take(ncb); lo.rec_amb = take(ncb);
     lo.c_gt = take(ncb); lo.c_eq = take(ncb); lo.o_base = take(ncb); lo.o_allow = take(ncb);
     lo.tmp_idx = take(4 * lo.tmp_cap); lo.tmp_x = take(4 * lo.tmp_cap); lo.tmp_h = take(4 * lo.tmp_cap);
     lo.row0 = take(8 * lo.dp_cells);
