@@ -219,18 +219,43 @@ struct MainCtx {
     uint32_t spill_key;
 };
 
-// histogram updates and spill flags of one chunk.  Keys, then all 16 table look-ups, then all 16
-// atomics: written in phases so that the LDS reads are issued together and waited for once.
+// histogram updates and spill flags of one chunk.  All 16 table look-ups first (the LDS reads are
+// issued together), then the atomics.  A chunk that lies inside the layer and holds only normal
+// numbers (no zeros, denormals, Inf, NaN) takes a branch-free path.
 __device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[NQ], uint32_t valid,
                                            uint32_t (&selm)[NQ]) {
     uint32_t slots[NQ];                        // four table bytes per quad, packed
+    uint32_t special = 0;
 #pragma unroll
     for (int u = 0; u < (int)NQ; ++u) {
         uint32_t p = 0;
 #pragma unroll
-        for (int c = 0; c < 4; ++c)
-            p |= (uint32_t)cx.lut[key_of(q[u].g[c] - q[u].h[c]) >> D1_SHIFT] << (8 * c);
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
+            p |= (uint32_t)cx.lut[k >> D1_SHIFT] << (8 * c);
+            special |= (k - 0x00800000u >= 0x7F000000u) ? 1u : 0u;     // exponent field 0 or 255
+        }
         slots[u] = p;
+    }
+    const bool plain = ballot(special != 0u || valid != (1u << (4 * NQ)) - 1u) == 0;
+    if (plain) {
+#pragma unroll
+        for (int u = 0; u < (int)NQ; ++u) {
+            uint32_t sel = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
+                const uint32_t slot = (slots[u] >> (8 * c)) & 0xFFu;
+                const uint32_t sub = D1_BINS + slot * D2_BINS + ((k >> D2_SHIFT) & (D2_BINS - 1));
+                const uint32_t e = slot == NO_SLOT ? (k >> D1_SHIFT) : sub;
+                const uint32_t m24 = (k & 0x7FFFFFu) | 0x800000u;
+                const unsigned long long t = ((unsigned long long)m24 * m24) >> PK_SHIFT;
+                atomicAdd(&cx.pk[e], PK_ONE | t);
+                sel |= (k >= cx.spill_key ? 1u : 0u) << c;
+            }
+            selm[u] = sel;
+        }
+        return;
     }
 #pragma unroll
     for (int u = 0; u < (int)NQ; ++u) {

@@ -47,7 +47,7 @@ struct Layout {
     uint64_t rec_start, rec_cnt, rec_amb, c_gt, c_eq, o_base, o_allow;
     uint64_t tmp_idx, tmp_x, tmp_h;
     // allocation
-    uint64_t row0, row1, choice, dp_flags;
+    uint64_t row0, row1, choice, dp_flags, dl_w, dl_jlo, dl_jhi, dl_n;
     uint64_t total = 0;
 };
 
@@ -182,6 +182,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.row1 = take(8 * lo.dp_cells);
     lo.choice = take((uint64_t)L * align_up(lo.dp_cells));
     lo.dp_flags = take(16);
+    lo.dl_w = take(4 * LJ); lo.dl_jlo = take(LJ); lo.dl_jhi = take(LJ); lo.dl_n = take(4ull * L);
     lo.total = off;
     return KIMAD_OK;
 }
@@ -498,7 +499,11 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     KLAUNCH(p, s, "k_dp_init", k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), ab);
     const double* last = ab.row0;
     if (cap + 1 <= DP_LDS_CELLS) {
-        KLAUNCH(p, s, "k_dp_lds", k_dp_lds, dim3(1), dim3(1024), ab);
+        DpLists dl;
+        dl.w = at<uint32_t>(p, lo.dl_w); dl.jlo = at<uint8_t>(p, lo.dl_jlo); dl.jhi = at<uint8_t>(p, lo.dl_jhi);
+        dl.n = at<uint32_t>(p, lo.dl_n);
+        KLAUNCH(p, s, "k_dp_prep", k_dp_prep, dim3(lo.L), dim3(64), ab, dl);
+        KLAUNCH(p, s, "k_dp_lds", k_dp_lds, dim3(1), dim3(1024), ab, dl);
     } else {
         double* rows[2] = {ab.row0, ab.row1};
         for (uint32_t i = 0; i < lo.L; ++i) {
