@@ -47,7 +47,7 @@ struct Layout {
     uint64_t rec_start, rec_cnt, rec_amb, c_gt, c_eq, o_base, o_allow;
     uint64_t tmp_idx, tmp_x, tmp_h;
     // allocation
-    uint64_t row0, row1, choice, dp_flags, dl_w, dl_jlo, dl_jhi, dl_n;
+    uint64_t row0, row1, choice, dp_flags, dl_w, dl_jj, dl_e, dl_n;
     uint64_t total = 0;
 };
 
@@ -182,7 +182,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.row1 = take(8 * lo.dp_cells);
     lo.choice = take((uint64_t)L * align_up(lo.dp_cells));
     lo.dp_flags = take(16);
-    lo.dl_w = take(4 * LJ); lo.dl_jlo = take(LJ); lo.dl_jhi = take(LJ); lo.dl_n = take(4ull * L);
+    lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
     lo.total = off;
     return KIMAD_OK;
 }
@@ -497,22 +497,21 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     if (rc) return rc;
     const uint32_t cell_blocks = (uint32_t)((cap + 1 + 255) / 256);
     KLAUNCH(p, s, "k_dp_init", k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), ab);
-    const double* last = ab.row0;
-    if (cap + 1 <= DP_LDS_CELLS) {
+    if (cap + 1 <= DP_ROW / 2) {
         DpLists dl;
-        dl.w = at<uint32_t>(p, lo.dl_w); dl.jlo = at<uint8_t>(p, lo.dl_jlo); dl.jhi = at<uint8_t>(p, lo.dl_jhi);
+        dl.w = at<uint32_t>(p, lo.dl_w); dl.jj = at<uint32_t>(p, lo.dl_jj); dl.e = at<double>(p, lo.dl_e);
         dl.n = at<uint32_t>(p, lo.dl_n);
         KLAUNCH(p, s, "k_dp_prep", k_dp_prep, dim3(lo.L), dim3(64), ab, dl);
-        KLAUNCH(p, s, "k_dp_lds", k_dp_lds, dim3(1), dim3(1024), ab, dl);
+        KLAUNCH(p, s, "k_dp_fused", k_dp_fused, dim3(1), dim3(1024), ab, (const uint32_t*)dl.w, (const uint32_t*)dl.jj,
+                (const double*)dl.e, (const uint32_t*)dl.n, (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
     } else {
         double* rows[2] = {ab.row0, ab.row1};
         for (uint32_t i = 0; i < lo.L; ++i) {
             KLAUNCH(p, s, "k_dp_layer", k_dp_layer, dim3(cell_blocks), dim3(256), ab, i, rows[i & 1], rows[(i + 1) & 1]);
         }
-        last = rows[lo.L & 1];
+        KLAUNCH(p, s, "k_dp_final", k_dp_final, dim3(1), dim3(1024), ab, (const double*)rows[lo.L & 1],
+                (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
     }
-    KLAUNCH(p, s, "k_dp_final", k_dp_final, dim3(1), dim3(1024), ab, last, (int32_t)KIMAD_ERR_INFEASIBLE,
-                       (int32_t)KIMAD_ERR_NONFINITE);
     return KIMAD_OK;
 }
 
