@@ -22,6 +22,7 @@ constexpr uint32_t KEY_INVALID = 0xFFFFFFFFu; // marks lanes outside the layer
 constexpr uint32_t SMALL_MAX = 8192;          // layers up to this size are sorted whole in LDS
 constexpr uint32_t CHUNK = 1024;              // elements one wave compacts at a time (4 quads per lane)
 constexpr uint32_t NQ = CHUNK / 256;          // quads per lane and chunk
+constexpr uint32_t CBLOCK = 1024;             // chunks per chunk block (one workgroup scans one block)
 constexpr uint32_t PRE_SLOTS = 96;            // digit-2 slots the single-pass profile can hold in LDS
 constexpr uint32_t SLOT_STRIDE = PRE_SLOTS + 64;  // slots per layer in the global digit-2 tables: 0..95 fixed
                                               // before a pass, 96..159 found after it (filled from candidates)
@@ -49,7 +50,7 @@ struct LayerDesc {
     uint32_t chunk0;   // first chunk of this layer in the chunk list
     uint32_t nchunks;
     uint32_t sstride;  // the sampling pre-pass reads one chunk out of every sstride
-    uint32_t pad;
+    uint32_t cblk0;    // first block of 1024 chunks of this layer in the chunk-block list
     uint64_t tmp0;     // start of this layer's region (n entries) in the candidate buffer
 };
 

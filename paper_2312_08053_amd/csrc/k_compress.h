@@ -41,6 +41,7 @@ struct CompressBuffers {
     uint32_t* c_eq;               // candidates equal to tau
     uint32_t* o_base;             // first payload slot of the chunk inside the layer
     uint32_t* o_allow;            // ties this chunk may keep
+    const uint32_t* cblk_big;     // block of 1024 chunks -> big index
     // candidate buffer
     uint32_t* tmp_idx;
     float* tmp_x;
@@ -334,29 +335,33 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Per big layer: scan its chunks in index order.  Ties are granted to the lowest indices first.
-__global__ __launch_bounds__(1024) void k_chunk_scan(CompressBuffers cb) {
+// Payload position and tie allowance of every chunk.  One workgroup per block of 1024 chunks, one
+// thread per chunk.  Ties are granted to the lowest indices first, so all chunks before this
+// block together keep min(their ties, quota) of them: the block's starting point follows from two
+// sums over the earlier chunks of the layer, which every workgroup takes for itself (no atomics,
+// no serial pass over the layer).
+__global__ __launch_bounds__(1024) void k_chunk_bases(CompressBuffers cb) {
     __shared__ uint32_t su[16];
-    const uint32_t b = blockIdx.x, tid = threadIdx.x;
+    const uint32_t blk = blockIdx.x, tid = threadIdx.x;
+    const uint32_t b = cb.cblk_big[blk];
     const uint32_t li = cb.big_layer[b];
     const LayerDesc L = cb.layers[li];
     const uint32_t quota = cb.quota[b];
-    uint32_t run_eq = 0, run_out = 0;
-    for (uint32_t c0 = 0; c0 < L.nchunks; c0 += 1024) {
-        const uint32_t c = c0 + tid;
-        const bool ok = c < L.nchunks;
-        const uint32_t gt = ok ? cb.c_gt[L.chunk0 + c] : 0u;
-        const uint32_t eq = ok ? cb.c_eq[L.chunk0 + c] : 0u;
-        uint32_t eq_tot;
-        const uint32_t eq_before = run_eq + block_exclusive_scan<uint32_t>(eq, su, &eq_tot);
-        uint32_t allow = 0;
-        if (eq_before < quota) allow = min(eq, quota - eq_before);
-        uint32_t out_tot;
-        const uint32_t ob = run_out + block_exclusive_scan<uint32_t>(gt + allow, su, &out_tot);
-        if (ok) { cb.o_base[L.chunk0 + c] = ob; cb.o_allow[L.chunk0 + c] = allow; }
-        run_eq += eq_tot;
-        run_out += out_tot;
-    }
+    const uint32_t kb = blk - L.cblk0;              // this block's number inside the layer
+    uint32_t pg = 0, pe = 0;
+    for (uint32_t c = tid; c < kb * CBLOCK; c += 1024) { pg += cb.c_gt[L.chunk0 + c]; pe += cb.c_eq[L.chunk0 + c]; }
+    uint32_t gt_before, eq_before0;
+    (void)block_exclusive_scan<uint32_t>(pg, su, &gt_before);
+    (void)block_exclusive_scan<uint32_t>(pe, su, &eq_before0);
+    const uint32_t out_before = gt_before + min(eq_before0, quota);
+    const uint32_t c = kb * CBLOCK + tid;
+    const bool ok = c < L.nchunks;
+    const uint32_t gt = ok ? cb.c_gt[L.chunk0 + c] : 0u;
+    const uint32_t eq = ok ? cb.c_eq[L.chunk0 + c] : 0u;
+    const uint32_t eq_before = eq_before0 + block_exclusive_scan<uint32_t>(eq, su, nullptr);
+    const uint32_t allow = eq_before < quota ? min(eq, quota - eq_before) : 0u;
+    const uint32_t ob = out_before + block_exclusive_scan<uint32_t>(gt + allow, su, nullptr);
+    if (ok) { cb.o_base[L.chunk0 + c] = ob; cb.o_allow[L.chunk0 + c] = allow; }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -407,7 +412,7 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
 
 // ---------------------------------------------------------------------------------------------
 // Small layers: sort in LDS, mark the first K of the order, emit in index order.
-__global__ __launch_bounds__(256) void k_small_compress(CompressBuffers cb) {
+__global__ __launch_bounds__(SMALL_THREADS) void k_small_compress(CompressBuffers cb) {
     __shared__ unsigned long long a[SMALL_MAX];
     __shared__ uint32_t flag[SMALL_MAX / 32];
     __shared__ uint32_t su[16];
@@ -424,17 +429,17 @@ __global__ __launch_bounds__(256) void k_small_compress(CompressBuffers cb) {
     const uint32_t K = (uint32_t)K64;
     const uint32_t P = next_pow2(L.n < 2 ? 2 : L.n);
     load_sorted_small(L, a, P);
-    bitonic_sort_lds<256>(a, P);
-    for (uint32_t w = tid; w < SMALL_MAX / 32; w += 256) flag[w] = 0u;
+    bitonic_sort_lds<SMALL_THREADS>(a, P);
+    for (uint32_t w = tid; w < SMALL_MAX / 32; w += SMALL_THREADS) flag[w] = 0u;
     __syncthreads();
-    for (uint32_t rk = tid; rk < K; rk += 256) {
+    for (uint32_t rk = tid; rk < K; rk += SMALL_THREADS) {
         const uint32_t idx = (uint32_t)a[rk];
         atomicOr(&flag[idx >> 5], 1u << (idx & 31));
     }
     __syncthreads();
     // emit in index order: thread t owns indices [t*per, (t+1)*per), per a multiple of 32 or the whole word range
     const uint32_t words = (L.n + 31) / 32;
-    const uint32_t wper = (words + 255) / 256;
+    const uint32_t wper = (words + SMALL_THREADS - 1) / SMALL_THREADS;
     uint32_t mine = 0;
     for (uint32_t w = tid * wper; w < min(words, (tid + 1) * wper); ++w) mine += __popc(flag[w]);
     uint32_t pos = block_exclusive_scan<uint32_t>(mine, su, nullptr);

@@ -506,6 +506,8 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
     __shared__ uint32_t tbin[MAX_SLOTS];
     __shared__ uint8_t lut[D1_BINS];
     __shared__ uint32_t sh_redo;
+    __shared__ uint32_t slot_c[PRE_SLOTS];
+    __shared__ unsigned long long slot_s[PRE_SLOTS];
     const uint32_t tid = threadIdx.x, big = blockIdx.x;
     const uint32_t li = pb.big_layer[big];
     const LayerDesc L = pb.layers[li];
@@ -522,6 +524,18 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
     if (tid == 0) sh_redo = 0u;
     __syncthreads();
 
+    // totals of the slots: one wave per slot, two digit-2 bins per lane
+    for (uint32_t slot = tid >> 6; slot < st.nslots_d; slot += 4) {
+        const uint32_t* c2 = pb.cnt2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
+        const uint64_t* s2 = pb.sq2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
+        const uint32_t l = lane_id();
+        uint32_t cc = c2[l] + c2[l + 64];
+        unsigned long long ss = s2[l] + s2[l + 64];
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) { cc += __shfl_xor(cc, d, 64); ss += __shfl_xor(ss, d, 64); }
+        if (l == 0) { slot_c[slot] = cc; slot_s[slot] = ss; }
+    }
+    __syncthreads();
     uint32_t c[16];
     double s[16];
     uint32_t csum = 0;
@@ -532,11 +546,7 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
         const uint32_t slot = lut[b];
         uint32_t cc = gcnt[b];
         unsigned long long ss = gsq[b];
-        if (slot != NO_SLOT) {
-            const uint32_t* c2 = pb.cnt2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
-            const uint64_t* s2 = pb.sq2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
-            for (uint32_t d = 0; d < D2_BINS; ++d) { cc += c2[d]; ss += s2[d]; }
-        }
+        if (slot != NO_SLOT) { cc += slot_c[slot]; ss += slot_s[slot]; }
         c[k] = cc;
         s[k] = sq_to_double(b, ss, cc);
         csum += cc;

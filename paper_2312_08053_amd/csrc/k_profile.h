@@ -529,17 +529,20 @@ __device__ __forceinline__ void load_sorted_small(const LayerDesc& L, unsigned l
     __syncthreads();
 }
 
-__global__ __launch_bounds__(256) void k_small_profile(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
-                                                       double* err_table) {
+constexpr uint32_t SMALL_THREADS = 1024;
+
+__global__ __launch_bounds__(SMALL_THREADS) void k_small_profile(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
+                                                                 double* err_table) {
     __shared__ unsigned long long a[SMALL_MAX];       // 64 KB
-    __shared__ double loc[256];
+    __shared__ double loc[SMALL_THREADS];             // per-thread sums, then exclusive suffix sums
+    __shared__ double sd[16];
     const uint32_t li = pb.small_layer[blockIdx.x];
     const LayerDesc L = pb.layers[li];
     const uint32_t P = next_pow2(L.n < 2 ? 2 : L.n);
     load_sorted_small(L, a, P);
-    bitonic_sort_lds<256>(a, P);
+    bitonic_sort_lds<SMALL_THREADS>(a, P);
     // thread t owns ranks [t*per, (t+1)*per) and sums their squares from the smallest upward
-    const uint32_t per = P / 256u ? P / 256u : 1u;
+    const uint32_t per = P / SMALL_THREADS ? P / SMALL_THREADS : 1u;
     const uint32_t tid = threadIdx.x;
     double local = 0.0;
     for (uint32_t k = per; k-- > 0;) {
@@ -552,14 +555,19 @@ __global__ __launch_bounds__(256) void k_small_profile(ProfileBuffers pb, const 
     }
     loc[tid] = local;
     __syncthreads();
+    // exclusive suffix over threads: scan the per-thread sums in reversed thread order
+    const double rv = loc[SMALL_THREADS - 1u - tid];
+    const double ex = block_exclusive_scan<double>(rv, sd, nullptr);
+    __syncthreads();
+    loc[SMALL_THREADS - 1u - tid] = ex;               // sum of the squares owned by all later threads
+    __syncthreads();
     if (tid < J) {
         const uint32_t K = Ktab[(size_t)li * J + tid];
         double E = 0.0;
         if (K < L.n) {
-            // ranks >= K are dropped: all later threads' sums (smallest first), then the tail of
-            // the thread that owns rank K
+            // ranks >= K are dropped: everything owned by later threads, then the tail of K's owner
             const uint32_t owner = K / per;
-            for (uint32_t w = 255; w > owner; --w) E += loc[w];
+            E = loc[owner];
             for (uint32_t rk = (owner + 1) * per; rk-- > K;) {
                 if (rk < L.n) {
                     const uint32_t key = 0x7FFFFFFFu - (uint32_t)(a[rk] >> 32);

@@ -32,7 +32,7 @@ inline uint64_t align_up(uint64_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 // Byte offsets of every array inside the workspace.
 struct Layout {
     uint32_t L = 0, J = 0, B = 0, S = 0;
-    uint32_t tile_elems = 0, ntiles = 0, nchunks = 0, nswg = 0;
+    uint32_t tile_elems = 0, ntiles = 0, nchunks = 0, nswg = 0, ncblk = 0;
     uint64_t dp_cells = 0, tmp_cap = 0, sum_kmax = 0;
     // static tables
     uint64_t layers, ktab, tile_layer, chunk_big, big_layer, small_layer;
@@ -43,7 +43,7 @@ struct Layout {
     uint64_t lut1, nslots, slot_bin;
     uint64_t tgt_slot, tgt_r, tgt_above1, tgt_below, sel_prefix, sel_above, sel_amb;
     // compress
-    uint64_t ksel, sel, zero2_begin, hist3, zero2_end, tau, quota;
+    uint64_t ksel, sel, zero2_begin, hist3, zero2_end, tau, quota, cblk_big;
     uint64_t rec_start, rec_cnt, rec_amb, c_gt, c_eq, o_base, o_allow;
     uint64_t tmp_idx, tmp_x, tmp_h;
     // allocation
@@ -56,6 +56,7 @@ struct HostLayer {
     int32_t big;
     uint32_t tile0, ntiles, chunk0, nchunks;
     uint32_t sstride, sgroups, swg0, nswg;   // sampling: stride in chunks, sampled groups, workgroups
+    uint32_t cblk0, ncblk;                   // blocks of 1024 chunks
     uint64_t tmp0;                           // region start in the candidate buffer
 };
 
@@ -89,7 +90,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.B = B; lo.S = S;
     lo.tile_elems = pick_tile_elems(d_big);
     uint64_t nt = 0, nc = 0, tmp_run = 0;
-    uint32_t nsw = 0;
+    uint32_t nsw = 0, ncblk = 0;
     if (hl) hl->resize(L);
     int32_t bi = 0;
     for (uint32_t i = 0; i < L; ++i) {
@@ -108,10 +109,12 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
             h.swg0 = nsw; h.nswg = (h.sgroups + SAMPLE_GROUPS_PER_WG - 1) / SAMPLE_GROUPS_PER_WG;
             nsw += h.nswg;
             h.tmp0 = tmp_run; tmp_run += n[i] + REGION_SLACK;
+            h.cblk0 = ncblk; h.ncblk = (h.nchunks + CBLOCK - 1) / CBLOCK; ncblk += h.ncblk;
         }
         if (hl) (*hl)[i] = h;
     }
     lo.nswg = nsw;
+    lo.ncblk = ncblk;
     if (nt > 0x7FFFFFFFull || nc > 0xFFFFFFFFull) return KIMAD_ERR_INVALID_ARG;
     lo.ntiles = (uint32_t)nt; lo.nchunks = (uint32_t)nc;
     lo.sum_kmax = d_all;                                  // the last grid ratio may be 1
@@ -172,6 +175,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.zero2_begin = off;
     lo.hist3 = take(4ull * B * D3_BINS);
     lo.zero2_end = off;
+    lo.cblk_big = take(4ull * (ncblk ? ncblk : 1));
     lo.tau = take(4ull * (B ? B : 1));
     lo.quota = take(4ull * (B ? B : 1));
     const uint64_t ncb = 4ull * (nc ? nc : 1);
@@ -341,6 +345,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     std::vector<uint32_t> tile_layer(lo.ntiles ? lo.ntiles : 1), chunk_big(lo.nchunks ? lo.nchunks : 1);
     std::vector<uint32_t> big_layer(lo.B ? lo.B : 1), small_layer(lo.S ? lo.S : 1);
     std::vector<uint32_t> swg_layer(lo.nswg ? lo.nswg : 1), swg_first(lo.nswg ? lo.nswg : 1);
+    std::vector<uint32_t> cblk_big(lo.ncblk ? lo.ncblk : 1);
     p->ktab.resize((size_t)L * J);
     p->kmax.resize(L);
     uint32_t si = 0;
@@ -356,7 +361,8 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
             for (uint32_t t = 0; t < h.ntiles; ++t) tile_layer[h.tile0 + t] = i;
             for (uint32_t c = 0; c < h.nchunks; ++c) chunk_big[h.chunk0 + c] = (uint32_t)h.big;
             d.tile0 = h.tile0; d.ntiles = h.ntiles; d.chunk0 = h.chunk0; d.nchunks = h.nchunks;
-            d.sstride = h.sstride; d.pad = 0; d.tmp0 = h.tmp0;
+            d.sstride = h.sstride; d.cblk0 = h.cblk0; d.tmp0 = h.tmp0;
+            for (uint32_t k = 0; k < h.ncblk; ++k) cblk_big[h.cblk0 + k] = (uint32_t)h.big;
             for (uint32_t w = 0; w < h.nswg; ++w) {
                 swg_layer[h.swg0 + w] = i;
                 swg_first[h.swg0 + w] = w * SAMPLE_GROUPS_PER_WG;
@@ -364,7 +370,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
             big_layer[h.big] = i;
         } else {
             d.tile0 = d.ntiles = d.chunk0 = d.nchunks = 0;
-            d.sstride = 1; d.pad = 0; d.tmp0 = 0;
+            d.sstride = 1; d.cblk0 = 0; d.tmp0 = 0;
             small_layer[si++] = i;
         }
         for (uint32_t j = 0; j < J; ++j) p->ktab[(size_t)i * J + j] = grid_size_K(ratios[j], h.n);
@@ -380,7 +386,8 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
               up(lo.big_layer, big_layer.data(), 4ull * big_layer.size()) &&
               up(lo.small_layer, small_layer.data(), 4ull * small_layer.size()) &&
               up(lo.swg_layer, swg_layer.data(), 4ull * swg_layer.size()) &&
-              up(lo.swg_first, swg_first.data(), 4ull * swg_first.size());
+              up(lo.swg_first, swg_first.data(), 4ull * swg_first.size()) &&
+              up(lo.cblk_big, cblk_big.data(), 4ull * cblk_big.size());
     ok = ok && hipStreamSynchronize(s) == hipSuccess;     // host vectors go out of scope below
     if (!ok) { delete p; return KIMAD_ERR_HIP; }
 
@@ -433,6 +440,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     cb.rec_start = at<uint32_t>(p, lo.rec_start); cb.rec_cnt = at<uint32_t>(p, lo.rec_cnt);
     cb.rec_amb = at<uint32_t>(p, lo.rec_amb); cb.c_gt = at<uint32_t>(p, lo.c_gt); cb.c_eq = at<uint32_t>(p, lo.c_eq);
     cb.o_base = at<uint32_t>(p, lo.o_base); cb.o_allow = at<uint32_t>(p, lo.o_allow);
+    cb.cblk_big = at<uint32_t>(p, lo.cblk_big);
     cb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); cb.tmp_x = at<float>(p, lo.tmp_x); cb.tmp_h = at<float>(p, lo.tmp_h);
     cb.state = pb.state;
     cb.K = nullptr; cb.offsets = nullptr; cb.idx_out = nullptr; cb.val_out = nullptr; cb.capacity_pairs = 0;
@@ -464,7 +472,7 @@ int kimad_profile(kimad_plan_t* p, double* err_table, uint64_t budget_hint_bytes
         rc = run_fused_profile(p, err_table, budget_hint_bytes / p->cfg.pair_bytes, s);
     if (rc) return rc;
     if (lo.S) {
-        KLAUNCH(p, s, "k_small_profile", k_small_profile, dim3(lo.S), dim3(256), p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
+        KLAUNCH(p, s, "k_small_profile", k_small_profile, dim3(lo.S), dim3(SMALL_THREADS), p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
     }
     return KIMAD_OK;
 }
@@ -545,11 +553,11 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
         KLAUNCH(p, s, "k_hist3c", k_hist3c, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
         KLAUNCH(p, s, "k_resolve", k_resolve, dim3(lo.B), dim3(256), cb);
         KLAUNCH(p, s, "k_chunk_count", k_chunk_count, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
-        KLAUNCH(p, s, "k_chunk_scan", k_chunk_scan, dim3(lo.B), dim3(1024), cb);
+        KLAUNCH(p, s, "k_chunk_bases", k_chunk_bases, dim3(lo.ncblk), dim3(1024), cb);
         KLAUNCH(p, s, "k_finalize", k_finalize, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
     }
     if (lo.S) {
-        KLAUNCH(p, s, "k_small_compress", k_small_compress, dim3(lo.S), dim3(256), cb);
+        KLAUNCH(p, s, "k_small_compress", k_small_compress, dim3(lo.S), dim3(SMALL_THREADS), cb);
     }
     return KIMAD_OK;
 }
