@@ -227,6 +227,29 @@ __device__ __forceinline__ uint32_t wave_reserve(WaveAlloc& wa, uint32_t total, 
     return start;
 }
 
+// Kernels that walk the candidates of chunks give 16 lanes to a chunk (a chunk holds ~20 candidates at
+// a 2 % spill), four chunks to a wave.  Ballots are wave-wide; these helpers cut out a group's part.
+constexpr uint32_t SUB = 16;                  // lanes per chunk
+constexpr uint32_t CHUNKS_PER_WG = 256 / SUB; // chunks a 256-thread workgroup handles
+struct SubGroup {
+    uint32_t sub;   // lane inside the group
+    uint32_t shift; // first lane of the group
+};
+__device__ __forceinline__ SubGroup sub_group() {
+    SubGroup g;
+    g.sub = threadIdx.x & (SUB - 1);
+    g.shift = (threadIdx.x & 63u) & ~(SUB - 1);
+    return g;
+}
+__device__ __forceinline__ uint32_t ballot_sub(const SubGroup& g, bool p) { return (uint32_t)(ballot(p) >> g.shift) & 0xFFFFu; }
+__device__ __forceinline__ uint32_t rank_sub(const SubGroup& g, uint32_t m) { return __popc(m & ((1u << g.sub) - 1u)); }
+// largest value over the groups of the wave (loop bounds must be wave-uniform)
+__device__ __forceinline__ uint32_t wave_max_over_groups(uint32_t v) {
+    v = max(v, (uint32_t)__shfl_xor(v, 16, 64));
+    v = max(v, (uint32_t)__shfl_xor(v, 32, 64));
+    return v;
+}
+
 // Block-wide exclusive scan over one value per thread (any block size that is a multiple of 64,
 // up to 1024).  `scratch` needs 16 entries.  Returns the exclusive prefix; *total gets the sum.
 template <typename T>

@@ -233,32 +233,40 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb, int32_t err
 
 // ---------------------------------------------------------------------------------------------
 // Last-digit histogram of the spilled candidates that share the threshold prefix (layers in
-// SEL_CAND mode).  One wave per chunk.
+// SEL_CAND mode).  Sixteen lanes per chunk.
 __global__ __launch_bounds__(256) void k_hist3c(CompressBuffers cb, uint32_t nchunks_total, const uint32_t* chunk_big) {
-    const uint32_t chunk = blockIdx.x * 4u + (threadIdx.x >> 6);
-    if (chunk >= nchunks_total) return;
-    const uint32_t b = chunk_big[chunk];
-    const SelRec S = cb.sel[b];
-    if (S.mode != SEL_CAND) return;
-    const uint32_t cnt = cb.rec_cnt[chunk];
-    if (cnt == 0u) return;
-    const uint64_t base = S.tmp_base + cb.rec_start[chunk];
-    uint32_t* hist3 = cb.hist3 + (size_t)b * D3_BINS;
-    const uint32_t lane = lane_id();
-    for (uint32_t k0 = 0; k0 < cnt; k0 += 64) {
-        const uint32_t k = k0 + lane;
+    const SubGroup g = sub_group();
+    const uint32_t chunk = blockIdx.x * CHUNKS_PER_WG + threadIdx.x / SUB;
+    uint32_t cnt = 0, prefix = 0;
+    uint64_t base = 0;
+    uint32_t* hist3 = cb.hist3;
+    if (chunk < nchunks_total) {
+        const uint32_t b = chunk_big[chunk];
+        const SelRec S = cb.sel[b];
+        if (S.mode == SEL_CAND) {
+            cnt = cb.rec_cnt[chunk];
+            base = S.tmp_base + cb.rec_start[chunk];
+            prefix = S.prefix;
+            hist3 = cb.hist3 + (size_t)b * D3_BINS;
+        }
+    }
+    const uint32_t cmax = wave_max_over_groups(cnt);
+    for (uint32_t k0 = 0; k0 < cmax; k0 += SUB) {
+        const uint32_t k = k0 + g.sub;
         uint32_t key = 0;
         bool a = false;
         if (k < cnt) {
             key = key_of(cb.tmp_x[base + k]);
-            a = (key >> D2_SHIFT) == S.prefix;
+            a = (key >> D2_SHIFT) == prefix;
         }
-        const uint64_t am = ballot(a);
+        const uint32_t am = ballot_sub(g, a);
         if (am == 0) continue;
-        const uint32_t first_lane = (uint32_t)__ffsll((long long)am) - 1u;
-        const uint32_t k0v = __shfl(key, first_lane, 64);
-        if (ballot(a && key != k0v) == 0) {
-            if (lane == first_lane) atomicAdd(&hist3[key & (D3_BINS - 1)], (uint32_t)__popcll(am));
+        // one atomic per group when all its matching lanes hold the same key (zeros, constants)
+        const uint32_t first = (uint32_t)__ffs((int)am) - 1u;
+        const uint32_t k0v = __shfl(key, g.shift + first, 64);
+        const bool uniform = ballot_sub(g, a && key != k0v) == 0;
+        if (uniform) {
+            if (g.sub == first) atomicAdd(&hist3[key & (D3_BINS - 1)], (uint32_t)__popc(am));
         } else if (a) {
             atomicAdd(&hist3[key & (D3_BINS - 1)], 1u);
         }
@@ -307,31 +315,36 @@ __global__ __launch_bounds__(256) void k_resolve(CompressBuffers cb) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Per chunk: how many candidates lie above tau and how many equal it.  One wave per chunk.
+// Per chunk: how many candidates lie above tau and how many equal it.  Sixteen lanes per chunk.
 __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_t nchunks_total,
                                                      const uint32_t* chunk_big) {
-    const uint32_t chunk = blockIdx.x * 4u + (threadIdx.x >> 6);
-    if (chunk >= nchunks_total) return;
-    const uint32_t lane = lane_id();
-    const uint32_t b = chunk_big[chunk];
-    const SelRec S = cb.sel[b];
-    const uint32_t cnt = cb.rec_cnt[chunk];
-    uint32_t gt = cnt, eq = 0;
-    // spilled candidates reach below the threshold and are always filtered; the classic pass wrote
-    // only entries at or above the threshold prefix, so chunks without ambiguous ones pass whole
-    if (S.mode == SEL_CAND || (S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0u)) {
-        const uint32_t tau = cb.tau[b];
-        const uint64_t base = S.tmp_base + cb.rec_start[chunk];
-        gt = 0;
-        for (uint32_t k = lane; k < cnt; k += 64) {
-            const uint32_t key = key_of(cb.tmp_x[base + k]);
-            gt += key > tau;
-            eq += key == tau;
+    const SubGroup g = sub_group();
+    const uint32_t chunk = blockIdx.x * CHUNKS_PER_WG + threadIdx.x / SUB;
+    const bool live = chunk < nchunks_total;
+    uint32_t cnt = 0, tau = 0, total = 0;
+    uint64_t base = 0;
+    if (live) {
+        const uint32_t b = chunk_big[chunk];
+        const SelRec S = cb.sel[b];
+        total = cb.rec_cnt[chunk];
+        // spilled candidates reach below the threshold and are always filtered; the classic pass wrote
+        // only entries at or above the threshold prefix, so chunks without ambiguous ones pass whole
+        if (S.mode == SEL_CAND || (S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0u)) {
+            cnt = total;
+            tau = cb.tau[b];
+            base = S.tmp_base + cb.rec_start[chunk];
         }
-#pragma unroll
-        for (int d = 32; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
     }
-    if (lane == 0) { cb.c_gt[chunk] = gt; cb.c_eq[chunk] = eq; }
+    uint32_t gt = 0, eq = 0;
+    for (uint32_t k = g.sub; k < cnt; k += SUB) {
+        const uint32_t key = key_of(cb.tmp_x[base + k]);
+        gt += key > tau;
+        eq += key == tau;
+    }
+#pragma unroll
+    for (int d = SUB / 2; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
+    if (cnt == 0) { gt = total; eq = 0; }
+    if (live && g.sub == 0) { cb.c_gt[chunk] = gt; cb.c_eq[chunk] = eq; }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -365,48 +378,51 @@ __global__ __launch_bounds__(1024) void k_chunk_bases(CompressBuffers cb) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Per chunk: write the surviving candidates as payload and update the estimator.
+// Per chunk (sixteen lanes each): write the surviving candidates as payload and update the estimator.
 __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t nchunks_total,
                                                   const uint32_t* chunk_big) {
-    const uint32_t chunk = blockIdx.x * 4u + (threadIdx.x >> 6);
-    if (chunk >= nchunks_total) return;
-    const uint32_t lane = lane_id();
-    const uint32_t b = chunk_big[chunk];
-    const SelRec S = cb.sel[b];
-    if (S.mode == SEL_NONE) return;
-    const uint32_t cnt = cb.rec_cnt[chunk];
-    if (cnt == 0) return;
-    const uint32_t li = cb.big_layer[b];
-    float* h = cb.layers[li].h;
-    const bool filter = S.mode == SEL_CAND || (S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0u);
-    const uint32_t tau = cb.tau[b];
-    const uint32_t allow = cb.o_allow[chunk];
-    const uint64_t src = S.tmp_base + cb.rec_start[chunk];
-    const uint64_t dst = cb.offsets[li];
-    const uint32_t room = S.K;                     // payload slots of this layer
-    uint32_t out_run = cb.o_base[chunk], eq_run = 0;
-    for (uint32_t k0 = 0; k0 < cnt; k0 += 64) {
-        const uint32_t k = k0 + lane;
+    const SubGroup g = sub_group();
+    const uint32_t chunk = blockIdx.x * CHUNKS_PER_WG + threadIdx.x / SUB;
+    uint32_t cnt = 0, tau = 0, allow = 0, room = 0, out_run = 0, eq_run = 0;
+    uint64_t src = 0, dst = 0;
+    bool filter = false;
+    float* h = nullptr;
+    if (chunk < nchunks_total) {
+        const uint32_t b = chunk_big[chunk];
+        const SelRec S = cb.sel[b];
+        if (S.mode != SEL_NONE) {
+            const uint32_t li = cb.big_layer[b];
+            cnt = cb.rec_cnt[chunk];
+            h = cb.layers[li].h;
+            filter = S.mode == SEL_CAND || (S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0u);
+            tau = cb.tau[b];
+            allow = cb.o_allow[chunk];
+            src = S.tmp_base + cb.rec_start[chunk];
+            dst = cb.offsets[li];
+            room = S.K;                            // payload slots of this layer
+            out_run = cb.o_base[chunk];
+        }
+    }
+    const uint32_t cmax = wave_max_over_groups(cnt);
+    for (uint32_t k0 = 0; k0 < cmax; k0 += SUB) {
+        const uint32_t k = k0 + g.sub;
         const bool in = k < cnt;
         uint32_t idx = 0; float x = 0.f, hv = 0.f;
         if (in) { idx = cb.tmp_idx[src + k]; x = cb.tmp_x[src + k]; hv = cb.tmp_h[src + k]; }
-        bool keep = in;
-        if (filter) {
-            const uint32_t key = key_of(x);
-            const bool iseq = in && key == tau;
-            const uint64_t eqm = ballot(iseq);
-            keep = in && (key > tau || (iseq && eq_run + mbcnt(eqm) < allow));
-            eq_run += (uint32_t)__popcll(eqm);
-        }
-        const uint64_t km = ballot(keep);
-        const uint32_t pos = out_run + mbcnt(km);
+        const uint32_t key = key_of(x);
+        const bool iseq = in && filter && key == tau;
+        const uint32_t eqm = ballot_sub(g, iseq);
+        const bool keep = in && (!filter || key > tau || (iseq && eq_run + rank_sub(g, eqm) < allow));
+        eq_run += __popc(eqm);
+        const uint32_t km = ballot_sub(g, keep);
+        const uint32_t pos = out_run + rank_sub(g, km);
         if (keep && pos < room) {
             const uint64_t o = dst + pos;
             cb.idx_out[o] = idx;
             cb.val_out[o] = x;
             gstore(h + idx, hv + x);
         }
-        out_run += (uint32_t)__popcll(km);
+        out_run += __popc(km);
     }
 }
 

@@ -651,9 +651,10 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Digit-2 histograms of the slots 96.. from the candidate buffer.  One wave per chunk.
+// Digit-2 histograms of the slots 96.. from the candidate buffer.  Sixteen lanes per chunk.
 __global__ __launch_bounds__(256) void k_hist2c(ProfileBuffers pb) {
-    const uint32_t chunk = blockIdx.x * 4u + (threadIdx.x >> 6);
+    const SubGroup g = sub_group();
+    const uint32_t chunk = blockIdx.x * CHUNKS_PER_WG + threadIdx.x / SUB;
     if (chunk >= pb.nchunks_total) return;
     const uint32_t big = pb.chunk_big[chunk];
     const LayerState st = pb.state[big];
@@ -665,7 +666,7 @@ __global__ __launch_bounds__(256) void k_hist2c(ProfileBuffers pb) {
     const uint8_t* lutc = pb.lutc + (size_t)big * D1_BINS;
     uint32_t* c2 = pb.cnt2 + (size_t)big * SLOT_STRIDE * D2_BINS;
     unsigned long long* s2 = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)big * SLOT_STRIDE * D2_BINS;
-    for (uint32_t k = lane_id(); k < cnt; k += 64) {
+    for (uint32_t k = g.sub; k < cnt; k += SUB) {
         const uint32_t key = key_of(pb.tmp_x[base + k]);
         const uint32_t bin = key >> D1_SHIFT;
         const uint32_t slot = lutc[bin];

@@ -293,7 +293,7 @@ int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, h
     KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs);
     KLAUNCH(p, s, "k_main", k_main, dim3(p->main_wgs), dim3(FUSED_THREADS), p->pb, p->chunks_per_wg);
     KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J);
-    KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + 3) / 4), dim3(256), p->pb);
+    KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG), dim3(256), p->pb);
     KLAUNCH(p, s, "k_hist2", k_hist2, dim3(lo.ntiles), dim3(512), p->pb);          // layers marked redo only
     KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(64), p->pb, ktab, lo.J, err_table, CERT_TOL);
     KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(lo.ntiles), dim3(256), p->pb);
@@ -548,7 +548,7 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
             (int32_t)KIMAD_ERR_BAD_OFFSETS, (uint32_t)((flags & KIMAD_REUSE_PROFILE) ? 1u : 0u));
     if (lo.B) {
         const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
-        const uint32_t cblocks = (lo.nchunks + 3) / 4;
+        const uint32_t cblocks = (lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG;
         KLAUNCH(p, s, "k_compact", k_compact, dim3(lo.ntiles), dim3(256), cb, (int32_t)KIMAD_ERR_INTERNAL);
         KLAUNCH(p, s, "k_hist3c", k_hist3c, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
         KLAUNCH(p, s, "k_resolve", k_resolve, dim3(lo.B), dim3(256), cb);
