@@ -75,6 +75,7 @@ __global__ __launch_bounds__(256) void k_dp_layer(AllocBuffers ab, uint32_t i, c
 // possible in a caller-supplied table) are kept as single candidates.  Candidates that cost more
 // than the capacity are dropped.
 struct DpLists {
+    uint32_t* wall;  // [L][J] cost in units of candidate j
     uint32_t* w;     // [L][J] cost in units of the entry
     uint32_t* jj;    // [L][J] first member of the run | last member << 8
     double* e;       // [L][J][2] error of the last member, error of the member before it (NaN for a single)
@@ -88,6 +89,7 @@ __global__ __launch_bounds__(64) void k_dp_prep(AllocBuffers ab, DpLists dl) {
     if (j < ab.J) {
         sw[j] = units_of(ab.Ktab[(size_t)i * ab.J + j], ab.unit);
         se[j] = ab.E[(size_t)i * ab.J + j];
+        dl.wall[(size_t)i * ab.J + j] = sw[j];
     }
     __syncthreads();
     if (j == 0) {
@@ -114,17 +116,21 @@ __global__ __launch_bounds__(64) void k_dp_prep(AllocBuffers ab, DpLists dl) {
 // test: it reads +inf and cannot win.  The candidate list is read with uniform addresses (scalar
 // loads); per entry and cell the work is one LDS read, one add, one compare and three selects.
 constexpr uint32_t DP_ROW = 6144;               // doubles per LDS row: pad + cells
-constexpr uint32_t DP_CELLS_PER_THREAD = 3;     // capacity + 1 <= 3072
+constexpr uint32_t DP_LIST_CAP = 2048;          // candidate-list entries held in LDS at a time
+constexpr uint32_t DP_GROUP_MAX = 1024;         // layers per group at most (one thread plans one layer)
 
 __global__ __launch_bounds__(1024) void k_dp_fused(AllocBuffers ab, const uint32_t* __restrict__ ent_w,
                                                    const uint32_t* __restrict__ ent_jj, const double* __restrict__ ent_e,
-                                                   const uint32_t* __restrict__ ent_n, int32_t err_infeasible,
+                                                   const uint32_t* __restrict__ ent_n,
+                                                   const uint32_t* __restrict__ wall, int32_t err_infeasible,
                                                    int32_t err_nonfinite) {
     __shared__ double rows[2][DP_ROW];          // 96 KB; reused for the choice rows afterwards
-    __shared__ double sE[2][2 * KIMAD_MAX_J_CONST];   // per entry: error of the last member, of the one before
-    __shared__ uint32_t sW[2][KIMAD_MAX_J_CONST];
-    __shared__ uint32_t sJ[2][KIMAD_MAX_J_CONST];
-    __shared__ uint32_t sN[2];
+    __shared__ double LE[2 * DP_LIST_CAP];      // 32 KB: per entry, error of the run's last member and of the one before
+    __shared__ uint32_t LW[DP_LIST_CAP];        // 8 KB: cost in units
+    __shared__ uint32_t LJ[DP_LIST_CAP];        // 8 KB: first member | last member << 8
+    __shared__ uint32_t loff[DP_GROUP_MAX + 1]; // first entry of each layer of the group
+    __shared__ uint32_t su[16];
+    __shared__ uint32_t sh_g;
     __shared__ double sv[16];
     __shared__ unsigned long long sc[16];
     __shared__ unsigned long long cstar;
@@ -137,64 +143,72 @@ __global__ __launch_bounds__(1024) void k_dp_fused(AllocBuffers ab, const uint32
         rows[1][c] = DP_INF;
     }
     // Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits for the
-    // acknowledgement of every global store and load in flight (the choice rows, the next layer's
-    // list), which would put a memory round trip into each of the L sequential steps.
+    // acknowledgement of every global store in flight (the choice rows), which would put a memory
+    // round trip into each of the L sequential steps.
     auto lds_barrier = [] { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); };
-    if (tid < ab.J) {
-        const size_t o = tid;
-        sW[0][tid] = ent_w[o]; sJ[0][tid] = ent_jj[o];
-        sE[0][2 * tid] = ent_e[2 * o]; sE[0][2 * tid + 1] = ent_e[2 * o + 1];
-    }
-    if (tid == 64) sN[0] = ent_n[0];
-    __syncthreads();
-    for (uint32_t i = 0; i < ab.L; ++i) {
-        const uint32_t buf = i & 1;
-        // issue the loads of the next layer's list now, park them in LDS after this layer's work
-        uint32_t nw = 0, nj = 0, nn = 0;
-        double ne0 = 0.0, ne1 = 0.0;
-        const bool more = i + 1 < ab.L;
-        if (more && tid < ab.J) {
-            const size_t o = (size_t)(i + 1) * ab.J + tid;
-            nw = ent_w[o]; nj = ent_jj[o]; ne0 = ent_e[2 * o]; ne1 = ent_e[2 * o + 1];
+    // Layers are taken in groups whose candidate lists fit the LDS list buffer; the lists of a group
+    // are copied in one sweep, so the memory latency is paid once per group, not once per layer.
+    uint32_t i0 = 0;
+    while (i0 < ab.L) {
+        const uint32_t mine = (tid < DP_GROUP_MAX && i0 + tid < ab.L) ? ent_n[i0 + tid] : 0u;
+        const uint32_t before = block_exclusive_scan<uint32_t>(mine, su, nullptr);
+        if (tid == 0) sh_g = 0u;
+        __syncthreads();
+        const bool fits = tid < DP_GROUP_MAX && i0 + tid < ab.L && before + mine <= DP_LIST_CAP;
+        if (fits) {
+            loff[tid] = before;
+            atomicMax(&sh_g, tid + 1u);          // layer counts are prefix-monotone: the group is layers 0..g-1
         }
-        if (more && tid == 64) nn = ent_n[i + 1];
-        const double* prev = rows[i & 1] + pad;
-        double* cur = rows[(i + 1) & 1] + pad;
-        const uint32_t n = sN[buf];
-        for (uint32_t c = tid; c < ncell; c += 1024) {
-            double best = DP_INF;
-            uint32_t bk = 0xFF;                 // winning entry | 0x100 if the run's previous member rounds to the same total
-            // branch-free over the entries, so that the LDS reads of several entries are in flight together
-#pragma unroll 4
-            for (uint32_t k = 0; k < n; ++k) {
-                const uint32_t w = sW[buf][k];
-                const double e_hi = sE[buf][2 * k], e_prev = sE[buf][2 * k + 1];
-                const double p = prev[(int32_t)c - (int32_t)w];
-                const double t = p + e_hi;
-                const bool upd = t < best;
-                const bool collide = p + e_prev == t;            // never for a single: e_prev is NaN
-                best = upd ? t : best;
-                bk = upd ? (k | (collide ? 0x100u : 0u)) : bk;
+        __syncthreads();
+        const uint32_t g = sh_g;                 // >= 1: one layer has at most J <= 64 entries
+        if (tid == g - 1u) loff[g] = before + mine;
+        __syncthreads();
+        for (uint32_t t = tid; t < g * ab.J; t += 1024) {
+            const uint32_t layer = t / ab.J, k = t % ab.J;
+            if (k < loff[layer + 1] - loff[layer]) {
+                const size_t o = (size_t)(i0 + layer) * ab.J + k;
+                const uint32_t d = loff[layer] + k;
+                LW[d] = ent_w[o]; LJ[d] = ent_jj[o];
+                LE[2 * d] = ent_e[2 * o]; LE[2 * d + 1] = ent_e[2 * o + 1];
             }
-            const uint32_t k = bk & 0xFFu;
-            uint32_t bj = k == 0xFFu ? 0xFFu : (sJ[buf][k] >> 8);
-            if (bk & 0x100u) {
-                // rare: the lowest member of the run whose rounded total equals the winner's
-                const uint32_t jlo = sJ[buf][k] & 0xFFu;
-                const double p = prev[(int32_t)c - (int32_t)sW[buf][k]];
-                uint32_t j = bj - 1u;
-                while (j > jlo && p + ab.E[(size_t)i * ab.J + j - 1] == best) --j;
-                bj = j;
+        }
+        __syncthreads();
+        for (uint32_t i = i0; i < i0 + g; ++i) {
+            const double* prev = rows[i & 1] + pad;
+            double* cur = rows[(i + 1) & 1] + pad;
+            const uint32_t e0 = loff[i - i0], n = loff[i - i0 + 1] - e0;
+            const uint32_t* lw = LW + e0;
+            const uint32_t* lj = LJ + e0;
+            const double* le = LE + 2 * e0;
+            for (uint32_t c = tid; c < ncell; c += 1024) {
+                double best = DP_INF;
+                uint32_t bk = 0xFF;             // winning entry
+#pragma unroll 8
+                for (uint32_t k = 0; k < n; ++k) {
+                    const double t = prev[(int32_t)c - (int32_t)lw[k]] + le[2 * k];
+                    const bool upd = t < best;
+                    best = upd ? t : best;
+                    bk = upd ? k : bk;
+                }
+                uint32_t bj = 0xFFu;
+                if (bk != 0xFFu) {
+                    // Only the winner's run matters: if the member before its last one rounds to the same
+                    // total (never for a single: that error is NaN), the lowest such member wins.
+                    bj = lj[bk] >> 8;
+                    const double p = prev[(int32_t)c - (int32_t)lw[bk]];
+                    if (p + le[2 * bk + 1] == best) {
+                        const uint32_t jlo = lj[bk] & 0xFFu;
+                        uint32_t j = bj - 1u;
+                        while (j > jlo && p + ab.E[(size_t)i * ab.J + j - 1] == best) --j;
+                        bj = j;
+                    }
+                }
+                cur[c] = best;
+                ab.choice[(size_t)i * ab.stride + c] = (uint8_t)bj;
             }
-            cur[c] = best;
-            ab.choice[(size_t)i * ab.stride + c] = (uint8_t)bj;
+            lds_barrier();
         }
-        if (more && tid < ab.J) {
-            sW[buf ^ 1][tid] = nw; sJ[buf ^ 1][tid] = nj;
-            sE[buf ^ 1][2 * tid] = ne0; sE[buf ^ 1][2 * tid + 1] = ne1;
-        }
-        if (more && tid == 64) sN[buf ^ 1] = nn;
-        lds_barrier();
+        i0 += g;
     }
     __syncthreads();
     // least total, smallest cost attaining it
@@ -229,37 +243,54 @@ __global__ __launch_bounds__(1024) void k_dp_fused(AllocBuffers ab, const uint32
         for (uint32_t i = tid; i <= ab.L; i += 1024) ab.offsets_out[i] = 0;
         return;
     }
-    // back-tracking: stage the choice rows of a group of layers in LDS, walk them, next group
+    // back-tracking: stage the choice rows and the candidates' costs of a group of layers in LDS,
+    // walk them, next group
     uint8_t* stage = reinterpret_cast<uint8_t*>(&rows[0][0]);
-    const uint32_t per_group = (uint32_t)(sizeof(rows) / ncell);
+    const uint32_t wbytes = 4u * ab.J;
+    const uint32_t per_layer = (ncell + wbytes + 3u) & ~3u;
+    const uint32_t per_group = (uint32_t)(sizeof(rows) / per_layer);
     uint32_t hi = ab.L;
     while (hi > 0) {
         const uint32_t lo_l = hi > per_group ? hi - per_group : 0u;
         __syncthreads();
         for (uint32_t x = tid; x < (hi - lo_l) * ncell; x += 1024) {
-            const uint32_t i = lo_l + x / ncell, c = x % ncell;
-            stage[x] = ab.choice[(size_t)i * ab.stride + c];
+            const uint32_t i = x / ncell, c = x % ncell;
+            stage[i * per_layer + wbytes + c] = ab.choice[(size_t)(lo_l + i) * ab.stride + c];
+        }
+        for (uint32_t x = tid; x < (hi - lo_l) * ab.J; x += 1024) {
+            const uint32_t i = x / ab.J, j = x % ab.J;
+            reinterpret_cast<uint32_t*>(stage + i * per_layer)[j] = wall[(size_t)(lo_l + i) * ab.J + j];
         }
         __syncthreads();
         if (tid == 0) {
             uint64_t c = cstar;
             for (uint32_t i = hi; i-- > lo_l;) {
-                const uint32_t j = stage[(i - lo_l) * ncell + c];
-                const uint32_t K = ab.Ktab[(size_t)i * ab.J + j];
+                const uint8_t* row = stage + (i - lo_l) * per_layer;
+                const uint32_t j = row[wbytes + c];
                 ab.j_out[i] = (int32_t)j;
-                ab.K_out[i] = K;
-                c -= units_of(K, ab.unit);
+                c -= reinterpret_cast<const uint32_t*>(row)[j];
             }
             cstar = c;
         }
         hi = lo_l;
     }
+    __threadfence_block();
     __syncthreads();
-    if (tid == 0) {
-        uint64_t run = 0;
-        for (uint32_t i = 0; i < ab.L; ++i) { ab.offsets_out[i] = run; run += ab.K_out[i]; }
-        ab.offsets_out[ab.L] = run;
+    // sizes and offsets, in parallel
+    unsigned long long carry = 0;
+    for (uint32_t i0b = 0; i0b < ab.L; i0b += 1024) {
+        const uint32_t i = i0b + tid;
+        unsigned long long K = 0;
+        if (i < ab.L) {
+            K = ab.Ktab[(size_t)i * ab.J + (uint32_t)ab.j_out[i]];
+            ab.K_out[i] = K;
+        }
+        unsigned long long tot;
+        const unsigned long long ex = block_exclusive_scan<unsigned long long>(K, sc, &tot);
+        if (i < ab.L) ab.offsets_out[i] = carry + ex;
+        carry += tot;
     }
+    if (tid == 0) ab.offsets_out[ab.L] = carry;
 }
 
 // Smallest cost attaining the least total, back-tracking, outputs.  One workgroup.

@@ -47,7 +47,7 @@ struct Layout {
     uint64_t rec_start, rec_cnt, rec_amb, c_gt, c_eq, o_base, o_allow;
     uint64_t tmp_idx, tmp_x, tmp_h;
     // allocation
-    uint64_t row0, row1, choice, dp_flags, dl_w, dl_jj, dl_e, dl_n;
+    uint64_t row0, row1, choice, dp_flags, dl_wall, dl_w, dl_jj, dl_e, dl_n;
     uint64_t total = 0;
 };
 
@@ -186,7 +186,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.row1 = take(8 * lo.dp_cells);
     lo.choice = take((uint64_t)L * align_up(lo.dp_cells));
     lo.dp_flags = take(16);
-    lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
+    lo.dl_wall = take(4 * LJ); lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
     lo.total = off;
     return KIMAD_OK;
 }
@@ -507,11 +507,12 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     KLAUNCH(p, s, "k_dp_init", k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), ab);
     if (cap + 1 <= DP_ROW / 2) {
         DpLists dl;
-        dl.w = at<uint32_t>(p, lo.dl_w); dl.jj = at<uint32_t>(p, lo.dl_jj); dl.e = at<double>(p, lo.dl_e);
+        dl.wall = at<uint32_t>(p, lo.dl_wall); dl.w = at<uint32_t>(p, lo.dl_w); dl.jj = at<uint32_t>(p, lo.dl_jj); dl.e = at<double>(p, lo.dl_e);
         dl.n = at<uint32_t>(p, lo.dl_n);
         KLAUNCH(p, s, "k_dp_prep", k_dp_prep, dim3(lo.L), dim3(64), ab, dl);
         KLAUNCH(p, s, "k_dp_fused", k_dp_fused, dim3(1), dim3(1024), ab, (const uint32_t*)dl.w, (const uint32_t*)dl.jj,
-                (const double*)dl.e, (const uint32_t*)dl.n, (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
+                (const double*)dl.e, (const uint32_t*)dl.n, (const uint32_t*)dl.wall, (int32_t)KIMAD_ERR_INFEASIBLE,
+                (int32_t)KIMAD_ERR_NONFINITE);
     } else {
         double* rows[2] = {ab.row0, ab.row1};
         for (uint32_t i = 0; i < lo.L; ++i) {
