@@ -231,7 +231,17 @@ struct kimad_plan {
     std::vector<hipEvent_t> ev;
     std::vector<const char*> ev_name;
     uint32_t ev_n = 0;
-    ~kimad_plan() { for (hipEvent_t e : ev) (void)hipEventDestroy(e); }
+    // The small layers (one workgroup each) do not depend on the tiled layers: their kernels run on a
+    // side stream, forked from and joined back into the caller's stream with events, so that they
+    // overlap the short kernels of the tiled path instead of standing in line with them.
+    hipStream_t side = nullptr;
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    ~kimad_plan() {
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+        if (ev_fork) (void)hipEventDestroy(ev_fork);
+        if (ev_join) (void)hipEventDestroy(ev_join);
+        if (side) (void)hipStreamDestroy(side);
+    }
 };
 
 namespace {
@@ -239,6 +249,22 @@ namespace {
 template <typename T> T* at(kimad_plan* p, uint64_t off) { return reinterpret_cast<T*>(p->ws + off); }
 
 constexpr uint32_t MAX_EVENTS = 1024;
+
+// Stream for work that may overlap what follows on `s`: the side stream, made to wait for
+// everything enqueued on `s` so far.  With per-kernel timing on (or if anything fails) it is `s`
+// itself, i.e. plain in-order execution.
+hipStream_t fork_side(kimad_plan* p, hipStream_t s) {
+    if (p->timing || !p->side) return s;
+    if (hipEventRecord(p->ev_fork, s) != hipSuccess) return s;
+    if (hipStreamWaitEvent(p->side, p->ev_fork, 0) != hipSuccess) return s;
+    return p->side;
+}
+int join_side(kimad_plan* p, hipStream_t s, hipStream_t used) {
+    if (used == s) return KIMAD_OK;
+    if (hipEventRecord(p->ev_join, used) != hipSuccess) return KIMAD_ERR_HIP;
+    if (hipStreamWaitEvent(s, p->ev_join, 0) != hipSuccess) return KIMAD_ERR_HIP;
+    return KIMAD_OK;
+}
 
 // With timing on, an event follows every launch; the interval between consecutive events is
 // that kernel's duration on the stream.
@@ -445,6 +471,15 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     cb.state = pb.state;
     cb.K = nullptr; cb.offsets = nullptr; cb.idx_out = nullptr; cb.val_out = nullptr; cb.capacity_pairs = 0;
     cb.status = nullptr;
+    if (lo.S && lo.B) {
+        // default priority; without the side stream everything simply runs in order on the caller's stream
+        if (hipStreamCreateWithFlags(&p->side, hipStreamNonBlocking) != hipSuccess) p->side = nullptr;
+        if (p->side && (hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming) != hipSuccess ||
+                        hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming) != hipSuccess)) {
+            (void)hipStreamDestroy(p->side);
+            p->side = nullptr;
+        }
+    }
     *plan_out = p;
     return KIMAD_OK;
 }
@@ -465,16 +500,18 @@ int kimad_profile(kimad_plan_t* p, double* err_table, uint64_t budget_hint_bytes
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Layout& lo = p->lo;
     mark(p, s, "begin");
+    hipStream_t ss = s;
+    if (lo.S) {
+        ss = fork_side(p, s);
+        KLAUNCH(p, ss, "k_small_profile", k_small_profile, dim3(lo.S), dim3(SMALL_THREADS), p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
+    }
     int rc;
     if (p->cfg.flags & KIMAD_CFG_CLASSIC_PROFILE)
         rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s);
     else
         rc = run_fused_profile(p, err_table, budget_hint_bytes / p->cfg.pair_bytes, s);
-    if (rc) return rc;
-    if (lo.S) {
-        KLAUNCH(p, s, "k_small_profile", k_small_profile, dim3(lo.S), dim3(SMALL_THREADS), p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
-    }
-    return KIMAD_OK;
+    const int rj = join_side(p, s, ss);       // always join, also after an error
+    return rc ? rc : rj;
 }
 
 int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_bytes, int32_t* j_out, uint64_t* K_out,
@@ -547,6 +584,11 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
     if (rc) return rc;
     KLAUNCH(p, s, "k_lookup", k_lookup, dim3(1), dim3(256), cb, (int32_t)KIMAD_ERR_OFFGRID,
             (int32_t)KIMAD_ERR_BAD_OFFSETS, (uint32_t)((flags & KIMAD_REUSE_PROFILE) ? 1u : 0u));
+    hipStream_t ss = s;
+    if (lo.S) {
+        ss = fork_side(p, s);                 // after the lookup: the small layers read its verdict
+        KLAUNCH(p, ss, "k_small_compress", k_small_compress, dim3(lo.S), dim3(SMALL_THREADS), cb);
+    }
     if (lo.B) {
         const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
         const uint32_t cblocks = (lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG;
@@ -557,10 +599,7 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
         KLAUNCH(p, s, "k_chunk_bases", k_chunk_bases, dim3(lo.ncblk), dim3(1024), cb);
         KLAUNCH(p, s, "k_finalize", k_finalize, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
     }
-    if (lo.S) {
-        KLAUNCH(p, s, "k_small_compress", k_small_compress, dim3(lo.S), dim3(SMALL_THREADS), cb);
-    }
-    return KIMAD_OK;
+    return join_side(p, s, ss);
 }
 
 int kimad_step(kimad_plan_t* p, uint64_t budget_bytes, double* err_table, int32_t* j_out, uint64_t* K_out,
