@@ -124,8 +124,15 @@ def main() -> int:
     alg_bytes = {"k_main": 8 * d_big, "k_hist1": 8 * d_big, "k_hist2": 8 * d_big, "k_compact": 8 * d_big}
     dom = max((n for n in STREAMING_KERNELS if n in kern), key=lambda n: kern[n]["ms_per_step"])
     ach = alg_bytes[dom] / (kern[dom]["avg_ms"] * 1e-3) / 1e9
+    # HBM bytes per launch from rocprofv3 counter runs, recorded under profiles/ (None if there is no record for
+    # this kernel and workload)
+    traffic = None
+    rec = os.path.join(ROOT, "profiles", f"hbm_traffic_{dom}_{work.name}.json")
+    if os.path.exists(rec):
+        with open(rec) as f:
+            traffic = json.load(f).get("traffic_bytes_per_launch")
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": alg_bytes[dom],
                 "avg_launch_ms": round(kern[dom]["avg_ms"], 5)}
 
