@@ -19,9 +19,11 @@
  * Conventions
  *   - Every pointer is marked HOST or DEVICE.  The library never allocates or frees device
  *     memory: gradients, estimator, outputs and the workspace belong to the caller.
- *   - All GPU work is enqueued on the given stream (a hipStream_t passed as void*; NULL is the
- *     default stream); no call waits for the device except kimad_plan_create, which uploads
- *     its tables synchronously.
+ *   - All GPU work is ordered with the given stream (a hipStream_t passed as void*; NULL is the
+ *     default stream): it is enqueued there, except that kernels for layers of at most 8192
+ *     entries run on a side stream of the plan between a fork and a join event on the given
+ *     stream.  No call waits for the device except kimad_plan_create (synchronous uploads) and
+ *     the diagnostics getters.
  *   - Return value: 0 on success, a negative kimad_status otherwise (argument errors are found
  *     on the host before anything is enqueued).  Data-dependent outcomes (infeasible budget,
  *     non-finite table, a K that is not on the grid) are written to a DEVICE status word.
