@@ -47,7 +47,8 @@ struct Layout {
     uint64_t rec_start, rec_cnt, rec_amb, c_gt, c_eq, o_base, o_allow;
     uint64_t tmp_idx, tmp_x, tmp_h;
     // allocation
-    uint64_t row0, row1, choice, dp_flags, dl_wall, dl_w, dl_jj, dl_e, dl_n;
+    uint64_t row0, row1, choice, dp_flags, dl_wall, dl_w, dl_jj, dl_e, dl_n, dl_bad, rows_g;
+    uint64_t rstride = 0;            // cells per stored DP row (LDS-resident recurrence only)
     uint64_t total = 0;
 };
 
@@ -187,6 +188,9 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.choice = take((uint64_t)L * align_up(lo.dp_cells));
     lo.dp_flags = take(16);
     lo.dl_wall = take(4 * LJ); lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
+    lo.dl_bad = take(4ull * L);
+    lo.rstride = (std::min<uint64_t>(lo.dp_cells, DP_PAD) + 31) & ~31ull;
+    lo.rows_g = take(8ull * (L + 1) * lo.rstride);
     lo.total = off;
     return KIMAD_OK;
 }
@@ -538,19 +542,32 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     ab.j_out = j_out; ab.K_out = K_out; ab.offsets_out = offsets_out; ab.status = status_out;
     ab.flags = at<uint32_t>(p, lo.dp_flags);
     mark(p, s, "begin");
-    int rc = zero_range(p, lo.dp_flags, lo.dp_flags + 16, s);
-    if (rc) return rc;
     const uint32_t cell_blocks = (uint32_t)((cap + 1 + 255) / 256);
-    KLAUNCH(p, s, "k_dp_init", k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), ab);
-    if (cap + 1 <= DP_ROW / 2) {
+    if (cap + 1 <= DP_PAD) {
         DpLists dl;
         dl.wall = at<uint32_t>(p, lo.dl_wall); dl.w = at<uint32_t>(p, lo.dl_w); dl.jj = at<uint32_t>(p, lo.dl_jj); dl.e = at<double>(p, lo.dl_e);
-        dl.n = at<uint32_t>(p, lo.dl_n);
+        dl.n = at<uint32_t>(p, lo.dl_n); dl.bad = at<uint32_t>(p, lo.dl_bad);
+        double* rows_g = at<double>(p, lo.rows_g);
+        const uint32_t rstride = (uint32_t)lo.rstride;
         KLAUNCH(p, s, "k_dp_prep", k_dp_prep, dim3(lo.L), dim3(64), ab, dl);
-        KLAUNCH(p, s, "k_dp_fused", k_dp_fused, dim3(1), dim3(1024), ab, (const uint32_t*)dl.w, (const uint32_t*)dl.jj,
-                (const double*)dl.e, (const uint32_t*)dl.n, (const uint32_t*)dl.wall, (int32_t)KIMAD_ERR_INFEASIBLE,
-                (int32_t)KIMAD_ERR_NONFINITE);
+        const uint32_t cpt = (uint32_t)((cap + 1 + DP_FWD_THREADS - 1) / DP_FWD_THREADS);
+        if (cpt <= 2) {
+            KLAUNCH(p, s, "k_dp_forward", k_dp_forward<2>, dim3(1), dim3(DP_FWD_THREADS), ab, (const uint32_t*)dl.w,
+                    (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
+        } else if (cpt <= 4) {
+            KLAUNCH(p, s, "k_dp_forward", k_dp_forward<4>, dim3(1), dim3(DP_FWD_THREADS), ab, (const uint32_t*)dl.w,
+                    (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
+        } else {
+            KLAUNCH(p, s, "k_dp_forward", k_dp_forward<6>, dim3(1), dim3(DP_FWD_THREADS), ab, (const uint32_t*)dl.w,
+                    (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
+        }
+        KLAUNCH(p, s, "k_dp_choice", k_dp_choice, dim3(cell_blocks, lo.L), dim3(256), ab, dl, (const double*)rows_g, rstride);
+        KLAUNCH(p, s, "k_dp_walk", k_dp_walk, dim3(1), dim3(1024), ab, (const double*)(rows_g + (size_t)lo.L * rstride),
+                (const uint32_t*)dl.wall, (const uint32_t*)dl.bad, (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
     } else {
+        int rc = zero_range(p, lo.dp_flags, lo.dp_flags + 16, s);
+        if (rc) return rc;
+        KLAUNCH(p, s, "k_dp_init", k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), ab);
         double* rows[2] = {ab.row0, ab.row1};
         for (uint32_t i = 0; i < lo.L; ++i) {
             KLAUNCH(p, s, "k_dp_layer", k_dp_layer, dim3(cell_blocks), dim3(256), ab, i, rows[i & 1], rows[(i + 1) & 1]);
