@@ -131,9 +131,7 @@ __global__ __launch_bounds__(64) void k_dp_prep(AllocBuffers ab, DpLists dl) {
 // needs no test: it reads +inf and cannot win.
 constexpr uint32_t DP_PAD = 3072;               // cells of +inf before cost 0; also the largest row
 constexpr uint32_t DP_ROW = 2 * DP_PAD;         // doubles per LDS row
-constexpr uint32_t DP_LIST_CAP = 4096;          // candidate-list entries held in LDS at a time
-constexpr uint32_t DP_FWD_THREADS = 512;
-constexpr uint32_t DP_GROUP_MAX = DP_FWD_THREADS;  // layers per group at most (one thread plans one layer)
+constexpr uint32_t DP_LIST_CAP = 3072;          // list records held in LDS at a time
 
 // Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits for the
 // acknowledgement of every global store in flight, which would put a memory round trip into each
@@ -149,106 +147,191 @@ __device__ __forceinline__ double min_f64(double a, double b) {
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-// Thread t owns cells t, t+512, ... (CPT of them).  A wave keeps the layer's list in registers, one
-// entry per lane, and broadcasts entry k with readlane: per entry and cell the work is one LDS
-// read, one add and one min.
-template <int CPT>
-__global__ __launch_bounds__(DP_FWD_THREADS) void k_dp_forward(AllocBuffers ab, const uint32_t* __restrict__ ent_w,
+// A wave holds 16 list records per register set, record k in lane k of every 16-lane row, and
+// uses them through DPP row_newbcast operands, which hand lane K of each row to all its lanes:
+//   row_addr_sub   LDS address of the row cell minus record K's cost (v_add_u32 with the negated cost)
+//   acc_rec_error  t += record K's error, as fma(error, 1.0, t): one rounding of the exact sum, the same
+//                  result as an add
+// Both forms were checked against a 64-lane test pattern on gfx950.  They are written as inline
+// assembly: when the compiler folds a DPP move into a subtraction itself, the instruction it emits
+// applied the broadcast to the other operand in that test.
+template <int K>
+__device__ __forceinline__ uint32_t row_addr_sub(uint32_t base, uint32_t neg_cost) {
+    uint32_t r;
+    asm("v_add_u32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+        : "=v"(r) : "v"(neg_cost), "v"(base), "n"(K));
+    return r;
+}
+template <int K>
+__device__ __forceinline__ double acc_rec_error(double t, double err, double one) {
+    asm("v_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+        : "+v"(t) : "v"(err), "v"(one), "n"(K));
+    return t;
+}
+// LDS pointers as 32-bit byte addresses, for address arithmetic in DPP instructions.
+using lds_cdouble_ptr = const __attribute__((address_space(3))) double*;
+__device__ __forceinline__ uint32_t lds_addr(const double* p) { return (uint32_t)(size_t)(lds_cdouble_ptr)p; }
+
+// A list record as stored in LDS: x, y = the error's fp64 bits, z = minus the cost as a byte
+// distance in the row.
+__device__ __forceinline__ double rec_err(const uint4& r) { return __hiloint2double((int)r.y, (int)r.x); }
+
+// One trip of the recurrence covers records 4*K4 .. 4*K4+3 of a block of 16: dp_issue starts its
+// row reads, dp_consume does its arithmetic.  (Issuing trip t+1 before consuming trip t was tried
+// and measured no faster: a wave issues an instruction every 8 to 10 cycles whatever it waits for,
+// and the trip is bound by its instruction count.)
+template <int NT, int CPT, int K4>
+__device__ __forceinline__ void dp_issue(uint32_t neg_cost, uint32_t prev, double (&p)[4][CPT]) {
+    constexpr int K = 4 * K4;
+    const uint32_t q[4] = {row_addr_sub<K>(prev, neg_cost), row_addr_sub<K + 1>(prev, neg_cost),
+                           row_addr_sub<K + 2>(prev, neg_cost), row_addr_sub<K + 3>(prev, neg_cost)};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int m = 0; m < CPT; ++m)
+            p[u][m] = *(lds_cdouble_ptr)(q[u] + (uint32_t)m * NT * 8u);
+    }
+}
+
+template <int CPT, int K4>
+__device__ __forceinline__ void dp_consume(const double (&p)[4][CPT], double err, double one, double (&best)[CPT]) {
+    constexpr int K = 4 * K4;
+#pragma unroll
+    for (int m = 0; m < CPT; ++m) {
+        best[m] = min_f64(best[m], acc_rec_error<K>(p[0][m], err, one));
+        best[m] = min_f64(best[m], acc_rec_error<K + 1>(p[1][m], err, one));
+        best[m] = min_f64(best[m], acc_rec_error<K + 2>(p[2][m], err, one));
+        best[m] = min_f64(best[m], acc_rec_error<K + 3>(p[3][m], err, one));
+    }
+}
+
+// Thread t owns cells t, t+NT, ... (CPT of them).  The lists of a group of layers sit in LDS as one
+// stream of 16-byte records, each layer padded to a multiple of DP_UNROLL with records (cost 0,
+// +inf) that change nothing.  A wave holds a layer's records in registers, record k of a block of
+// 16 in lane k of every 16-lane row, and hands record k to all lanes with a DPP row broadcast
+// (a readlane or a broadcast LDS read per record and wave costs several times the arithmetic).
+// Per record and cell the work is one LDS read, one add and one min.  The records of the next
+// layer are fetched while the current one is computed.
+template <int NT, int CPT>
+__global__ __launch_bounds__(NT) void k_dp_forward(AllocBuffers ab, const uint32_t* __restrict__ ent_w,
                                                                const double* __restrict__ ent_e,
                                                                const uint32_t* __restrict__ ent_n,
                                                                double* __restrict__ rows_g, uint32_t rstride) {
-    __shared__ double rows[2][DP_ROW];          // 96 KB
-    __shared__ double LE[DP_LIST_CAP];          // 32 KB: error of the run's last member
-    __shared__ uint32_t LW[DP_LIST_CAP];        // 16 KB: cost in bytes of row (units * 8)
-    __shared__ uint32_t loff[DP_GROUP_MAX + 1]; // first entry of each layer of the group
+    __shared__ double rows[2][DP_ROW];                  // 96 KB
+    __shared__ uint4 recs[DP_LIST_CAP + 64];            // 49 KB; a layer's fetch may run 63 records past its list
+    __shared__ uint32_t loff[NT + 1];         // first record of each layer of the group
+    __shared__ uint32_t ln[NT];               // entries of each layer before padding
+    __shared__ uint32_t ltr[NT + 1];          // trips of each layer; 0 after the last
     __shared__ uint32_t su[16];
     __shared__ uint32_t sh_g;
-    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t tid = threadIdx.x;
     const uint32_t ncell = ab.cap + 1;
-    for (uint32_t c = tid; c < DP_ROW; c += DP_FWD_THREADS) {
+    for (uint32_t c = tid; c < DP_ROW; c += NT) {
         rows[0][c] = c == DP_PAD ? 0.0 : DP_INF;
         rows[1][c] = DP_INF;
     }
-    for (uint32_t c = tid; c < ncell; c += DP_FWD_THREADS) rows_g[c] = c ? DP_INF : 0.0;
+    for (uint32_t c = tid; c < ncell; c += NT) rows_g[c] = c ? DP_INF : 0.0;
     // Layers are taken in groups whose candidate lists fit the LDS list buffer; the lists of a group
     // are copied in one sweep, so the memory latency is paid once per group, not once per layer.
     uint32_t i0 = 0;
     while (i0 < ab.L) {
-        const uint32_t mine = (i0 + tid < ab.L) ? ent_n[i0 + tid] : 0u;
+        const uint32_t n_mine = (i0 + tid < ab.L) ? ent_n[i0 + tid] : 0u;
+        const uint32_t mine = (n_mine + DP_UNROLL - 1u) & ~(DP_UNROLL - 1u);
         const uint32_t before = block_exclusive_scan<uint32_t>(mine, su, nullptr);
         if (tid == 0) sh_g = 0u;
         __syncthreads();
         const bool fits = i0 + tid < ab.L && before + mine <= DP_LIST_CAP;
         if (fits) {
             loff[tid] = before;
+            ln[tid] = n_mine;
             atomicMax(&sh_g, tid + 1u);          // layer counts are prefix-monotone: the group is layers 0..g-1
         }
         __syncthreads();
         const uint32_t g = sh_g;                 // >= 1: one layer has at most J <= 64 entries
         if (tid == g - 1u) loff[g] = before + mine;
         __syncthreads();
-        for (uint32_t t = tid; t < g * ab.J; t += DP_FWD_THREADS) {
-            const uint32_t layer = t / ab.J, k = t % ab.J;
+        const uint32_t jp = (ab.J + DP_UNROLL - 1u) & ~(DP_UNROLL - 1u);   // a padded list may exceed J
+        for (uint32_t t = tid; t < g * jp; t += NT) {
+            const uint32_t layer = t / jp, k = t % jp;
             if (k < loff[layer + 1] - loff[layer]) {
-                const size_t o = (size_t)(i0 + layer) * ab.J + k;
-                const uint32_t d = loff[layer] + k;
-                LW[d] = ent_w[o] * 8u;
-                LE[d] = ent_e[2 * o];
+                double e = DP_INF;
+                uint32_t w8 = 0u;
+                if (k < ln[layer]) {
+                    const size_t o = (size_t)(i0 + layer) * ab.J + k;
+                    e = ent_e[2 * o];
+                    w8 = ent_w[o] * 8u;
+                }
+                recs[loff[layer] + k] = make_uint4((uint32_t)__double2loint(e), (uint32_t)__double2hiint(e), 0u - w8, 0u);
             }
         }
+        // a layer's fetch and the row reads issued one trip ahead may run past the group's last
+        // record: what they find there is (cost 0, +inf) as well
+        if (tid < 64) recs[loff[g] + tid] = make_uint4(0u, 0x7FF00000u, 0u, 0u);
+        for (uint32_t l = tid; l <= g; l += NT) ltr[l] = l < g ? (loff[l + 1] - loff[l]) / DP_UNROLL : 0u;
         __syncthreads();
-        // The list of the next layer is fetched into registers while the current layer is computed, and
-        // the bounds of the one after that: nothing but the row itself is read on the critical path.
-        auto fetch_list = [&](uint32_t b0, uint32_t b1, uint32_t& fw, double& fe) {
-            fw = 0u; fe = DP_INF;
-            if (lane < b1 - b0) { fw = LW[b0 + lane]; fe = LE[b0 + lane]; }
+
+        // The stream is contiguous, so the first record of the next layer follows from the trip
+        // counts alone: its records are fetched while the current layer is computed, and the trip
+        // counts are read two layers ahead, which keeps every list access off the critical path.
+        const uint32_t sub = tid & 15u;
+        auto fetch_layer = [&](uint32_t first, uint4 (&R)[4]) {
+#pragma unroll
+            for (int b = 0; b < 4; ++b) R[b] = recs[first + 16u * b + sub];
         };
-        uint32_t n_next = loff[1] - loff[0], vw_next;
-        double ve_next;
-        fetch_list(loff[0], loff[1], vw_next, ve_next);
-        uint32_t b0 = loff[min(1u, g)], b1 = loff[min(2u, g)];
+        double one = 1.0;
+        asm volatile("" : "+v"(one));          // keep 1.0 in a vector register pair
+        uint4 Rn[4];
+        fetch_layer(0u, Rn);
+        uint32_t first = 0u;
+        uint32_t nt_cur = __builtin_amdgcn_readfirstlane(ltr[0]);
+        uint32_t nt_n1 = __builtin_amdgcn_readfirstlane(ltr[min(1u, g)]);
+        uint32_t nt_n2 = ltr[min(2u, g)];
         for (uint32_t i = i0; i < i0 + g; ++i) {
-            const char* prev = reinterpret_cast<const char*>(rows[i & 1] + DP_PAD + tid);
+            // LDS byte address of this thread's first cell in the previous row
+            const uint32_t prev = lds_addr(rows[i & 1] + DP_PAD + tid);
             double* cur = rows[(i + 1) & 1] + DP_PAD + tid;
-            const uint32_t n = __builtin_amdgcn_readfirstlane(n_next);
-            const uint32_t vw = vw_next;
-            const double ve = ve_next;
-            n_next = b1 - b0;
-            fetch_list(b0, b1, vw_next, ve_next);
-            b0 = loff[min(i - i0 + 2u, g)]; b1 = loff[min(i - i0 + 3u, g)];
-            const int ve_lo = (int)(uint32_t)__double_as_longlong(ve), ve_hi = (int)((uint64_t)__double_as_longlong(ve) >> 32);
+            const uint32_t nt = nt_cur;
+            const uint4 R0 = Rn[0], R1 = Rn[1], R2 = Rn[2], R3 = Rn[3];
+            first += DP_UNROLL * nt;
+            fetch_layer(first, Rn);
+            nt_cur = nt_n1;
+            nt_n1 = __builtin_amdgcn_readfirstlane(nt_n2);
+            nt_n2 = ltr[min(i - i0 + 3u, g)];
             double best[CPT];
 #pragma unroll
             for (int m = 0; m < CPT; ++m) best[m] = DP_INF;
-            // DP_UNROLL entries per trip: all their row reads are issued before the first add.  Lanes
-            // past the list hold (cost 0, +inf), so a padded trip changes nothing.
-            for (uint32_t k0 = 0; k0 < n; k0 += DP_UNROLL) {
-                double e[DP_UNROLL], p[DP_UNROLL][CPT];
-#pragma unroll
-                for (int u = 0; u < (int)DP_UNROLL; ++u) {
-                    const uint32_t w8 = (uint32_t)__builtin_amdgcn_readlane((int)vw, (int)(k0 + u));
-                    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(ve_lo, (int)(k0 + u));
-                    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane(ve_hi, (int)(k0 + u));
-                    e[u] = __longlong_as_double((long long)(((uint64_t)hi << 32) | lo));
-                    const char* q = prev - w8;
-#pragma unroll
-                    for (int m = 0; m < CPT; ++m)
-                        p[u][m] = *reinterpret_cast<const double*>(q + (size_t)m * DP_FWD_THREADS * 8u);
-                }
-#pragma unroll
-                for (int u = 0; u < (int)DP_UNROLL; ++u) {
-#pragma unroll
-                    for (int m = 0; m < CPT; ++m) best[m] = min_f64(best[m], p[u][m] + e[u]);
+            // trips in blocks of four: one register set of records per block
+            if (nt) {
+                uint4 Q0 = R0, Q1 = R1, Q2 = R2, Q3 = R3;
+                uint32_t rem = nt;
+                double p[4][CPT];
+                for (;;) {
+                    const double err = rec_err(Q0);
+                    dp_issue<NT, CPT, 0>(Q0.z, prev, p);
+                    dp_consume<CPT, 0>(p, err, one, best);
+                    if (rem == 1) break;
+                    dp_issue<NT, CPT, 1>(Q0.z, prev, p);
+                    dp_consume<CPT, 1>(p, err, one, best);
+                    if (rem == 2) break;
+                    dp_issue<NT, CPT, 2>(Q0.z, prev, p);
+                    dp_consume<CPT, 2>(p, err, one, best);
+                    if (rem == 3) break;
+                    dp_issue<NT, CPT, 3>(Q0.z, prev, p);
+                    dp_consume<CPT, 3>(p, err, one, best);
+                    if (rem == 4) break;
+                    rem -= 4u;
+                    Q0 = Q1; Q1 = Q2; Q2 = Q3;
                 }
             }
             double* out = rows_g + (size_t)(i + 1) * rstride + tid;
 #pragma unroll
             for (int m = 0; m < CPT; ++m) {
-                cur[m * DP_FWD_THREADS] = best[m];
-                if (tid + m * DP_FWD_THREADS < ncell) out[m * DP_FWD_THREADS] = best[m];
+                cur[m * NT] = best[m];
+                if (tid + m * NT < ncell) out[m * NT] = best[m];
             }
             lds_barrier();
         }
+        __syncthreads();                         // the next group overwrites the records
         i0 += g;
     }
 }

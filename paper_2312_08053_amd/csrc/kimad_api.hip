@@ -550,15 +550,16 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
         double* rows_g = at<double>(p, lo.rows_g);
         const uint32_t rstride = (uint32_t)lo.rstride;
         KLAUNCH(p, s, "k_dp_prep", k_dp_prep, dim3(lo.L), dim3(64), ab, dl);
-        const uint32_t cpt = (uint32_t)((cap + 1 + DP_FWD_THREADS - 1) / DP_FWD_THREADS);
+        // 512 threads: two waves per SIMD leave each thread the registers for two trips in flight
+        const uint32_t cpt = (uint32_t)((cap + 1 + 511) / 512);
         if (cpt <= 2) {
-            KLAUNCH(p, s, "k_dp_forward", k_dp_forward<2>, dim3(1), dim3(DP_FWD_THREADS), ab, (const uint32_t*)dl.w,
+            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 2>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
                     (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
         } else if (cpt <= 4) {
-            KLAUNCH(p, s, "k_dp_forward", k_dp_forward<4>, dim3(1), dim3(DP_FWD_THREADS), ab, (const uint32_t*)dl.w,
+            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 4>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
                     (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
         } else {
-            KLAUNCH(p, s, "k_dp_forward", k_dp_forward<6>, dim3(1), dim3(DP_FWD_THREADS), ab, (const uint32_t*)dl.w,
+            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 6>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
                     (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
         }
         KLAUNCH(p, s, "k_dp_choice", k_dp_choice, dim3(cell_blocks, lo.L), dim3(256), ab, dl, (const double*)rows_g, rstride);
