@@ -427,30 +427,45 @@ __global__ __launch_bounds__(1024) void k_dp_walk(AllocBuffers ab, const double*
         return;
     }
     // back-tracking: stage the choice rows and the candidates' costs of a group of layers in LDS,
-    // walk them, next group
+    // walk them, next group.  Choice rows are contiguous in memory (pitch ab.stride, a multiple of
+    // 16 bytes), so a group is one flat copy with every load in flight at once.
+    const uint32_t pitch = (uint32_t)ab.stride;
     const uint32_t wbytes = 4u * ab.J;
-    const uint32_t per_layer = (ncell + wbytes + 3u) & ~3u;
-    const uint32_t per_group = DP_STAGE_BYTES / per_layer;
+    const uint32_t per_group = DP_STAGE_BYTES / (pitch + wbytes);
     uint32_t hi = ab.L;
     while (hi > 0) {
         const uint32_t lo_l = hi > per_group ? hi - per_group : 0u;
+        const uint32_t nrows = hi - lo_l;
+        uint8_t* wpart = stage + (size_t)per_group * pitch;
         __syncthreads();
-        // one wave per layer row, four cells per lane and trip (rows start on 4-byte boundaries)
-        for (uint32_t i = tid >> 6; i < hi - lo_l; i += 16) {
-            const uint32_t* src = reinterpret_cast<const uint32_t*>(ab.choice + (size_t)(lo_l + i) * ab.stride);
-            uint32_t* dst = reinterpret_cast<uint32_t*>(stage + i * per_layer + wbytes);
-            for (uint32_t x = tid & 63u; x < (ncell + 3u) / 4u; x += 64) dst[x] = src[x];
-            uint32_t* dw = reinterpret_cast<uint32_t*>(stage + i * per_layer);
-            for (uint32_t j = tid & 63u; j < ab.J; j += 64) dw[j] = wall[(size_t)(lo_l + i) * ab.J + j];
+        {
+            const uint4* src = reinterpret_cast<const uint4*>(ab.choice + (size_t)lo_l * pitch);
+            uint4* dst = reinterpret_cast<uint4*>(stage);
+            const uint32_t n16 = nrows * (pitch / 16u);
+            for (uint32_t x0 = 0; x0 < n16; x0 += 8u * 1024u) {
+                uint4 v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const uint32_t x = x0 + k * 1024u + tid;
+                    v[k] = x < n16 ? src[x] : make_uint4(0u, 0u, 0u, 0u);
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const uint32_t x = x0 + k * 1024u + tid;
+                    if (x < n16) dst[x] = v[k];
+                }
+            }
+            const uint32_t* wsrc = wall + (size_t)lo_l * ab.J;
+            uint32_t* wdst = reinterpret_cast<uint32_t*>(wpart);
+            for (uint32_t x = tid; x < nrows * ab.J; x += 1024) wdst[x] = wsrc[x];
         }
         __syncthreads();
         if (tid == 0) {
             uint64_t c = cstar;
             for (uint32_t i = hi; i-- > lo_l;) {
-                const uint8_t* row = stage + (i - lo_l) * per_layer;
-                const uint32_t j = row[wbytes + c];
+                const uint32_t j = stage[(size_t)(i - lo_l) * pitch + c];
                 ab.j_out[i] = (int32_t)j;
-                c -= reinterpret_cast<const uint32_t*>(row)[j];
+                c -= reinterpret_cast<const uint32_t*>(wpart)[(i - lo_l) * ab.J + j];
             }
             cstar = c;
         }

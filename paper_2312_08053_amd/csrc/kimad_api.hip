@@ -538,7 +538,7 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     ab.E = err_table; ab.Ktab = at<uint32_t>(p, lo.ktab); ab.L = lo.L; ab.J = lo.J;
     ab.unit = unit; ab.cap = (uint32_t)cap;
     ab.row0 = at<double>(p, lo.row0); ab.row1 = at<double>(p, lo.row1);
-    ab.choice = at<uint8_t>(p, lo.choice); ab.stride = align_up(lo.dp_cells);
+    ab.choice = at<uint8_t>(p, lo.choice); ab.stride = align_up(cap + 1);   // row pitch: <= align_up(lo.dp_cells), as allocated
     ab.j_out = j_out; ab.K_out = K_out; ab.offsets_out = offsets_out; ab.status = status_out;
     ab.flags = at<uint32_t>(p, lo.dp_flags);
     mark(p, s, "begin");
