@@ -23,7 +23,7 @@ constexpr uint32_t SMALL_MAX = 8192;          // layers up to this size are sort
 constexpr uint32_t CHUNK = 1024;              // elements one wave compacts at a time (4 quads per lane)
 constexpr uint32_t NQ = CHUNK / 256;          // quads per lane and chunk
 constexpr uint32_t CBLOCK = 1024;             // chunks per chunk block (one workgroup scans one block)
-constexpr uint32_t PRE_SLOTS = 96;            // digit-2 slots the single-pass profile can hold in LDS
+constexpr uint32_t PRE_SLOTS = 108;           // digit-2 slots the single-pass profile can hold in LDS
 constexpr uint32_t SLOT_STRIDE = PRE_SLOTS + 64;  // slots per layer in the global digit-2 tables: 0..95 fixed
                                               // before a pass, 96..159 found after it (filled from candidates)
 // LDS entry of a slot in the single-pass profile: [count:20 | sum of (significand^2 >> 24):44]
@@ -62,7 +62,8 @@ struct LayerState {
     uint32_t redo;         // prediction missed: digit 2 is recounted by a full pass over this layer
     uint32_t spill_cnt;    // entries in the candidate region
     uint32_t spill_valid;  // the region holds every entry with bin >= spill_bin, in index order per chunk
-    uint32_t pad[2];
+    uint32_t slot_lo;      // single-pass profile: the predicted slots 0..nslots_d-1 are the bins slot_lo, slot_lo+1, ...
+    uint32_t pad;
 };
 
 // Per big layer, what the compaction pass needs.
@@ -252,6 +253,28 @@ __device__ __forceinline__ uint32_t wave_max_over_groups(uint32_t v) {
 
 // Block-wide exclusive scan over one value per thread (any block size that is a multiple of 64,
 // up to 1024).  `scratch` needs 16 entries.  Returns the exclusive prefix; *total gets the sum.
+// Inclusive add-scan of a 32-bit value over the 64 lanes with DPP shifts: no LDS traffic and six
+// vector instructions (the shuffle version costs twelve plus six LDS permutes).  Lanes without a
+// source keep their value.  A DPP operand must not be read within two cycles of the vector
+// instruction that wrote it; the compiler does not know that this assembly reads through DPP, so
+// the waits are written out, before the first step as well.
+__device__ __forceinline__ uint32_t wave_scan_add_u32(uint32_t v) {
+    asm("s_nop 1\n\t"
+        "v_add_u32_dpp %0, %0, %0 row_shr:1 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_u32_dpp %0, %0, %0 row_shr:2 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_u32_dpp %0, %0, %0 row_shr:4 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_u32_dpp %0, %0, %0 row_shr:8 row_mask:0xf bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_u32_dpp %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\t"
+        "s_nop 1\n\t"
+        "v_add_u32_dpp %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf"
+        : "+v"(v));
+    return v;
+}
+
 template <typename T>
 __device__ __forceinline__ T wave_inclusive_scan(T v) {
 #pragma unroll

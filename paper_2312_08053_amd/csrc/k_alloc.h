@@ -154,17 +154,19 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 //                  result as an add
 // Both forms were checked against a 64-lane test pattern on gfx950.  They are written as inline
 // assembly: when the compiler folds a DPP move into a subtraction itself, the instruction it emits
-// applied the broadcast to the other operand in that test.
+// applied the broadcast to the other operand in that test.  Each waits two cycles first: a DPP
+// operand must not be read directly after the vector instruction that wrote it, and the compiler
+// does not know that the assembly reads through DPP.
 template <int K>
 __device__ __forceinline__ uint32_t row_addr_sub(uint32_t base, uint32_t neg_cost) {
     uint32_t r;
-    asm("v_add_u32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+    asm("s_nop 1\n\tv_add_u32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
         : "=v"(r) : "v"(neg_cost), "v"(base), "n"(K));
     return r;
 }
 template <int K>
 __device__ __forceinline__ double acc_rec_error(double t, double err, double one) {
-    asm("v_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+    asm("s_nop 1\n\tv_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
         : "+v"(t) : "v"(err), "v"(one), "n"(K));
     return t;
 }

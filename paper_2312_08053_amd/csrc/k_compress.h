@@ -45,7 +45,6 @@ struct CompressBuffers {
     // candidate buffer
     uint32_t* tmp_idx;
     float* tmp_x;
-    float* tmp_h;
     const LayerState* state;      // fused-profile state (spill range) per big layer
     // outputs
     const uint64_t* K;
@@ -202,7 +201,6 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb, int32_t err
                         const uint64_t o = base + pos;
                         cb.tmp_idx[o] = vbase + u * 256u + lane * 4u + c - L.mis;
                         cb.tmp_x[o] = q[u].g[c] - q[u].h[c];
-                        cb.tmp_h[o] = q[u].h[c];
                     }
                     ++pos;
                 }
@@ -407,8 +405,8 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
     for (uint32_t k0 = 0; k0 < cmax; k0 += SUB) {
         const uint32_t k = k0 + g.sub;
         const bool in = k < cnt;
-        uint32_t idx = 0; float x = 0.f, hv = 0.f;
-        if (in) { idx = cb.tmp_idx[src + k]; x = cb.tmp_x[src + k]; hv = cb.tmp_h[src + k]; }
+        uint32_t idx = 0; float x = 0.f;
+        if (in) { idx = cb.tmp_idx[src + k]; x = cb.tmp_x[src + k]; }
         const uint32_t key = key_of(x);
         const bool iseq = in && filter && key == tau;
         const uint32_t eqm = ballot_sub(g, iseq);
@@ -420,7 +418,7 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
             const uint64_t o = dst + pos;
             cb.idx_out[o] = idx;
             cb.val_out[o] = x;
-            gstore(h + idx, hv + x);
+            gstore(h + idx, gload(h + idx) + x);   // the estimator is read here: candidates carry (index, x) only
         }
         out_run += __popc(km);
     }

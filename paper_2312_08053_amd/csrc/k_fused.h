@@ -166,27 +166,35 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
         }
     }
     __syncthreads();
-    // (4) slots for the marked bins, lowest bins first (they hold the most entries), at most PRE_SLOTS;
-    // what is cut off lies in the spilled range or makes the layer a redo
+    // (4) slots: one run of consecutive bins from the lowest marked bin (low bins hold the most
+    // entries) to the highest, at most PRE_SLOTS.  A run lets the streaming pass find an entry's slot
+    // with a subtraction instead of a table look-up; what is cut off at the top lies in the spilled
+    // range or makes the layer a redo.
     uint8_t* lut = pb.lut1 + (size_t)big * D1_BINS;
     for (uint32_t b = tid; b < D1_BINS; b += 256) lut[b] = (uint8_t)NO_SLOT;
     __syncthreads();
     if (tid == 0) {
-        uint32_t ns = 0;
-        for (uint32_t w = 0; w < D1_BINS / 32 && ns < PRE_SLOTS; ++w) {
-            uint32_t m = bitmap[w];
-            while (m && ns < PRE_SLOTS) {
-                const uint32_t bit = (uint32_t)__ffs((int)m) - 1u;
-                m &= m - 1u;
-                const uint32_t b = w * 32u + bit;
-                lut[b] = (uint8_t)ns;
-                pb.slot_bin[(size_t)big * SLOT_STRIDE + ns] = b;
-                ++ns;
+        uint32_t lo_bin = D1_BINS, hi_bin = 0;
+        for (uint32_t w = 0; w < D1_BINS / 32; ++w) {
+            const uint32_t m = bitmap[w];
+            if (m) {
+                if (lo_bin == D1_BINS) lo_bin = w * 32u + (uint32_t)__ffs((int)m) - 1u;
+                hi_bin = w * 32u + 31u - (uint32_t)__clz((int)m);
             }
+        }
+        uint32_t ns = 0;
+        if (lo_bin < D1_BINS) {
+            ns = min(PRE_SLOTS, hi_bin - lo_bin + 1u);
+            for (uint32_t k = 0; k < ns; ++k) {
+                lut[lo_bin + k] = (uint8_t)k;
+                pb.slot_bin[(size_t)big * SLOT_STRIDE + k] = lo_bin + k;
+            }
+        } else {
+            lo_bin = 0;
         }
         LayerState st;
         st.spill_bin = spill_bin; st.nslots_d = ns; st.nslots_t = 0; st.redo = 0;
-        st.spill_cnt = 0; st.spill_valid = 0; st.pad[0] = st.pad[1] = 0;
+        st.spill_cnt = 0; st.spill_valid = 0; st.slot_lo = lo_bin; st.pad = 0;
         pb.state[big] = st;
     }
 }
@@ -215,27 +223,30 @@ __device__ __forceinline__ unsigned long long pk_term(uint32_t key) {
 struct MainCtx {
     unsigned long long* pk;
     unsigned long long* sq0;
-    const uint8_t* lut;
+    uint32_t lo19;         // 19-bit key prefix of the first digit-2 entry of the first slot
+    uint32_t span;         // digit-2 entries of all slots: a key is in a slot bin iff (key >> 12) - lo19 < span
     uint32_t spill_key;
 };
 
-// histogram updates and spill flags of one chunk.  All 16 table look-ups first (the LDS reads are
-// issued together), then the atomics.  A chunk that lies inside the layer and holds only normal
-// numbers (no zeros, denormals, Inf, NaN) takes a branch-free path.
+// LDS entry of a key: inside the run of slot bins the digit-2 entries of consecutive bins are
+// consecutive 19-bit prefixes, so the entry is the prefix minus the run's first one
+__device__ __forceinline__ uint32_t main_entry(const MainCtx& cx, uint32_t k) {
+    const uint32_t rel = (k >> D2_SHIFT) - cx.lo19;
+    return rel < cx.span ? D1_BINS + rel : (k >> D1_SHIFT);
+}
+
+// histogram updates and spill flags of one chunk.  A chunk that lies inside the layer and holds
+// only normal numbers (no zeros, denormals, Inf, NaN) takes a branch-free path.
 __device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[NQ], uint32_t valid,
                                            uint32_t (&selm)[NQ]) {
-    uint32_t slots[NQ];                        // four table bytes per quad, packed
     uint32_t special = 0;
 #pragma unroll
     for (int u = 0; u < (int)NQ; ++u) {
-        uint32_t p = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
-            p |= (uint32_t)cx.lut[k >> D1_SHIFT] << (8 * c);
             special |= (k - 0x00800000u >= 0x7F000000u) ? 1u : 0u;     // exponent field 0 or 255
         }
-        slots[u] = p;
     }
     const bool plain = ballot(special != 0u || valid != (1u << (4 * NQ)) - 1u) == 0;
     if (plain) {
@@ -245,12 +256,9 @@ __device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
-                const uint32_t slot = (slots[u] >> (8 * c)) & 0xFFu;
-                const uint32_t sub = D1_BINS + slot * D2_BINS + ((k >> D2_SHIFT) & (D2_BINS - 1));
-                const uint32_t e = slot == NO_SLOT ? (k >> D1_SHIFT) : sub;
                 const uint32_t m24 = (k & 0x7FFFFFu) | 0x800000u;
                 const unsigned long long t = ((unsigned long long)m24 * m24) >> PK_SHIFT;
-                atomicAdd(&cx.pk[e], PK_ONE | t);
+                atomicAdd(&cx.pk[main_entry(cx, k)], PK_ONE | t);
                 sel |= (k >= cx.spill_key ? 1u : 0u) << c;
             }
             selm[u] = sel;
@@ -264,11 +272,8 @@ __device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[
         for (int c = 0; c < 4; ++c) {
             if (!(valid & (1u << (4 * u + c)))) continue;
             const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
-            const uint32_t bin = k >> D1_SHIFT;
-            const uint32_t slot = (slots[u] >> (8 * c)) & 0xFFu;
-            const uint32_t e = slot == NO_SLOT ? bin : D1_BINS + slot * D2_BINS + ((k >> D2_SHIFT) & (D2_BINS - 1));
-            if (bin != 0u) {
-                atomicAdd(&cx.pk[e], PK_ONE | pk_term(k));
+            if ((k >> D1_SHIFT) != 0u) {
+                atomicAdd(&cx.pk[main_entry(cx, k)], PK_ONE | pk_term(k));
             } else {
                 atomicAdd(&cx.pk[0], PK_ONE);
                 if (k) atomicAdd(cx.sq0, sq_exact(k));
@@ -289,9 +294,7 @@ __device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[
 constexpr uint32_t PEND = 16;                   // chunk records a wave holds back
 
 struct WaveSpill {
-    uint32_t* win_i;      // LDS window of the current block: indices
-    float* win_x;
-    float* win_h;
+    uint2* win;           // LDS window of the current block: (index, bits of x)
     uint32_t* pend;       // LDS: PEND x (chunk, start, count)
     uint32_t* lds_cursor; // blocks handed out in this workgroup's slice
     uint64_t slice0;      // first entry of the slice in the candidate buffer
@@ -315,9 +318,9 @@ __device__ __forceinline__ void spill_flush(const ProfileBuffers& pb, WaveSpill&
     if (ws.have_blk) {
         for (uint32_t k = ws.flushed + lane; k < ws.fill; k += 64) {
             const uint64_t o = tmp0 + ws.blk + k;
-            pb.tmp_idx[o] = ws.win_i[k];
-            pb.tmp_x[o] = ws.win_x[k];
-            pb.tmp_h[o] = ws.win_h[k];
+            const uint2 e = ws.win[k];
+            pb.tmp_idx[o] = e.x;
+            pb.tmp_x[o] = __uint_as_float(e.y);
         }
         ws.flushed = ws.fill;
     }
@@ -346,14 +349,19 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
     const uint32_t vbase = (chunk - L.chunk0) * CHUNK;
     uint32_t selm[NQ];
     main_count(cx, q, valid, selm);
-    uint32_t total = 0, rowbase[NQ];
-#pragma unroll
-    for (int u = 0; u < (int)NQ; ++u) {
-        const uint32_t n1 = __popc(selm[u]);
-        const uint64_t b0 = ballot(n1 & 1u), b1 = ballot(n1 & 2u), b2 = ballot(n1 & 4u);
-        rowbase[u] = total + mbcnt(b0) + 2u * mbcnt(b1) + 4u * mbcnt(b2);
-        total += (uint32_t)__popcll(b0) + 2u * (uint32_t)__popcll(b1) + 4u * (uint32_t)__popcll(b2);
-    }
+    // ranks in index order (quad, lane, element): per quad a prefix sum over the lanes of the lane's
+    // count (0..4); two quads share a scan in 16-bit fields (a quad holds at most 256)
+    static_assert(NQ == 4, "two packed scans cover four quads");
+    const uint32_t n0 = __popc(selm[0]), n1 = __popc(selm[1]), n2 = __popc(selm[2]), n3 = __popc(selm[3]);
+    const uint32_t s01 = wave_scan_add_u32(n0 | (n1 << 16)), s23 = wave_scan_add_u32(n2 | (n3 << 16));
+    const uint32_t t01 = (uint32_t)__builtin_amdgcn_readlane((int)s01, 63), t23 = (uint32_t)__builtin_amdgcn_readlane((int)s23, 63);
+    const uint32_t t0 = t01 & 0xFFFFu, t1 = t01 >> 16, t2 = t23 & 0xFFFFu;
+    const uint32_t total = t0 + t1 + t2 + (t23 >> 16);
+    uint32_t rowbase[NQ];
+    rowbase[0] = (s01 & 0xFFFFu) - n0;
+    rowbase[1] = t0 + (s01 >> 16) - n1;
+    rowbase[2] = t0 + t1 + (s23 & 0xFFFFu) - n2;
+    rowbase[3] = t0 + t1 + t2 + (s23 >> 16) - n3;
     if (total == 0) return;                      // records start out as "nothing spilled"
     if (total <= STAGE) {
         if (!ws.have_blk || ws.fill + total > STAGE || ws.npend == PEND) {
@@ -370,9 +378,7 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 if (selm[u] & (1u << c)) {
-                    ws.win_i[pos] = vbase + u * 256u + lane * 4u + c - L.mis;
-                    ws.win_x[pos] = q[u].g[c] - q[u].h[c];
-                    ws.win_h[pos] = q[u].h[c];
+                    ws.win[pos] = make_uint2(vbase + u * 256u + lane * 4u + c - L.mis, __float_as_uint(q[u].g[c] - q[u].h[c]));
                     ++pos;
                 }
             }
@@ -399,9 +405,7 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
                     if (selm[u] & (1u << c)) {
                         const uint32_t k = pos - r0;
                         if (k < STAGE) {
-                            ws.win_i[k] = vbase + u * 256u + lane * 4u + c - L.mis;
-                            ws.win_x[k] = q[u].g[c] - q[u].h[c];
-                            ws.win_h[k] = q[u].h[c];
+                            ws.win[k] = make_uint2(vbase + u * 256u + lane * 4u + c - L.mis, __float_as_uint(q[u].g[c] - q[u].h[c]));
                         }
                         ++pos;
                     }
@@ -412,9 +416,9 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
             for (uint32_t k = lane; k < STAGE; k += 64) {
                 if (r0 + k < total) {
                     const uint64_t o = base + r0 + k;
-                    pb.tmp_idx[o] = ws.win_i[k];
-                    pb.tmp_x[o] = ws.win_x[k];
-                    pb.tmp_h[o] = ws.win_h[k];
+                    const uint2 e = ws.win[k];
+                    pb.tmp_idx[o] = e.x;
+                    pb.tmp_x[o] = __uint_as_float(e.y);
                 }
             }
             wave_sync_lds();
@@ -426,10 +430,7 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
 __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint32_t chunks_per_wg) {
     __shared__ unsigned long long pk[PK_ENTRIES];                 // 128 KB
     __shared__ unsigned long long sq0;
-    __shared__ uint8_t lut[D1_BINS];                              // 4 KB
-    __shared__ uint32_t stage_i[FUSED_WAVES * STAGE];             // 3 x 8 KB: per-wave block windows
-    __shared__ float stage_x[FUSED_WAVES * STAGE];
-    __shared__ float stage_h[FUSED_WAVES * STAGE];
+    __shared__ uint2 stage[FUSED_WAVES * STAGE];                  // 16 KB: per-wave block windows
     __shared__ uint32_t pend[FUSED_WAVES * PEND * 3];             // 3 KB
     __shared__ uint32_t lds_cursor;
     const uint32_t tid = threadIdx.x, wave = tid >> 6;
@@ -445,17 +446,13 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         const uint32_t used = D1_BINS + st.nslots_d * D2_BINS;
         for (uint32_t b = tid; b < used; b += FUSED_THREADS) pk[b] = 0ull;
         if (tid == 0) { sq0 = 0ull; lds_cursor = 0u; }
-        {
-            const uint32_t* src = reinterpret_cast<const uint32_t*>(pb.lut1 + (size_t)big * D1_BINS);
-            uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
-            for (uint32_t b = tid; b < D1_BINS / 4; b += FUSED_THREADS) dst[b] = src[b];
-        }
         __syncthreads();
         MainCtx cx;
-        cx.pk = pk; cx.sq0 = &sq0; cx.lut = lut;
+        cx.pk = pk; cx.sq0 = &sq0;
+        cx.lo19 = st.slot_lo << (D1_SHIFT - D2_SHIFT); cx.span = st.nslots_d * D2_BINS;
         cx.spill_key = st.spill_bin >= D1_BINS ? 0x80000000u : (st.spill_bin << D1_SHIFT);
         WaveSpill ws;
-        ws.win_i = stage_i + wave * STAGE; ws.win_x = stage_x + wave * STAGE; ws.win_h = stage_h + wave * STAGE;
+        ws.win = stage + wave * STAGE;
         ws.pend = pend + wave * PEND * 3; ws.lds_cursor = &lds_cursor;
         ws.slice_rel = (cur - L.chunk0) * CHUNK; ws.slice0 = L.tmp0 + ws.slice_rel;
         ws.blk = 0; ws.fill = 0; ws.flushed = 0; ws.npend = 0; ws.have_blk = false;

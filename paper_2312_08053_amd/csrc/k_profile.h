@@ -59,7 +59,6 @@ struct ProfileBuffers {
     uint32_t* rec_cnt;            // per chunk: candidates written
     uint32_t* tmp_idx;
     float* tmp_x;
-    float* tmp_h;
 };
 
 constexpr uint32_t POOL_MAX = 256;
@@ -203,7 +202,7 @@ __global__ __launch_bounds__(256) void k_scan1(ProfileBuffers pb, const uint32_t
         pb.nslots[big] = ns;
         LayerState st;
         st.spill_bin = D1_BINS; st.nslots_d = ns; st.nslots_t = 0; st.redo = 1;
-        st.spill_cnt = 0; st.spill_valid = 0; st.pad[0] = st.pad[1] = 0;
+        st.spill_cnt = 0; st.spill_valid = 0; st.slot_lo = 0; st.pad = 0;
         pb.state[big] = st;
     }
 }

@@ -45,7 +45,7 @@ struct Layout {
     // compress
     uint64_t ksel, sel, zero2_begin, hist3, zero2_end, tau, quota, cblk_big;
     uint64_t rec_start, rec_cnt, rec_amb, c_gt, c_eq, o_base, o_allow;
-    uint64_t tmp_idx, tmp_x, tmp_h;
+    uint64_t tmp_idx, tmp_x;
     // allocation
     uint64_t row0, row1, choice, dp_flags, dl_wall, dl_w, dl_jj, dl_e, dl_n, dl_bad, rows_g;
     uint64_t rstride = 0;            // cells per stored DP row (LDS-resident recurrence only)
@@ -182,7 +182,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     const uint64_t ncb = 4ull * (nc ? nc : 1);
     lo.rec_start = take(ncb); lo.rec_amb = take(ncb);
     lo.c_gt = take(ncb); lo.c_eq = take(ncb); lo.o_base = take(ncb); lo.o_allow = take(ncb);
-    lo.tmp_idx = take(4 * lo.tmp_cap); lo.tmp_x = take(4 * lo.tmp_cap); lo.tmp_h = take(4 * lo.tmp_cap);
+    lo.tmp_idx = take(4 * lo.tmp_cap); lo.tmp_x = take(4 * lo.tmp_cap);
     lo.row0 = take(8 * lo.dp_cells);
     lo.row1 = take(8 * lo.dp_cells);
     lo.choice = take((uint64_t)L * align_up(lo.dp_cells));
@@ -446,7 +446,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.lutc = at<uint8_t>(p, lo.lutc); pb.cursor = at<uint32_t>(p, lo.cursor);
     pb.spill_over = at<uint32_t>(p, lo.spill_over);
     pb.rec_start = at<uint32_t>(p, lo.rec_start); pb.rec_cnt = at<uint32_t>(p, lo.rec_cnt);
-    pb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); pb.tmp_x = at<float>(p, lo.tmp_x); pb.tmp_h = at<float>(p, lo.tmp_h);
+    pb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); pb.tmp_x = at<float>(p, lo.tmp_x);
     {
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device) != hipSuccess || cus <= 0) cus = 256;
@@ -471,7 +471,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     cb.rec_amb = at<uint32_t>(p, lo.rec_amb); cb.c_gt = at<uint32_t>(p, lo.c_gt); cb.c_eq = at<uint32_t>(p, lo.c_eq);
     cb.o_base = at<uint32_t>(p, lo.o_base); cb.o_allow = at<uint32_t>(p, lo.o_allow);
     cb.cblk_big = at<uint32_t>(p, lo.cblk_big);
-    cb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); cb.tmp_x = at<float>(p, lo.tmp_x); cb.tmp_h = at<float>(p, lo.tmp_h);
+    cb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); cb.tmp_x = at<float>(p, lo.tmp_x);
     cb.state = pb.state;
     cb.K = nullptr; cb.offsets = nullptr; cb.idx_out = nullptr; cb.val_out = nullptr; cb.capacity_pairs = 0;
     cb.status = nullptr;
