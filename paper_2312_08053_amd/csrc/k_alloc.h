@@ -149,27 +149,36 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 
 // A wave holds 16 list records per register set, record k in lane k of every 16-lane row, and
 // uses them through DPP row_newbcast operands, which hand lane K of each row to all its lanes:
-//   row_addr_sub   LDS address of the row cell minus record K's cost (v_add_u32 with the negated cost)
-//   acc_rec_error  t += record K's error, as fma(error, 1.0, t): one rounding of the exact sum, the same
+//   row_addr_sub4  LDS address of the row cell minus record K's cost (v_add_u32 with the negated cost)
+//   acc_rec_error4 t += record K's error, as fma(error, 1.0, t): one rounding of the exact sum, the same
 //                  result as an add
-// Both forms were checked against a 64-lane test pattern on gfx950.  They are written as inline
-// assembly: when the compiler folds a DPP move into a subtraction itself, the instruction it emits
+// Both forms were checked against a 64-lane test pattern on gfx950, four records per call.  They
+// are written as inline assembly: when the compiler folds a DPP move into a subtraction itself, the instruction it emits
 // applied the broadcast to the other operand in that test.  Each waits two cycles first: a DPP
 // operand must not be read directly after the vector instruction that wrote it, and the compiler
 // does not know that the assembly reads through DPP.
 template <int K>
-__device__ __forceinline__ uint32_t row_addr_sub(uint32_t base, uint32_t neg_cost) {
-    uint32_t r;
-    asm("s_nop 1\n\tv_add_u32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
-        : "=v"(r) : "v"(neg_cost), "v"(base), "n"(K));
-    return r;
+__device__ __forceinline__ void row_addr_sub4(uint32_t base, uint32_t neg_cost, uint32_t (&q)[4]) {
+    asm("s_nop 1\n\t"
+        "v_add_u32_dpp %0, %4, %5 row_newbcast:%6 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "v_add_u32_dpp %1, %4, %5 row_newbcast:%7 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "v_add_u32_dpp %2, %4, %5 row_newbcast:%8 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "v_add_u32_dpp %3, %4, %5 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+        : "=&v"(q[0]), "=&v"(q[1]), "=&v"(q[2]), "=&v"(q[3])
+        : "v"(neg_cost), "v"(base), "n"(K), "n"(K + 1), "n"(K + 2), "n"(K + 3));
 }
+// t[u] += error of record K+u, four records at once (one wait for all of them)
 template <int K>
-__device__ __forceinline__ double acc_rec_error(double t, double err, double one) {
-    asm("s_nop 1\n\tv_fmac_f64_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
-        : "+v"(t) : "v"(err), "v"(one), "n"(K));
-    return t;
+__device__ __forceinline__ void acc_rec_error4(double (&t)[4], double err, double one) {
+    asm("s_nop 1\n\t"
+        "v_fmac_f64_dpp %0, %4, %5 row_newbcast:%6 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "v_fmac_f64_dpp %1, %4, %5 row_newbcast:%7 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "v_fmac_f64_dpp %2, %4, %5 row_newbcast:%8 row_mask:0xf bank_mask:0xf bound_ctrl:1\n\t"
+        "v_fmac_f64_dpp %3, %4, %5 row_newbcast:%9 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+        : "+v"(t[0]), "+v"(t[1]), "+v"(t[2]), "+v"(t[3])
+        : "v"(err), "v"(one), "n"(K), "n"(K + 1), "n"(K + 2), "n"(K + 3));
 }
+
 // LDS pointers as 32-bit byte addresses, for address arithmetic in DPP instructions.
 using lds_cdouble_ptr = const __attribute__((address_space(3))) double*;
 __device__ __forceinline__ uint32_t lds_addr(const double* p) { return (uint32_t)(size_t)(lds_cdouble_ptr)p; }
@@ -185,8 +194,8 @@ __device__ __forceinline__ double rec_err(const uint4& r) { return __hiloint2dou
 template <int NT, int CPT, int K4>
 __device__ __forceinline__ void dp_issue(uint32_t neg_cost, uint32_t prev, double (&p)[4][CPT]) {
     constexpr int K = 4 * K4;
-    const uint32_t q[4] = {row_addr_sub<K>(prev, neg_cost), row_addr_sub<K + 1>(prev, neg_cost),
-                           row_addr_sub<K + 2>(prev, neg_cost), row_addr_sub<K + 3>(prev, neg_cost)};
+    uint32_t q[4];
+    row_addr_sub4<K>(prev, neg_cost, q);
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
 #pragma unroll
@@ -200,10 +209,9 @@ __device__ __forceinline__ void dp_consume(const double (&p)[4][CPT], double err
     constexpr int K = 4 * K4;
 #pragma unroll
     for (int m = 0; m < CPT; ++m) {
-        best[m] = min_f64(best[m], acc_rec_error<K>(p[0][m], err, one));
-        best[m] = min_f64(best[m], acc_rec_error<K + 1>(p[1][m], err, one));
-        best[m] = min_f64(best[m], acc_rec_error<K + 2>(p[2][m], err, one));
-        best[m] = min_f64(best[m], acc_rec_error<K + 3>(p[3][m], err, one));
+        double t[4] = {p[0][m], p[1][m], p[2][m], p[3][m]};
+        acc_rec_error4<K>(t, err, one);
+        best[m] = min_f64(min_f64(best[m], t[0]), min_f64(t[1], min_f64(t[2], t[3])));
     }
 }
 

@@ -257,8 +257,11 @@ __device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[
             for (int c = 0; c < 4; ++c) {
                 const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
                 const uint32_t m24 = (k & 0x7FFFFFu) | 0x800000u;
-                const unsigned long long t = ((unsigned long long)m24 * m24) >> PK_SHIFT;
-                atomicAdd(&cx.pk[main_entry(cx, k)], PK_ONE | t);
+                // the shifted square has 24 bits: as a 32-bit value it is the low word of the packed
+                // operand and the count's 1 is a constant high word
+                const unsigned long long sq = (unsigned long long)m24 * m24;
+                const uint32_t t = __builtin_amdgcn_alignbit((uint32_t)(sq >> 32), (uint32_t)sq, PK_SHIFT);
+                atomicAdd(&cx.pk[main_entry(cx, k)], PK_ONE | (unsigned long long)t);
                 sel |= (k >= cx.spill_key ? 1u : 0u) << c;
             }
             selm[u] = sel;
