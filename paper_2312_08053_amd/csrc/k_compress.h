@@ -45,6 +45,7 @@ struct CompressBuffers {
     // candidate buffer
     uint32_t* tmp_idx;
     float* tmp_x;
+    uint32_t* ncompact;       // layers whose selection needs the streaming compaction pass
     const LayerState* state;      // fused-profile state (spill range) per big layer
     // outputs
     const uint64_t* K;
@@ -61,8 +62,9 @@ struct CompressBuffers {
 __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_offgrid, int32_t err_offsets,
                                                 uint32_t use_candidates) {
     __shared__ int bad;
+    __shared__ uint32_t need_pass;
     const uint32_t tid = threadIdx.x;
-    if (tid == 0) bad = 0;
+    if (tid == 0) { bad = 0; need_pass = 0u; }
     __syncthreads();
     // validate offsets / K for every layer
     for (uint32_t i = tid; i < cb.L; i += 256) {
@@ -108,8 +110,10 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
         cb.sel[b] = r;
         // the classic pass reserves its candidates from zero; the spilled ones keep their records
         if (r.mode != SEL_CAND) cb.cursor[b] = 0u;
+        if (r.mode == SEL_PREFIX || r.mode == SEL_ALL) atomicAdd(&need_pass, 1u);
     }
     __syncthreads();
+    if (tid == 0) *cb.ncompact = bad ? 0u : need_pass;
     if (bad) {
         // refuse the whole call: nothing is written by the later kernels
         for (uint32_t b = tid; b < cb.B; b += 256) { cb.sel[b].mode = SEL_NONE; cb.sel[b].cap = 0; cb.sel[b].K = 0; }
@@ -124,17 +128,21 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
 // when no fused profile preceded).  One wave per chunk; a workgroup of 4 waves walks the chunks
 // of one tile.  Each lane holds 4 quads (16 elements); positions come from ballots, so
 // the candidates of a chunk are written in index order at a range reserved with one atomic.
-__global__ __launch_bounds__(256) void k_compact(CompressBuffers cb, int32_t err_internal) {
-    const uint32_t tile = blockIdx.x;
+// Tiles are taken in a grid-stride loop; *cb.ncompact (set by k_lookup) is the number of layers that
+// need this pass, so that after a single-pass profile, when the candidates serve every layer, a
+// small grid leaves after one load.
+__global__ __launch_bounds__(256) void k_compact(CompressBuffers cb, uint32_t ntiles, int32_t err_internal) {
+    if (*cb.ncompact == 0u) return;
+    const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+    const uint32_t chunks_per_tile = cb.tile_elems / CHUNK;
+    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const uint32_t li = cb.chunk_layer[tile];
     const LayerDesc L = cb.layers[li];
     const SelRec S = cb.sel[L.big];
-    const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-    const uint32_t chunks_per_tile = cb.tile_elems / CHUNK;
     const uint32_t tile_in_layer = tile - L.tile0;
     uint32_t* hist3 = cb.hist3 + (size_t)L.big * D3_BINS;
     // layers served from the spilled candidates (or with K = 0) need no pass over g, h
-    if (S.mode == SEL_NONE || S.mode == SEL_CAND) return;
+    if (S.mode == SEL_NONE || S.mode == SEL_CAND) continue;
     WaveAlloc wa{0u, 0u};
 
     for (uint32_t cc = wave; cc < chunks_per_tile; cc += 4) {
@@ -226,6 +234,7 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb, int32_t err
                 }
             }
         }
+    }
     }
 }
 

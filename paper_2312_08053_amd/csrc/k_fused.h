@@ -524,16 +524,24 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
     if (tid == 0) sh_redo = 0u;
     __syncthreads();
 
-    // totals of the slots: one wave per slot, two digit-2 bins per lane
-    for (uint32_t slot = tid >> 6; slot < st.nslots_d; slot += 4) {
-        const uint32_t* c2 = pb.cnt2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
-        const uint64_t* s2 = pb.sq2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
-        const uint32_t l = lane_id();
-        uint32_t cc = c2[l] + c2[l + 64];
-        unsigned long long ss = s2[l] + s2[l + 64];
+    // totals of the slots: two threads per slot, 64 digit-2 bins each, every load issued at once
+    static_assert(PRE_SLOTS <= 128, "two threads per slot in a workgroup of 256");
+    {
+        const uint32_t slot = tid >> 1, half = tid & 1u;
+        uint32_t cc = 0;
+        unsigned long long ss = 0;
+        if (slot < st.nslots_d) {
+            const size_t e0 = ((size_t)big * SLOT_STRIDE + slot) * D2_BINS + half * (D2_BINS / 2);
+            const uint4* c4 = reinterpret_cast<const uint4*>(pb.cnt2 + e0);
+            const ulonglong2* s2 = reinterpret_cast<const ulonglong2*>(pb.sq2 + e0);
 #pragma unroll
-        for (int d = 32; d > 0; d >>= 1) { cc += __shfl_xor(cc, d, 64); ss += __shfl_xor(ss, d, 64); }
-        if (l == 0) { slot_c[slot] = cc; slot_s[slot] = ss; }
+            for (int k = 0; k < (int)D2_BINS / 8; ++k) { const uint4 v = c4[k]; cc += v.x + v.y + v.z + v.w; }
+#pragma unroll
+            for (int k = 0; k < (int)D2_BINS / 4; ++k) { const ulonglong2 v = s2[k]; ss += v.x + v.y; }
+        }
+        cc += __shfl_xor(cc, 1, 64);
+        ss += __shfl_xor(ss, 1, 64);
+        if (half == 0u && slot < st.nslots_d) { slot_c[slot] = cc; slot_s[slot] = ss; }
     }
     __syncthreads();
     uint32_t c[16];

@@ -209,17 +209,21 @@ __global__ __launch_bounds__(256) void k_scan1(ProfileBuffers pb, const uint32_t
 
 // ---------------------------------------------------------------------------------------------
 // Pass 2: digit-2 histograms (count + squares) of the entries that fall in a boundary bin.
-__global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb) {
+// Workgroups take tiles in a grid-stride loop.  `gate` (optional) points at a device word that is
+// zero when no layer needs this pass: the single-pass profile launches it as a fallback that
+// normally has nothing to do, with a small grid that leaves after one load.
+__global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb, uint32_t ntiles, const uint32_t* gate) {
     __shared__ unsigned long long sub[MAX_SLOTS * D2_BINS];   // 64 KB
     __shared__ unsigned long long sub0[D2_BINS];              // exact squares when the slot is bin 0
     __shared__ uint8_t lut[D1_BINS];
     const uint32_t tid = threadIdx.x;
-    const uint32_t tile = blockIdx.x;
+    if (gate && *gate == 0u) return;
+    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const uint32_t li = pb.tile_layer[tile];
     const LayerDesc L = pb.layers[li];
     const LayerState st = pb.state[L.big];
     const uint32_t ns = st.nslots_d;
-    if (!st.redo || ns == 0) return;
+    if (!st.redo || ns == 0) continue;
     {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(pb.lut1 + (size_t)L.big * D1_BINS);
         uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
@@ -269,6 +273,8 @@ __global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb) {
             if (s) atomicAdd(&sq[b], s);
         }
     }
+    __syncthreads();                            // the next tile reuses the LDS tables
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -279,46 +285,58 @@ __global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb) {
 // bounds.  Entries whose bound is not tight enough are counted in diag[0].
 __device__ __forceinline__ float prefix_lo(uint32_t prefix) { return __uint_as_float(prefix << D2_SHIFT); }
 
+// One wave per candidate: every lane holds two digit-2 bins of the candidate's boundary bin.
+// `flagged` and `prefix_out` come back the same in every lane.
 __device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uint32_t* Ktab, uint32_t J,
                                              double* err_table, double tol, uint32_t big, uint32_t li,
                                              uint32_t j, bool* flagged, uint32_t* prefix_out) {
+    const uint32_t lane = lane_id();
     const LayerDesc L = pb.layers[li];
     const size_t t = (size_t)li * J + j;
     const uint32_t K = Ktab[t];
     const uint32_t slot = pb.tgt_slot[t];
     if (slot == NO_SLOT) {                      // K == n (or K == 0): nothing / everything dropped
-        if (err_table) err_table[t] = 0.0;
-        pb.sel_prefix[t] = 0u;
-        pb.sel_above[t] = (K == 0u) ? 0u : L.n;
-        pb.sel_amb[t] = 0u;
-        pb.tgt_unsel[t] = 0u;
-        pb.tgt_base[t] = 0.0;
+        if (lane == 0) {
+            if (err_table) err_table[t] = 0.0;
+            pb.sel_prefix[t] = 0u;
+            pb.sel_above[t] = (K == 0u) ? 0u : L.n;
+            pb.sel_amb[t] = 0u;
+            pb.tgt_unsel[t] = 0u;
+            pb.tgt_base[t] = 0.0;
+        }
         return;
     }
     const uint32_t bin = pb.slot_bin[(size_t)big * SLOT_STRIDE + slot];
     const uint32_t r = pb.tgt_r[t];
-    const uint32_t* cnt = pb.cnt2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
-    const uint64_t* sq = pb.sq2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS;
-    // walk digit 2 from the top until r entries are covered
-    uint32_t acc = 0;
-    int u = (int)D2_BINS - 1;
-    for (; u > 0; --u) {
-        const uint32_t cu = cnt[u];
-        if (acc + cu >= r) break;
-        acc += cu;
-    }
-    const uint32_t m = cnt[u];
+    const uint2 c = reinterpret_cast<const uint2*>(pb.cnt2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS)[lane];
+    const ulonglong2 q = reinterpret_cast<const ulonglong2*>(pb.sq2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS)[lane];
+    // walk digit 2 from the top until r entries are covered: the boundary is the highest bin u > 0
+    // with (entries above u) + cnt[u] >= r, or bin 0
+    const uint32_t incl = wave_scan_add_u32(c.x + c.y);
+    const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+    const uint32_t above_hi = tot - incl;       // entries above bin 2*lane+1
+    const uint32_t above_lo = above_hi + c.y;   // entries above bin 2*lane
+    const uint64_t m_hi = ballot(above_hi + c.y >= r), m_lo = ballot(above_lo + c.x >= r);
+    const int u_hi = m_hi ? 2 * (63 - __clzll((long long)m_hi)) + 1 : 0;
+    const int u_lo = m_lo ? 2 * (63 - __clzll((long long)m_lo)) : 0;
+    const int u = max(u_hi, u_lo);
+    const int src = u >> 1;
+    const uint32_t acc = (u & 1) ? __shfl(above_hi, src, 64) : __shfl(above_lo, src, 64);
+    const uint32_t m = (u & 1) ? __shfl(c.y, src, 64) : __shfl(c.x, src, 64);
+    const unsigned long long squ = (u & 1) ? __shfl(q.y, src, 64) : __shfl(q.x, src, 64);
     const uint32_t rsel = r - acc;              // 1..m selected inside the prefix bin
     const uint32_t unsel = m - rsel;
-    double below2 = 0.0;
-    for (int k = 0; k < u; ++k) below2 += sq_to_double(bin, sq[k], cnt[k]);
+    double below2 = ((int)(2u * lane) < u ? sq_to_double(bin, q.x, c.x) : 0.0) +
+                    ((int)(2u * lane + 1u) < u ? sq_to_double(bin, q.y, c.y) : 0.0);
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) below2 += __shfl_xor(below2, d, 64);
     const uint32_t prefix = (bin << D2_BITS) | (uint32_t)u;
     double est = 0.0, half_gap = 0.0;
     if (unsel) {
-        const double Q = sq_to_double(bin, sq[u], m);
+        const double Q = sq_to_double(bin, squ, m);
         if ((bin >> 4) == 255u) {
             // Inf/NaN entries: the dropped ones are the lowest keys, i.e. the infinities first.
-            const uint64_t nans = sq[u];
+            const uint64_t nans = squ;
             const uint64_t infs = (uint64_t)m - nans;
             est = (uint64_t)unsel > infs ? __longlong_as_double(0x7FF8000000000000ll)
                                          : __longlong_as_double(0x7FF0000000000000ll);
@@ -336,27 +354,39 @@ __device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uin
     const double E = base + est;
     // single-pass slots hold midpoints of intervals 2^-23 wide (relative): part of the bound
     if (!pb.state[big].redo) half_gap += E * 1.2e-7;
-    if (err_table) err_table[t] = E;
-    pb.sel_prefix[t] = prefix;
-    pb.sel_above[t] = pb.tgt_above1[t] + acc;
-    pb.sel_amb[t] = m;
-    pb.tgt_unsel[t] = unsel;
-    pb.tgt_base[t] = base;
+    if (lane == 0) {
+        if (err_table) err_table[t] = E;
+        pb.sel_prefix[t] = prefix;
+        pb.sel_above[t] = pb.tgt_above1[t] + acc;
+        pb.sel_amb[t] = m;
+        pb.tgt_unsel[t] = unsel;
+        pb.tgt_base[t] = base;
+    }
     *flagged = err_table != nullptr && half_gap > tol * E;
     *prefix_out = prefix;
 }
 
-// One wave per big layer: thread j handles candidate j.  Candidates whose error bound is too
-// wide are grouped by prefix (equal prefixes are adjacent because K ascends) and each group gets
-// one pool entry for the exact last-digit pass.
-__global__ __launch_bounds__(64) void k_scan2(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
-                                              double* err_table, double tol) {
+// One workgroup per big layer, one wave per candidate at a time.  Candidates whose error bound is
+// too wide are then grouped by prefix (equal prefixes are adjacent because K ascends) and each
+// group gets one pool entry for the exact last-digit pass.
+constexpr uint32_t SCAN2_THREADS = 1024;
+__global__ __launch_bounds__(SCAN2_THREADS) void k_scan2(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
+                                                         double* err_table, double tol) {
+    __shared__ uint32_t sh_prefix[KIMAD_MAX_J_CONST];
+    __shared__ uint32_t sh_flag[KIMAD_MAX_J_CONST];
     const uint32_t big = blockIdx.x;
     const uint32_t li = pb.big_layer[big];
+    for (uint32_t jj = threadIdx.x >> 6; jj < KIMAD_MAX_J_CONST; jj += SCAN2_THREADS / 64) {
+        bool fl = false;
+        uint32_t px = 0xFFFFFFFFu - jj;         // distinct dummy for idle slots and K == n
+        if (jj < J) scan2_target(pb, Ktab, J, err_table, tol, big, li, jj, &fl, &px);
+        if (lane_id() == 0) { sh_prefix[jj] = px; sh_flag[jj] = fl ? 1u : 0u; }
+    }
+    __syncthreads();
+    if (threadIdx.x >= 64) return;
     const uint32_t j = threadIdx.x;
-    bool flagged = false;
-    uint32_t prefix = 0xFFFFFFFFu - j;          // distinct dummy for idle lanes and K == n
-    if (j < J) scan2_target(pb, Ktab, J, err_table, tol, big, li, j, &flagged, &prefix);
+    const bool flagged = sh_flag[j] != 0u;
+    const uint32_t prefix = sh_prefix[j];
     const uint32_t prev = __shfl_up(prefix, 1, 64);
     const bool head = j == 0 || prev != prefix;
     const uint64_t heads = ballot(head), flags = ballot(flagged);
@@ -383,14 +413,17 @@ __global__ __launch_bounds__(64) void k_scan2(ProfileBuffers pb, const uint32_t*
 
 // Exact fallback, pass: last-digit histogram of every pooled prefix bin.  One workgroup per tile;
 // tiles of layers without pool entries return at once.
-__global__ __launch_bounds__(256) void k_hist3p(ProfileBuffers pb) {
+__global__ __launch_bounds__(256) void k_hist3p(ProfileBuffers pb, uint32_t ntiles) {
     __shared__ uint32_t pfx[POOL_MAX];
     __shared__ uint32_t pid[POOL_MAX];
     __shared__ uint32_t npool;
-    const uint32_t tile = blockIdx.x, tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x;
+    if (pb.diag[2] == 0u) return;               // no pool entries at all: the usual case
+    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
     const uint32_t li = pb.tile_layer[tile];
     const LayerDesc L = pb.layers[li];
-    if (!pb.layer_flag[L.big]) return;
+    if (!pb.layer_flag[L.big]) continue;
+    __syncthreads();                            // the previous tile's readers are done with the lists
     if (tid == 0) npool = 0;
     __syncthreads();
     const uint32_t total = min(pb.diag[2], POOL_MAX);
@@ -428,6 +461,7 @@ __global__ __launch_bounds__(256) void k_hist3p(ProfileBuffers pb) {
                 atomicAdd(&pb.pool_hist[(size_t)f * D3_BINS + (key & (D3_BINS - 1))], 1u);
             }
         }
+    }
     }
 }
 

@@ -47,6 +47,7 @@ struct Layout {
     uint64_t rec_start, rec_cnt, rec_amb, c_gt, c_eq, o_base, o_allow;
     uint64_t tmp_idx, tmp_x;
     // allocation
+    uint64_t ncompact;
     uint64_t row0, row1, choice, dp_flags, dl_wall, dl_w, dl_jj, dl_e, dl_n, dl_bad, rows_g;
     uint64_t rstride = 0;            // cells per stored DP row (LDS-resident recurrence only)
     uint64_t total = 0;
@@ -187,6 +188,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.row1 = take(8 * lo.dp_cells);
     lo.choice = take((uint64_t)L * align_up(lo.dp_cells));
     lo.dp_flags = take(16);
+    lo.ncompact = take(16);
     lo.dl_wall = take(4 * LJ); lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
     lo.dl_bad = take(4ull * L);
     lo.rstride = (std::min<uint64_t>(lo.dp_cells, DP_PAD) + 31) & ~31ull;
@@ -201,6 +203,8 @@ kimad_config_t normalise(const kimad_config_t* cfg) {
     if (c.pair_bytes == 0) c.pair_bytes = 8;
     return c;
 }
+
+constexpr uint32_t FALLBACK_GRID = 1024;   // workgroups of a pass that usually has nothing to do
 
 __global__ __launch_bounds__(256) void k_zero16(uint4* p, uint64_t n16) {
     const uint64_t stride = (uint64_t)gridDim.x * 256u;
@@ -300,11 +304,11 @@ int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, doubl
     if (lo.B) {
         KLAUNCH(p, s, "k_hist1", k_hist1, dim3(lo.ntiles), dim3(256), p->pb);
         KLAUNCH(p, s, "k_scan1", k_scan1, dim3(lo.B), dim3(256), p->pb, ktab_dev, J);
-        KLAUNCH(p, s, "k_hist2", k_hist2, dim3(lo.ntiles), dim3(512), p->pb);
-        KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(64), p->pb, ktab_dev, J, err_table, CERT_TOL);
+        KLAUNCH(p, s, "k_hist2", k_hist2, dim3(lo.ntiles), dim3(512), p->pb, lo.ntiles, (const uint32_t*)nullptr);
+        KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(SCAN2_THREADS), p->pb, ktab_dev, J, err_table, CERT_TOL);
         if (err_table) {
             // exact last-digit pass for the entries scan 2 could not certify (usually none)
-            KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(lo.ntiles), dim3(256), p->pb);
+            KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(lo.ntiles), dim3(256), p->pb, lo.ntiles);
             KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(POOL_MAX), dim3(256), p->pb, err_table);
         }
     }
@@ -324,9 +328,11 @@ int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, h
     KLAUNCH(p, s, "k_main", k_main, dim3(p->main_wgs), dim3(FUSED_THREADS), p->pb, p->chunks_per_wg);
     KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J);
     KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG), dim3(256), p->pb);
-    KLAUNCH(p, s, "k_hist2", k_hist2, dim3(lo.ntiles), dim3(512), p->pb);          // layers marked redo only
-    KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(64), p->pb, ktab, lo.J, err_table, CERT_TOL);
-    KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(lo.ntiles), dim3(256), p->pb);
+    // fallbacks that normally find nothing to do: small grids
+    KLAUNCH(p, s, "k_hist2", k_hist2, dim3(std::min<uint32_t>(lo.ntiles, FALLBACK_GRID)), dim3(512), p->pb, lo.ntiles,
+            (const uint32_t*)(at<uint32_t>(p, lo.diag) + 3));   // layers marked redo only
+    KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(SCAN2_THREADS), p->pb, ktab, lo.J, err_table, CERT_TOL);
+    KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(std::min<uint32_t>(lo.ntiles, FALLBACK_GRID)), dim3(256), p->pb, lo.ntiles);
     KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(POOL_MAX), dim3(256), p->pb, err_table);
     return KIMAD_OK;
 }
@@ -472,6 +478,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     cb.o_base = at<uint32_t>(p, lo.o_base); cb.o_allow = at<uint32_t>(p, lo.o_allow);
     cb.cblk_big = at<uint32_t>(p, lo.cblk_big);
     cb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); cb.tmp_x = at<float>(p, lo.tmp_x);
+    cb.ncompact = at<uint32_t>(p, lo.ncompact);
     cb.state = pb.state;
     cb.K = nullptr; cb.offsets = nullptr; cb.idx_out = nullptr; cb.val_out = nullptr; cb.capacity_pairs = 0;
     cb.status = nullptr;
@@ -610,7 +617,8 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
     if (lo.B) {
         const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
         const uint32_t cblocks = (lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG;
-        KLAUNCH(p, s, "k_compact", k_compact, dim3(lo.ntiles), dim3(256), cb, (int32_t)KIMAD_ERR_INTERNAL);
+        KLAUNCH(p, s, "k_compact", k_compact, dim3(std::min<uint32_t>(lo.ntiles, 4u * FALLBACK_GRID)), dim3(256), cb, lo.ntiles,
+                (int32_t)KIMAD_ERR_INTERNAL);
         KLAUNCH(p, s, "k_hist3c", k_hist3c, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
         KLAUNCH(p, s, "k_resolve", k_resolve, dim3(lo.B), dim3(256), cb);
         KLAUNCH(p, s, "k_chunk_count", k_chunk_count, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
