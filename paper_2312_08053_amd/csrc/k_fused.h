@@ -237,25 +237,25 @@ __device__ __forceinline__ uint32_t main_entry(const MainCtx& cx, uint32_t k) {
 
 // histogram updates and spill flags of one chunk.  A chunk that lies inside the layer and holds
 // only normal numbers (no zeros, denormals, Inf, NaN) takes a branch-free path.
-__device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[NQ], uint32_t valid,
+__device__ __forceinline__ void main_count(const MainCtx& cx, const float (&x)[NQ][4], uint32_t valid,
                                            uint32_t (&selm)[NQ]) {
-    uint32_t special = 0;
+    // exponent field 0 or 255 anywhere in the lane's 16 keys: smallest and largest key
+    uint32_t kmin = 0xFFFFFFFFu, kmax = 0u;
 #pragma unroll
     for (int u = 0; u < (int)NQ; ++u) {
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
-            special |= (k - 0x00800000u >= 0x7F000000u) ? 1u : 0u;     // exponent field 0 or 255
-        }
+        const uint32_t k0 = key_of(x[u][0]), k1 = key_of(x[u][1]), k2 = key_of(x[u][2]), k3 = key_of(x[u][3]);
+        kmin = min(min(kmin, k0), min(min(k1, k2), k3));
+        kmax = max(max(kmax, k0), max(max(k1, k2), k3));
     }
-    const bool plain = ballot(special != 0u || valid != (1u << (4 * NQ)) - 1u) == 0;
+    const bool special = kmin < 0x00800000u || kmax >= 0x7F800000u;
+    const bool plain = ballot(special || valid != (1u << (4 * NQ)) - 1u) == 0;
     if (plain) {
 #pragma unroll
         for (int u = 0; u < (int)NQ; ++u) {
             uint32_t sel = 0;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
+                const uint32_t k = key_of(x[u][c]);
                 const uint32_t m24 = (k & 0x7FFFFFu) | 0x800000u;
                 // the shifted square has 24 bits: as a 32-bit value it is the low word of the packed
                 // operand and the count's 1 is a constant high word
@@ -274,7 +274,7 @@ __device__ __forceinline__ void main_count(const MainCtx& cx, const QuadGH (&q)[
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             if (!(valid & (1u << (4 * u + c)))) continue;
-            const uint32_t k = key_of(q[u].g[c] - q[u].h[c]);
+            const uint32_t k = key_of(x[u][c]);
             if ((k >> D1_SHIFT) != 0u) {
                 atomicAdd(&cx.pk[main_entry(cx, k)], PK_ONE | pk_term(k));
             } else {
@@ -347,11 +347,11 @@ __device__ __forceinline__ uint32_t spill_take_blocks(WaveSpill& ws, uint32_t nb
 // One chunk of the streaming pass for one wave: histogram updates, ranks of the entries to spill,
 // space for them, window writes, chunk record.
 __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainCtx& cx, const LayerDesc& L, WaveSpill& ws,
-                                           uint32_t chunk, const QuadGH (&q)[NQ], uint32_t valid) {
+                                           uint32_t chunk, const float (&x)[NQ][4], uint32_t valid) {
     const uint32_t lane = lane_id();
     const uint32_t vbase = (chunk - L.chunk0) * CHUNK;
     uint32_t selm[NQ];
-    main_count(cx, q, valid, selm);
+    main_count(cx, x, valid, selm);
     // ranks in index order (quad, lane, element): per quad a prefix sum over the lanes of the lane's
     // count (0..4); two quads share a scan in 16-bit fields (a quad holds at most 256)
     static_assert(NQ == 4, "two packed scans cover four quads");
@@ -375,14 +375,20 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
             }
         }
         const uint32_t at = ws.fill;
+        // Few entries are spilled, so a lane rarely holds more than one per quad: write in rounds,
+        // every lane its next selected entry of the quad (ascending element), until no lane has one
+        // left.  On average that is fewer than two wave-wide writes per quad instead of four.
 #pragma unroll
         for (int u = 0; u < (int)NQ; ++u) {
+            uint32_t m = selm[u];
             uint32_t pos = at + rowbase[u];
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (selm[u] & (1u << c)) {
-                    ws.win[pos] = make_uint2(vbase + u * 256u + lane * 4u + c - L.mis, __float_as_uint(q[u].g[c] - q[u].h[c]));
+            const uint32_t idx0 = vbase + u * 256u + lane * 4u - L.mis;
+            while (ballot(m != 0u)) {
+                if (m) {
+                    const float xv = (m & 1u) ? x[u][0] : (m & 2u) ? x[u][1] : (m & 4u) ? x[u][2] : x[u][3];
+                    ws.win[pos] = make_uint2(idx0 + (uint32_t)__builtin_ctz(m), __float_as_uint(xv));
                     ++pos;
+                    m &= m - 1u;
                 }
             }
         }
@@ -408,7 +414,7 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
                     if (selm[u] & (1u << c)) {
                         const uint32_t k = pos - r0;
                         if (k < STAGE) {
-                            ws.win[k] = make_uint2(vbase + u * 256u + lane * 4u + c - L.mis, __float_as_uint(q[u].g[c] - q[u].h[c]));
+                            ws.win[k] = make_uint2(vbase + u * 256u + lane * 4u + c - L.mis, __float_as_uint(x[u][c]));
                         }
                         ++pos;
                     }
@@ -460,11 +466,19 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         ws.slice_rel = (cur - L.chunk0) * CHUNK; ws.slice0 = L.tmp0 + ws.slice_rel;
         ws.blk = 0; ws.fill = 0; ws.flushed = 0; ws.npend = 0; ws.have_blk = false;
 
+        // (Fetching the wave's next chunk while the current one is worked on was tried, with the
+        // loads verified to stay in flight across the chunk: it was slower.  The pass is bound by
+        // instruction issue and LDS traffic, not by exposed memory latency.)
         for (uint32_t chunk = cur + wave; chunk < seg_end; chunk += FUSED_WAVES) {
             QuadGH q[NQ];
+            float x[NQ][4];
             uint32_t valid = 0;
             load_chunk<NQ>(L, (chunk - L.chunk0) * CHUNK, q, valid);
-            main_chunk(pb, cx, L, ws, chunk, q, valid);
+#pragma unroll
+            for (int u = 0; u < (int)NQ; ++u)
+#pragma unroll
+                for (int c = 0; c < 4; ++c) x[u][c] = q[u].g[c] - q[u].h[c];
+            main_chunk(pb, cx, L, ws, chunk, x, valid);
         }
         spill_flush(pb, ws, L.tmp0);
         __syncthreads();

@@ -317,15 +317,29 @@ int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, doubl
 
 // Single-pass profile: sample, predict, one streaming pass, candidate-fed digit-2 slots, and the
 // classic recount only for layers whose prediction missed.
-int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, hipStream_t s) {
+// Small layers (one workgroup each, LDS-heavy) go to the side stream once the streaming pass is
+// enqueued on `s`: they then run beside the scans that follow it, which occupy a few dozen
+// workgroups, instead of taking compute units from the persistent grid of the streaming pass.
+// *side gets the stream they were put on (to be joined by the caller).
+int launch_small_profile(kimad_plan* p, double* err_table, hipStream_t s, hipStream_t* side) {
+    const Layout& lo = p->lo;
+    if (!lo.S) return KIMAD_OK;
+    *side = fork_side(p, s);
+    KLAUNCH(p, *side, "k_small_profile", k_small_profile, dim3(lo.S), dim3(SMALL_THREADS), p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
+    return KIMAD_OK;
+}
+
+int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, hipStream_t s, hipStream_t* side) {
     const Layout& lo = p->lo;
     const uint32_t* ktab = at<uint32_t>(p, lo.ktab);
     int rc = zero_range(p, lo.zero1_begin, lo.zero1_end, s);
     if (rc) return rc;
-    if (!lo.B) return KIMAD_OK;
+    if (!lo.B) return launch_small_profile(p, err_table, s, side);
     KLAUNCH(p, s, "k_sample", k_sample, dim3(lo.nswg), dim3(256), p->pb);
     KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs);
     KLAUNCH(p, s, "k_main", k_main, dim3(p->main_wgs), dim3(FUSED_THREADS), p->pb, p->chunks_per_wg);
+    rc = launch_small_profile(p, err_table, s, side);
+    if (rc) return rc;
     KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J);
     KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG), dim3(256), p->pb);
     // fallbacks that normally find nothing to do: small grids
@@ -512,15 +526,13 @@ int kimad_profile(kimad_plan_t* p, double* err_table, uint64_t budget_hint_bytes
     const Layout& lo = p->lo;
     mark(p, s, "begin");
     hipStream_t ss = s;
-    if (lo.S) {
-        ss = fork_side(p, s);
-        KLAUNCH(p, ss, "k_small_profile", k_small_profile, dim3(lo.S), dim3(SMALL_THREADS), p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
-    }
     int rc;
-    if (p->cfg.flags & KIMAD_CFG_CLASSIC_PROFILE)
-        rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s);
-    else
-        rc = run_fused_profile(p, err_table, budget_hint_bytes / p->cfg.pair_bytes, s);
+    if (p->cfg.flags & KIMAD_CFG_CLASSIC_PROFILE) {
+        rc = launch_small_profile(p, err_table, s, &ss);
+        if (!rc) rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s);
+    } else {
+        rc = run_fused_profile(p, err_table, budget_hint_bytes / p->cfg.pair_bytes, s, &ss);
+    }
     const int rj = join_side(p, s, ss);       // always join, also after an error
     return rc ? rc : rj;
 }
