@@ -247,10 +247,12 @@ __global__ __launch_bounds__(256) void k_hist3c(CompressBuffers cb, uint32_t nch
     uint32_t cnt = 0, prefix = 0;
     uint64_t base = 0;
     uint32_t* hist3 = cb.hist3;
+    bool is_cand = false;
     if (chunk < nchunks_total) {
         const uint32_t b = chunk_big[chunk];
         const SelRec S = cb.sel[b];
         if (S.mode == SEL_CAND) {
+            is_cand = true;
             cnt = cb.rec_cnt[chunk];
             base = S.tmp_base + cb.rec_start[chunk];
             prefix = S.prefix;
@@ -258,15 +260,19 @@ __global__ __launch_bounds__(256) void k_hist3c(CompressBuffers cb, uint32_t nch
         }
     }
     const uint32_t cmax = wave_max_over_groups(cnt);
+    uint32_t n_above = 0, n_amb = 0;            // of this chunk: threshold prefix exceeded / shared
     for (uint32_t k0 = 0; k0 < cmax; k0 += SUB) {
         const uint32_t k = k0 + g.sub;
         uint32_t key = 0;
-        bool a = false;
+        bool a = false, hi = false;
         if (k < cnt) {
             key = key_of(cb.tmp_x[base + k]);
             a = (key >> D2_SHIFT) == prefix;
+            hi = (key >> D2_SHIFT) > prefix;
         }
         const uint32_t am = ballot_sub(g, a);
+        n_above += __popc(ballot_sub(g, hi));
+        n_amb += __popc(am);
         if (am == 0) continue;
         // one atomic per group when all its matching lanes hold the same key (zeros, constants)
         const uint32_t first = (uint32_t)__ffs((int)am) - 1u;
@@ -278,6 +284,10 @@ __global__ __launch_bounds__(256) void k_hist3c(CompressBuffers cb, uint32_t nch
             atomicAdd(&hist3[key & (D3_BINS - 1)], 1u);
         }
     }
+    // A chunk without an entry in the threshold's prefix bin (nearly all of them) is settled here:
+    // every entry above the prefix is above the threshold, none equals it.  The others are counted
+    // again once the threshold key is known.
+    if (is_cand && g.sub == 0) { cb.c_gt[chunk] = n_above; cb.c_eq[chunk] = 0u; cb.rec_amb[chunk] = n_amb; }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -330,17 +340,20 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
     const bool live = chunk < nchunks_total;
     uint32_t cnt = 0, tau = 0, total = 0;
     uint64_t base = 0;
+    bool settled = false;
     if (live) {
         const uint32_t b = chunk_big[chunk];
         const SelRec S = cb.sel[b];
         total = cb.rec_cnt[chunk];
-        // spilled candidates reach below the threshold and are always filtered; the classic pass wrote
-        // only entries at or above the threshold prefix, so chunks without ambiguous ones pass whole
-        if (S.mode == SEL_CAND || (S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0u)) {
+        // Only chunks with entries in the threshold's prefix bin are read again.  Of the others, those
+        // of the classic pass hold nothing below the threshold prefix and pass whole; those of the
+        // spilled candidates were counted by k_hist3c.
+        if ((S.mode == SEL_CAND || S.mode == SEL_PREFIX) && cb.rec_amb[chunk] != 0u) {
             cnt = total;
             tau = cb.tau[b];
             base = S.tmp_base + cb.rec_start[chunk];
         }
+        settled = S.mode == SEL_CAND && cnt == 0u;      // counted by k_hist3c
     }
     uint32_t gt = 0, eq = 0;
     for (uint32_t k = g.sub; k < cnt; k += SUB) {
@@ -351,7 +364,7 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
 #pragma unroll
     for (int d = SUB / 2; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
     if (cnt == 0) { gt = total; eq = 0; }
-    if (live && g.sub == 0) { cb.c_gt[chunk] = gt; cb.c_eq[chunk] = eq; }
+    if (live && !settled && g.sub == 0) { cb.c_gt[chunk] = gt; cb.c_eq[chunk] = eq; }
 }
 
 // ---------------------------------------------------------------------------------------------

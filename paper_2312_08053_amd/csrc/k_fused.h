@@ -40,15 +40,17 @@ __device__ __forceinline__ uint32_t sampled_chunk(uint32_t gidx, uint32_t stride
 
 // ---------------------------------------------------------------------------------------------
 // Sampling pre-pass: digit-1 counts of the sampled chunks.
-__global__ __launch_bounds__(256) void k_sample(ProfileBuffers pb) {
+// One wave per sampled chunk: all of a workgroup's loads are in flight together.
+constexpr uint32_t SAMPLE_THREADS = 64 * SAMPLE_GROUPS_PER_WG;
+__global__ __launch_bounds__(SAMPLE_THREADS) void k_sample(ProfileBuffers pb) {
     __shared__ uint32_t hist[D1_BINS];
     const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
-    for (uint32_t b = tid; b < D1_BINS; b += 256) hist[b] = 0u;
+    for (uint32_t b = tid; b < D1_BINS; b += SAMPLE_THREADS) hist[b] = 0u;
     __syncthreads();
     const uint32_t li = pb.swg_layer[blockIdx.x];
     const LayerDesc L = pb.layers[li];
     const uint32_t first = pb.swg_first[blockIdx.x];
-    for (uint32_t k = wave; k < SAMPLE_GROUPS_PER_WG; k += 4) {
+    for (uint32_t k = wave; k < SAMPLE_GROUPS_PER_WG; k += SAMPLE_THREADS / 64) {
         const uint32_t chunk = sampled_chunk(first + k, L.sstride);
         if (chunk >= L.nchunks) continue;
         const uint32_t vbase = chunk * CHUNK;
@@ -63,7 +65,7 @@ __global__ __launch_bounds__(256) void k_sample(ProfileBuffers pb) {
     }
     __syncthreads();
     uint32_t* sh = pb.shist + (size_t)L.big * D1_BINS;
-    for (uint32_t b = tid; b < D1_BINS; b += 256) {
+    for (uint32_t b = tid; b < D1_BINS; b += SAMPLE_THREADS) {
         const uint32_t v = hist[b];
         if (v) {
             atomicAdd(&sh[b], v);

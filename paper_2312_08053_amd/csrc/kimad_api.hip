@@ -335,7 +335,7 @@ int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, h
     int rc = zero_range(p, lo.zero1_begin, lo.zero1_end, s);
     if (rc) return rc;
     if (!lo.B) return launch_small_profile(p, err_table, s, side);
-    KLAUNCH(p, s, "k_sample", k_sample, dim3(lo.nswg), dim3(256), p->pb);
+    KLAUNCH(p, s, "k_sample", k_sample, dim3(lo.nswg), dim3(SAMPLE_THREADS), p->pb);
     KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs);
     KLAUNCH(p, s, "k_main", k_main, dim3(p->main_wgs), dim3(FUSED_THREADS), p->pb, p->chunks_per_wg);
     rc = launch_small_profile(p, err_table, s, side);
