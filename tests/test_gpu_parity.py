@@ -143,3 +143,110 @@ def test_step_entry_point_matches_separate_calls():
     assert st == ko.OK
     assert np.array_equal(plan.K.cpu().numpy().astype(np.uint64), K_ref)
     gh.check_compress(work, plan, h, K_ref, off_ref, plan.idx, plan.val)
+
+
+@pytest.mark.timeout(600)
+def test_gpt2_full_size_in_the_benchmark_configuration():
+    """The 124M-element set exactly as bench.py runs it (one kimad_step).  The oracle checks a sample of
+    layers element by element (error rows, payload, estimator); properties that hold at any size
+    are checked on every layer; the allocation is checked against the oracle's DP on the same table."""
+    import torch
+    import paper_2312_08053_amd as kimad
+    work = ks.make_workload("gpt2")
+    g = torch.from_numpy(work.g).cuda()
+    h = torch.from_numpy(work.h).cuda()
+    plan = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes,
+                      D=work.cost_units_D, max_budget_bytes=work.budget_bytes,
+                      capacity_pairs=work.budget_bytes // work.pair_bytes + 1)
+    status = plan.step(work.budget_bytes)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    diag = plan.diagnostics()
+    assert diag["uncertified"] == diag["recomputed"]
+    Kt = plan.grid_sizes()
+    E_gpu = plan.err_table.cpu().numpy().reshape(work.L, -1)
+    K = plan.K.cpu().numpy().astype(np.uint64)
+    off = plan.offsets.cpu().numpy().astype(np.uint64)
+
+    # allocation: the oracle's DP on the library's table, bit for bit
+    st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, work.budget_bytes, work.pair_bytes, work.cost_units_D)
+    assert st == ko.OK
+    assert np.array_equal(plan.j.cpu().numpy(), j_ref)
+    assert np.array_equal(K, K_ref) and np.array_equal(off, off_ref)
+    assert work.pair_bytes * int(off[-1]) <= work.budget_bytes
+
+    gL, hL = gh.oracle_layers(work)
+    idx = gh.u32(plan.idx)
+    val = plan.val.cpu().numpy()
+    h_new = h.cpu().numpy()
+    # every layer: payload is ascending, in range, carries x = g - h bit for bit, the estimator moved
+    # on the support only, and nothing dropped is larger than anything kept (ties: lower index kept)
+    for i in range(work.L):
+        a, b = int(off[i]), int(off[i + 1])
+        assert b - a == int(K[i])
+        ii = idx[a:b].astype(np.int64)
+        x = ko.operand(gL[i], hL[i])
+        assert np.all(ii[1:] > ii[:-1]) and (len(ii) == 0 or ii[-1] < len(x))
+        assert np.array_equal(val[a:b].view(np.uint32), x[ii].view(np.uint32))
+        want = hL[i].copy()
+        want[ii] = hL[i][ii] + x[ii]
+        assert np.array_equal(h_new[work.starts[i]:work.starts[i + 1]].view(np.uint32), want.view(np.uint32))
+        if 0 < len(ii) < len(x):
+            key = ko.magnitude_key(x).astype(np.int64)
+            kept = np.zeros(len(x), dtype=bool)
+            kept[ii] = True
+            tau = key[kept].min()
+            assert key[~kept].max() <= tau
+            ties_dropped = np.flatnonzero(~kept & (key == tau))
+            ties_kept = np.flatnonzero(kept & (key == tau))
+            if len(ties_dropped):
+                assert ties_kept.max() < ties_dropped.min()
+
+    # a sample of layers against the oracle, element by element: the embedding (largest), one tensor of
+    # each kind of the first block, a middle matrix, the last tensors
+    sample = [0, 1] + list(range(2, 14)) + [70, 146, 147]
+    for i in sample:
+        x = ko.operand(gL[i], hL[i])
+        row = ko.topk_error_profile(x, Kt[i])
+        gh.assert_table_close(E_gpu[i:i + 1], row[None, :], Kt[i:i + 1], work.sizes[i:i + 1])
+    gh.check_compress(work, plan, h, K, off, plan.idx, plan.val, layers=sample)
+
+
+def test_chain_of_steps_with_persistent_estimator_and_bandwidth_trace():
+    """Four rounds of one worker: a fresh gradient every round, the estimator carried over on the
+    device, the budget following a bandwidth trace (Algorithm 1, worker side).  Payload and
+    estimator must match the oracle bit for bit after every round."""
+    import torch
+    steps = 4
+    kw = dict(n_layer=1, hidden=512, ffn=1408, vocab=3001)
+    w0 = ks.make_workload("llama", step=0, **kw)
+    trace = ks.bandwidth_trace(steps, seed=3, b0=0.02, sigma=0.01, lo=0.005, hi=0.05)
+    budgets = [max(8 * w0.L, ks.budget_from_bandwidth(b, seconds=0.05)) for b in trace]
+    g = torch.from_numpy(w0.g).cuda()
+    h = torch.from_numpy(w0.h).cuda()
+    plan = gh.make_plan(w0, g, h, max_budget_bytes=max(budgets))
+    h_ref = [x.copy() for x in w0.layer_views(w0.h)]
+    for t in range(steps):
+        wt = ks.make_workload("llama", step=t, **kw)
+        g.copy_(torch.from_numpy(wt.g))
+        status = plan.step(budgets[t])
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [0, 0], (t, status)
+        gL = wt.layer_views(wt.g)
+        E_gpu = plan.err_table.cpu().numpy().reshape(w0.L, -1)
+        E_ref, Kt = ko.profile(gL, h_ref, w0.ratios)
+        gh.assert_table_close(E_gpu, E_ref, Kt, w0.sizes)
+        st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, budgets[t], w0.pair_bytes, w0.cost_units_D)
+        assert st == ko.OK
+        assert np.array_equal(plan.K.cpu().numpy().astype(np.uint64), K_ref)
+        idx = gh.u32(plan.idx)
+        val = plan.val.cpu().numpy().view(np.uint32)
+        h_now = h.cpu().numpy()
+        for i in range(w0.L):
+            li, lv, lh = ko.compress_ef_layer(gL[i], h_ref[i], int(K_ref[i]))
+            a, b = int(off_ref[i]), int(off_ref[i + 1])
+            assert np.array_equal(idx[a:b], li), (t, i)
+            assert np.array_equal(val[a:b], lv.view(np.uint32)), (t, i)
+            assert np.array_equal(h_now[w0.starts[i]:w0.starts[i + 1]].view(np.uint32), lh.view(np.uint32)), (t, i)
+            h_ref[i] = lh
+        assert w0.pair_bytes * int(off_ref[-1]) <= budgets[t]
