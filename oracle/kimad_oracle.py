@@ -17,6 +17,12 @@ worker lines "Select compressor" and "Upload the compressed vector"; Section 3.2
 
 In the code below g = u (fresh update), h = u_hat (estimator), x = g - h.
 
+And, per round, for the server (Algorithm 1, server lines "Aggregate all update estimators"
+and "Updates the model"):
+
+    u_hat_m  += C_m(u_m - u_hat_m)                     decode worker m's payload into its estimator
+    x_model  -= gamma * sum_m w_m u_hat_m              model step from the M estimators
+
 Parts that are plain definitions (written out as such): the operand, TopK by a
 full sort, the error as the sum of squares of what TopK drops, the payload and
 the estimator update.  The part that is an algorithm (followed step by step, in
@@ -47,11 +53,16 @@ the design notes of this repository):
       with a non-finite entry as NONFINITE.
   R9  Payload layout: per layer, pairs in ascending layer-local index; layer i
       occupies [offsets[i], offsets[i+1]) with offsets the exclusive scan of K.
+  R13 Server model step: the paper fixes no precision.  The weighted sum over
+      workers is taken in fp64, workers in order m = 0..M-1, each term the fp64
+      product w_m * u_hat_m; the model is fp32 and gets fl32(x - gamma * sum),
+      the subtraction and the product with gamma in fp64.
 
 Pins (tests/test_oracle_*.py): brute force over all subsets / all assignments on
 tiny inputs, closed forms for constant vectors, numpy partition on distinct
 magnitudes, the contraction bound of the paper's compressor class, monotonicity,
-the worker/server estimator round trip.  No function here is unpinned.
+the worker/server estimator round trip; for the server step, exact rational
+arithmetic on tiny inputs and closed forms.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -231,3 +242,34 @@ def step(g_layers, h_layers, ratios, budget_bytes, pair_bytes: int = 8, D: int =
     offsets2, idx, val, h_new = compress_ef(g_layers, h_layers, K)
     assert np.array_equal(offsets, offsets2)
     return dict(status=OK, E=E, K_table=Kt, j=j, K=K, offsets=offsets, idx=idx, val=val, h=h_new)
+
+
+# --------------------------------------------------------------------------- server side
+def server_apply(payloads, u_hats: Sequence[np.ndarray], weights: Sequence[float], x_model,
+                 gamma: float, layer_starts: Sequence[int]):
+    """Algorithm 1, server lines "Aggregate all update estimators" and "Updates the model".
+
+    payloads[m] = (offsets, idx, val) of worker m as produced by `compress_ef` (layer-local
+    indices); u_hats[m] is the server's flat fp32 copy of worker m's estimator, layer i at
+    [layer_starts[i], layer_starts[i+1]).  Returns (new u_hats, new model); `x_model` may be None
+    (aggregate only).  Decoding adds each value to its entry in fp32, which is exactly what the
+    worker did to its own estimator; the model step follows reading R13."""
+    M = len(u_hats)
+    assert len(payloads) == M and len(weights) == M
+    L = len(layer_starts) - 1
+    new_hats = []
+    for m in range(M):
+        offsets, idx, val = payloads[m]
+        u = np.array(u_hats[m], dtype=np.float32, copy=True)
+        for i in range(L):
+            a, b = int(offsets[i]), int(offsets[i + 1])
+            where = int(layer_starts[i]) + idx[a:b].astype(np.int64)
+            u[where] = u[where] + val[a:b].astype(np.float32)       # fp32 add; indices of a layer are distinct
+        new_hats.append(u)
+    if x_model is None:
+        return new_hats, None
+    acc = np.zeros(len(x_model), dtype=np.float64)
+    for m in range(M):
+        acc = acc + np.float64(weights[m]) * new_hats[m].astype(np.float64)
+    x_new = (np.asarray(x_model, dtype=np.float32).astype(np.float64) - np.float64(gamma) * acc).astype(np.float32)
+    return new_hats, x_new
