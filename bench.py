@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--D", type=int, default=None, help="cost discretisation factor (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-blocks", type=int, default=4)
+    ap.add_argument("--server-workers", type=int, default=4,
+                    help="workers of the server-step measurement reported beside the headline (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one worker on one GPU; --gpus must be 1 "
@@ -150,6 +152,7 @@ def main() -> int:
                    "tile_elems": None},
         "wall_ms_per_step": round(wall_ms, 4),
         "min_ms_per_step": round(float(np.min(per_step)), 4),
+        "median_ms_per_step": round(float(np.median(per_step)), 4),
         "path_roofline": {"bytes_min": bytes_min, "frac_of_hbm_peak": round(bytes_min / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                           "frac_without_allocate": round(bytes_min / (t_no_alloc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
                           "gradient_GBs_without_allocate": round(4.0 * d / (t_no_alloc * 1e-3) / 1e9, 2)},
@@ -158,6 +161,35 @@ def main() -> int:
         "roofline": roofline,
         "input_generation_s": round(t_gen, 1),
     }
+
+    # ---- beside the headline: the server's step of the same round (decode M payloads into M estimators,
+    # x <- x - gamma * sum_m w_m u_hat_m), timed with events on the same stream.  Not part of `value`.
+    if args.server_workers > 0:
+        M = args.server_workers
+        hats = [h0.clone() for _ in range(M)]
+        xm = torch.zeros(d, dtype=torch.float32, device="cuda")
+        starts_dev = torch.from_numpy(np.asarray(work.starts, dtype=np.int64)).cuda()
+        pl = [(plan.idx, plan.val, plan.offsets)] * M
+        wts = [1.0 / M] * M
+
+        def timed(fn, reps=10):
+            for _ in range(2):
+                fn()
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+            for a, b in ev:
+                a.record(stream); fn(); b.record(stream)
+            torch.cuda.synchronize()
+            return float(np.mean([a.elapsed_time(b) for a, b in ev]))
+
+        t_dec = timed(lambda: kimad.kimad_server_apply(pl, hats, wts, starts_dev, d, None, 0.0))
+        t_all = timed(lambda: kimad.kimad_server_apply(pl, hats, wts, starts_dev, d, xm, 1e-3))
+        t_step = max(t_all - t_dec, 1e-6)
+        step_bytes = 4 * (M + 2) * d
+        out["server_step"] = {"workers": M, "decode_ms": round(t_dec, 4), "model_step_ms": round(t_step, 4),
+                              "model_step_algorithmic_bytes": step_bytes,
+                              "model_step_GBs": round(step_bytes / (t_step * 1e-3) / 1e9, 1),
+                              "model_step_frac_of_hbm_peak": round(step_bytes / (t_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        del hats, xm
 
     # ---- the CPU oracle on a bounded sample of the same workload (rank 0, reported baseline)
     if not args.no_cpu_baseline:

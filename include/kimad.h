@@ -163,6 +163,36 @@ int kimad_profile_diagnostics(kimad_plan_t* plan, uint32_t* out4, void* stream);
 int kimad_plan_layer_states(kimad_plan_t* plan, uint32_t* out, uint32_t max_layers, uint32_t* count_out,
                             void* stream);
 
+/* Server side of a round (paper Algorithm 1, server lines "Aggregate all update estimators" and
+ * "Updates the model"): for every worker m = 0..M-1 decode its payload into the server's copy
+ * of its estimator,
+ *     u_hat_m[layer_start[i] + idx] = fl32(u_hat_m[...] + val)   for the pairs of layer i,
+ * which is the very addition the worker applied to its own estimator, so the two copies stay
+ * equal bit for bit; then, if x is not NULL, step the model:
+ *     x[t] = fl32( (double)x[t] - gamma * sum_m (double)weights[m] * (double)u_hat_m[t] ),
+ * the sum in fp64 in worker order (the paper fixes no precision; this is the reading taken).
+ *   payloads     HOST array[M] of {idx, val, offsets}: DEVICE pointers to one worker's payload as
+ *                written by kimad_compress_ef (layer-local ascending indices; offsets uint64[L+1])
+ *   u_hat        HOST array[M] of DEVICE float[d] buffers (flat: layer i at layer_start[i]), updated
+ *                in place; the M buffers and x must not overlap
+ *   weights      HOST double[M]
+ *   M            1..KIMAD_MAX_WORKERS
+ *   layer_start  DEVICE uint64[L+1], element offsets of the layers, layer_start[L] = d
+ *   d            elements per flat buffer (HOST value of layer_start[L])
+ *   x            DEVICE float[d] or NULL (aggregate only)
+ * Nothing is allocated; all work is enqueued on `stream`.  Indices are not range-checked against
+ * the layer sizes: payloads must come from kimad_compress_ef of plans with the same layer sizes.
+ * Returns KIMAD_ERR_INVALID_ARG for null pointers or M out of range. */
+#define KIMAD_MAX_WORKERS 16
+typedef struct kimad_payload {
+    const uint32_t* idx;      /* DEVICE */
+    const float* val;         /* DEVICE */
+    const uint64_t* offsets;  /* DEVICE uint64[L+1] */
+} kimad_payload_t;
+int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, const double* weights,
+                       uint32_t M, const uint64_t* layer_start, uint32_t L, uint64_t d,
+                       float* x, double gamma, void* stream);
+
 /* Per-kernel timing (tracing aid for benchmarks).  With timing enabled the library records a
  * HIP event on the stream after every kernel it launches.  kimad_plan_get_timings waits for the
  * last recorded event, then writes one entry per launch since the last call: the kernel names,

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "kimad_workspace_bytes", "kimad_plan_create", "kimad_plan_destroy", "kimad_plan_grid_sizes",
     "kimad_profile", "kimad_allocate", "kimad_compress_ef", "kimad_step",
     "kimad_profile_diagnostics", "kimad_plan_layer_states", "kimad_plan_set_timing", "kimad_plan_get_timings",
-    "kimad_strerror", "kimad_version",
+    "kimad_server_apply", "kimad_strerror", "kimad_version",
 ]
 
 
@@ -29,6 +29,10 @@ class KimadError(RuntimeError):
 
 class _Layer(C.Structure):
     _fields_ = [("g", C.c_void_p), ("h", C.c_void_p), ("n", C.c_uint64)]
+
+
+class _Payload(C.Structure):
+    _fields_ = [("idx", C.c_void_p), ("val", C.c_void_p), ("offsets", C.c_void_p)]
 
 
 class _Config(C.Structure):
@@ -62,6 +66,8 @@ def lib() -> C.CDLL:
     L.kimad_plan_layer_states.argtypes = [vp, C.POINTER(C.c_uint32), u32, C.POINTER(C.c_uint32), vp]
     L.kimad_plan_set_timing.argtypes = [vp, C.c_int]
     L.kimad_plan_get_timings.argtypes = [vp, C.c_char_p, u32, C.POINTER(C.c_float), u32, C.POINTER(C.c_uint32)]
+    L.kimad_server_apply.argtypes = [C.POINTER(_Payload), C.POINTER(C.c_void_p), C.POINTER(C.c_double), u32, vp, u32, u64,
+                                     vp, C.c_double, vp]
     L.kimad_strerror.argtypes = [C.c_int]
     L.kimad_strerror.restype = C.c_char_p
     L.kimad_version.restype = C.c_char_p
@@ -155,6 +161,19 @@ def kimad_step(plan: int, budget_bytes: int, err_table, j_out, K_out, offsets_ou
                             C.c_void_p(_ptr(j_out)), C.c_void_p(_ptr(K_out)), C.c_void_p(_ptr(offsets_out)),
                             C.c_void_p(_ptr(idx_out)), C.c_void_p(_ptr(val_out)), int(capacity_pairs),
                             C.c_void_p(_ptr(status_out)), C.c_void_p(_stream(stream))), "kimad_step")
+
+
+def kimad_server_apply(payloads, u_hats, weights, layer_start, d: int, x=None, gamma: float = 0.0, stream=None) -> None:
+    """payloads: list of (idx, val, offsets) device tensors, one per worker; u_hats: list of flat fp32
+    device tensors (updated in place); layer_start: device uint64/int64 tensor [L+1]; x: flat fp32 model
+    or None."""
+    M = len(u_hats)
+    pl = (_Payload * M)(*[_Payload(_ptr(i), _ptr(v), _ptr(o)) for (i, v, o) in payloads])
+    uh = (C.c_void_p * M)(*[_ptr(u) for u in u_hats])
+    w = (C.c_double * M)(*[float(t) for t in weights])
+    _check(lib().kimad_server_apply(pl, uh, w, M, C.c_void_p(_ptr(layer_start)), int(layer_start.numel()) - 1, int(d),
+                                    C.c_void_p(_ptr(x) if x is not None else 0), float(gamma),
+                                    C.c_void_p(_stream(stream))), "kimad_server_apply")
 
 
 class Plan:

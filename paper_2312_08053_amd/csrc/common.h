@@ -92,6 +92,12 @@ __device__ __forceinline__ float4 gload4(const float* p) {
     return make_float4(v.x, v.y, v.z, v.w);
 }
 __device__ __forceinline__ void gstore(float* p, float v) { *reinterpret_cast<g_float*>((uintptr_t)p) = v; }
+typedef __attribute__((address_space(1))) f32x4 g_f32x4;
+__device__ __forceinline__ void gstore4(float* p, float4 v) {
+    f32x4 t;
+    t.x = v.x; t.y = v.y; t.z = v.z; t.w = v.w;
+    *reinterpret_cast<g_f32x4*>((uintptr_t)p) = t;
+}
 
 // ---- small device helpers ----------------------------------------------------------------
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }

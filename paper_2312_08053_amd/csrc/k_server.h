@@ -1,0 +1,74 @@
+// Server side of a round (paper Algorithm 1, server lines "Aggregate all update estimators" and
+// "Updates the model"): decode M sparse payloads into the M estimator copies, then one dense pass
+//     x <- x - gamma * sum_m w_m u_hat_m.
+// The decode touches a few percent of the estimators; the model step reads M + 1 dense vectors and
+// writes one: it is the other HBM-bound kernel of the method, 4 (M + 2) bytes per element.
+#pragma once
+#include "common.h"
+
+namespace kimad {
+
+constexpr uint32_t MAX_WORKERS = 16;         // must equal KIMAD_MAX_WORKERS of the public header
+
+// The estimators and weights of the model step.  The arrays are indexed with compile-time
+// constants only (unrolled loops): a run-time index into a by-value kernel argument makes the
+// compiler copy the whole table to scratch memory in every thread.
+struct ServerArgs {
+    const float* u_hat[MAX_WORKERS];
+    double w[MAX_WORKERS];
+    uint32_t M;
+    uint64_t d;
+};
+
+// One worker's payload into its estimator: one thread per pair.  The pair's layer is found by
+// bisection in the worker's offsets; indices inside a payload are distinct, so the additions need
+// no atomics.
+__global__ __launch_bounds__(256) void k_server_decode(const uint32_t* __restrict__ idx, const float* __restrict__ val,
+                                                       const uint64_t* __restrict__ off, float* u_hat,
+                                                       const uint64_t* __restrict__ layer_start, uint32_t L) {
+    const uint64_t total = off[L];
+    const uint64_t stride = (uint64_t)gridDim.x * 256u;
+    for (uint64_t p = (uint64_t)blockIdx.x * 256u + threadIdx.x; p < total; p += stride) {
+        uint32_t lo = 0, hi = L;                 // largest layer i with off[i] <= p
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (off[mid] <= p) lo = mid; else hi = mid;
+        }
+        float* u = u_hat + layer_start[lo] + idx[p];
+        gstore(u, gload(u) + val[p]);
+    }
+}
+
+// The model step, four elements per thread and trip; the tail and unaligned buffers take the
+// scalar loop.  fp64 arithmetic per element, workers in order: every result is reproducible and
+// equal to a plain sequential evaluation.
+__global__ __launch_bounds__(256) void k_server_step(ServerArgs a, float* x, double gamma, uint32_t vec_ok) {
+    const uint64_t gid = (uint64_t)blockIdx.x * 256u + threadIdx.x, stride = (uint64_t)gridDim.x * 256u;
+    const uint64_t n4 = vec_ok ? a.d / 4 : 0;
+    for (uint64_t q = gid; q < n4; q += stride) {
+        const float4 xv = gload4(x + 4 * q);
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+        for (uint32_t m = 0; m < MAX_WORKERS; ++m) {
+            if (m < a.M) {
+                const float4 u = gload4(a.u_hat[m] + 4 * q);
+                const double w = a.w[m];
+                s0 = s0 + w * (double)u.x; s1 = s1 + w * (double)u.y;
+                s2 = s2 + w * (double)u.z; s3 = s3 + w * (double)u.w;
+            }
+        }
+        float4 r;
+        r.x = (float)((double)xv.x - gamma * s0); r.y = (float)((double)xv.y - gamma * s1);
+        r.z = (float)((double)xv.z - gamma * s2); r.w = (float)((double)xv.w - gamma * s3);
+        gstore4(x + 4 * q, r);
+    }
+    for (uint64_t t = 4 * n4 + gid; t < a.d; t += stride) {
+        double acc = 0.0;
+#pragma unroll
+        for (uint32_t m = 0; m < MAX_WORKERS; ++m)
+            if (m < a.M) acc = acc + a.w[m] * (double)gload(a.u_hat[m] + t);
+        gstore(x + t, (float)((double)gload(x + t) - gamma * acc));
+    }
+}
+
+}  // namespace kimad

