@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--D", type=int, default=None, help="cost discretisation factor (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-blocks", type=int, default=4)
+    ap.add_argument("--compare-allocators", action="store_true",
+                    help="also report the total error of Kimad+, uniform-ratio Kimad and whole-model TopK (Section 4.3)")
     ap.add_argument("--server-workers", type=int, default=4,
                     help="workers of the server-step measurement reported beside the headline (0 = skip)")
     args = ap.parse_args()
@@ -190,6 +192,12 @@ def main() -> int:
                               "model_step_GBs": round(step_bytes / (t_step * 1e-3) / 1e9, 1),
                               "model_step_frac_of_hbm_peak": round(step_bytes / (t_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del hats, xm
+
+    if args.compare_allocators:
+        from paper_2312_08053_amd.baselines import allocator_errors
+        h.copy_(h0)
+        out["allocator_comparison"] = allocator_errors(g, h, work.sizes.tolist(), work.ratios.tolist(), work.budget_bytes,
+                                                       work.pair_bytes, work.cost_units_D)
 
     # ---- the CPU oracle on a bounded sample of the same workload (rank 0, reported baseline)
     if not args.no_cpu_baseline:
