@@ -109,7 +109,10 @@ int kimad_plan_grid_sizes(const kimad_plan_t* plan, uint64_t* K_table_out);
  * largest entries (index, x, h) for KIMAD_REUSE_PROFILE.
  *   budget_hint_bytes  the budget the following kimad_allocate will get, or 0 if unknown.  It only
  *                      sizes how many of the largest entries are kept for the compression; no
- *                      result depends on it. */
+ *                      result depends on it.
+ * Every entry is certified to 4e-6 relative or recomputed exactly from a last-digit histogram; the
+ * plan holds min(L_big * J, 65536) such histograms, and an entry that finds none left is NaN (which
+ * kimad_allocate reports as KIMAD_ERR_NONFINITE) rather than a loosely bounded value. */
 int kimad_profile(kimad_plan_t* plan, double* err_table, uint64_t budget_hint_bytes, void* stream);
 
 /* Allocation (Section 3.2 Eq. optimisation; Appendix C): choose j_i minimising

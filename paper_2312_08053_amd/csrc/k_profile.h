@@ -37,11 +37,12 @@ struct ProfileBuffers {
                                   // [2] pool entries handed out
     // exact fallback for entries whose bound is not tight: last-digit histograms of their prefix bins
     uint32_t* layer_flag;         // [B] layer has at least one pool entry
-    uint32_t* pool_prefix;        // [POOL_MAX]
-    uint32_t* pool_big;           // [POOL_MAX]
-    uint32_t* pool_t0;            // [POOL_MAX] first target (li * J + j) of the run sharing the prefix
-    uint32_t* pool_cnt;           // [POOL_MAX] targets in that run
-    uint32_t* pool_hist;          // [POOL_MAX][4096]
+    uint32_t pool_cap;            // pool entries the plan holds: min(B * J, POOL_LIMIT)
+    uint32_t* pool_prefix;        // [pool_cap]
+    uint32_t* pool_big;           // [pool_cap]
+    uint32_t* pool_t0;            // [pool_cap] first target (li * J + j) of the run sharing the prefix
+    uint32_t* pool_cnt;           // [pool_cap] targets in that run
+    uint32_t* pool_hist;          // [pool_cap][4096]
     uint32_t* tgt_unsel;          // dropped entries inside the prefix bin
     double* tgt_base;             // E without the prefix bin's share
     // fused single-pass profile
@@ -61,8 +62,13 @@ struct ProfileBuffers {
     float* tmp_x;
 };
 
-constexpr uint32_t POOL_MAX = 256;
-constexpr uint32_t POOL_NONE = 0xFFFFu;
+// Pool of exact last-digit histograms: one entry per (layer, threshold prefix) whose error bound is
+// too wide.  A layer has at most J such prefixes, so B * J entries can never run out; plans with
+// more than POOL_LIMIT of them hold POOL_LIMIT, and a candidate that finds the pool full gets NaN
+// in the table (the allocation then reports a non-finite table instead of using a loose value).
+constexpr uint32_t POOL_LIMIT = 65536;          // 16 KB each: at most 1 GB
+constexpr uint32_t POOL_GRID = 256;             // workgroups of the exact scan (it normally finds nothing)
+constexpr uint32_t POOL_NONE = 0xFFFFFFFFu;
 
 // ---------------------------------------------------------------------------------------------
 // Pass 1: per-layer histogram of digit 1 with counts and integer sums of squares.
@@ -401,12 +407,16 @@ __global__ __launch_bounds__(SCAN2_THREADS) void k_scan2(ProfileBuffers pb, cons
     if (flagged) atomicAdd(&pb.diag[0], 1u);
     if (head && run_flagged && j < J) {
         const uint32_t f = atomicAdd(&pb.diag[2], 1u);
-        if (f < POOL_MAX) {
+        if (f < pb.pool_cap) {
             pb.pool_prefix[f] = prefix;
             pb.pool_big[f] = big;
             pb.pool_t0[f] = li * J + j;
             pb.pool_cnt[f] = h1 - h0;
             pb.layer_flag[big] = 1u;
+        } else {
+            // pool full: no loose value leaves this call
+            for (uint32_t k = h0; k < h1 && k < J; ++k)
+                err_table[(size_t)li * J + k] = __longlong_as_double(0x7FF8000000000000ll);
         }
     }
 }
@@ -414,8 +424,8 @@ __global__ __launch_bounds__(SCAN2_THREADS) void k_scan2(ProfileBuffers pb, cons
 // Exact fallback, pass: last-digit histogram of every pooled prefix bin.  One workgroup per tile;
 // tiles of layers without pool entries return at once.
 __global__ __launch_bounds__(256) void k_hist3p(ProfileBuffers pb, uint32_t ntiles) {
-    __shared__ uint32_t pfx[POOL_MAX];
-    __shared__ uint32_t pid[POOL_MAX];
+    __shared__ uint32_t pfx[KIMAD_MAX_J_CONST];   // a layer has at most J pooled prefixes
+    __shared__ uint32_t pid[KIMAD_MAX_J_CONST];
     __shared__ uint32_t npool;
     const uint32_t tid = threadIdx.x;
     if (pb.diag[2] == 0u) return;               // no pool entries at all: the usual case
@@ -426,16 +436,15 @@ __global__ __launch_bounds__(256) void k_hist3p(ProfileBuffers pb, uint32_t ntil
     __syncthreads();                            // the previous tile's readers are done with the lists
     if (tid == 0) npool = 0;
     __syncthreads();
-    const uint32_t total = min(pb.diag[2], POOL_MAX);
+    const uint32_t total = min(pb.diag[2], pb.pool_cap);
     for (uint32_t f = tid; f < total; f += 256) {
         if (pb.pool_big[f] == (uint32_t)L.big) {
             const uint32_t k = atomicAdd(&npool, 1u);
-            pfx[k] = pb.pool_prefix[f];
-            pid[k] = f;
+            if (k < KIMAD_MAX_J_CONST) { pfx[k] = pb.pool_prefix[f]; pid[k] = f; }
         }
     }
     __syncthreads();
-    const uint32_t np = npool;
+    const uint32_t np = min(npool, (uint32_t)KIMAD_MAX_J_CONST);
     const uint32_t vbase = (tile - L.tile0) * pb.tile_elems;
     const uint32_t iters = pb.tile_elems / 1024u;
     for (uint32_t it = 0; it < iters; ++it) {
@@ -472,8 +481,10 @@ __global__ __launch_bounds__(256) void k_scan3p(ProfileBuffers pb, double* err_t
     __shared__ double sd[16];
     __shared__ uint32_t cum[D3_BINS];      // entries in lower digits
     __shared__ double sumsq[D3_BINS];      // their squares
-    const uint32_t f = blockIdx.x, tid = threadIdx.x;
-    if (f >= min(pb.diag[2], POOL_MAX)) return;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t total = min(pb.diag[2], pb.pool_cap);
+    for (uint32_t f = blockIdx.x; f < total; f += gridDim.x) {
+    __syncthreads();                            // the previous entry's readers are done with the tables
     const uint32_t prefix = pb.pool_prefix[f];
     const uint32_t* h = pb.pool_hist + (size_t)f * D3_BINS;
     uint32_t c[16];
@@ -521,6 +532,7 @@ __global__ __launch_bounds__(256) void k_scan3p(ProfileBuffers pb, double* err_t
         }
         err_table[t] = pb.tgt_base[t] + U;
         atomicAdd(&pb.diag[1], 1u);
+    }
     }
 }
 

@@ -41,6 +41,7 @@ struct Layout {
     uint64_t swg_layer, swg_first, state, lutc;
     uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, shist, ghist, cursor, spill_over, zero1_end;
     uint64_t pool_prefix, pool_big, pool_t0, pool_cnt, pool_hist, tgt_unsel, tgt_base;
+    uint32_t pool_cap = 1;
     uint64_t lut1, nslots, slot_bin;
     uint64_t tgt_slot, tgt_r, tgt_above1, tgt_below, sel_prefix, sel_above, sel_amb;
     // compress
@@ -156,11 +157,12 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.spill_over = take(4ull * (B ? B : 1));
     lo.rec_cnt = take(4ull * (nc ? nc : 1));              // chunk records start out as "nothing spilled"
     lo.zero1_end = off;
-    lo.pool_prefix = take(4ull * POOL_MAX);
-    lo.pool_big = take(4ull * POOL_MAX);
-    lo.pool_t0 = take(4ull * POOL_MAX);
-    lo.pool_cnt = take(4ull * POOL_MAX);
-    lo.pool_hist = take(4ull * POOL_MAX * D3_BINS);      // zero between calls: cleared by its reader
+    lo.pool_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>((uint64_t)B * J, 1), POOL_LIMIT);
+    lo.pool_prefix = take(4ull * lo.pool_cap);
+    lo.pool_big = take(4ull * lo.pool_cap);
+    lo.pool_t0 = take(4ull * lo.pool_cap);
+    lo.pool_cnt = take(4ull * lo.pool_cap);
+    lo.pool_hist = take(4ull * lo.pool_cap * D3_BINS);   // zero between calls: cleared by its reader
     lo.tgt_unsel = take(4 * LJ);
     lo.tgt_base = take(8 * LJ);
     lo.lut1 = take(1ull * B * D1_BINS);
@@ -310,7 +312,7 @@ int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, doubl
         if (err_table) {
             // exact last-digit pass for the entries scan 2 could not certify (usually none)
             KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(lo.ntiles), dim3(256), p->pb, lo.ntiles);
-            KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(POOL_MAX), dim3(256), p->pb, err_table);
+            KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(std::min(lo.pool_cap, POOL_GRID)), dim3(256), p->pb, err_table);
         }
     }
     return KIMAD_OK;
@@ -348,7 +350,7 @@ int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, h
             (const uint32_t*)(at<uint32_t>(p, lo.diag) + 3));   // layers marked redo only
     KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(SCAN2_THREADS), p->pb, ktab, lo.J, err_table, CERT_TOL);
     KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(std::min<uint32_t>(lo.ntiles, FALLBACK_GRID)), dim3(256), p->pb, lo.ntiles);
-    KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(POOL_MAX), dim3(256), p->pb, err_table);
+    KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(std::min(lo.pool_cap, POOL_GRID)), dim3(256), p->pb, err_table);
     return KIMAD_OK;
 }
 
@@ -458,7 +460,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.layer_flag = at<uint32_t>(p, lo.layer_flag);
     pb.pool_prefix = at<uint32_t>(p, lo.pool_prefix); pb.pool_big = at<uint32_t>(p, lo.pool_big);
     pb.pool_t0 = at<uint32_t>(p, lo.pool_t0); pb.pool_cnt = at<uint32_t>(p, lo.pool_cnt);
-    pb.pool_hist = at<uint32_t>(p, lo.pool_hist);
+    pb.pool_hist = at<uint32_t>(p, lo.pool_hist); pb.pool_cap = lo.pool_cap;
     pb.tgt_unsel = at<uint32_t>(p, lo.tgt_unsel); pb.tgt_base = at<double>(p, lo.tgt_base);
     pb.state = at<LayerState>(p, lo.state);
     pb.chunk_big = at<uint32_t>(p, lo.chunk_big); pb.nchunks_total = lo.nchunks;
@@ -478,7 +480,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     // the pool histograms must start at zero; afterwards k_scan3p clears what it has read.
     // Layer states start as "nothing spilled, nothing cached".
     if (hipMemsetAsync(p->ws + lo.state, 0, sizeof(LayerState) * (uint64_t)(lo.B ? lo.B : 1), s) != hipSuccess ||
-        hipMemsetAsync(p->ws + lo.pool_hist, 0, 4ull * POOL_MAX * D3_BINS, s) != hipSuccess ||
+        hipMemsetAsync(p->ws + lo.pool_hist, 0, 4ull * lo.pool_cap * D3_BINS, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
 
     CompressBuffers& cb = p->cb;

@@ -31,7 +31,8 @@ def _full_check(work, reuse=True, classic=False, hint=True, expect_redo=None):
     torch.cuda.synchronize()
     gh.assert_table_close(E_gpu, E_ref, Kt, work.sizes)
     diag = plan.diagnostics()
-    assert diag["uncertified"] == diag["recomputed"], "every entry with a loose bound must be recomputed exactly"
+    # an entry with a loose bound is recomputed exactly, together with the entries sharing its threshold prefix
+    assert diag["recomputed"] >= diag["uncertified"] and (diag["uncertified"] == 0) == (diag["pool_entries"] == 0), diag
     if expect_redo is not None:
         assert diag["redo_layers"] == expect_redo, diag
     assert np.array_equal(h.cpu().numpy().view(np.uint32), work.h.view(np.uint32)), "profile must not touch h"
@@ -162,7 +163,7 @@ def test_gpt2_full_size_in_the_benchmark_configuration():
     torch.cuda.synchronize()
     assert status.cpu().tolist() == [0, 0]
     diag = plan.diagnostics()
-    assert diag["uncertified"] == diag["recomputed"]
+    assert diag["recomputed"] >= diag["uncertified"]
     Kt = plan.grid_sizes()
     E_gpu = plan.err_table.cpu().numpy().reshape(work.L, -1)
     K = plan.K.cpu().numpy().astype(np.uint64)
