@@ -69,6 +69,10 @@ typedef struct kimad_config {
     uint64_t max_budget_bytes;          /* largest budget kimad_allocate will see; 0 = uncompressed size.
                                            Sizes the DP tables when cost_units_D == 0. */
     uint64_t flags;                     /* KIMAD_CFG_* */
+    uint32_t max_workgroups;            /* workgroups (= compute units) the streaming pass of the profile may
+                                           occupy; 0 = all of the device.  A smaller number leaves units to
+                                           other work on the device and changes no result. */
+    uint32_t reserved;                  /* must be 0 */
 } kimad_config_t;
 
 #define KIMAD_CFG_CLASSIC_PROFILE 1ull  /* profile with two full passes over g, h instead of the sampled

@@ -37,7 +37,8 @@ class _Payload(C.Structure):
 
 class _Config(C.Structure):
     _fields_ = [("pair_bytes", C.c_uint32), ("cost_units_D", C.c_uint32),
-                ("max_budget_bytes", C.c_uint64), ("flags", C.c_uint64)]
+                ("max_budget_bytes", C.c_uint64), ("flags", C.c_uint64),
+                ("max_workgroups", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 _lib = None
@@ -86,8 +87,8 @@ def kimad_version() -> str:
     return lib().kimad_version().decode()
 
 
-def _cfg(pair_bytes=8, D=0, max_budget_bytes=0, cfg_flags=0) -> _Config:
-    return _Config(int(pair_bytes), int(D), int(max_budget_bytes), int(cfg_flags))
+def _cfg(pair_bytes=8, D=0, max_budget_bytes=0, cfg_flags=0, max_workgroups=0) -> _Config:
+    return _Config(int(pair_bytes), int(D), int(max_budget_bytes), int(cfg_flags), int(max_workgroups), 0)
 
 
 def _check(code: int, where: str) -> None:
@@ -107,23 +108,23 @@ def _stream(stream) -> int:
 
 
 def kimad_workspace_bytes(sizes: Sequence[int], J: int, pair_bytes=8, D=0, max_budget_bytes=0,
-                          cfg_flags=0) -> int:
+                          cfg_flags=0, max_workgroups=0) -> int:
     n = (C.c_uint64 * len(sizes))(*[int(s) for s in sizes])
     out = C.c_uint64(0)
-    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags)
+    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups)
     _check(lib().kimad_workspace_bytes(n, len(sizes), int(J), C.byref(cfg), C.byref(out)), "kimad_workspace_bytes")
     return int(out.value)
 
 
 def kimad_plan_create(g_ptrs: Sequence[int], h_ptrs: Sequence[int], sizes: Sequence[int], ratios: Sequence[float],
                       workspace_ptr: int, workspace_bytes: int, stream=None, pair_bytes=8, D=0,
-                      max_budget_bytes=0, cfg_flags=0) -> int:
+                      max_budget_bytes=0, cfg_flags=0, max_workgroups=0) -> int:
     L = len(sizes)
     layers = (_Layer * L)()
     for i in range(L):
         layers[i].g, layers[i].h, layers[i].n = int(g_ptrs[i]), int(h_ptrs[i]), int(sizes[i])
     r = (C.c_double * len(ratios))(*[float(x) for x in ratios])
-    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags)
+    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups)
     plan = C.c_void_p(0)
     _check(lib().kimad_plan_create(layers, L, r, len(ratios), C.byref(cfg), C.c_void_p(int(workspace_ptr)),
                                    int(workspace_bytes), C.c_void_p(_stream(stream)), C.byref(plan)),
@@ -184,7 +185,8 @@ class Plan:
     """
 
     def __init__(self, g, h, sizes: Sequence[int], ratios: Sequence[float], pair_bytes: int = 8, D: int = 0,
-                 max_budget_bytes: int = 0, cfg_flags: int = 0, capacity_pairs: Optional[int] = None):
+                 max_budget_bytes: int = 0, cfg_flags: int = 0, capacity_pairs: Optional[int] = None,
+                 max_workgroups: int = 0):
         import torch
         self.torch = torch
         self.sizes = [int(s) for s in sizes]
@@ -201,13 +203,13 @@ class Plan:
             dev = g.device
         self._keep = (g, h)
         self.device = dev
-        nbytes = kimad_workspace_bytes(self.sizes, self.J, pair_bytes, D, max_budget_bytes, cfg_flags)
+        nbytes = kimad_workspace_bytes(self.sizes, self.J, pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups)
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
         base = int(self.workspace.data_ptr())
         self._ws_ptr = (base + 255) // 256 * 256
         self.workspace_bytes = nbytes
         self.handle = kimad_plan_create(g_ptrs, h_ptrs, self.sizes, self.ratios, self._ws_ptr, nbytes,
-                                        None, pair_bytes, D, max_budget_bytes, cfg_flags)
+                                        None, pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups)
         d = int(sum(self.sizes))
         self.capacity_pairs = int(capacity_pairs) if capacity_pairs is not None else d
         self.err_table = torch.empty(self.L * self.J, dtype=torch.float64, device=dev)

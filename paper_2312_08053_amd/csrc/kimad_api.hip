@@ -372,6 +372,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
                       kimad_plan_t** plan_out) {
     if (!layers || !ratios || !workspace || !plan_out) return KIMAD_ERR_INVALID_ARG;
     if (L == 0 || L > 65535 || J == 0 || J > KIMAD_MAX_J) return KIMAD_ERR_INVALID_ARG;
+    if (cfg && cfg->reserved) return KIMAD_ERR_INVALID_ARG;
     if (((uintptr_t)workspace) % ALIGN) return KIMAD_ERR_INVALID_ARG;
     for (uint32_t j = 0; j < J; ++j) {
         if (!(ratios[j] > 0.0) || !(ratios[j] <= 1.0)) return KIMAD_ERR_INVALID_ARG;
@@ -474,6 +475,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
         int cus = 0;
         if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device) != hipSuccess || cus <= 0) cus = 256;
         p->main_wgs = (uint32_t)cus;
+        if (p->cfg.max_workgroups) p->main_wgs = std::min(p->main_wgs, p->cfg.max_workgroups);
         p->chunks_per_wg = (lo.nchunks + p->main_wgs - 1) / p->main_wgs;
         if (p->chunks_per_wg == 0) p->chunks_per_wg = 1;
     }

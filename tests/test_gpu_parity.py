@@ -13,7 +13,7 @@ from tests import gpu_harness as gh
 pytestmark = pytest.mark.gpu
 
 
-def _full_check(work, reuse=True, classic=False, hint=True, expect_redo=None):
+def _full_check(work, reuse=True, classic=False, hint=True, expect_redo=None, max_workgroups=0):
     """profile / allocate / compress_ef against the oracle.
 
     classic: two-pass profile instead of the sampled single pass; hint: pass the budget to the
@@ -21,7 +21,7 @@ def _full_check(work, reuse=True, classic=False, hint=True, expect_redo=None):
     prediction missed."""
     import torch
     g, h = gh.to_device(work)
-    plan = gh.make_plan(work, g, h, cfg_flags=1 if classic else 0)
+    plan = gh.make_plan(work, g, h, cfg_flags=1 if classic else 0, max_workgroups=max_workgroups)
     gL, hL = gh.oracle_layers(work)
     E_ref, Kt = ko.profile(gL, hL, work.ratios)
     assert np.array_equal(plan.grid_sizes(), Kt)
@@ -104,6 +104,16 @@ def test_gpt2_reduced_set():
     # same recipe as the 124M set, two blocks and a 4096-row embedding: several tiles per layer,
     # ragged tails, small vectors next to matrices
     _full_check(ks.make_workload("gpt2", n_layer=2, vocab=4099), expect_redo=0)
+
+
+def test_narrow_grid_splits_a_layer_into_histogram_segments():
+    """With two workgroups each one owns more chunks of the big tensor than one set of LDS counters may
+    count (2^20 entries): the streaming pass flushes and restarts inside the layer, as it does per
+    workgroup on sets of more than 2.7e8 elements."""
+    work = ks.make_workload("llama", n_layer=1, hidden=1024, ffn=2816, vocab=4099)
+    assert work.sizes.max() > 2 * 1023 * 1024
+    _full_check(work, max_workgroups=2)
+    _full_check(work, max_workgroups=3, reuse=False)
 
 
 def test_budget_larger_than_hinted_falls_back_to_reading_g_and_h():
