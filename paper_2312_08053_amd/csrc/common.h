@@ -75,6 +75,8 @@ struct SelRec {
     uint64_t tmp_base; // start of this layer's region in the candidate buffer
     uint32_t cap;      // candidates this layer may write
     uint32_t K;
+    float* h;          // the layer's estimator
+    uint64_t dst;      // first payload slot of the layer
 };
 
 // ---- global-memory accessors ----------------------------------------------------------------
@@ -100,6 +102,10 @@ __device__ __forceinline__ void gstore4(float* p, float4 v) {
 }
 
 // ---- small device helpers ----------------------------------------------------------------
+// Makes the compiler hold a loaded value in a register here.  Placed after a group of independent
+// loads and before the first branch on one of them, it keeps the loads together in front of the
+// branch: one memory round trip instead of one per load.
+__device__ __forceinline__ void materialise(uint32_t v) { asm volatile("" ::"v"(v)); }
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
 
 __device__ __forceinline__ uint32_t mbcnt(uint64_t mask) {

@@ -80,6 +80,8 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
         const uint32_t li = cb.big_layer[b];
         const uint32_t n = cb.layers[li].n;
         r.tmp_base = cb.layers[li].tmp0;
+        r.h = cb.layers[li].h;
+        r.dst = cb.offsets[li];
         if (!offsets_bad) {
             const uint32_t K = (uint32_t)cb.K[li];
             r.K = K;
@@ -408,27 +410,32 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
     bool filter = false;
     float* h = nullptr;
     if (chunk < nchunks_total) {
+        // everything indexed by the chunk is fetched at once; one more round trip brings the layer's record
         const uint32_t b = chunk_big[chunk];
-        const SelRec S = cb.sel[b];
-        if (S.mode != SEL_NONE) {
-            const uint32_t li = cb.big_layer[b];
-            cnt = cb.rec_cnt[chunk];
-            h = cb.layers[li].h;
-            filter = S.mode == SEL_CAND || (S.mode == SEL_PREFIX && cb.rec_amb[chunk] != 0u);
+        const uint32_t keepn = cb.c_gt[chunk];
+        const uint32_t n_rec = cb.rec_cnt[chunk], start = cb.rec_start[chunk], amb = cb.rec_amb[chunk];
+        allow = cb.o_allow[chunk];
+        out_run = cb.o_base[chunk];
+        materialise(b); materialise(keepn); materialise(n_rec); materialise(start); materialise(amb);
+        materialise(allow); materialise(out_run);
+        // most chunks keep nothing (the candidates are several times the payload): not read at all
+        if (keepn + allow != 0u) {
+            // every field of the record is valid whatever the mode; SEL_NONE only empties the chunk.
+            // (Kept free of a nested branch on the mode: with one, the generated code left dst undefined
+            // for SEL_CAND lanes.)
+            const SelRec S = cb.sel[b];
             tau = cb.tau[b];
-            allow = cb.o_allow[chunk];
-            src = S.tmp_base + cb.rec_start[chunk];
-            dst = cb.offsets[li];
+            cnt = S.mode != SEL_NONE ? n_rec : 0u;
+            h = S.h;
+            filter = S.mode == SEL_CAND || (S.mode == SEL_PREFIX && amb != 0u);
+            src = S.tmp_base + start;
+            dst = S.dst;
             room = S.K;                            // payload slots of this layer
-            out_run = cb.o_base[chunk];
         }
     }
     const uint32_t cmax = wave_max_over_groups(cnt);
-    for (uint32_t k0 = 0; k0 < cmax; k0 += SUB) {
-        const uint32_t k = k0 + g.sub;
-        const bool in = k < cnt;
-        uint32_t idx = 0; float x = 0.f;
-        if (in) { idx = cb.tmp_idx[src + k]; x = cb.tmp_x[src + k]; }
+    // one round: sixteen candidates of the chunk, in index order
+    auto round = [&](bool in, uint32_t idx, float x) {
         const uint32_t key = key_of(x);
         const bool iseq = in && filter && key == tau;
         const uint32_t eqm = ballot_sub(g, iseq);
@@ -443,6 +450,28 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
             gstore(h + idx, gload(h + idx) + x);   // the estimator is read here: candidates carry (index, x) only
         }
         out_run += __popc(km);
+    };
+    // A chunk rarely holds more than 64 candidates: the loads of the first four rounds go out together,
+    // so the wave pays one memory round trip for them instead of four.
+    constexpr int AHEAD = 4;
+    uint32_t pidx[AHEAD];
+    float px[AHEAD];
+    // (positions past the chunk's last candidate read its first one again, a valid address, and are dropped)
+#pragma unroll
+    for (int t = 0; t < AHEAD; ++t) {
+        const uint32_t k = (uint32_t)t * SUB + g.sub;
+        const uint32_t kc = k < cnt ? k : 0u;
+        pidx[t] = cb.tmp_idx[src + kc]; px[t] = cb.tmp_x[src + kc];
+    }
+#pragma unroll
+    for (int t = 0; t < AHEAD; ++t)
+        if ((uint32_t)t * SUB < cmax) round((uint32_t)t * SUB + g.sub < cnt, pidx[t], px[t]);
+    for (uint32_t k0 = AHEAD * SUB; k0 < cmax; k0 += SUB) {
+        const uint32_t k = k0 + g.sub;
+        const bool in = k < cnt;
+        uint32_t idx = 0; float x = 0.f;
+        if (in) { idx = cb.tmp_idx[src + k]; x = cb.tmp_x[src + k]; }
+        round(in, idx, x);
     }
 }
 

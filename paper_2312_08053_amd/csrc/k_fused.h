@@ -680,25 +680,38 @@ __global__ __launch_bounds__(256) void k_hist2c(ProfileBuffers pb) {
     const SubGroup g = sub_group();
     const uint32_t chunk = blockIdx.x * CHUNKS_PER_WG + threadIdx.x / SUB;
     if (chunk >= pb.nchunks_total) return;
+    // what the chunk index alone addresses is fetched together; the layer's state and region follow
     const uint32_t big = pb.chunk_big[chunk];
-    const LayerState st = pb.state[big];
-    if (st.redo || st.nslots_t == 0u) return;
     const uint32_t cnt = pb.rec_cnt[chunk];
+    const uint32_t start = pb.rec_start[chunk];
+    materialise(big); materialise(cnt); materialise(start);
     if (cnt == 0u) return;
-    const uint32_t li = pb.big_layer[big];
-    const uint64_t base = pb.layers[li].tmp0 + pb.rec_start[chunk];
+    const LayerState st = pb.state[big];
+    const uint64_t base = pb.big_tmp0[big] + start;
+    materialise((uint32_t)base);
+    if (st.redo || st.nslots_t == 0u) return;
     const uint8_t* lutc = pb.lutc + (size_t)big * D1_BINS;
     uint32_t* c2 = pb.cnt2 + (size_t)big * SLOT_STRIDE * D2_BINS;
     unsigned long long* s2 = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)big * SLOT_STRIDE * D2_BINS;
-    for (uint32_t k = g.sub; k < cnt; k += SUB) {
-        const uint32_t key = key_of(pb.tmp_x[base + k]);
-        const uint32_t bin = key >> D1_SHIFT;
-        const uint32_t slot = lutc[bin];
-        if (slot == NO_SLOT) continue;
-        const uint32_t e = slot * D2_BINS + ((key >> D2_SHIFT) & (D2_BINS - 1));
-        const unsigned long long s = bin ? (unsigned long long)sq_fixed(key) : sq_exact(key);
-        atomicAdd(&c2[e], 1u);
-        if (s) atomicAdd(&s2[e], s);
+    // Four rounds at a time: their keys are loaded together, then their slots.  Positions past the
+    // chunk's last candidate read that last candidate again (always a valid address) and are dropped.
+    constexpr int AHEAD = 4;
+    for (uint32_t k0 = g.sub; k0 < cnt; k0 += AHEAD * SUB) {
+        uint32_t key[AHEAD], slot[AHEAD];
+#pragma unroll
+        for (int t = 0; t < AHEAD; ++t)
+            key[t] = key_of(pb.tmp_x[base + min(k0 + (uint32_t)t * SUB, cnt - 1u)]);
+#pragma unroll
+        for (int t = 0; t < AHEAD; ++t) slot[t] = (uint32_t)lutc[key[t] >> D1_SHIFT];
+#pragma unroll
+        for (int t = 0; t < AHEAD; ++t) {
+            if (slot[t] == NO_SLOT || k0 + (uint32_t)t * SUB >= cnt) continue;
+            const uint32_t bin = key[t] >> D1_SHIFT;
+            const uint32_t e = slot[t] * D2_BINS + ((key[t] >> D2_SHIFT) & (D2_BINS - 1));
+            const unsigned long long s = bin ? (unsigned long long)sq_fixed(key[t]) : sq_exact(key[t]);
+            atomicAdd(&c2[e], 1u);
+            if (s) atomicAdd(&s2[e], s);
+        }
     }
 }
 

@@ -47,6 +47,7 @@ struct ProfileBuffers {
     double* tgt_base;             // E without the prefix bin's share
     // fused single-pass profile
     LayerState* state;            // [B]
+    const uint64_t* big_tmp0;     // [B] start of the layer's region in the candidate buffer (LayerDesc::tmp0)
     const uint32_t* chunk_big;    // chunk -> big index
     uint32_t nchunks_total;
     const uint32_t* swg_layer;    // sampling workgroup -> layer

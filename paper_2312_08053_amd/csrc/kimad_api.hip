@@ -40,6 +40,7 @@ struct Layout {
     // zeroed before every profile
     uint64_t swg_layer, swg_first, state, lutc;
     uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, shist, ghist, cursor, spill_over, zero1_end;
+    uint64_t big_tmp0;
     uint64_t pool_prefix, pool_big, pool_t0, pool_cnt, pool_hist, tgt_unsel, tgt_base;
     uint32_t pool_cap = 1;
     uint64_t lut1, nslots, slot_bin;
@@ -139,6 +140,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.tile_layer = take(4ull * (nt ? nt : 1));
     lo.chunk_big = take(4ull * (nc ? nc : 1));
     lo.big_layer = take(4ull * (B ? B : 1));
+    lo.big_tmp0 = take(8ull * (B ? B : 1));
     lo.small_layer = take(4ull * (S ? S : 1));
     lo.swg_layer = take(4ull * (nsw ? nsw : 1));
     lo.swg_first = take(4ull * (nsw ? nsw : 1));
@@ -398,6 +400,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     std::vector<LayerDesc> ld(L);
     std::vector<uint32_t> tile_layer(lo.ntiles ? lo.ntiles : 1), chunk_big(lo.nchunks ? lo.nchunks : 1);
     std::vector<uint32_t> big_layer(lo.B ? lo.B : 1), small_layer(lo.S ? lo.S : 1);
+    std::vector<uint64_t> big_tmp0(lo.B ? lo.B : 1);
     std::vector<uint32_t> swg_layer(lo.nswg ? lo.nswg : 1), swg_first(lo.nswg ? lo.nswg : 1);
     std::vector<uint32_t> cblk_big(lo.ncblk ? lo.ncblk : 1);
     p->ktab.resize((size_t)L * J);
@@ -422,6 +425,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
                 swg_first[h.swg0 + w] = w * SAMPLE_GROUPS_PER_WG;
             }
             big_layer[h.big] = i;
+            big_tmp0[h.big] = h.tmp0;
         } else {
             d.tile0 = d.ntiles = d.chunk0 = d.nchunks = 0;
             d.sstride = 1; d.cblk0 = 0; d.tmp0 = 0;
@@ -438,6 +442,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
               up(lo.tile_layer, tile_layer.data(), 4ull * tile_layer.size()) &&
               up(lo.chunk_big, chunk_big.data(), 4ull * chunk_big.size()) &&
               up(lo.big_layer, big_layer.data(), 4ull * big_layer.size()) &&
+              up(lo.big_tmp0, big_tmp0.data(), 8ull * big_tmp0.size()) &&
               up(lo.small_layer, small_layer.data(), 4ull * small_layer.size()) &&
               up(lo.swg_layer, swg_layer.data(), 4ull * swg_layer.size()) &&
               up(lo.swg_first, swg_first.data(), 4ull * swg_first.size()) &&
@@ -463,7 +468,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.pool_t0 = at<uint32_t>(p, lo.pool_t0); pb.pool_cnt = at<uint32_t>(p, lo.pool_cnt);
     pb.pool_hist = at<uint32_t>(p, lo.pool_hist); pb.pool_cap = lo.pool_cap;
     pb.tgt_unsel = at<uint32_t>(p, lo.tgt_unsel); pb.tgt_base = at<double>(p, lo.tgt_base);
-    pb.state = at<LayerState>(p, lo.state);
+    pb.state = at<LayerState>(p, lo.state); pb.big_tmp0 = at<uint64_t>(p, lo.big_tmp0);
     pb.chunk_big = at<uint32_t>(p, lo.chunk_big); pb.nchunks_total = lo.nchunks;
     pb.swg_layer = at<uint32_t>(p, lo.swg_layer); pb.swg_first = at<uint32_t>(p, lo.swg_first);
     pb.shist = at<uint32_t>(p, lo.shist); pb.ghist = at<unsigned long long>(p, lo.ghist);
