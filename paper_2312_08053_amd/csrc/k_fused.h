@@ -215,6 +215,7 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
 // half that interval (2^-23 relative).
 constexpr uint32_t PK_ENTRIES = D1_BINS + PRE_SLOTS * D2_BINS;     // 16384 entries, 128 KB
 constexpr uint32_t STAGE = 128;                                    // candidates a wave stages per round
+constexpr uint32_t PART_STRIDE = PK_ENTRIES + 8;                   // entries of one part: the LDS array, then the bin-0 sum
 
 __device__ __forceinline__ unsigned long long pk_term(uint32_t key) {
     const uint32_t m = key & 0x7FFFFFu, e = key >> 23;
@@ -439,7 +440,7 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
 }
 
 __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint32_t chunks_per_wg) {
-    __shared__ unsigned long long pk[PK_ENTRIES];                 // 128 KB
+    __shared__ __align__(16) unsigned long long pk[PK_ENTRIES];   // 140 KB
     __shared__ unsigned long long sq0;
     __shared__ uint2 stage[FUSED_WAVES * STAGE];                  // 16 KB: per-wave block windows
     __shared__ uint32_t pend[FUSED_WAVES * PEND * 3];             // 3 KB
@@ -448,6 +449,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
     const uint32_t c_begin = blockIdx.x * chunks_per_wg;
     const uint32_t c_end = min(pb.nchunks_total, c_begin + chunks_per_wg);
     uint32_t cur = c_begin;
+    uint32_t part = pb.wg_part0[blockIdx.x];
     while (cur < c_end) {
         const uint32_t big = pb.chunk_big[cur];
         const uint32_t li = pb.big_layer[big];
@@ -484,26 +486,81 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         }
         spill_flush(pb, ws, L.tmp0);
         __syncthreads();
-        // flush this layer's share: counts as they are, sums as midpoints in units of 2^16
-        uint32_t* gc1 = pb.cnt1 + (size_t)big * D1_BINS;
-        unsigned long long* gs1 = reinterpret_cast<unsigned long long*>(pb.sq1) + (size_t)big * D1_BINS;
-        uint32_t* gc2 = pb.cnt2 + (size_t)big * SLOT_STRIDE * D2_BINS;
-        unsigned long long* gs2 = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)big * SLOT_STRIDE * D2_BINS;
-        for (uint32_t b = tid; b < used; b += FUSED_THREADS) {
-            const unsigned long long v = pk[b];
-            if (v) {
-                const uint32_t n1 = (uint32_t)(v >> 44);
-                const unsigned long long t = v & PK_MASK;
-                const uint32_t bin = b < D1_BINS ? b : pb.slot_bin[(size_t)big * SLOT_STRIDE + (b - D1_BINS) / D2_BINS];
-                // exponent 255: t counts NaNs and is kept; bin 0: exact squares from sq0
-                const unsigned long long s2 = (bin >> 4) == 255u ? t
-                                            : (b == 0u ? sq0 : (t << 8) + ((unsigned long long)n1 << 7));
-                if (b < D1_BINS) { atomicAdd(&gc1[b], n1); if (s2) atomicAdd(&gs1[b], s2); }
-                else { atomicAdd(&gc2[b - D1_BINS], n1); if (s2) atomicAdd(&gs2[b - D1_BINS], s2); }
+        // This segment's histogram goes out as it is, with plain coalesced stores, as one "part" of the
+        // layer; k_reduce_parts adds the parts up.  (Adding into the layer's arrays with global atomics
+        // from here held every workgroup of a layer up on the same cache lines at the same moment.)
+        ulonglong2* out = reinterpret_cast<ulonglong2*>(pb.parts + (size_t)part * PART_STRIDE);
+        const ulonglong2* pk2 = reinterpret_cast<const ulonglong2*>(pk);
+        for (uint32_t b = tid; b < used / 2u; b += FUSED_THREADS) out[b] = pk2[b];   // `used` is even
+        if (tid == 0) pb.parts[(size_t)part * PART_STRIDE + PK_ENTRIES] = sq0;
+        ++part;
+        // the next segment clears the LDS array: its reads above must be done, the stores need not be
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        cur = seg_end;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Sum of a layer's parts, written in the layout the scans read: digit-1 counts and sums, then the
+// digit-2 tables of all SLOT_STRIDE slots (zero beyond the slots the pass counted, where k_hist2c
+// adds).  Counts as they are; sums as midpoints in units of 2^16 (exponent 255: the NaN count;
+// bin 0: the exact squares).  One thread per entry, the parts' loads issued four at a time.
+constexpr uint32_t LAYER_ENTRIES = D1_BINS + SLOT_STRIDE * D2_BINS;
+constexpr uint32_t REDUCE_ENTRIES = 128;        // entries per workgroup: two per lane, each of the 4 waves takes a quarter of the parts
+__global__ __launch_bounds__(256) void k_reduce_parts(ProfileBuffers pb) {
+    __shared__ unsigned long long sh_c[3][REDUCE_ENTRIES], sh_t[3][REDUCE_ENTRIES];
+    const uint32_t big = blockIdx.y, lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
+    const uint32_t e = blockIdx.x * REDUCE_ENTRIES + 2u * lane;     // and e + 1; `used` is even
+    const uint32_t used = D1_BINS + pb.state[big].nslots_d * D2_BINS;
+    const uint32_t p0 = pb.big_part0[big], np = pb.big_nparts[big];
+    unsigned long long cnt[2] = {0, 0}, t[2] = {0, 0};
+    if (e < used) {
+        const unsigned long long* src = pb.parts + (size_t)p0 * PART_STRIDE + e;
+        auto take = [&](const ulonglong2 v) {
+            cnt[0] += v.x >> 44; t[0] += v.x & PK_MASK;
+            cnt[1] += v.y >> 44; t[1] += v.y & PK_MASK;
+        };
+        auto part = [&](uint32_t k) { return *reinterpret_cast<const ulonglong2*>(src + (size_t)k * PART_STRIDE); };
+        uint32_t k = w;
+        for (; k + 12 < np; k += 16) {
+            const ulonglong2 v0 = part(k), v1 = part(k + 4), v2 = part(k + 8), v3 = part(k + 12);
+            take(v0); take(v1); take(v2); take(v3);
+        }
+        for (; k < np; k += 4) take(part(k));
+    }
+    if (w) {
+        sh_c[w - 1][2 * lane] = cnt[0]; sh_c[w - 1][2 * lane + 1] = cnt[1];
+        sh_t[w - 1][2 * lane] = t[0]; sh_t[w - 1][2 * lane + 1] = t[1];
+    }
+    __syncthreads();
+    if (w || e >= LAYER_ENTRIES) return;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+        cnt[0] += sh_c[q][2 * lane]; cnt[1] += sh_c[q][2 * lane + 1];
+        t[0] += sh_t[q][2 * lane]; t[1] += sh_t[q][2 * lane + 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const uint32_t eu = e + (uint32_t)u;
+        unsigned long long s2 = 0;
+        if (cnt[u]) {
+            const uint32_t bin = eu < D1_BINS ? eu : pb.slot_bin[(size_t)big * SLOT_STRIDE + (eu - D1_BINS) / D2_BINS];
+            if ((bin >> 4) == 255u) {
+                s2 = t[u];
+            } else if (eu == 0u) {
+                for (uint32_t q = 0; q < np; ++q) s2 += pb.parts[(size_t)(p0 + q) * PART_STRIDE + PK_ENTRIES];
+            } else {
+                s2 = (t[u] << 8) + (cnt[u] << 7);
             }
         }
-        __syncthreads();
-        cur = seg_end;
+        if (eu < D1_BINS) {
+            pb.cnt1[(size_t)big * D1_BINS + eu] = (uint32_t)cnt[u];
+            reinterpret_cast<unsigned long long*>(pb.sq1)[(size_t)big * D1_BINS + eu] = s2;
+        } else {
+            const size_t o = (size_t)big * SLOT_STRIDE * D2_BINS + (eu - D1_BINS);
+            pb.cnt2[o] = (uint32_t)cnt[u];
+            reinterpret_cast<unsigned long long*>(pb.sq2)[o] = s2;
+        }
     }
 }
 

@@ -48,6 +48,11 @@ struct ProfileBuffers {
     // fused single-pass profile
     LayerState* state;            // [B]
     const uint64_t* big_tmp0;     // [B] start of the layer's region in the candidate buffer (LayerDesc::tmp0)
+    // histograms of the streaming pass, one copy ("part") per workgroup and segment of a layer
+    unsigned long long* parts;    // [nparts][PART_STRIDE] packed LDS entries as they were, then the exact bin-0 sum
+    const uint32_t* wg_part0;     // [workgroups] first part of each workgroup (its parts follow in order)
+    const uint32_t* big_part0;    // [B] first part of each big layer
+    const uint32_t* big_nparts;   // [B]
     const uint32_t* chunk_big;    // chunk -> big index
     uint32_t nchunks_total;
     const uint32_t* swg_layer;    // sampling workgroup -> layer

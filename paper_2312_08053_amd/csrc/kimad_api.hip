@@ -40,7 +40,8 @@ struct Layout {
     // zeroed before every profile
     uint64_t swg_layer, swg_first, state, lutc;
     uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, shist, ghist, cursor, spill_over, zero1_end;
-    uint64_t big_tmp0;
+    uint64_t big_tmp0, parts, wg_part0, big_part0, big_nparts, zero1_mid;
+    uint32_t main_wgs = 256, chunks_per_wg = 1, nparts = 0;
     uint64_t pool_prefix, pool_big, pool_t0, pool_cnt, pool_hist, tgt_unsel, tgt_base;
     uint32_t pool_cap = 1;
     uint64_t lut1, nslots, slot_bin;
@@ -81,8 +82,52 @@ uint32_t grid_size_K(double r, uint64_t n) {
 
 // Shapes only: misalignment is taken as the worst case (3) so that the layout does not depend on
 // pointer values and kimad_workspace_bytes can be called before the tensors exist.
+// Workgroups of the streaming pass: one per compute unit of the current device (256 if no device
+// answers, as when only the workspace size is asked for on a machine without one), at most 1024,
+// and at most cfg.max_workgroups.
+uint32_t stream_workgroups(const kimad_config_t& cfg) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        (void)hipGetLastError();
+        cus = 256;
+    }
+    uint32_t w = (uint32_t)std::min(cus, 1024);
+    if (cfg.max_workgroups) w = std::min(w, cfg.max_workgroups);
+    return w;
+}
+
+// The parts of the streaming pass: workgroup w walks chunks [w * per, (w + 1) * per) and starts a new
+// histogram at every layer boundary and after PK_MAX_CHUNKS chunks, exactly as k_main does.
+struct PartTables {
+    std::vector<uint32_t> wg_part0, big_part0, big_nparts;
+};
+uint32_t plan_parts(const std::vector<HostLayer>& hl, uint32_t B, uint32_t nchunks, uint32_t wgs, uint32_t per,
+                    PartTables* out) {
+    std::vector<uint32_t> c0(B ? B : 1), c1(B ? B : 1);
+    for (const HostLayer& h : hl)
+        if (h.big >= 0) { c0[h.big] = h.chunk0; c1[h.big] = h.chunk0 + h.nchunks; }
+    if (out) { out->wg_part0.assign(wgs, 0); out->big_part0.assign(B ? B : 1, 0); out->big_nparts.assign(B ? B : 1, 0); }
+    uint32_t part = 0, b = 0;
+    for (uint32_t w = 0; w < wgs; ++w) {
+        uint64_t cur = (uint64_t)w * per;
+        const uint64_t c_end = std::min<uint64_t>(nchunks, cur + per);
+        if (out) out->wg_part0[w] = part;
+        while (cur < c_end) {
+            while (cur >= c1[b]) ++b;
+            const uint64_t seg_end = std::min<uint64_t>(std::min<uint64_t>(c_end, c1[b]), cur + PK_MAX_CHUNKS);
+            if (out) { if (out->big_nparts[b]++ == 0) out->big_part0[b] = part; }
+            ++part;
+            cur = seg_end;
+        }
+    }
+    return part;
+}
+
 int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t& cfg, Layout& lo,
-                std::vector<HostLayer>* hl) {
+                std::vector<HostLayer>* hl_out, PartTables* parts_out = nullptr) {
+    std::vector<HostLayer> hl_local;
+    std::vector<HostLayer>* hl = hl_out ? hl_out : &hl_local;
     if (!n || L == 0 || L > 65535 || J == 0 || J > KIMAD_MAX_J) return KIMAD_ERR_INVALID_ARG;
     lo.L = L; lo.J = J;
     uint64_t d_big = 0, d_all = 0;
@@ -96,7 +141,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.tile_elems = pick_tile_elems(d_big);
     uint64_t nt = 0, nc = 0, tmp_run = 0;
     uint32_t nsw = 0, ncblk = 0;
-    if (hl) hl->resize(L);
+    hl->resize(L);
     int32_t bi = 0;
     for (uint32_t i = 0; i < L; ++i) {
         HostLayer h{};
@@ -116,7 +161,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
             h.tmp0 = tmp_run; tmp_run += n[i] + REGION_SLACK;
             h.cblk0 = ncblk; h.ncblk = (h.nchunks + CBLOCK - 1) / CBLOCK; ncblk += h.ncblk;
         }
-        if (hl) (*hl)[i] = h;
+        (*hl)[i] = h;
     }
     lo.nswg = nsw;
     lo.ncblk = ncblk;
@@ -131,6 +176,9 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
         lo.dp_cells = std::min<uint64_t>(pmax, d_all) + 1;
     }
     lo.tmp_cap = tmp_run;                                 // one region of n + REGION_SLACK entries per tiled layer
+    lo.main_wgs = stream_workgroups(cfg);
+    lo.chunks_per_wg = std::max<uint32_t>(1, (lo.nchunks + lo.main_wgs - 1) / lo.main_wgs);
+    lo.nparts = plan_parts(*hl, B, lo.nchunks, lo.main_wgs, lo.chunks_per_wg, parts_out);
 
     uint64_t off = 0;
     auto take = [&](uint64_t bytes) { uint64_t o = off; off = align_up(off + bytes); return o; };
@@ -141,6 +189,10 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.chunk_big = take(4ull * (nc ? nc : 1));
     lo.big_layer = take(4ull * (B ? B : 1));
     lo.big_tmp0 = take(8ull * (B ? B : 1));
+    lo.wg_part0 = take(4ull * lo.main_wgs);
+    lo.big_part0 = take(4ull * (B ? B : 1));
+    lo.big_nparts = take(4ull * (B ? B : 1));
+    lo.parts = take(8ull * PART_STRIDE * (lo.nparts ? lo.nparts : 1));
     lo.small_layer = take(4ull * (S ? S : 1));
     lo.swg_layer = take(4ull * (nsw ? nsw : 1));
     lo.swg_first = take(4ull * (nsw ? nsw : 1));
@@ -151,6 +203,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.sq1 = take(8ull * B * D1_BINS);
     lo.cnt2 = take(4ull * B * SLOT_STRIDE * D2_BINS);
     lo.sq2 = take(8ull * B * SLOT_STRIDE * D2_BINS);
+    lo.zero1_mid = off;                                   // the single-pass profile writes the tables above whole
     lo.diag = take(16);
     lo.layer_flag = take(4ull * (B ? B : 1));
     lo.shist = take(4ull * B * D1_BINS);
@@ -337,12 +390,13 @@ int launch_small_profile(kimad_plan* p, double* err_table, hipStream_t s, hipStr
 int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, hipStream_t s, hipStream_t* side) {
     const Layout& lo = p->lo;
     const uint32_t* ktab = at<uint32_t>(p, lo.ktab);
-    int rc = zero_range(p, lo.zero1_begin, lo.zero1_end, s);
+    int rc = zero_range(p, lo.zero1_mid, lo.zero1_end, s);   // the histogram tables are written whole by k_reduce_parts
     if (rc) return rc;
     if (!lo.B) return launch_small_profile(p, err_table, s, side);
     KLAUNCH(p, s, "k_sample", k_sample, dim3(lo.nswg), dim3(SAMPLE_THREADS), p->pb);
     KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs);
     KLAUNCH(p, s, "k_main", k_main, dim3(p->main_wgs), dim3(FUSED_THREADS), p->pb, p->chunks_per_wg);
+    KLAUNCH(p, s, "k_reduce_parts", k_reduce_parts, dim3((LAYER_ENTRIES + REDUCE_ENTRIES - 1) / REDUCE_ENTRIES, lo.B), dim3(256), p->pb);
     rc = launch_small_profile(p, err_table, s, side);
     if (rc) return rc;
     KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J);
@@ -389,7 +443,8 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     kimad_plan* p = new (std::nothrow) kimad_plan();
     if (!p) return KIMAD_ERR_INVALID_ARG;
     p->cfg = normalise(cfg);
-    int rc = make_layout(n.data(), L, J, p->cfg, p->lo, &p->hl);
+    PartTables pt;
+    int rc = make_layout(n.data(), L, J, p->cfg, p->lo, &p->hl, &pt);
     if (rc) { delete p; return rc; }
     if (workspace_bytes < p->lo.total) { delete p; return KIMAD_ERR_WORKSPACE_TOO_SMALL; }
     p->ws = static_cast<char*>(workspace);
@@ -443,6 +498,9 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
               up(lo.chunk_big, chunk_big.data(), 4ull * chunk_big.size()) &&
               up(lo.big_layer, big_layer.data(), 4ull * big_layer.size()) &&
               up(lo.big_tmp0, big_tmp0.data(), 8ull * big_tmp0.size()) &&
+              up(lo.wg_part0, pt.wg_part0.data(), 4ull * pt.wg_part0.size()) &&
+              up(lo.big_part0, pt.big_part0.data(), 4ull * pt.big_part0.size()) &&
+              up(lo.big_nparts, pt.big_nparts.data(), 4ull * pt.big_nparts.size()) &&
               up(lo.small_layer, small_layer.data(), 4ull * small_layer.size()) &&
               up(lo.swg_layer, swg_layer.data(), 4ull * swg_layer.size()) &&
               up(lo.swg_first, swg_first.data(), 4ull * swg_first.size()) &&
@@ -469,6 +527,8 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.pool_hist = at<uint32_t>(p, lo.pool_hist); pb.pool_cap = lo.pool_cap;
     pb.tgt_unsel = at<uint32_t>(p, lo.tgt_unsel); pb.tgt_base = at<double>(p, lo.tgt_base);
     pb.state = at<LayerState>(p, lo.state); pb.big_tmp0 = at<uint64_t>(p, lo.big_tmp0);
+    pb.parts = at<unsigned long long>(p, lo.parts); pb.wg_part0 = at<uint32_t>(p, lo.wg_part0);
+    pb.big_part0 = at<uint32_t>(p, lo.big_part0); pb.big_nparts = at<uint32_t>(p, lo.big_nparts);
     pb.chunk_big = at<uint32_t>(p, lo.chunk_big); pb.nchunks_total = lo.nchunks;
     pb.swg_layer = at<uint32_t>(p, lo.swg_layer); pb.swg_first = at<uint32_t>(p, lo.swg_first);
     pb.shist = at<uint32_t>(p, lo.shist); pb.ghist = at<unsigned long long>(p, lo.ghist);
@@ -476,14 +536,8 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.spill_over = at<uint32_t>(p, lo.spill_over);
     pb.rec_start = at<uint32_t>(p, lo.rec_start); pb.rec_cnt = at<uint32_t>(p, lo.rec_cnt);
     pb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); pb.tmp_x = at<float>(p, lo.tmp_x);
-    {
-        int cus = 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, p->device) != hipSuccess || cus <= 0) cus = 256;
-        p->main_wgs = (uint32_t)cus;
-        if (p->cfg.max_workgroups) p->main_wgs = std::min(p->main_wgs, p->cfg.max_workgroups);
-        p->chunks_per_wg = (lo.nchunks + p->main_wgs - 1) / p->main_wgs;
-        if (p->chunks_per_wg == 0) p->chunks_per_wg = 1;
-    }
+    p->main_wgs = lo.main_wgs;
+    p->chunks_per_wg = lo.chunks_per_wg;
     // the pool histograms must start at zero; afterwards k_scan3p clears what it has read.
     // Layer states start as "nothing spilled, nothing cached".
     if (hipMemsetAsync(p->ws + lo.state, 0, sizeof(LayerState) * (uint64_t)(lo.B ? lo.B : 1), s) != hipSuccess ||
