@@ -175,25 +175,24 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
     uint8_t* lut = pb.lut1 + (size_t)big * D1_BINS;
     for (uint32_t b = tid; b < D1_BINS; b += 256) lut[b] = (uint8_t)NO_SLOT;
     __syncthreads();
+    // lowest and highest marked bin: one bitmap word per thread
+    if (tid == 0) { sh_gbin = D1_BINS; sh_ns = 0u; }      // reused: lowest / highest marked bin
+    __syncthreads();
+    if (tid < D1_BINS / 32) {
+        const uint32_t m = bitmap[tid];
+        if (m) {
+            atomicMin(&sh_gbin, tid * 32u + (uint32_t)__ffs((int)m) - 1u);
+            atomicMax(&sh_ns, tid * 32u + 31u - (uint32_t)__clz((int)m));
+        }
+    }
+    __syncthreads();
+    uint32_t lo_bin = sh_gbin, ns = 0;
+    if (lo_bin < D1_BINS) ns = min(PRE_SLOTS, sh_ns - lo_bin + 1u); else lo_bin = 0;
+    if (tid < ns) {
+        lut[lo_bin + tid] = (uint8_t)tid;
+        pb.slot_bin[(size_t)big * SLOT_STRIDE + tid] = lo_bin + tid;
+    }
     if (tid == 0) {
-        uint32_t lo_bin = D1_BINS, hi_bin = 0;
-        for (uint32_t w = 0; w < D1_BINS / 32; ++w) {
-            const uint32_t m = bitmap[w];
-            if (m) {
-                if (lo_bin == D1_BINS) lo_bin = w * 32u + (uint32_t)__ffs((int)m) - 1u;
-                hi_bin = w * 32u + 31u - (uint32_t)__clz((int)m);
-            }
-        }
-        uint32_t ns = 0;
-        if (lo_bin < D1_BINS) {
-            ns = min(PRE_SLOTS, hi_bin - lo_bin + 1u);
-            for (uint32_t k = 0; k < ns; ++k) {
-                lut[lo_bin + k] = (uint8_t)k;
-                pb.slot_bin[(size_t)big * SLOT_STRIDE + k] = lo_bin + k;
-            }
-        } else {
-            lo_bin = 0;
-        }
         LayerState st;
         st.spill_bin = spill_bin; st.nslots_d = ns; st.nslots_t = 0; st.redo = 0;
         st.spill_cnt = 0; st.spill_valid = 0; st.slot_lo = lo_bin; st.pad = 0;
@@ -673,18 +672,20 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
         tbin[tid] = bin;
     }
     __syncthreads();
-    if (tid == 0) {
-        // candidates ascend in K, so equal boundary bins are adjacent
-        uint32_t nt = 0, last = 0xFFFFFFFFu;
-        bool redo = sh_redo != 0u;
-        if (!redo) {
-            for (uint32_t j = 0; j < J; ++j) {
-                const uint32_t bin = tbin[j];
-                if (bin != 0xFFFFFFFFu && lut[bin] == NO_SLOT && bin != last) { last = bin; ++nt; }
-            }
-            if (nt > SLOT_STRIDE - PRE_SLOTS) redo = true;
-        }
-        sh_redo = redo ? 1u : 0u;
+    // Slots for the boundary bins, by the first wave: lane j holds candidate j.  Candidates ascend in
+    // K, so their boundary bins never ascend and equal bins are adjacent: a run of equal bins starts
+    // where the bin differs from the lane before, and its number among the runs is a prefix count.
+    uint32_t bin = 0xFFFFFFFFu, pslot = NO_SLOT;
+    bool valid = false, newrun = false;
+    uint64_t heads_c = 0;
+    if (tid < 64) {
+        if (tid < J) bin = tbin[tid];
+        valid = bin != 0xFFFFFFFFu;
+        if (valid) pslot = lut[bin];                       // slot fixed before the pass, if any
+        const uint32_t prevbin = __shfl_up(bin, 1, 64);
+        newrun = valid && (tid == 0 || prevbin != bin);
+        heads_c = ballot(newrun && pslot == NO_SLOT);      // runs that need a slot filled from the candidates
+        if (tid == 0 && (uint32_t)__popcll(heads_c) > SLOT_STRIDE - PRE_SLOTS) sh_redo = 1u;
     }
     __syncthreads();
     const bool redo = sh_redo != 0u;
@@ -696,38 +697,36 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
         for (uint32_t e = tid; e < PRE_SLOTS * D2_BINS; e += 256) { c2[e] = 0u; s2[e] = 0ull; }
         __syncthreads();
     }
-    if (tid == 0) {
-        uint32_t nd = redo ? 0u : st.nslots_d, nt = 0, last = 0xFFFFFFFFu, last_slot = NO_SLOT;
-        for (uint32_t j = 0; j < J; ++j) {
-            const uint32_t bin = tbin[j];
-            uint32_t slot = NO_SLOT;
-            if (bin != 0xFFFFFFFFu) {
-                if (redo) {
-                    if (bin != last) {
-                        glut[bin] = (uint8_t)nd;
-                        pb.slot_bin[(size_t)big * SLOT_STRIDE + nd] = bin;
-                        last = bin; last_slot = nd; ++nd;
-                    }
-                    slot = last_slot;
-                } else if (lut[bin] != NO_SLOT) {
-                    slot = lut[bin];
-                } else {
-                    if (bin != last) {
-                        const uint32_t sl = PRE_SLOTS + nt;
-                        glutc[bin] = (uint8_t)sl;
-                        pb.slot_bin[(size_t)big * SLOT_STRIDE + sl] = bin;
-                        last = bin; last_slot = sl; ++nt;
-                    }
-                    slot = last_slot;
+    if (tid < 64) {
+        const uint64_t upto = (2ull << tid) - 1ull;        // this lane and the lanes before it
+        const uint64_t heads_all = ballot(newrun);
+        uint32_t slot = NO_SLOT;
+        if (redo) {
+            if (valid) slot = (uint32_t)__popcll(heads_all & upto) - 1u;
+            if (newrun) {
+                glut[bin] = (uint8_t)slot;
+                pb.slot_bin[(size_t)big * SLOT_STRIDE + slot] = bin;
+            }
+        } else if (valid) {
+            if (pslot != NO_SLOT) {
+                slot = pslot;
+            } else {
+                slot = PRE_SLOTS + (uint32_t)__popcll(heads_c & upto) - 1u;
+                if (newrun) {
+                    glutc[bin] = (uint8_t)slot;
+                    pb.slot_bin[(size_t)big * SLOT_STRIDE + slot] = bin;
                 }
             }
-            pb.tgt_slot[(size_t)li * J + j] = slot;
         }
-        if (redo) atomicAdd(&pb.diag[3], 1u);
-        st.nslots_d = nd; st.nslots_t = nt; st.redo = redo ? 1u : 0u;
-        st.spill_cnt = spill_cnt; st.spill_valid = spill_valid ? 1u : 0u;
-        pb.state[big] = st;
-        pb.nslots[big] = nd;
+        if (tid < J) pb.tgt_slot[(size_t)li * J + tid] = slot;
+        if (tid == 0) {
+            if (redo) atomicAdd(&pb.diag[3], 1u);
+            const uint32_t nd = redo ? (uint32_t)__popcll(heads_all) : st.nslots_d;
+            st.nslots_d = nd; st.nslots_t = redo ? 0u : (uint32_t)__popcll(heads_c); st.redo = redo ? 1u : 0u;
+            st.spill_cnt = spill_cnt; st.spill_valid = spill_valid ? 1u : 0u;
+            pb.state[big] = st;
+            pb.nslots[big] = nd;
+        }
     }
 }
 
