@@ -19,6 +19,7 @@ struct AllocBuffers {
     double* row0;            // [cap+1]
     double* row1;            // [cap+1]
     uint8_t* choice;         // [L][stride]
+    uint16_t* cprev;         // [L][stride] rows that fit LDS only: the cell the winning candidate came from
     uint64_t stride;         // >= cap+1
     int32_t* j_out;
     uint64_t* K_out;
@@ -385,12 +386,13 @@ __global__ __launch_bounds__(256) void k_dp_choice(AllocBuffers ab, DpLists dl, 
         }
     }
     ab.choice[(size_t)i * ab.stride + c] = (uint8_t)bj;
+    ab.cprev[(size_t)i * ab.stride + c] = bk != 0xFFu ? (uint16_t)(c - lw[bk]) : (uint16_t)0xFFFFu;
 }
 
 constexpr uint32_t DP_STAGE_BYTES = 128u * 1024u;
 
 __global__ __launch_bounds__(1024) void k_dp_walk(AllocBuffers ab, const double* __restrict__ last,
-                                                  const uint32_t* __restrict__ wall, const uint32_t* __restrict__ bad,
+                                                  const uint32_t* __restrict__ bad,
                                                   int32_t err_infeasible, int32_t err_nonfinite) {
     __shared__ __attribute__((aligned(16))) uint8_t stage[DP_STAGE_BYTES];
     __shared__ double sv[16];
@@ -436,22 +438,22 @@ __global__ __launch_bounds__(1024) void k_dp_walk(AllocBuffers ab, const double*
         for (uint32_t i = tid; i <= ab.L; i += 1024) ab.offsets_out[i] = 0;
         return;
     }
-    // back-tracking: stage the choice rows and the candidates' costs of a group of layers in LDS,
-    // walk them, next group.  Choice rows are contiguous in memory (pitch ab.stride, a multiple of
-    // 16 bytes), so a group is one flat copy with every load in flight at once.
-    const uint32_t pitch = (uint32_t)ab.stride;
-    const uint32_t wbytes = 4u * ab.J;
-    const uint32_t per_group = DP_STAGE_BYTES / (pitch + wbytes);
+    // Back-tracking.  The sequential part follows only the chain of cells: k_dp_choice stored, beside
+    // every winner, the cell it came from, so a step is one LDS read.  The rows of a group of layers
+    // are staged in LDS with one flat copy (they are contiguous, pitch a multiple of 16 bytes), walked
+    // by one thread that notes each layer's cell, next group.  The winners are then looked up in parallel.
+    const uint32_t pitch = (uint32_t)ab.stride;                      // cells per row
+    const uint32_t per_group = DP_STAGE_BYTES / (2u * pitch);
+    const uint16_t* srow = reinterpret_cast<const uint16_t*>(stage);
     uint32_t hi = ab.L;
     while (hi > 0) {
         const uint32_t lo_l = hi > per_group ? hi - per_group : 0u;
         const uint32_t nrows = hi - lo_l;
-        uint8_t* wpart = stage + (size_t)per_group * pitch;
         __syncthreads();
         {
-            const uint4* src = reinterpret_cast<const uint4*>(ab.choice + (size_t)lo_l * pitch);
+            const uint4* src = reinterpret_cast<const uint4*>(ab.cprev + (size_t)lo_l * pitch);
             uint4* dst = reinterpret_cast<uint4*>(stage);
-            const uint32_t n16 = nrows * (pitch / 16u);
+            const uint32_t n16 = nrows * (pitch / 8u);
             for (uint32_t x0 = 0; x0 < n16; x0 += 8u * 1024u) {
                 uint4 v[8];
 #pragma unroll
@@ -465,22 +467,24 @@ __global__ __launch_bounds__(1024) void k_dp_walk(AllocBuffers ab, const double*
                     if (x < n16) dst[x] = v[k];
                 }
             }
-            const uint32_t* wsrc = wall + (size_t)lo_l * ab.J;
-            uint32_t* wdst = reinterpret_cast<uint32_t*>(wpart);
-            for (uint32_t x = tid; x < nrows * ab.J; x += 1024) wdst[x] = wsrc[x];
         }
         __syncthreads();
         if (tid == 0) {
-            uint64_t c = cstar;
+            uint32_t c = (uint32_t)cstar;
+            const uint16_t* row = srow + (size_t)nrows * pitch;
             for (uint32_t i = hi; i-- > lo_l;) {
-                const uint32_t j = stage[(size_t)(i - lo_l) * pitch + c];
-                ab.j_out[i] = (int32_t)j;
-                c -= reinterpret_cast<const uint32_t*>(wpart)[(i - lo_l) * ab.J + j];
+                row -= pitch;
+                ab.j_out[i] = (int32_t)c;                  // the layer's cell for now
+                c = min((uint32_t)row[c], ab.cap);         // (a feasible path never meets the 0xFFFF of an empty cell)
             }
             cstar = c;
         }
         hi = lo_l;
     }
+    __threadfence_block();
+    __syncthreads();
+    for (uint32_t i = tid; i < ab.L; i += 1024)
+        ab.j_out[i] = (int32_t)ab.choice[(size_t)i * ab.stride + (uint32_t)ab.j_out[i]];
     __threadfence_block();
     __syncthreads();
     // sizes and offsets, in parallel

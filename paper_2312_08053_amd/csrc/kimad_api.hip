@@ -40,6 +40,7 @@ struct Layout {
     // zeroed before every profile
     uint64_t swg_layer, swg_first, state, lutc;
     uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, shist, ghist, cursor, spill_over, zero1_end;
+    uint64_t cprev = 0;
     uint64_t big_tmp0, parts, wg_part0, big_part0, big_nparts, zero1_mid;
     uint32_t main_wgs = 256, chunks_per_wg = 1, nparts = 0;
     uint64_t pool_prefix, pool_big, pool_t0, pool_cnt, pool_hist, tgt_unsel, tgt_base;
@@ -245,6 +246,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.row0 = take(8 * lo.dp_cells);
     lo.row1 = take(8 * lo.dp_cells);
     lo.choice = take((uint64_t)L * align_up(lo.dp_cells));
+    lo.cprev = take(2ull * L * align_up(std::min<uint64_t>(lo.dp_cells, DP_PAD)));
     lo.dp_flags = take(16);
     lo.ncompact = take(16);
     lo.dl_wall = take(4 * LJ); lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
@@ -621,7 +623,7 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     ab.E = err_table; ab.Ktab = at<uint32_t>(p, lo.ktab); ab.L = lo.L; ab.J = lo.J;
     ab.unit = unit; ab.cap = (uint32_t)cap;
     ab.row0 = at<double>(p, lo.row0); ab.row1 = at<double>(p, lo.row1);
-    ab.choice = at<uint8_t>(p, lo.choice); ab.stride = align_up(cap + 1);   // row pitch: <= align_up(lo.dp_cells), as allocated
+    ab.choice = at<uint8_t>(p, lo.choice); ab.cprev = at<uint16_t>(p, lo.cprev); ab.stride = align_up(cap + 1);   // row pitch: <= align_up(lo.dp_cells), as allocated
     ab.j_out = j_out; ab.K_out = K_out; ab.offsets_out = offsets_out; ab.status = status_out;
     ab.flags = at<uint32_t>(p, lo.dp_flags);
     mark(p, s, "begin");
@@ -647,7 +649,7 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
         }
         KLAUNCH(p, s, "k_dp_choice", k_dp_choice, dim3(cell_blocks, lo.L), dim3(256), ab, dl, (const double*)rows_g, rstride);
         KLAUNCH(p, s, "k_dp_walk", k_dp_walk, dim3(1), dim3(1024), ab, (const double*)(rows_g + (size_t)lo.L * rstride),
-                (const uint32_t*)dl.wall, (const uint32_t*)dl.bad, (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
+                (const uint32_t*)dl.bad, (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
     } else {
         int rc = zero_range(p, lo.dp_flags, lo.dp_flags + 16, s);
         if (rc) return rc;
