@@ -58,6 +58,11 @@ the design notes of this repository):
       product w_m * u_hat_m; the model is fp32 and gets fl32(x - gamma * sum),
       the subtraction and the product with gamma in fp64.
 
+  R14 Budget rule (Section 3.1, Eq. budget): the paper prints c = B (t - T_comp) / 2, which is
+      its time split t = c/B + T_comp + alpha c/B solved for c at alpha = 1; for another alpha the
+      same equation gives c = B (t - T_comp) / (1 + alpha).  B in bits per second, c in bits;
+      the byte budget is floor(c / 8); a step with t <= T_comp has no budget.
+
 Pins (tests/test_oracle_*.py): brute force over all subsets / all assignments on
 tiny inputs, closed forms for constant vectors, numpy partition on distinct
 magnitudes, the contraction bound of the paper's compressor class, monotonicity,
@@ -273,3 +278,18 @@ def server_apply(payloads, u_hats: Sequence[np.ndarray], weights: Sequence[float
         acc = acc + np.float64(weights[m]) * new_hats[m].astype(np.float64)
     x_new = (np.asarray(x_model, dtype=np.float32).astype(np.float64) - np.float64(gamma) * acc).astype(np.float32)
     return new_hats, x_new
+
+
+def budget_bytes(bandwidth_bits_per_s: float, t: float, t_comp: float, alpha: float = 1.0,
+                 cap_bytes: int = 0) -> int:
+    """Compression budget of one round (Section 3.1, Eq. budget; reading R14): the bytes that fit
+    into the up-link share of the time budget t at the monitored bandwidth.  cap_bytes > 0 limits
+    the result (the uncompressed size: the plateau of the communication-size figure, Section 4.2)."""
+    B, t, t_comp, alpha = float(bandwidth_bits_per_s), float(t), float(t_comp), float(alpha)
+    if not (B > 0.0) or not (t > t_comp) or not (alpha >= 0.0) or B == np.inf or t == np.inf:
+        return 0
+    c_bits = B * (t - t_comp) / (1.0 + alpha)
+    nbytes = int(np.floor(c_bits / 8.0))
+    if cap_bytes > 0:
+        nbytes = min(nbytes, int(cap_bytes))
+    return nbytes
