@@ -210,6 +210,15 @@ int kimad_plan_set_timing(kimad_plan_t* plan, int enable);
 int kimad_plan_get_timings(kimad_plan_t* plan, char* names, uint32_t names_bytes, float* ms,
                            uint32_t max_entries, uint32_t* count_out);
 
+/* Compression budget of one round (Section 3.1, Eq. budget): the bytes that fit into the up-link share
+ * of the time budget t at the monitored bandwidth.  The paper's time split t = c/B + T_comp + alpha c/B
+ * gives c = B (t - T_comp) / (1 + alpha) bits (alpha = 1: the printed B (t - T_comp) / 2); the result is
+ * floor(c / 8), at most cap_bytes if that is not 0 (the uncompressed size).  HOST arithmetic in fp64, no
+ * device work.  Returns 0 for t <= T_comp and for a bandwidth or alpha that is negative, zero (bandwidth)
+ * or not finite. */
+uint64_t kimad_budget_bytes(double bandwidth_bits_per_s, double t_seconds, double t_comp_seconds, double alpha,
+                            uint64_t cap_bytes);
+
 const char* kimad_strerror(int status);
 const char* kimad_version(void);
 

@@ -190,6 +190,19 @@ def bandwidth_trace(steps: int, seed: int = 0, b0: float = 5.5, sigma: float = 0
     return out
 
 
+def sin2_bandwidth_trace(times: Sequence[float], eta: float = 300e6, theta: float = 0.05,
+                         delta: float = 30e6, noise: float = 0.0, seed: int = 0) -> np.ndarray:
+    """The bandwidth pattern of the paper's deep-model experiment (Section 4.2, Bandwidth):
+    eta * sin(theta * time)^2 + delta in bits per second; the defaults span its 30..330 Mbps.
+    `noise` adds seeded Gaussian noise of that relative size per worker, clipped at delta / 2."""
+    t = np.asarray(times, dtype=np.float64)
+    b = eta * np.sin(theta * t) ** 2 + delta
+    if noise > 0.0:
+        rng = np.random.default_rng([seed, 5, 2_000_003])
+        b = np.maximum(b * (1.0 + noise * rng.standard_normal(b.shape)), delta / 2.0)
+    return b
+
+
 def budget_from_bandwidth(gbit_per_s: float, seconds: float = 0.05) -> int:
     """Bytes that fit through a link of the given rate in the given time."""
     return int(np.floor(gbit_per_s * 1e9 * seconds / 8.0))

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "kimad_workspace_bytes", "kimad_plan_create", "kimad_plan_destroy", "kimad_plan_grid_sizes",
     "kimad_profile", "kimad_allocate", "kimad_compress_ef", "kimad_step",
     "kimad_profile_diagnostics", "kimad_plan_layer_states", "kimad_plan_set_timing", "kimad_plan_get_timings",
-    "kimad_server_apply", "kimad_strerror", "kimad_version",
+    "kimad_server_apply", "kimad_budget_bytes", "kimad_strerror", "kimad_version",
 ]
 
 
@@ -73,14 +73,22 @@ def lib() -> C.CDLL:
     L.kimad_strerror.restype = C.c_char_p
     L.kimad_version.restype = C.c_char_p
     for name in EXPORTED_SYMBOLS:
-        if name not in ("kimad_strerror", "kimad_version"):
+        if name not in ("kimad_strerror", "kimad_version", "kimad_budget_bytes"):
             getattr(L, name).restype = C.c_int
+    L.kimad_budget_bytes.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.c_uint64]
+    L.kimad_budget_bytes.restype = C.c_uint64
     _lib = L
     return L
 
 
 def kimad_strerror(code: int) -> str:
     return lib().kimad_strerror(int(code)).decode()
+
+
+def kimad_budget_bytes(bandwidth_bits_per_s: float, t_seconds: float, t_comp_seconds: float, alpha: float = 1.0,
+                       cap_bytes: int = 0) -> int:
+    return int(lib().kimad_budget_bytes(float(bandwidth_bits_per_s), float(t_seconds), float(t_comp_seconds),
+                                        float(alpha), int(cap_bytes)))
 
 
 def kimad_version() -> str:

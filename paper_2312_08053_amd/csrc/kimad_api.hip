@@ -818,6 +818,17 @@ int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, con
     return KIMAD_OK;
 }
 
+uint64_t kimad_budget_bytes(double bandwidth_bits_per_s, double t_seconds, double t_comp_seconds, double alpha,
+                            uint64_t cap_bytes) {
+    const double B = bandwidth_bits_per_s, t = t_seconds, tc = t_comp_seconds;
+    if (!(B > 0.0) || !(t > tc) || !(alpha >= 0.0) || std::isinf(B) || std::isinf(t)) return 0;
+    const double c_bits = B * (t - tc) / (1.0 + alpha);
+    const double bytes = std::floor(c_bits / 8.0);
+    uint64_t out = bytes >= 18446744073709551615.0 ? ~0ull : (uint64_t)bytes;
+    if (cap_bytes && out > cap_bytes) out = cap_bytes;
+    return out;
+}
+
 const char* kimad_strerror(int status) {
     switch (status) {
         case KIMAD_OK: return "ok";
