@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--D", type=int, default=None, help="cost discretisation factor (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-blocks", type=int, default=4)
+    ap.add_argument("--block-min", type=int, default=0,
+                    help="also time the step with tensors below this many elements merged into blocks (Section 6 remark)")
     ap.add_argument("--compare-allocators", action="store_true",
                     help="also report the total error of Kimad+, uniform-ratio Kimad and whole-model TopK (Section 4.3)")
     ap.add_argument("--server-workers", type=int, default=4,
@@ -192,6 +194,30 @@ def main() -> int:
                               "model_step_GBs": round(step_bytes / (t_step * 1e-3) / 1e9, 1),
                               "model_step_frac_of_hbm_peak": round(step_bytes / (t_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del hats, xm
+
+    if args.block_min > 0:
+        # beside the headline: block granularity (one block = a run of consecutive tensors).  Not part of `value`.
+        from paper_2312_08053_amd.blocks import merge_small
+        bsizes = merge_small(work.sizes.tolist(), args.block_min)
+        bplan = kimad.Plan(g, h, bsizes, work.ratios.tolist(), pair_bytes=work.pair_bytes, D=work.cost_units_D,
+                           max_budget_bytes=work.budget_bytes, capacity_pairs=work.budget_bytes // work.pair_bytes + 1)
+        for _ in range(max(1, args.warmup)):
+            h.copy_(h0)
+            bplan.step(work.budget_bytes)
+        torch.cuda.synchronize()
+        bs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        be = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        for k in range(args.steps):
+            h.copy_(h0)
+            bs[k].record(stream)
+            bplan.step(work.budget_bytes)
+            be[k].record(stream)
+        torch.cuda.synchronize()
+        bms = float(np.mean([bs[k].elapsed_time(be[k]) for k in range(args.steps)]))
+        out["blocked"] = {"min_elems": args.block_min, "blocks": len(bsizes), "status": bplan.status.cpu().tolist(),
+                          "ms_per_step": round(bms, 4), "gradient_GBs": round(4.0 * d / (bms * 1e-3) / 1e9, 2),
+                          "payload_pairs": int(bplan.offsets[-1].item())}
+        del bplan
 
     if args.compare_allocators:
         from paper_2312_08053_amd.baselines import allocator_errors

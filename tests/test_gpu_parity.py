@@ -116,6 +116,20 @@ def test_narrow_grid_splits_a_layer_into_histogram_segments():
     _full_check(work, max_workgroups=3, reuse=False)
 
 
+def test_block_granularity_small_tensors_merged_into_their_neighbours():
+    """The paper's remark on blocks (Section 6): the same set with every tensor below 8193 elements
+    merged into a block with its neighbours is just another segmentation of the flat buffers."""
+    from paper_2312_08053_amd.blocks import merge_small
+    from kimad_synth.gen import Workload
+    w = ks.make_workload("gpt2", n_layer=2, vocab=4099)
+    blocks = merge_small(w.sizes.tolist(), 8193)
+    assert sum(blocks) == w.d and len(blocks) < w.L and min(blocks) >= 8193
+    assert set(np.cumsum(blocks).tolist()) <= set(np.cumsum(w.sizes).tolist())
+    wb = Workload(name="gpt2-blocks", sizes=np.asarray(blocks, dtype=np.uint64), g=w.g, h=w.h, ratios=w.ratios,
+                  budget_bytes=w.budget_bytes, cost_units_D=w.cost_units_D)
+    _full_check(wb)
+
+
 def test_budget_larger_than_hinted_falls_back_to_reading_g_and_h():
     # the profile keeps the top few percent for a 1 % budget; the allocation then gets 30 %
     import torch
