@@ -33,10 +33,10 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="gpt2", choices=["mlp", "resnet18", "resnet50", "gpt2"])
+    ap.add_argument("--workload", default="gpt2", choices=["mlp", "resnet18", "resnet50", "gpt2", "llama"])
     ap.add_argument("--D", type=int, default=None, help="cost discretisation factor (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-blocks", type=int, default=4)
+    ap.add_argument("--cpu-sample-blocks", type=int, default=12)
     ap.add_argument("--block-min", type=int, default=0,
                     help="also time the step with tensors below this many elements merged into blocks (Section 6 remark)")
     ap.add_argument("--compare-allocators", action="store_true",
@@ -233,6 +233,9 @@ def main() -> int:
             # tensors of the first transformer blocks (12 per block, after wte and wpe)
             sel = list(range(2, 2 + 12 * args.cpu_sample_blocks))
             what = f"first {args.cpu_sample_blocks} transformer blocks"
+        elif work.name == "llama":
+            sel = list(range(1, 1 + 9 * 2))        # 9 tensors per block, after the embedding
+            what = "first 2 transformer blocks"
         else:
             sel = list(range(L))
             what = "all tensors"
