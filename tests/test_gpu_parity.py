@@ -100,6 +100,24 @@ def test_resnet50_set_discretised_budget():
     _full_check(ks.make_workload("resnet50", D=1000))
 
 
+@pytest.mark.parametrize("D", [1500, 3000, 3071, 3072])
+def test_cost_axes_of_every_width_of_the_single_kernel_allocation(D):
+    """Rows of 1501, 3001 and 3072 cells take the forward kernel with 4 and 6 cells per thread; 3073 cells
+    no longer fit LDS and go through one launch per layer.  Allocation only (the oracle's table in, j out)."""
+    import torch
+    work = ks.make_workload("resnet18", D=D)
+    g, h = gh.to_device(work)
+    plan = gh.make_plan(work, g, h)
+    gL, hL = gh.oracle_layers(work)
+    E_ref, Kt = ko.profile(gL, hL, work.ratios)
+    st, j_ref, K_ref, off_ref = ko.allocate(E_ref, Kt, work.budget_bytes, work.pair_bytes, D)
+    assert st == ko.OK
+    j, K, off, status = plan.allocate(work.budget_bytes, torch.from_numpy(E_ref.reshape(-1).copy()).cuda())
+    assert int(status.item()) == 0
+    assert np.array_equal(j.cpu().numpy(), j_ref)
+    assert np.array_equal(off.cpu().numpy().astype(np.uint64), off_ref)
+
+
 def test_gpt2_reduced_set():
     # same recipe as the 124M set, two blocks and a 4096-row embedding: several tiles per layer,
     # ragged tails, small vectors next to matrices
