@@ -24,8 +24,8 @@ constexpr uint32_t CHUNK = 1024;              // elements one wave compacts at a
 constexpr uint32_t NQ = CHUNK / 256;          // quads per lane and chunk
 constexpr uint32_t CBLOCK = 1024;             // chunks per chunk block (one workgroup scans one block)
 constexpr uint32_t PRE_SLOTS = 108;           // digit-2 slots the single-pass profile can hold in LDS
-constexpr uint32_t SLOT_STRIDE = PRE_SLOTS + 64;  // slots per layer in the global digit-2 tables: 0..95 fixed
-                                              // before a pass, 96..159 found after it (filled from candidates)
+constexpr uint32_t SLOT_STRIDE = PRE_SLOTS + 64;  // slots per layer in the global digit-2 tables: 0..PRE_SLOTS-1 fixed
+                                              // before a pass, PRE_SLOTS.. found after it (filled from candidates)
 // LDS entry of a slot in the single-pass profile: [count:20 | sum of (significand^2 >> 24):44]
 constexpr uint32_t PK_SHIFT = 24;
 constexpr uint64_t PK_ONE = 1ull << 44;
@@ -58,7 +58,7 @@ struct LayerDesc {
 struct LayerState {
     uint32_t spill_bin;    // entries whose digit-1 bin is >= spill_bin were written to the candidate buffer
     uint32_t nslots_d;     // boundary-bin slots fixed before the pass (predicted, or exact after a redo)
-    uint32_t nslots_t;     // slots 64.. assigned after the pass and filled from the candidates
+    uint32_t nslots_t;     // slots PRE_SLOTS.. assigned after the pass and filled from the candidates
     uint32_t redo;         // prediction missed: digit 2 is recounted by a full pass over this layer
     uint32_t spill_cnt;    // entries in the candidate region
     uint32_t spill_valid;  // the region holds every entry with bin >= spill_bin, in index order per chunk

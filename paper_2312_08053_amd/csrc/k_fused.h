@@ -203,16 +203,16 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
 // ---------------------------------------------------------------------------------------------
 // The streaming pass.  Persistent grid: workgroup w owns a contiguous range of chunks, walks it
 // layer by layer, and keeps that layer's histograms in LDS as one array of packed entries
-// [count:20 | sum:44] of (significand^2 >> 24): 4096 digit-1 bins, then up to 96 slots x 128 digit-2
+// [count:20 | sum:44] of (significand^2 >> 24): 4096 digit-1 bins, then up to PRE_SLOTS slots x 128 digit-2
 // bins.  Entries whose bin has a slot are counted only there.  Bin 0 (zeros, tiniest denormals)
 // keeps exact squares in a separate accumulator.  One wave handles one chunk at a time: 4 quads per
-// lane, one LDS atomic per entry, then ballot-ranked spilling of the entries at or above the layer's
+// lane, one LDS atomic per entry, then spilling, ranked by prefix scans over the lanes, of the entries at or above the layer's
 // spill bin, staged through LDS so that the candidate writes are coalesced.
 //
 // The packed sums drop the low 24 bits of each square: the true sum of (square >> 16) lies in
-// [256 S, 256 S + 256 count); the flush stores the midpoint and the scans widen their bounds by
+// [256 S, 256 S + 256 count); k_reduce_parts stores the midpoint and the scans widen their bounds by
 // half that interval (2^-23 relative).
-constexpr uint32_t PK_ENTRIES = D1_BINS + PRE_SLOTS * D2_BINS;     // 16384 entries, 128 KB
+constexpr uint32_t PK_ENTRIES = D1_BINS + PRE_SLOTS * D2_BINS;     // 17920 entries, 140 KB
 constexpr uint32_t STAGE = 128;                                    // candidates a wave stages per round
 constexpr uint32_t PART_STRIDE = PK_ENTRIES + 8;                   // entries of one part: the LDS array, then the bin-0 sum
 
@@ -567,7 +567,7 @@ __global__ __launch_bounds__(256) void k_reduce_parts(ProfileBuffers pb) {
 // After the pass: exact digit-1 histogram (slot bins contribute the totals of their digit-2
 // bins), boundary bin per candidate, and what each boundary needs:
 //   - its bin already has a slot                          -> nothing
-//   - its bin is in the spilled range                     -> a slot 96.. filled from the candidates
+//   - its bin is in the spilled range                     -> a slot PRE_SLOTS.. filled from the candidates
 //   - neither (prediction missed), or slots run out       -> redo: exact slots, full recount
 __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J) {
     __shared__ uint32_t cnt[D1_BINS];
@@ -731,7 +731,7 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Digit-2 histograms of the slots 96.. from the candidate buffer.  Sixteen lanes per chunk.
+// Digit-2 histograms of the slots PRE_SLOTS.. from the candidate buffer.  Sixteen lanes per chunk.
 __global__ __launch_bounds__(256) void k_hist2c(ProfileBuffers pb) {
     const SubGroup g = sub_group();
     const uint32_t chunk = blockIdx.x * CHUNKS_PER_WG + threadIdx.x / SUB;

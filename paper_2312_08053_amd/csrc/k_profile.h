@@ -59,7 +59,7 @@ struct ProfileBuffers {
     const uint32_t* swg_first;    // sampling workgroup -> its first sampled group in that layer
     uint32_t* shist;              // [B][4096] digit-1 counts of the sample
     unsigned long long* ghist;    // [4096] sample counts of all layers, scaled by the sampling stride
-    uint8_t* lutc;                // [B][4096] digit-1 bin -> slot 64.. filled from the candidates
+    uint8_t* lutc;                // [B][4096] digit-1 bin -> slot PRE_SLOTS.. filled from the candidates
     uint32_t* cursor;             // [B] candidate entries handed out so far
     uint32_t* spill_over;         // [B] a reservation did not fit the layer's region
     uint32_t* rec_start;          // per chunk: start inside the layer's candidate region
