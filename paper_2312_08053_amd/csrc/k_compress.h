@@ -5,7 +5,7 @@
 // (Section 3.3, Eq. EF21-2).  Equal magnitudes are kept in order of lower index.
 //
 // Tiled layers: one streaming pass writes every entry whose 19-bit key prefix is >= the layer's
-// threshold prefix into a candidate buffer (in index order inside each 2048-element chunk) and
+// threshold prefix into a candidate buffer (in index order inside each 1024-element chunk) and
 // histograms the last 12 key bits of the entries whose prefix is equal.  Four small kernels then
 // fix the exact threshold key and tie quota, count survivors per chunk, scan the chunks in index
 // order and write payload and estimator.

@@ -6,7 +6,7 @@
 //   * which digit-1 bins can hold the boundary of a "dense" candidate (K beyond the top few
 //     percent): those bins get digit-2 slots before the pass, and
 //   * a spill bin: every entry at or above it (the top few percent, sized from the budget hint)
-//     is written to the candidate buffer as (index, x, h), in index order inside each chunk.
+//     is written to the candidate buffer as (index, x), in index order inside each chunk.
 // One streaming pass then builds the exact digit-1 histogram, the digit-2 histograms of the
 // predicted bins and the candidate buffer.  Candidates whose boundary lies in the spilled range
 // get their digit-2 histograms from the candidate buffer (a few percent of the data), and the
