@@ -261,18 +261,36 @@ __global__ __launch_bounds__(NT) void k_dp_forward(AllocBuffers ab, const uint32
         const uint32_t g = sh_g;                 // >= 1: one layer has at most J <= 64 entries
         if (tid == g - 1u) loff[g] = before + mine;
         __syncthreads();
-        const uint32_t jp = (ab.J + DP_UNROLL - 1u) & ~(DP_UNROLL - 1u);   // a padded list may exceed J
-        for (uint32_t t = tid; t < g * jp; t += NT) {
-            const uint32_t layer = t / jp, k = t % jp;
-            if (k < loff[layer + 1] - loff[layer]) {
-                double e = DP_INF;
-                uint32_t w8 = 0u;
-                if (k < ln[layer]) {
-                    const size_t o = (size_t)(i0 + layer) * ab.J + k;
-                    e = ent_e[2 * o];
-                    w8 = ent_w[o] * 8u;
+        // Lane k of a wave copies record k (a padded list has at most 64 of them) of one layer at a time,
+        // four layers per trip with their loads issued together: the copy costs a few memory round trips,
+        // not one per layer.  Idle positions read entry 0 of the table (a valid address) and drop it.
+        static_assert(KIMAD_MAX_J_CONST == 64, "one lane per list record");
+        {
+            const uint32_t k = tid & 63u;
+            constexpr uint32_t LSTEP = NT / 64;              // layers one trip of the workgroup covers
+            for (uint32_t l0 = tid >> 6; l0 < g; l0 += 4u * LSTEP) {
+                uint32_t at[4], w8[4];
+                double e[4];
+                bool act[4], real[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint32_t layer = l0 + (uint32_t)u * LSTEP;
+                    const bool in = layer < g;
+                    const uint32_t first = in ? loff[layer] : 0u;
+                    act[u] = in && k < loff[layer + 1] - first;
+                    real[u] = act[u] && k < ln[layer];
+                    at[u] = first + k;
+                    const size_t o = real[u] ? (size_t)(i0 + layer) * ab.J + k : 0;
+                    e[u] = ent_e[2 * o];
+                    w8[u] = ent_w[o];
                 }
-                recs[loff[layer] + k] = make_uint4((uint32_t)__double2loint(e), (uint32_t)__double2hiint(e), 0u - w8, 0u);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (!act[u]) continue;
+                    const double ee = real[u] ? e[u] : DP_INF;
+                    const uint32_t ww = real[u] ? w8[u] * 8u : 0u;
+                    recs[at[u]] = make_uint4((uint32_t)__double2loint(ee), (uint32_t)__double2hiint(ee), 0u - ww, 0u);
+                }
             }
         }
         // a layer's fetch and the row reads issued one trip ahead may run past the group's last
@@ -297,6 +315,7 @@ __global__ __launch_bounds__(NT) void k_dp_forward(AllocBuffers ab, const uint32
         uint32_t nt_cur = __builtin_amdgcn_readfirstlane(ltr[0]);
         uint32_t nt_n1 = __builtin_amdgcn_readfirstlane(ltr[min(1u, g)]);
         uint32_t nt_n2 = ltr[min(2u, g)];
+        double* out = rows_g + (size_t)i0 * rstride + tid;
         for (uint32_t i = i0; i < i0 + g; ++i) {
             // LDS byte address of this thread's first cell in the previous row
             const uint32_t prev = lds_addr(rows[i & 1] + DP_PAD + tid);
@@ -334,11 +353,11 @@ __global__ __launch_bounds__(NT) void k_dp_forward(AllocBuffers ab, const uint32
                     Q0 = Q1; Q1 = Q2; Q2 = Q3;
                 }
             }
-            double* out = rows_g + (size_t)(i + 1) * rstride + tid;
+            out += rstride;                      // row i + 1; a stored row holds NT * CPT cells, so no cell is tested
 #pragma unroll
             for (int m = 0; m < CPT; ++m) {
                 cur[m * NT] = best[m];
-                if (tid + m * NT < ncell) out[m * NT] = best[m];
+                out[m * NT] = best[m];
             }
             lds_barrier();
         }

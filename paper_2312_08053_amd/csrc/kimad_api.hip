@@ -251,7 +251,11 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.ncompact = take(16);
     lo.dl_wall = take(4 * LJ); lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
     lo.dl_bad = take(4ull * L);
-    lo.rstride = (std::min<uint64_t>(lo.dp_cells, DP_PAD) + 31) & ~31ull;
+    {
+        // a stored row holds a whole number of the forward kernel's 512-thread sweeps (2, 4 or 6 cells per thread)
+        const uint64_t cells = std::min<uint64_t>(lo.dp_cells, DP_PAD);
+        lo.rstride = 512ull * (cells <= 1024 ? 2 : cells <= 2048 ? 4 : 6);
+    }
     lo.rows_g = take(8ull * (L + 1) * lo.rstride);
     lo.total = off;
     return KIMAD_OK;
