@@ -372,6 +372,7 @@ __global__ __launch_bounds__(256) void k_dp_choice(AllocBuffers ab, DpLists dl, 
                                                    uint32_t rstride) {
     __shared__ uint32_t lw[KIMAD_MAX_J_CONST], lj[KIMAD_MAX_J_CONST];
     __shared__ double le[2 * KIMAD_MAX_J_CONST];
+    __shared__ double prev[DP_PAD];            // the previous row up to this workgroup's last cell
     const uint32_t i = blockIdx.y, tid = threadIdx.x;
     const uint32_t n = dl.n[i];
     if (tid < n) {
@@ -379,10 +380,16 @@ __global__ __launch_bounds__(256) void k_dp_choice(AllocBuffers ab, DpLists dl, 
         lw[tid] = dl.w[o]; lj[tid] = dl.jj[o];
         le[2 * tid] = dl.e[2 * o]; le[2 * tid + 1] = dl.e[2 * o + 1];
     }
+    // every candidate of a cell reads one cell of the previous row: from LDS, not one dependent
+    // memory round trip per candidate
+    {
+        const double* prow = rows_g + (size_t)i * rstride;
+        const uint32_t upto = min(blockIdx.x * 256u + 256u, ab.cap + 1u);
+        for (uint32_t x = tid; x < upto; x += 256u) prev[x] = prow[x];
+    }
     __syncthreads();
     const uint32_t c = blockIdx.x * 256u + tid;
     if (c > ab.cap) return;
-    const double* prev = rows_g + (size_t)i * rstride;
     double best = DP_INF;
     uint32_t bk = 0xFFu;
     for (uint32_t k = 0; k < n; ++k) {

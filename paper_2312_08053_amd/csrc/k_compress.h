@@ -384,7 +384,20 @@ __global__ __launch_bounds__(1024) void k_chunk_bases(CompressBuffers cb) {
     const uint32_t quota = cb.quota[b];
     const uint32_t kb = blk - L.cblk0;              // this block's number inside the layer
     uint32_t pg = 0, pe = 0;
-    for (uint32_t c = tid; c < kb * CBLOCK; c += 1024) { pg += cb.c_gt[L.chunk0 + c]; pe += cb.c_eq[L.chunk0 + c]; }
+    {
+        // kb * CBLOCK is a multiple of 1024: every thread takes kb entries, eight loads of each table at a time
+        const uint32_t* pgt = cb.c_gt + L.chunk0 + tid;
+        const uint32_t* peq = cb.c_eq + L.chunk0 + tid;
+        uint32_t k = 0;
+        for (; k + 4 <= kb; k += 4) {
+            uint32_t a[4], e[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { a[u] = pgt[(size_t)(k + u) * 1024u]; e[u] = peq[(size_t)(k + u) * 1024u]; }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { pg += a[u]; pe += e[u]; }
+        }
+        for (; k < kb; ++k) { pg += pgt[(size_t)k * 1024u]; pe += peq[(size_t)k * 1024u]; }
+    }
     uint32_t gt_before, eq_before0;
     (void)block_exclusive_scan<uint32_t>(pg, su, &gt_before);
     (void)block_exclusive_scan<uint32_t>(pe, su, &eq_before0);
