@@ -90,9 +90,17 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
             } else if (K == n) {
                 r.mode = SEL_ALL; r.cap = n + REGION_SLACK; r.above = n;
             } else {
+                // the row of grid sizes is read eight entries at a time (a look-up that stops at the
+                // first hit would wait for one load per entry)
                 int found = -1;
-                for (uint32_t j = 0; j < cb.J; ++j)
-                    if (cb.Ktab[(size_t)li * cb.J + j] == K) { found = (int)j; break; }
+                for (uint32_t j0 = 0; j0 < cb.J && found < 0; j0 += 8) {
+                    uint32_t kt[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) kt[u] = cb.Ktab[(size_t)li * cb.J + min(j0 + (uint32_t)u, cb.J - 1u)];
+#pragma unroll
+                    for (int u = 7; u >= 0; --u)
+                        if (j0 + (uint32_t)u < cb.J && kt[u] == K) found = (int)(j0 + (uint32_t)u);
+                }
                 if (found < 0) {
                     atomicMax(&bad, 2);
                 } else {
@@ -251,31 +259,27 @@ __global__ __launch_bounds__(256) void k_hist3c(CompressBuffers cb, uint32_t nch
     uint32_t* hist3 = cb.hist3;
     bool is_cand = false;
     if (chunk < nchunks_total) {
+        // what the chunk index alone addresses goes out together, then the layer's record
         const uint32_t b = chunk_big[chunk];
+        const uint32_t n_rec = cb.rec_cnt[chunk], start = cb.rec_start[chunk];
+        materialise(b); materialise(n_rec); materialise(start);
         const SelRec S = cb.sel[b];
-        if (S.mode == SEL_CAND) {
-            is_cand = true;
-            cnt = cb.rec_cnt[chunk];
-            base = S.tmp_base + cb.rec_start[chunk];
-            prefix = S.prefix;
-            hist3 = cb.hist3 + (size_t)b * D3_BINS;
-        }
+        is_cand = S.mode == SEL_CAND;
+        cnt = is_cand ? n_rec : 0u;
+        base = S.tmp_base + start;
+        prefix = S.prefix;
+        hist3 = cb.hist3 + (size_t)b * D3_BINS;
     }
     const uint32_t cmax = wave_max_over_groups(cnt);
     uint32_t n_above = 0, n_amb = 0;            // of this chunk: threshold prefix exceeded / shared
-    for (uint32_t k0 = 0; k0 < cmax; k0 += SUB) {
-        const uint32_t k = k0 + g.sub;
-        uint32_t key = 0;
-        bool a = false, hi = false;
-        if (k < cnt) {
-            key = key_of(cb.tmp_x[base + k]);
-            a = (key >> D2_SHIFT) == prefix;
-            hi = (key >> D2_SHIFT) > prefix;
-        }
+    // one round: sixteen candidates of the chunk
+    auto round = [&](bool in, uint32_t key) {
+        const bool a = in && (key >> D2_SHIFT) == prefix;
+        const bool hi = in && (key >> D2_SHIFT) > prefix;
         const uint32_t am = ballot_sub(g, a);
         n_above += __popc(ballot_sub(g, hi));
         n_amb += __popc(am);
-        if (am == 0) continue;
+        if (am == 0) return;
         // one atomic per group when all its matching lanes hold the same key (zeros, constants)
         const uint32_t first = (uint32_t)__ffs((int)am) - 1u;
         const uint32_t k0v = __shfl(key, g.shift + first, 64);
@@ -285,6 +289,23 @@ __global__ __launch_bounds__(256) void k_hist3c(CompressBuffers cb, uint32_t nch
         } else if (a) {
             atomicAdd(&hist3[key & (D3_BINS - 1)], 1u);
         }
+    };
+    // the first four rounds' loads go out together (positions past the chunk's last candidate read entry 0
+    // of the buffer, always a valid address, and are dropped; a chunk without candidates has no valid start)
+    constexpr int AHEAD = 4;
+    float px[AHEAD];
+#pragma unroll
+    for (int t = 0; t < AHEAD; ++t) {
+        const uint32_t k = (uint32_t)t * SUB + g.sub;
+        px[t] = cb.tmp_x[k < cnt ? base + k : 0ull];
+    }
+#pragma unroll
+    for (int t = 0; t < AHEAD; ++t)
+        if ((uint32_t)t * SUB < cmax) round((uint32_t)t * SUB + g.sub < cnt, key_of(px[t]));
+    for (uint32_t k0 = AHEAD * SUB; k0 < cmax; k0 += SUB) {
+        const uint32_t k = k0 + g.sub;
+        const bool in = k < cnt;
+        round(in, in ? key_of(cb.tmp_x[base + k]) : 0u);
     }
     // A chunk without an entry in the threshold's prefix bin (nearly all of them) is settled here:
     // every entry above the prefix is above the threshold, none equals it.  The others are counted
@@ -344,16 +365,20 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
     uint64_t base = 0;
     bool settled = false;
     if (live) {
+        // what the chunk index alone addresses goes out together, then the layer's record
         const uint32_t b = chunk_big[chunk];
-        const SelRec S = cb.sel[b];
+        const uint32_t amb = cb.rec_amb[chunk], start = cb.rec_start[chunk];
         total = cb.rec_cnt[chunk];
+        materialise(b); materialise(amb); materialise(start); materialise(total);
+        const SelRec S = cb.sel[b];
+        const uint32_t t = cb.tau[b];
         // Only chunks with entries in the threshold's prefix bin are read again.  Of the others, those
         // of the classic pass hold nothing below the threshold prefix and pass whole; those of the
         // spilled candidates were counted by k_hist3c.
-        if ((S.mode == SEL_CAND || S.mode == SEL_PREFIX) && cb.rec_amb[chunk] != 0u) {
+        if ((S.mode == SEL_CAND || S.mode == SEL_PREFIX) && amb != 0u) {
             cnt = total;
-            tau = cb.tau[b];
-            base = S.tmp_base + cb.rec_start[chunk];
+            tau = t;
+            base = S.tmp_base + start;
         }
         settled = S.mode == SEL_CAND && cnt == 0u;      // counted by k_hist3c
     }
@@ -469,12 +494,12 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
     constexpr int AHEAD = 4;
     uint32_t pidx[AHEAD];
     float px[AHEAD];
-    // (positions past the chunk's last candidate read its first one again, a valid address, and are dropped)
+    // (positions past the chunk's last candidate read entry 0 of the buffer, a valid address, and are dropped)
 #pragma unroll
     for (int t = 0; t < AHEAD; ++t) {
         const uint32_t k = (uint32_t)t * SUB + g.sub;
-        const uint32_t kc = k < cnt ? k : 0u;
-        pidx[t] = cb.tmp_idx[src + kc]; px[t] = cb.tmp_x[src + kc];
+        const uint64_t at = k < cnt ? src + k : 0ull;
+        pidx[t] = cb.tmp_idx[at]; px[t] = cb.tmp_x[at];
     }
 #pragma unroll
     for (int t = 0; t < AHEAD; ++t)
