@@ -24,7 +24,10 @@
 
 namespace kimad {
 
-constexpr uint32_t SAMPLE_GROUPS_PER_WG = 16;   // sampled chunks one sampling workgroup reads
+constexpr uint32_t SAMPLE_GROUPS_PER_WG = 48;   // sampled chunks one sampling workgroup reads: three per wave (every
+                                                // workgroup ends with a flush of its histogram through global
+                                                // atomics, which is what the kernel's time is made of: fewer, longer
+                                                // workgroups were faster at every size tried, 4 to 48)
 constexpr uint32_t FUSED_THREADS = 1024;
 constexpr uint32_t FUSED_WAVES = FUSED_THREADS / 64;
 
@@ -41,7 +44,7 @@ __device__ __forceinline__ uint32_t sampled_chunk(uint32_t gidx, uint32_t stride
 // ---------------------------------------------------------------------------------------------
 // Sampling pre-pass: digit-1 counts of the sampled chunks.
 // One wave per sampled chunk: all of a workgroup's loads are in flight together.
-constexpr uint32_t SAMPLE_THREADS = 64 * SAMPLE_GROUPS_PER_WG;
+constexpr uint32_t SAMPLE_THREADS = 1024;
 __global__ __launch_bounds__(SAMPLE_THREADS) void k_sample(ProfileBuffers pb) {
     __shared__ uint32_t hist[D1_BINS];
     const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = lane_id();
