@@ -91,11 +91,21 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
     const uint32_t li = pb.big_layer[big];
     const LayerDesc L = pb.layers[li];
 
+    // this layer's sample counts are asked for together with the global ones of step (1)
+    uint32_t c[16], csum = 0;
+    {
+        const uint4* sh4 = reinterpret_cast<const uint4*>(pb.shist + (size_t)big * D1_BINS + tid * 16u);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const uint4 v = sh4[k];
+            c[4 * k] = v.x; c[4 * k + 1] = v.y; c[4 * k + 2] = v.z; c[4 * k + 3] = v.w;
+        }
+    }
     // (1) global threshold bin: the highest bin b with (entries of all layers in bins >= b) >= 2.5 x budget
     {
-        unsigned long long c[16], sum = 0;
+        unsigned long long gc[16], sum = 0;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) { c[k] = pb.ghist[tid * 16u + k]; sum += c[k]; }
+        for (int k = 0; k < 16; ++k) { gc[k] = pb.ghist[tid * 16u + k]; sum += gc[k]; }
         unsigned long long tot;
         const unsigned long long ex = block_exclusive_scan<unsigned long long>(sum, s64, &tot);
         unsigned long long ab = tot - ex - sum;            // entries above this thread's bins
@@ -105,17 +115,15 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
         if (budget_pairs && ab < want && ab + sum >= want) {
 #pragma unroll
             for (int k = 15; k >= 0; --k) {
-                if (ab + c[k] >= want) { sh_gbin = tid * 16u + k; break; }
-                ab += c[k];
+                if (ab + gc[k] >= want) { sh_gbin = tid * 16u + k; break; }
+                ab += gc[k];
             }
         }
         __syncthreads();
     }
     // (2) this layer's sample: suffix counts
-    uint32_t c[16], csum = 0;
-    const uint32_t* sh = pb.shist + (size_t)big * D1_BINS;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) { c[k] = sh[tid * 16u + k]; csum += c[k]; }
+    for (int k = 0; k < 16; ++k) csum += c[k];
     uint32_t ns_total;
     const uint32_t cex = block_exclusive_scan<uint32_t>(csum, su, &ns_total);
     {
@@ -591,6 +599,18 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
     const uint64_t* gsq = pb.sq1 + (size_t)big * D1_BINS;
     uint8_t* glut = pb.lut1 + (size_t)big * D1_BINS;
     uint8_t* glutc = pb.lutc + (size_t)big * D1_BINS;
+    // this thread's sixteen digit-1 entries: asked for now, with the table and the slot totals below, so
+    // that the three groups of loads share one memory round trip instead of taking one per phase
+    uint4 craw[4];
+    ulonglong2 sraw[8];
+    {
+        const uint4* c4 = reinterpret_cast<const uint4*>(gcnt + tid * 16u);
+        const ulonglong2* s2 = reinterpret_cast<const ulonglong2*>(gsq + tid * 16u);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) craw[k] = c4[k];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) sraw[k] = s2[k];
+    }
     {
         const uint32_t* src = reinterpret_cast<const uint32_t*>(glut);
         uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
@@ -627,8 +647,9 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
     for (int k = 0; k < 16; ++k) {
         const uint32_t b = tid * 16u + k;
         const uint32_t slot = lut[b];
-        uint32_t cc = gcnt[b];
-        unsigned long long ss = gsq[b];
+        const uint4 cq = craw[k >> 2];
+        uint32_t cc = (k & 3) == 0 ? cq.x : (k & 3) == 1 ? cq.y : (k & 3) == 2 ? cq.z : cq.w;
+        unsigned long long ss = (k & 1) ? sraw[k >> 1].y : sraw[k >> 1].x;
         if (slot != NO_SLOT) { cc += slot_c[slot]; ss += slot_s[slot]; }
         c[k] = cc;
         s[k] = sq_to_double(b, ss, cc);
