@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 
-STREAMING_KERNELS = ("k_main", "k_hist1", "k_hist2", "k_compact")
+STREAMING_KERNELS = ("k_main", "k_hist1", "k_hist2", "k_candidates")
 
 
 def main() -> int:
@@ -127,7 +127,7 @@ def main() -> int:
 
     d_big = int(sum(int(n) for n in work.sizes if int(n) > 8192))
     # algorithmic bytes of a streaming kernel: it must read g and h of the tiled layers once
-    alg_bytes = {"k_main": 8 * d_big, "k_hist1": 8 * d_big, "k_hist2": 8 * d_big, "k_compact": 8 * d_big}
+    alg_bytes = {"k_main": 8 * d_big, "k_hist1": 8 * d_big, "k_hist2": 8 * d_big, "k_candidates": 8 * d_big}
     dom = max((n for n in STREAMING_KERNELS if n in kern), key=lambda n: kern[n]["ms_per_step"])
     ach = alg_bytes[dom] / (kern[dom]["avg_ms"] * 1e-3) / 1e9
     # HBM bytes per launch from rocprofv3 counter runs, recorded under profiles/ (None if there is no record for

@@ -141,11 +141,13 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
 // Tiles are taken in a grid-stride loop; *cb.ncompact (set by k_lookup) is the number of layers that
 // need this pass, so that after a single-pass profile, when the candidates serve every layer, a
 // small grid leaves after one load.
-__global__ __launch_bounds__(256) void k_compact(CompressBuffers cb, uint32_t ntiles, int32_t err_internal) {
+// (Workgroups `block` of `nblocks` of the launch that also histograms the spilled candidates: k_candidates.)
+__device__ __forceinline__ void compact_tiles(const CompressBuffers& cb, uint32_t ntiles, int32_t err_internal,
+                                              uint32_t block, uint32_t nblocks) {
     if (*cb.ncompact == 0u) return;
     const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
     const uint32_t chunks_per_tile = cb.tile_elems / CHUNK;
-    for (uint32_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x) {
+    for (uint32_t tile = block; tile < ntiles; tile += nblocks) {
     const uint32_t li = cb.chunk_layer[tile];
     const LayerDesc L = cb.layers[li];
     const SelRec S = cb.sel[L.big];
@@ -251,9 +253,10 @@ __global__ __launch_bounds__(256) void k_compact(CompressBuffers cb, uint32_t nt
 // ---------------------------------------------------------------------------------------------
 // Last-digit histogram of the spilled candidates that share the threshold prefix (layers in
 // SEL_CAND mode).  Sixteen lanes per chunk.
-__global__ __launch_bounds__(256) void k_hist3c(CompressBuffers cb, uint32_t nchunks_total, const uint32_t* chunk_big) {
+__device__ __forceinline__ void hist3_candidates(const CompressBuffers& cb, uint32_t nchunks_total,
+                                                 const uint32_t* chunk_big, uint32_t block) {
     const SubGroup g = sub_group();
-    const uint32_t chunk = blockIdx.x * CHUNKS_PER_WG + threadIdx.x / SUB;
+    const uint32_t chunk = block * CHUNKS_PER_WG + threadIdx.x / SUB;
     uint32_t cnt = 0, prefix = 0;
     uint64_t base = 0;
     uint32_t* hist3 = cb.hist3;
@@ -313,6 +316,16 @@ __global__ __launch_bounds__(256) void k_hist3c(CompressBuffers cb, uint32_t nch
     if (is_cand && g.sub == 0) { cb.c_gt[chunk] = n_above; cb.c_eq[chunk] = 0u; cb.rec_amb[chunk] = n_amb; }
 }
 
+// One launch for both sources of candidates: the first `hist_blocks` workgroups histogram the last
+// digit of the spilled candidates (layers in SEL_CAND mode), the others run the streaming compaction
+// for the layers that need it (none after a single-pass profile whose spilled range serves every
+// layer: they leave after one load).  The two touch different layers.
+__global__ __launch_bounds__(256) void k_candidates(CompressBuffers cb, uint32_t nchunks_total, const uint32_t* chunk_big,
+                                                    uint32_t hist_blocks, uint32_t ntiles, int32_t err_internal) {
+    if (blockIdx.x < hist_blocks) hist3_candidates(cb, nchunks_total, chunk_big, blockIdx.x);
+    else compact_tiles(cb, ntiles, err_internal, blockIdx.x - hist_blocks, gridDim.x - hist_blocks);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Exact threshold key and tie quota per big layer from the last-digit histogram.
 __global__ __launch_bounds__(256) void k_resolve(CompressBuffers cb) {
@@ -320,16 +333,25 @@ __global__ __launch_bounds__(256) void k_resolve(CompressBuffers cb) {
     __shared__ uint32_t res[2];
     const uint32_t b = blockIdx.x, tid = threadIdx.x;
     const SelRec S = cb.sel[b];
+    // The histogram is left at zero for the next call, whatever the mode: this kernel is its only reader.
+    uint4* h4 = reinterpret_cast<uint4*>(cb.hist3 + (size_t)b * D3_BINS + tid * 16u);
     if (S.mode != SEL_PREFIX && S.mode != SEL_CAND) {
         if (tid == 0) { cb.tau[b] = 0u; cb.quota[b] = 0u; }   // SEL_ALL / SEL_NONE: decided by the mode alone
+#pragma unroll
+        for (int k = 0; k < 4; ++k) h4[k] = make_uint4(0u, 0u, 0u, 0u);
         return;
     }
     const uint32_t need = S.K - S.above;           // 1..amb entries to take from the ambiguous ones
-    const uint32_t* h = cb.hist3 + (size_t)b * D3_BINS;
     // thread t owns digits 16t..16t+15; we need, from the top, the digit where the running count reaches `need`
     uint32_t c[16], sum = 0;
 #pragma unroll
-    for (int k = 0; k < 16; ++k) { c[k] = h[tid * 16u + k]; sum += c[k]; }
+    for (int k = 0; k < 4; ++k) {
+        const uint4 v = h4[k];
+        c[4 * k] = v.x; c[4 * k + 1] = v.y; c[4 * k + 2] = v.z; c[4 * k + 3] = v.w;
+        h4[k] = make_uint4(0u, 0u, 0u, 0u);
+    }
+#pragma unroll
+    for (int k = 0; k < 16; ++k) sum += c[k];
     uint32_t tot;
     const uint32_t ex = block_exclusive_scan<uint32_t>(sum, su, &tot);
     // entries in digits above this thread's range

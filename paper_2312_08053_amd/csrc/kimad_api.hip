@@ -548,6 +548,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     // Layer states start as "nothing spilled, nothing cached".
     if (hipMemsetAsync(p->ws + lo.state, 0, sizeof(LayerState) * (uint64_t)(lo.B ? lo.B : 1), s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.pool_hist, 0, 4ull * lo.pool_cap * D3_BINS, s) != hipSuccess ||
+        hipMemsetAsync(p->ws + lo.zero2_begin, 0, lo.zero2_end - lo.zero2_begin, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
 
     CompressBuffers& cb = p->cb;
@@ -687,8 +688,7 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
         cb.Ktab = ksel;
         cb.J = 1;
     }
-    int rc = zero_range(p, lo.zero2_begin, lo.zero2_end, s);
-    if (rc) return rc;
+    // (the last-digit histograms are zero here: k_resolve clears what it has read)
     KLAUNCH(p, s, "k_lookup", k_lookup, dim3(1), dim3(256), cb, (int32_t)KIMAD_ERR_OFFGRID,
             (int32_t)KIMAD_ERR_BAD_OFFSETS, (uint32_t)((flags & KIMAD_REUSE_PROFILE) ? 1u : 0u));
     hipStream_t ss = s;
@@ -699,9 +699,8 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
     if (lo.B) {
         const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
         const uint32_t cblocks = (lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG;
-        KLAUNCH(p, s, "k_compact", k_compact, dim3(std::min<uint32_t>(lo.ntiles, 4u * FALLBACK_GRID)), dim3(256), cb, lo.ntiles,
-                (int32_t)KIMAD_ERR_INTERNAL);
-        KLAUNCH(p, s, "k_hist3c", k_hist3c, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
+        KLAUNCH(p, s, "k_candidates", k_candidates, dim3(cblocks + std::min<uint32_t>(lo.ntiles, 4u * FALLBACK_GRID)), dim3(256), cb,
+                lo.nchunks, chunk_big, cblocks, lo.ntiles, (int32_t)KIMAD_ERR_INTERNAL);
         KLAUNCH(p, s, "k_resolve", k_resolve, dim3(lo.B), dim3(256), cb);
         KLAUNCH(p, s, "k_chunk_count", k_chunk_count, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
         KLAUNCH(p, s, "k_chunk_bases", k_chunk_bases, dim3(lo.ncblk), dim3(1024), cb);
