@@ -57,11 +57,24 @@ __global__ __launch_bounds__(256) void k_dp_layer(AllocBuffers ab, uint32_t i, c
     if (c > ab.cap) return;
     double best = DP_INF;
     uint32_t bj = 0xFF;
-    for (uint32_t j = 0; j < ab.J; ++j) {
-        const uint32_t w = sW[j];
-        if (w > c) break;                          // costs ascend with j
-        const double t = prev[c - w] + sE[j];
-        if (t < best) { best = t; bj = j; }
+    // candidates in ascending j with a strict "<", sixteen row reads asked for at a time (a candidate that
+    // costs more than the cell reads cell 0 instead and is skipped; costs ascend with j)
+    constexpr int BATCH = 16;
+    for (uint32_t j0 = 0; j0 < ab.J; j0 += BATCH) {
+        if (sW[j0] > c) break;
+        double p[BATCH];
+        uint32_t w[BATCH];
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            w[u] = j0 + (uint32_t)u < ab.J ? sW[j0 + u] : 0xFFFFFFFFu;
+            p[u] = prev[w[u] <= c ? c - w[u] : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) {
+            if (w[u] > c) continue;
+            const double t = p[u] + sE[j0 + u];
+            if (t < best) { best = t; bj = j0 + (uint32_t)u; }
+        }
     }
     cur[c] = best;
     ab.choice[(size_t)i * ab.stride + c] = (uint8_t)bj;
@@ -568,19 +581,40 @@ __global__ __launch_bounds__(1024) void k_dp_final(AllocBuffers ab, const double
         for (uint32_t i = tid; i <= ab.L; i += 1024) ab.offsets_out[i] = 0;
         return;
     }
+    // Back-tracking: one thread follows the chain of cells, one choice per layer read from memory.  The
+    // candidates' costs wait in LDS (when the table fits) so that the chain holds no second memory read
+    // and no division; sizes and offsets follow in parallel.
+    constexpr uint32_t W_LDS = 12288;
+    __shared__ uint32_t sw[W_LDS];
+    const uint32_t LJ = ab.L * ab.J;
+    const bool w_in_lds = LJ <= W_LDS;
+    if (w_in_lds)
+        for (uint32_t t = tid; t < LJ; t += 1024) sw[t] = units_of(ab.Ktab[t], ab.unit);
+    __syncthreads();
     if (tid == 0) {
         uint64_t c = cstar;
         for (uint32_t i = ab.L; i-- > 0;) {
             const uint32_t j = ab.choice[(size_t)i * ab.stride + c];
-            const uint32_t K = ab.Ktab[(size_t)i * ab.J + j];
             ab.j_out[i] = (int32_t)j;
-            ab.K_out[i] = K;
-            c -= units_of(K, ab.unit);
+            c -= w_in_lds ? sw[i * ab.J + j] : units_of(ab.Ktab[(size_t)i * ab.J + j], ab.unit);
         }
-        uint64_t run = 0;
-        for (uint32_t i = 0; i < ab.L; ++i) { ab.offsets_out[i] = run; run += ab.K_out[i]; }
-        ab.offsets_out[ab.L] = run;
     }
+    __threadfence_block();
+    __syncthreads();
+    unsigned long long carry = 0;
+    for (uint32_t i0b = 0; i0b < ab.L; i0b += 1024) {
+        const uint32_t i = i0b + tid;
+        unsigned long long K = 0;
+        if (i < ab.L) {
+            K = ab.Ktab[(size_t)i * ab.J + (uint32_t)ab.j_out[i]];
+            ab.K_out[i] = K;
+        }
+        unsigned long long tot;
+        const unsigned long long ex = block_exclusive_scan<unsigned long long>(K, sc, &tot);
+        if (i < ab.L) ab.offsets_out[i] = carry + ex;
+        carry += tot;
+    }
+    if (tid == 0) ab.offsets_out[ab.L] = carry;
 }
 
 }  // namespace kimad
