@@ -62,3 +62,23 @@ def test_budget_rule_matches_the_oracle_on_the_host():
         assert kimad.kimad_budget_bytes(B, t, tc, alpha, cap) == ko.budget_bytes(B, t, tc, alpha, cap), (B, t, tc, alpha, cap)
     # the paper's setting: alpha = 1, 30..330 Mbps, a 50 ms step of which 10 ms is computation
     assert kimad.kimad_budget_bytes(330e6, 0.05, 0.01) == 825000
+
+
+def test_benchmark_refuses_more_than_one_gpu():
+    """One worker is one GPU: bench.py --gpus N with N above 1 exits with a message, before any device work."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2 and "one GPU" in r.stderr and r.stdout == ""
+
+
+def test_product_package_never_imports_the_oracle():
+    """The oracle is test infrastructure: no source line of the package or of the input generators imports it."""
+    for pkg in ("paper_2312_08053_amd", "kimad_synth"):
+        for dirpath, _, files in os.walk(os.path.join(ROOT, pkg)):
+            for f in files:
+                if not f.endswith((".py", ".h", ".hip")):
+                    continue
+                for line in open(os.path.join(dirpath, f)):
+                    if "oracle" in line:
+                        assert "import" not in line and "#include" not in line, (dirpath, f, line)
