@@ -143,9 +143,12 @@ __global__ __launch_bounds__(64) void k_dp_prep(AllocBuffers ab, DpLists dl) {
 //
 // LDS rows are stored behind DP_PAD cells of +inf, so a candidate that costs more than the cell
 // needs no test: it reads +inf and cannot win.
-constexpr uint32_t DP_PAD = 3072;               // cells of +inf before cost 0; also the largest row
-constexpr uint32_t DP_ROW = 2 * DP_PAD;         // doubles per LDS row
-constexpr uint32_t DP_LIST_CAP = 3072;          // list records held in LDS at a time
+// Two LDS shapes: rows of up to 3072 cells beside 3072 list records, or rows of up to 4224 cells (a
+// discretisation factor of 4096 fits) beside 1024 records, i.e. more groups of fewer layers.
+constexpr uint32_t DP_PAD = 3072;               // cells of +inf before cost 0; also the largest row of the first shape
+constexpr uint32_t DP_LIST_CAP = 3072;          // list records held in LDS at a time, first shape
+constexpr uint32_t DP_PAD_WIDE = 4224;          // the same for the second shape
+constexpr uint32_t DP_LIST_CAP_WIDE = 1024;
 
 // Workgroup barrier for data exchanged through LDS only.  __syncthreads() also waits for the
 // acknowledgement of every global store in flight, which would put a memory round trip into each
@@ -236,13 +239,13 @@ __device__ __forceinline__ void dp_consume(const double (&p)[4][CPT], double err
 // (a readlane or a broadcast LDS read per record and wave costs several times the arithmetic).
 // Per record and cell the work is one LDS read, one add and one min.  The records of the next
 // layer are fetched while the current one is computed.
-template <int NT, int CPT>
+template <int NT, int CPT, uint32_t PAD = DP_PAD, uint32_t LCAP = DP_LIST_CAP>
 __global__ __launch_bounds__(NT) void k_dp_forward(AllocBuffers ab, const uint32_t* __restrict__ ent_w,
                                                                const double* __restrict__ ent_e,
                                                                const uint32_t* __restrict__ ent_n,
                                                                double* __restrict__ rows_g, uint32_t rstride) {
-    __shared__ double rows[2][DP_ROW];                  // 96 KB
-    __shared__ uint4 recs[DP_LIST_CAP + 64];            // 49 KB; a layer's fetch may run 63 records past its list
+    __shared__ double rows[2][2 * PAD];                 // 96 KB (132 KB in the wide shape)
+    __shared__ uint4 recs[LCAP + 64];                   // 49 KB (17 KB); a layer's fetch may run 63 records past its list
     __shared__ uint32_t loff[NT + 1];         // first record of each layer of the group
     __shared__ uint32_t ln[NT];               // entries of each layer before padding
     __shared__ uint32_t ltr[NT + 1];          // trips of each layer; 0 after the last
@@ -250,8 +253,8 @@ __global__ __launch_bounds__(NT) void k_dp_forward(AllocBuffers ab, const uint32
     __shared__ uint32_t sh_g;
     const uint32_t tid = threadIdx.x;
     const uint32_t ncell = ab.cap + 1;
-    for (uint32_t c = tid; c < DP_ROW; c += NT) {
-        rows[0][c] = c == DP_PAD ? 0.0 : DP_INF;
+    for (uint32_t c = tid; c < 2 * PAD; c += NT) {
+        rows[0][c] = c == PAD ? 0.0 : DP_INF;
         rows[1][c] = DP_INF;
     }
     for (uint32_t c = tid; c < ncell; c += NT) rows_g[c] = c ? DP_INF : 0.0;
@@ -264,7 +267,7 @@ __global__ __launch_bounds__(NT) void k_dp_forward(AllocBuffers ab, const uint32
         const uint32_t before = block_exclusive_scan<uint32_t>(mine, su, nullptr);
         if (tid == 0) sh_g = 0u;
         __syncthreads();
-        const bool fits = i0 + tid < ab.L && before + mine <= DP_LIST_CAP;
+        const bool fits = i0 + tid < ab.L && before + mine <= LCAP;
         if (fits) {
             loff[tid] = before;
             ln[tid] = n_mine;
@@ -331,8 +334,8 @@ __global__ __launch_bounds__(NT) void k_dp_forward(AllocBuffers ab, const uint32
         double* out = rows_g + (size_t)i0 * rstride + tid;
         for (uint32_t i = i0; i < i0 + g; ++i) {
             // LDS byte address of this thread's first cell in the previous row
-            const uint32_t prev = lds_addr(rows[i & 1] + DP_PAD + tid);
-            double* cur = rows[(i + 1) & 1] + DP_PAD + tid;
+            const uint32_t prev = lds_addr(rows[i & 1] + PAD + tid);
+            double* cur = rows[(i + 1) & 1] + PAD + tid;
             const uint32_t nt = nt_cur;
             const uint4 R0 = Rn[0], R1 = Rn[1], R2 = Rn[2], R3 = Rn[3];
             first += DP_UNROLL * nt;
@@ -369,7 +372,8 @@ __global__ __launch_bounds__(NT) void k_dp_forward(AllocBuffers ab, const uint32
             out += rstride;                      // row i + 1; a stored row holds NT * CPT cells, so no cell is tested
 #pragma unroll
             for (int m = 0; m < CPT; ++m) {
-                cur[m * NT] = best[m];
+                // (the last sweep of the wide shape runs past the row: those cells exist in the stored row only)
+                if ((uint32_t)(m + 1) * NT <= PAD || tid + (uint32_t)m * NT < PAD) cur[m * NT] = best[m];
                 out[m * NT] = best[m];
             }
             lds_barrier();
@@ -385,7 +389,7 @@ __global__ __launch_bounds__(256) void k_dp_choice(AllocBuffers ab, DpLists dl, 
                                                    uint32_t rstride) {
     __shared__ uint32_t lw[KIMAD_MAX_J_CONST], lj[KIMAD_MAX_J_CONST];
     __shared__ double le[2 * KIMAD_MAX_J_CONST];
-    __shared__ double prev[DP_PAD];            // the previous row up to this workgroup's last cell
+    __shared__ double prev[DP_PAD_WIDE];       // the previous row up to this workgroup's last cell
     const uint32_t i = blockIdx.y, tid = threadIdx.x;
     const uint32_t n = dl.n[i];
     if (tid < n) {

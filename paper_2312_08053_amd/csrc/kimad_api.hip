@@ -246,15 +246,15 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.row0 = take(8 * lo.dp_cells);
     lo.row1 = take(8 * lo.dp_cells);
     lo.choice = take((uint64_t)L * align_up(lo.dp_cells));
-    lo.cprev = take(2ull * L * align_up(std::min<uint64_t>(lo.dp_cells, DP_PAD)));
+    lo.cprev = take(2ull * L * align_up(std::min<uint64_t>(lo.dp_cells, DP_PAD_WIDE)));
     lo.dp_flags = take(16);
     lo.ncompact = take(16);
     lo.dl_wall = take(4 * LJ); lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
     lo.dl_bad = take(4ull * L);
     {
         // a stored row holds a whole number of the forward kernel's 512-thread sweeps (2, 4 or 6 cells per thread)
-        const uint64_t cells = std::min<uint64_t>(lo.dp_cells, DP_PAD);
-        lo.rstride = 512ull * (cells <= 1024 ? 2 : cells <= 2048 ? 4 : 6);
+        const uint64_t cells = std::min<uint64_t>(lo.dp_cells, DP_PAD_WIDE);
+        lo.rstride = 512ull * (cells <= 1024 ? 2 : cells <= 2048 ? 4 : cells <= DP_PAD ? 6 : 9);
     }
     lo.rows_g = take(8ull * (L + 1) * lo.rstride);
     lo.total = off;
@@ -633,7 +633,7 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     ab.flags = at<uint32_t>(p, lo.dp_flags);
     mark(p, s, "begin");
     const uint32_t cell_blocks = (uint32_t)((cap + 1 + 255) / 256);
-    if (cap + 1 <= DP_PAD) {
+    if (cap + 1 <= DP_PAD_WIDE) {
         DpLists dl;
         dl.wall = at<uint32_t>(p, lo.dl_wall); dl.w = at<uint32_t>(p, lo.dl_w); dl.jj = at<uint32_t>(p, lo.dl_jj); dl.e = at<double>(p, lo.dl_e);
         dl.n = at<uint32_t>(p, lo.dl_n); dl.bad = at<uint32_t>(p, lo.dl_bad);
@@ -648,9 +648,12 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
         } else if (cpt <= 4) {
             KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 4>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
                     (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
-        } else {
+        } else if (cpt <= 6) {
             KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 6>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
                     (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
+        } else {
+            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 9, DP_PAD_WIDE, DP_LIST_CAP_WIDE>), dim3(1), dim3(512), ab,
+                    (const uint32_t*)dl.w, (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
         }
         KLAUNCH(p, s, "k_dp_choice", k_dp_choice, dim3(cell_blocks, lo.L), dim3(256), ab, dl, (const double*)rows_g, rstride);
         KLAUNCH(p, s, "k_dp_walk", k_dp_walk, dim3(1), dim3(1024), ab, (const double*)(rows_g + (size_t)lo.L * rstride),

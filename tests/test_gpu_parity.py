@@ -100,10 +100,11 @@ def test_resnet50_set_discretised_budget():
     _full_check(ks.make_workload("resnet50", D=1000))
 
 
-@pytest.mark.parametrize("D", [1500, 3000, 3071, 3072])
+@pytest.mark.parametrize("D", [1500, 3000, 3071, 3072, 4096, 4223, 4224])
 def test_cost_axes_of_every_width_of_the_single_kernel_allocation(D):
-    """Rows of 1501, 3001 and 3072 cells take the forward kernel with 4 and 6 cells per thread; 3073 cells
-    no longer fit LDS and go through one launch per layer.  Allocation only (the oracle's table in, j out)."""
+    """Rows of 1501, 3001 and 3072 cells take the forward kernel with 4 and 6 cells per thread; 3073, 4097 and
+    4224 cells its wide shape (9 per thread, shorter groups of layers); 4225 cells no longer fit LDS and go
+    through one launch per layer.  Allocation only (the oracle's table in, j out)."""
     import torch
     work = ks.make_workload("resnet18", D=D)
     g, h = gh.to_device(work)
