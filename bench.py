@@ -37,6 +37,8 @@ def main() -> int:
     ap.add_argument("--D", type=int, default=None, help="cost discretisation factor (default: the workload's)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-blocks", type=int, default=12)
+    ap.add_argument("--also-D", type=int, default=4096,
+                    help="also time the step with this discretisation factor, reported beside the headline (0 = skip)")
     ap.add_argument("--block-min", type=int, default=0,
                     help="also time the step with tensors below this many elements merged into blocks (Section 6 remark)")
     ap.add_argument("--compare-allocators", action="store_true",
@@ -194,6 +196,29 @@ def main() -> int:
                               "model_step_GBs": round(step_bytes / (t_step * 1e-3) / 1e9, 1),
                               "model_step_frac_of_hbm_peak": round(step_bytes / (t_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
         del hats, xm
+
+    if args.also_D > 0 and args.also_D != work.cost_units_D:
+        # beside the headline: the same step with another discretisation factor of the allocation (rows of
+        # also_D + 1 cost cells).  Not part of `value`.
+        dplan = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes, D=args.also_D,
+                           max_budget_bytes=work.budget_bytes, capacity_pairs=work.budget_bytes // work.pair_bytes + 1)
+        for _ in range(max(1, args.warmup)):
+            h.copy_(h0)
+            dplan.step(work.budget_bytes)
+        torch.cuda.synchronize()
+        ds_ = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        de_ = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+        for k in range(args.steps):
+            h.copy_(h0)
+            ds_[k].record(stream)
+            dplan.step(work.budget_bytes)
+            de_[k].record(stream)
+        torch.cuda.synchronize()
+        dms = float(np.mean([ds_[k].elapsed_time(de_[k]) for k in range(args.steps)]))
+        out["other_D"] = {"cost_units_D": args.also_D, "status": dplan.status.cpu().tolist(), "ms_per_step": round(dms, 4),
+                          "gradient_GBs": round(4.0 * d / (dms * 1e-3) / 1e9, 2),
+                          "payload_pairs": int(dplan.offsets[-1].item())}
+        del dplan
 
     if args.block_min > 0:
         # beside the headline: block granularity (one block = a run of consecutive tensors).  Not part of `value`.
