@@ -257,11 +257,11 @@ def test_gpt2_full_size_in_the_benchmark_configuration():
 
 
 def test_chain_of_steps_with_persistent_estimator_and_bandwidth_trace():
-    """Four rounds of one worker: a fresh gradient every round, the estimator carried over on the
+    """Ten rounds of one worker: a fresh gradient every round, the estimator carried over on the
     device, the budget following a bandwidth trace (Algorithm 1, worker side).  Payload and
     estimator must match the oracle bit for bit after every round."""
     import torch
-    steps = 4
+    steps = 10
     kw = dict(n_layer=1, hidden=512, ffn=1408, vocab=3001)
     w0 = ks.make_workload("llama", step=0, **kw)
     trace = ks.bandwidth_trace(steps, seed=3, b0=0.02, sigma=0.01, lo=0.005, hi=0.05)
