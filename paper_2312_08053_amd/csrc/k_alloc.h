@@ -217,7 +217,7 @@ __device__ __forceinline__ void dp_issue(uint32_t neg_cost, uint32_t prev, doubl
     for (int u = 0; u < 4; ++u) {
 #pragma unroll
         for (int m = 0; m < CPT; ++m)
-            p[u][m] = *(lds_cdouble_ptr)(q[u] + (uint32_t)m * NT * 8u);
+            p[u][m] = *(lds_cdouble_ptr)(uintptr_t)(q[u] + (uint32_t)m * NT * 8u);
     }
 }
 
