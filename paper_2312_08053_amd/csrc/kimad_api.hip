@@ -177,7 +177,9 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
         lo.dp_cells = std::min<uint64_t>(pmax, d_all) + 1;
     }
     lo.tmp_cap = tmp_run;                                 // one region of n + REGION_SLACK entries per tiled layer
-    lo.main_wgs = stream_workgroups(cfg);
+    // a workgroup of the streaming pass writes its histograms out whole (140 KB a part): on small sets fewer
+    // workgroups with at least 16 chunks each do less of that than one per compute unit would
+    lo.main_wgs = std::max<uint32_t>(1, std::min<uint32_t>(stream_workgroups(cfg), (lo.nchunks + 15) / 16));
     lo.chunks_per_wg = std::max<uint32_t>(1, (lo.nchunks + lo.main_wgs - 1) / lo.main_wgs);
     lo.nparts = plan_parts(*hl, B, lo.nchunks, lo.main_wgs, lo.chunks_per_wg, parts_out);
 
