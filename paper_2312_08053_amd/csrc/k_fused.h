@@ -455,7 +455,8 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
     __shared__ uint2 stage[FUSED_WAVES * STAGE];                  // 16 KB: per-wave block windows
     __shared__ uint32_t pend[FUSED_WAVES * PEND * 3];             // 3 KB
     __shared__ uint32_t lds_cursor;
-    const uint32_t tid = threadIdx.x, wave = tid >> 6;
+    __shared__ uint32_t next_chunk;                               // first chunk of the segment no wave has taken yet
+    const uint32_t tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t c_begin = blockIdx.x * chunks_per_wg;
     const uint32_t c_end = min(pb.nchunks_total, c_begin + chunks_per_wg);
     uint32_t cur = c_begin;
@@ -468,7 +469,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         const uint32_t seg_end = min(min(c_end, L.chunk0 + L.nchunks), cur + PK_MAX_CHUNKS);
         const uint32_t used = D1_BINS + st.nslots_d * D2_BINS;
         for (uint32_t b = tid; b < used; b += FUSED_THREADS) pk[b] = 0ull;
-        if (tid == 0) { sq0 = 0ull; lds_cursor = 0u; }
+        if (tid == 0) { sq0 = 0ull; lds_cursor = 0u; next_chunk = cur + FUSED_WAVES; }
         __syncthreads();
         MainCtx cx;
         cx.pk = pk; cx.sq0 = &sq0;
@@ -483,7 +484,15 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         // (Fetching the wave's next chunk while the current one is worked on was tried, with the
         // loads verified to stay in flight across the chunk: it was slower.  The pass is bound by
         // instruction issue and LDS traffic, not by exposed memory latency.)
-        for (uint32_t chunk = cur + wave; chunk < seg_end; chunk += FUSED_WAVES) {
+        // Waves take chunks from a counter, not in a fixed rotation: a wave's pace varies with what it
+        // finds (spills, flushes, memory), and with fixed shares the segment's end waited for its slowest
+        // wave for a good tenth of the pass.  The next chunk is asked for before the current one is
+        // worked on, so the counter's round trip is never waited for.  No result depends on which wave
+        // had which chunk.
+        uint32_t chunk = cur + wave;
+        while (chunk < seg_end) {
+            uint32_t taken = 0;
+            if (lane_id() == 0) taken = atomicAdd(&next_chunk, 1u);
             QuadGH q[NQ];
             float x[NQ][4];
             uint32_t valid = 0;
@@ -493,6 +502,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
 #pragma unroll
                 for (int c = 0; c < 4; ++c) x[u][c] = q[u].g[c] - q[u].h[c];
             main_chunk(pb, cx, L, ws, chunk, x, valid);
+            chunk = __builtin_amdgcn_readfirstlane(taken);
         }
         spill_flush(pb, ws, L.tmp0);
         __syncthreads();
