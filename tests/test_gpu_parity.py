@@ -294,3 +294,29 @@ def test_chain_of_steps_with_persistent_estimator_and_bandwidth_trace():
             assert np.array_equal(h_now[w0.starts[i]:w0.starts[i + 1]].view(np.uint32), lh.view(np.uint32)), (t, i)
             h_ref[i] = lh
         assert w0.pair_bytes * int(off_ref[-1]) <= budgets[t]
+
+
+def test_repeated_step_on_the_same_input_is_bit_identical():
+    """The streaming pass hands chunks to waves in whatever order they ask, candidates land in the
+    blocks the waves happened to take, and histogram parts are summed later: none of that may show.
+    Five steps from the same (g, h), with 256, 7 and 1 streaming workgroups: error table, K, payload
+    and estimator are compared as bit patterns against the first run."""
+    import torch
+    w = ks.make_workload("llama", n_layer=2, hidden=768, ffn=2048, vocab=5003)
+    g = torch.from_numpy(w.g).cuda()
+    first = None
+    for max_wgs in (0, 0, 7, 0, 1):
+        h = torch.from_numpy(w.h).cuda()
+        plan = gh.make_plan(w, g, h, max_workgroups=max_wgs)
+        status = plan.step(w.budget_bytes)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [0, 0]
+        total = int(plan.offsets.cpu().numpy()[-1])
+        out = (plan.err_table.cpu().numpy().view(np.uint64).copy(), plan.K.cpu().numpy().copy(),
+               gh.u32(plan.idx)[:total].copy(), plan.val.cpu().numpy().view(np.uint32)[:total].copy(),
+               h.cpu().numpy().view(np.uint32).copy())
+        if first is None:
+            first = out
+            continue
+        for a, b, name in zip(first, out, ("E", "K", "idx", "val", "h")):
+            assert np.array_equal(a, b), (name, max_wgs)
