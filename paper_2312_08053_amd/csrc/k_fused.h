@@ -482,8 +482,10 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         ws.blk = 0; ws.fill = 0; ws.flushed = 0; ws.npend = 0; ws.have_blk = false;
 
         // (Fetching the wave's next chunk while the current one is worked on was tried, with the
-        // loads verified to stay in flight across the chunk: it was slower.  The pass is bound by
-        // instruction issue and LDS traffic, not by exposed memory latency.)
+        // loads verified to stay in flight across the chunk, at 16, 12 and 8 waves per workgroup: no
+        // gain.  What holds the pass below the speed of a plain read is the stores it issues while it
+        // reads, candidates above all: on this machine stores mixed into a read stream cost about
+        // four times their share of the bandwidth, however they are batched or aligned.)
         // Waves take chunks from a counter, not in a fixed rotation: a wave's pace varies with what it
         // finds (spills, flushes, memory), and with fixed shares the segment's end waited for its slowest
         // wave for a good tenth of the pass.  The next chunk is asked for before the current one is
