@@ -46,12 +46,12 @@ __global__ __launch_bounds__(256) void k_server_step(ServerArgs a, float* x, dou
     const uint64_t gid = (uint64_t)blockIdx.x * 256u + threadIdx.x, stride = (uint64_t)gridDim.x * 256u;
     const uint64_t n4 = vec_ok ? a.d / 4 : 0;
     for (uint64_t q = gid; q < n4; q += stride) {
-        const float4 xv = gload4(x + 4 * q);
+        const float4 xv = gload4_stream(x + 4 * q);
         double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
 #pragma unroll
         for (uint32_t m = 0; m < MAX_WORKERS; ++m) {
             if (m < a.M) {
-                const float4 u = gload4(a.u_hat[m] + 4 * q);
+                const float4 u = gload4_stream(a.u_hat[m] + 4 * q);   // read once per step
                 const double w = a.w[m];
                 s0 = s0 + w * (double)u.x; s1 = s1 + w * (double)u.y;
                 s2 = s2 + w * (double)u.z; s3 = s3 + w * (double)u.w;
