@@ -15,6 +15,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import re
 import os
 import sys
 import time
@@ -135,10 +136,11 @@ def main() -> int:
     # HBM bytes per launch from rocprofv3 counter runs, recorded under profiles/ (None if there is no record for
     # this kernel and workload)
     traffic = None
-    rec = os.path.join(ROOT, "profiles", f"hbm_traffic_{dom}_{work.name}.json")
+    rec = os.path.join(ROOT, "profiles", f"hbm_traffic_{dom}_{work.name}.txt")
     if os.path.exists(rec):
         with open(rec) as f:
-            traffic = json.load(f).get("traffic_bytes_per_launch")
+            m = re.search(r"traffic_bytes_per_launch\s*=\s*(\d+)", f.read())
+        traffic = float(m.group(1)) if m else None
     roofline = {"bound": "hbm", "kernel": dom, "achieved": round(ach, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "algorithmic_bytes_per_launch": alg_bytes[dom],
