@@ -148,7 +148,10 @@ def main() -> int:
 
     bytes_min = 8 * d + (work.pair_bytes + 4) * sumK + 8 * L * J + 8 * (L + 1)
     value = 4.0 * d / (ms * 1e-3) / 1e9
-    t_no_alloc = ms - stage_ms["allocate"]
+    # the step without its allocation stage: the stages are timed with an event after every launch, which
+    # stretches them (most where launches are many), so the allocation's share of the stages is taken off the
+    # step's own time rather than its stretched duration
+    t_no_alloc = ms * (1.0 - stage_ms["allocate"] / max(sum(stage_ms.values()), 1e-12))
     out = {
         "metric": "gradient GB/s compressed per step (profile+select+EF)",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
