@@ -110,7 +110,7 @@ int kimad_plan_grid_sizes(const kimad_plan_t* plan, uint64_t* K_table_out);
  *   err_table[i*J + j] = || x_i - TopK_{K_ij}(x_i) ||^2  = sum of squares of the entries dropped,
  * fp64, DEVICE, L*J row-major.  Exactly 0 where K_ij = n_i.  Pure: g and h are not modified.
  * Also records, inside the workspace, each candidate's selection threshold and the layer's
- * largest entries (index, x, h) for KIMAD_REUSE_PROFILE.
+ * largest entries (index, x) for KIMAD_REUSE_PROFILE.
  *   budget_hint_bytes  the budget the following kimad_allocate will get, or 0 if unknown.  It only
  *                      sizes how many of the largest entries are kept for the compression; no
  *                      result depends on it.
