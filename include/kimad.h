@@ -45,14 +45,13 @@ typedef enum kimad_status {
     KIMAD_OK = 0,
     KIMAD_ERR_INVALID_ARG = -1,
     KIMAD_ERR_WORKSPACE_TOO_SMALL = -2,
-    KIMAD_ERR_CAPACITY_TOO_SMALL = -3,
     KIMAD_ERR_HIP = -4,
-    KIMAD_ERR_NOT_IMPLEMENTED = -5,
     KIMAD_ERR_INFEASIBLE = -6,          /* device status: budget below the cheapest allocation */
     KIMAD_ERR_NONFINITE = -7,           /* device status: error table holds Inf or NaN */
     KIMAD_ERR_OFFGRID = -8,             /* device status: KIMAD_REUSE_PROFILE given but K is not a grid size */
     KIMAD_ERR_INTERNAL = -9,            /* device status: an internal capacity bound was violated (a bug) */
-    KIMAD_ERR_BAD_OFFSETS = -10         /* device status: offsets/K do not fit capacity_pairs */
+    KIMAD_ERR_BAD_OFFSETS = -10,        /* device status: offsets/K do not fit capacity_pairs */
+    KIMAD_ERR_STATIC_LIMIT = -11        /* kimad_allocate_static: more layers or longer rows than its fixed tables hold */
 } kimad_status;
 
 /* One layer: DEVICE pointers to n fp32 values each.  g is read-only; h is updated in place by
@@ -134,6 +133,21 @@ int kimad_profile(kimad_plan_t* plan, double* err_table, uint64_t budget_hint_by
 int kimad_allocate(kimad_plan_t* plan, const double* err_table, uint64_t budget_bytes,
                    int32_t* j_out, uint64_t* K_out, uint64_t* offsets_out,
                    int32_t* status_out, void* stream);
+
+/* kimad_allocate for callers that cannot allocate device memory or hand over a workspace at the point of
+ * the call: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same kernels, same results as kimad_allocate, but the dynamic programme's tables live in a
+ * fixed array inside the library (3.5 MiB per device, held until the process ends) instead of the plan's
+ * workspace; nothing is allocated or freed, by HIP or otherwise.  The plan supplies sizes, configuration and
+ * the candidate sizes K_ij only.  Limits: at most KIMAD_STATIC_MAX_L layers and rows of at most
+ * KIMAD_STATIC_MAX_CELLS cost cells (capacity + 1; a cost_units_D of up to 1023 always fits): beyond them
+ * the call returns KIMAD_ERR_STATIC_LIMIT and enqueues nothing.  Every call on a device shares that device's
+ * array, whatever the plan: calls that overlap on one device race, also with each other across streams. */
+#define KIMAD_STATIC_MAX_L 256u
+#define KIMAD_STATIC_MAX_CELLS 1024u
+int kimad_allocate_static(kimad_plan_t* plan, const double* err_table, uint64_t budget_bytes,
+                          int32_t* j_out, uint64_t* K_out, uint64_t* offsets_out,
+                          int32_t* status_out, void* stream);
 
 /* TopK selection, payload and estimator update (Section 2.2; Algorithm 1 upload line;
  * Section 3.3 Eq. EF21-2).  For each layer i with x = g_i - h_i (fp32):

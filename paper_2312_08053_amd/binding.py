@@ -15,7 +15,7 @@ KIMAD_MAX_J = 64
 
 EXPORTED_SYMBOLS = [
     "kimad_workspace_bytes", "kimad_plan_create", "kimad_plan_destroy", "kimad_plan_grid_sizes",
-    "kimad_profile", "kimad_allocate", "kimad_compress_ef", "kimad_step",
+    "kimad_profile", "kimad_allocate", "kimad_allocate_static", "kimad_compress_ef", "kimad_step",
     "kimad_profile_diagnostics", "kimad_plan_layer_states", "kimad_plan_set_timing", "kimad_plan_get_timings",
     "kimad_server_apply", "kimad_budget_bytes", "kimad_strerror", "kimad_version",
 ]
@@ -61,6 +61,7 @@ def lib() -> C.CDLL:
     L.kimad_plan_grid_sizes.argtypes = [vp, C.POINTER(C.c_uint64)]
     L.kimad_profile.argtypes = [vp, vp, u64, vp]
     L.kimad_allocate.argtypes = [vp, vp, u64, vp, vp, vp, i32p, vp]
+    L.kimad_allocate_static.argtypes = [vp, vp, u64, vp, vp, vp, i32p, vp]
     L.kimad_compress_ef.argtypes = [vp, vp, vp, vp, vp, u64, u32, i32p, vp]
     L.kimad_step.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, u64, i32p, vp]
     L.kimad_profile_diagnostics.argtypes = [vp, C.POINTER(C.c_uint32), vp]
@@ -154,6 +155,13 @@ def kimad_allocate(plan: int, err_table, budget_bytes: int, j_out, K_out, offset
     _check(lib().kimad_allocate(C.c_void_p(plan), C.c_void_p(_ptr(err_table)), int(budget_bytes),
                                 C.c_void_p(_ptr(j_out)), C.c_void_p(_ptr(K_out)), C.c_void_p(_ptr(offsets_out)),
                                 C.c_void_p(_ptr(status_out)), C.c_void_p(_stream(stream))), "kimad_allocate")
+
+
+def kimad_allocate_static(plan: int, err_table, budget_bytes: int, j_out, K_out, offsets_out, status_out,
+                          stream=None) -> None:
+    _check(lib().kimad_allocate_static(C.c_void_p(plan), C.c_void_p(_ptr(err_table)), int(budget_bytes),
+                                       C.c_void_p(_ptr(j_out)), C.c_void_p(_ptr(K_out)), C.c_void_p(_ptr(offsets_out)),
+                                       C.c_void_p(_ptr(status_out)), C.c_void_p(_stream(stream))), "kimad_allocate_static")
 
 
 def kimad_compress_ef(plan: int, K, offsets, idx_out, val_out, capacity_pairs: int, flags: int, status_out,

@@ -6,6 +6,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -418,6 +419,101 @@ int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, h
     return KIMAD_OK;
 }
 
+// ---- allocation: the same kernels on two homes of their tables ----------------------------------
+// Device memory the allocation's kernels work in besides their inputs and outputs.
+struct AllocScratch {
+    double* row0; double* row1;          // per-layer-launch path only
+    uint8_t* choice; uint16_t* cprev;    // [L][pitch]
+    uint32_t* flags;                     // 16 bytes
+    DpLists dl;
+    double* rows_g;                      // [(L + 1)][rstride]
+    uint32_t rstride;
+    uint64_t max_cells;                  // longest row (capacity + 1) the tables hold
+};
+
+// Table memory for callers that cannot allocate (kimad_allocate_static): one array per device, inside the
+// loaded code object.  Host code never passes the array's name to a kernel: it is a host-side stand-in,
+// not a device address; the address of each device's copy is looked up once and kept.
+constexpr uint64_t STATIC_SCRATCH_BYTES = 3584ull * 1024ull;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Address of the current device's copy of `scratch`, or nullptr on a HIP error.
+unsigned char* static_scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) { (void)hipGetLastError(); return nullptr; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) { (void)hipGetLastError(); return nullptr; }
+        g_scratch_ptr[dev] = static_cast<unsigned char*>(ptr);
+    }
+    return g_scratch_ptr[dev];
+}
+
+int enqueue_allocate(kimad_plan* p, const AllocScratch& ws, const double* err_table, uint64_t budget_bytes,
+                     int32_t* j_out, uint64_t* K_out, uint64_t* offsets_out, int32_t* status_out, hipStream_t s) {
+    const Layout& lo = p->lo;
+    const uint64_t P = budget_bytes / p->cfg.pair_bytes;
+    const uint64_t D = p->cfg.cost_units_D;
+    const uint64_t unit = (D == 0 || P <= D) ? 1 : (P + D - 1) / D;
+    uint64_t cap = P / unit;
+    // Costs above the dearest allocation are unreachable (+inf for ever): cutting the rows there
+    // changes no finite cell and so neither the least total nor the smallest cost attaining it.
+    uint64_t wmax = 0;
+    for (uint32_t i = 0; i < lo.L; ++i) wmax += ((uint64_t)p->kmax[i] + unit - 1) / unit;
+    if (cap > wmax) cap = wmax;
+    if (cap + 1 > ws.max_cells) return KIMAD_ERR_INVALID_ARG;   // budget beyond what the tables were sized for
+
+    AllocBuffers ab;
+    ab.E = err_table; ab.Ktab = at<uint32_t>(p, lo.ktab); ab.L = lo.L; ab.J = lo.J;
+    ab.unit = unit; ab.cap = (uint32_t)cap;
+    ab.row0 = ws.row0; ab.row1 = ws.row1;
+    ab.choice = ws.choice; ab.cprev = ws.cprev; ab.stride = align_up(cap + 1);   // row pitch: <= align_up(max_cells)
+    ab.j_out = j_out; ab.K_out = K_out; ab.offsets_out = offsets_out; ab.status = status_out;
+    ab.flags = ws.flags;
+    mark(p, s, "begin");
+    const uint32_t cell_blocks = (uint32_t)((cap + 1 + 255) / 256);
+    if (cap + 1 <= DP_PAD_WIDE) {
+        const DpLists& dl = ws.dl;
+        double* rows_g = ws.rows_g;
+        const uint32_t rstride = ws.rstride;
+        KLAUNCH(p, s, "k_dp_prep", k_dp_prep, dim3(lo.L), dim3(64), ab, dl);
+        // 512 threads: two waves per SIMD leave each thread the registers for two trips in flight
+        const uint32_t cpt = (uint32_t)((cap + 1 + 511) / 512);
+        if (cpt <= 2) {
+            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 2>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
+                    (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
+        } else if (cpt <= 4) {
+            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 4>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
+                    (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
+        } else if (cpt <= 6) {
+            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 6>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
+                    (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
+        } else {
+            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 9, DP_PAD_WIDE, DP_LIST_CAP_WIDE>), dim3(1), dim3(512), ab,
+                    (const uint32_t*)dl.w, (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
+        }
+        KLAUNCH(p, s, "k_dp_choice", k_dp_choice, dim3(cell_blocks, lo.L), dim3(256), ab, dl, (const double*)rows_g, rstride);
+        KLAUNCH(p, s, "k_dp_walk", k_dp_walk, dim3(1), dim3(1024), ab, (const double*)(rows_g + (size_t)lo.L * rstride),
+                (const uint32_t*)dl.bad, (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
+    } else {
+        // (clears with a kernel, not hipMemsetAsync: the call may be recorded into a graph)
+        KLAUNCH(p, s, "k_zero16", k_zero16, dim3(1), dim3(256), reinterpret_cast<uint4*>(ws.flags), (uint64_t)1);
+        KLAUNCH(p, s, "k_dp_init", k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), ab);
+        double* rows[2] = {ab.row0, ab.row1};
+        for (uint32_t i = 0; i < lo.L; ++i) {
+            KLAUNCH(p, s, "k_dp_layer", k_dp_layer, dim3(cell_blocks), dim3(256), ab, i, rows[i & 1], rows[(i + 1) & 1]);
+        }
+        KLAUNCH(p, s, "k_dp_final", k_dp_final, dim3(1), dim3(1024), ab, (const double*)rows[lo.L & 1],
+                (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
+    }
+    return KIMAD_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -457,6 +553,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     if (workspace_bytes < p->lo.total) { delete p; return KIMAD_ERR_WORKSPACE_TOO_SMALL; }
     p->ws = static_cast<char*>(workspace);
     if (hipGetDevice(&p->device) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
+    (void)static_scratch_of_current_device();   // set-up: the address of this device's fixed tables is known from here on
     const Layout& lo = p->lo;
 
     // host tables
@@ -613,65 +710,50 @@ int kimad_profile(kimad_plan_t* p, double* err_table, uint64_t budget_hint_bytes
 int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_bytes, int32_t* j_out, uint64_t* K_out,
                    uint64_t* offsets_out, int32_t* status_out, void* stream) {
     if (!p || !err_table || !j_out || !K_out || !offsets_out || !status_out) return KIMAD_ERR_INVALID_ARG;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     const Layout& lo = p->lo;
-    const uint64_t P = budget_bytes / p->cfg.pair_bytes;
-    const uint64_t D = p->cfg.cost_units_D;
-    const uint64_t unit = (D == 0 || P <= D) ? 1 : (P + D - 1) / D;
-    uint64_t cap = P / unit;
-    // Costs above the dearest allocation are unreachable (+inf for ever): cutting the rows there
-    // changes no finite cell and so neither the least total nor the smallest cost attaining it.
-    uint64_t wmax = 0;
-    for (uint32_t i = 0; i < lo.L; ++i) wmax += ((uint64_t)p->kmax[i] + unit - 1) / unit;
-    if (cap > wmax) cap = wmax;
-    if (cap + 1 > lo.dp_cells) return KIMAD_ERR_INVALID_ARG;   // budget beyond cfg.max_budget_bytes
+    AllocScratch ws;
+    ws.row0 = at<double>(p, lo.row0); ws.row1 = at<double>(p, lo.row1);
+    ws.choice = at<uint8_t>(p, lo.choice); ws.cprev = at<uint16_t>(p, lo.cprev);
+    ws.flags = at<uint32_t>(p, lo.dp_flags);
+    ws.dl.wall = at<uint32_t>(p, lo.dl_wall); ws.dl.w = at<uint32_t>(p, lo.dl_w); ws.dl.jj = at<uint32_t>(p, lo.dl_jj);
+    ws.dl.e = at<double>(p, lo.dl_e); ws.dl.n = at<uint32_t>(p, lo.dl_n); ws.dl.bad = at<uint32_t>(p, lo.dl_bad);
+    ws.rows_g = at<double>(p, lo.rows_g);
+    ws.rstride = (uint32_t)lo.rstride;
+    ws.max_cells = lo.dp_cells;
+    return enqueue_allocate(p, ws, err_table, budget_bytes, j_out, K_out, offsets_out, status_out,
+                            static_cast<hipStream_t>(stream));
+}
 
-    AllocBuffers ab;
-    ab.E = err_table; ab.Ktab = at<uint32_t>(p, lo.ktab); ab.L = lo.L; ab.J = lo.J;
-    ab.unit = unit; ab.cap = (uint32_t)cap;
-    ab.row0 = at<double>(p, lo.row0); ab.row1 = at<double>(p, lo.row1);
-    ab.choice = at<uint8_t>(p, lo.choice); ab.cprev = at<uint16_t>(p, lo.cprev); ab.stride = align_up(cap + 1);   // row pitch: <= align_up(lo.dp_cells), as allocated
-    ab.j_out = j_out; ab.K_out = K_out; ab.offsets_out = offsets_out; ab.status = status_out;
-    ab.flags = at<uint32_t>(p, lo.dp_flags);
-    mark(p, s, "begin");
-    const uint32_t cell_blocks = (uint32_t)((cap + 1 + 255) / 256);
-    if (cap + 1 <= DP_PAD_WIDE) {
-        DpLists dl;
-        dl.wall = at<uint32_t>(p, lo.dl_wall); dl.w = at<uint32_t>(p, lo.dl_w); dl.jj = at<uint32_t>(p, lo.dl_jj); dl.e = at<double>(p, lo.dl_e);
-        dl.n = at<uint32_t>(p, lo.dl_n); dl.bad = at<uint32_t>(p, lo.dl_bad);
-        double* rows_g = at<double>(p, lo.rows_g);
-        const uint32_t rstride = (uint32_t)lo.rstride;
-        KLAUNCH(p, s, "k_dp_prep", k_dp_prep, dim3(lo.L), dim3(64), ab, dl);
-        // 512 threads: two waves per SIMD leave each thread the registers for two trips in flight
-        const uint32_t cpt = (uint32_t)((cap + 1 + 511) / 512);
-        if (cpt <= 2) {
-            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 2>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
-                    (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
-        } else if (cpt <= 4) {
-            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 4>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
-                    (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
-        } else if (cpt <= 6) {
-            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 6>), dim3(1), dim3(512), ab, (const uint32_t*)dl.w,
-                    (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
-        } else {
-            KLAUNCH(p, s, "k_dp_forward", (k_dp_forward<512, 9, DP_PAD_WIDE, DP_LIST_CAP_WIDE>), dim3(1), dim3(512), ab,
-                    (const uint32_t*)dl.w, (const double*)dl.e, (const uint32_t*)dl.n, rows_g, rstride);
-        }
-        KLAUNCH(p, s, "k_dp_choice", k_dp_choice, dim3(cell_blocks, lo.L), dim3(256), ab, dl, (const double*)rows_g, rstride);
-        KLAUNCH(p, s, "k_dp_walk", k_dp_walk, dim3(1), dim3(1024), ab, (const double*)(rows_g + (size_t)lo.L * rstride),
-                (const uint32_t*)dl.bad, (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
-    } else {
-        int rc = zero_range(p, lo.dp_flags, lo.dp_flags + 16, s);
-        if (rc) return rc;
-        KLAUNCH(p, s, "k_dp_init", k_dp_init, dim3(std::min<uint32_t>(cell_blocks, 1024)), dim3(256), ab);
-        double* rows[2] = {ab.row0, ab.row1};
-        for (uint32_t i = 0; i < lo.L; ++i) {
-            KLAUNCH(p, s, "k_dp_layer", k_dp_layer, dim3(cell_blocks), dim3(256), ab, i, rows[i & 1], rows[(i + 1) & 1]);
-        }
-        KLAUNCH(p, s, "k_dp_final", k_dp_final, dim3(1), dim3(1024), ab, (const double*)rows[lo.L & 1],
-                (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
-    }
-    return KIMAD_OK;
+int kimad_allocate_static(kimad_plan_t* p, const double* err_table, uint64_t budget_bytes, int32_t* j_out,
+                          uint64_t* K_out, uint64_t* offsets_out, int32_t* status_out, void* stream) {
+    if (!p || !err_table || !j_out || !K_out || !offsets_out || !status_out) return KIMAD_ERR_INVALID_ARG;
+    const Layout& lo = p->lo;
+    if (lo.L > KIMAD_STATIC_MAX_L) return KIMAD_ERR_STATIC_LIMIT;
+    unsigned char* base = static_scratch_of_current_device();
+    if (!base) return KIMAD_ERR_HIP;
+    // Fixed carving of the array for the largest case it admits (KIMAD_STATIC_MAX_L layers, KIMAD_MAX_J
+    // ratios, rows of KIMAD_STATIC_MAX_CELLS cost cells), so the offsets do not depend on the plan.
+    constexpr uint64_t LJ = (uint64_t)KIMAD_STATIC_MAX_L * KIMAD_MAX_J;
+    constexpr uint64_t CELLS = KIMAD_STATIC_MAX_CELLS;
+    uint64_t off = 0;
+    auto take = [&](uint64_t bytes) { unsigned char* q = base + off; off = align_up(off + bytes); return q; };
+    AllocScratch ws;
+    ws.row0 = nullptr; ws.row1 = nullptr;                       // only the per-layer-launch path uses them
+    ws.choice = reinterpret_cast<uint8_t*>(take((uint64_t)KIMAD_STATIC_MAX_L * CELLS));
+    ws.cprev = reinterpret_cast<uint16_t*>(take(2ull * KIMAD_STATIC_MAX_L * CELLS));
+    ws.flags = reinterpret_cast<uint32_t*>(take(16));
+    ws.dl.wall = reinterpret_cast<uint32_t*>(take(4 * LJ)); ws.dl.w = reinterpret_cast<uint32_t*>(take(4 * LJ));
+    ws.dl.jj = reinterpret_cast<uint32_t*>(take(4 * LJ)); ws.dl.e = reinterpret_cast<double*>(take(16 * LJ));
+    ws.dl.n = reinterpret_cast<uint32_t*>(take(4ull * KIMAD_STATIC_MAX_L));
+    ws.dl.bad = reinterpret_cast<uint32_t*>(take(4ull * KIMAD_STATIC_MAX_L));
+    ws.rows_g = reinterpret_cast<double*>(take(8ull * (KIMAD_STATIC_MAX_L + 1) * CELLS));
+    ws.rstride = (uint32_t)CELLS;
+    ws.max_cells = CELLS;
+    static_assert(KIMAD_STATIC_MAX_CELLS == 1024, "a stored row is two sweeps of the forward kernel's 512 threads");
+    if (off > STATIC_SCRATCH_BYTES) return KIMAD_ERR_INTERNAL;
+    const int rc = enqueue_allocate(p, ws, err_table, budget_bytes, j_out, K_out, offsets_out, status_out,
+                                    static_cast<hipStream_t>(stream));
+    return rc == KIMAD_ERR_INVALID_ARG ? KIMAD_ERR_STATIC_LIMIT : rc;   // the one argument left to reject: rows too long
 }
 
 int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offsets, uint32_t* idx_out, float* val_out,
@@ -842,14 +924,13 @@ const char* kimad_strerror(int status) {
         case KIMAD_OK: return "ok";
         case KIMAD_ERR_INVALID_ARG: return "invalid argument";
         case KIMAD_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
-        case KIMAD_ERR_CAPACITY_TOO_SMALL: return "payload capacity too small";
         case KIMAD_ERR_HIP: return "HIP runtime error";
-        case KIMAD_ERR_NOT_IMPLEMENTED: return "not implemented";
         case KIMAD_ERR_INFEASIBLE: return "budget below the cheapest allocation";
         case KIMAD_ERR_NONFINITE: return "error table holds a non-finite entry";
         case KIMAD_ERR_OFFGRID: return "K is not one of the layer's grid sizes";
         case KIMAD_ERR_INTERNAL: return "internal error: candidate region overflow";
         case KIMAD_ERR_BAD_OFFSETS: return "K/offsets do not fit the payload capacity";
+        case KIMAD_ERR_STATIC_LIMIT: return "too many layers or cost cells for the fixed tables of kimad_allocate_static";
         default: return "unknown status";
     }
 }
