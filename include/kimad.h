@@ -77,6 +77,13 @@ typedef struct kimad_config {
 #define KIMAD_CFG_CLASSIC_PROFILE 1ull  /* profile with two full passes over g, h instead of the sampled
                                            single pass (same results; for comparison and testing) */
 
+#define KIMAD_CFG_FULL_DP 2ull          /* allocation: always run the recurrence over whole rows of cost cells */
+#define KIMAD_CFG_BAND_DP 4ull          /* allocation: always run it inside the band of cells that Lagrangian bounds
+                                           leave.  Same results either way; by default rows of 1537 cells or more
+                                           take the band (its cost hardly grows with the row), shorter ones the
+                                           whole rows.  Rows that do not fit LDS (more than 4224 cells) and plans
+                                           of more than 1024 layers always take whole rows. */
+
 /* flags of kimad_compress_ef */
 #define KIMAD_REUSE_PROFILE 1u          /* every K[i] is one of layer i's grid sizes and g, h are unchanged
                                            since the last kimad_profile on this plan: reuse its thresholds */
@@ -137,7 +144,7 @@ int kimad_allocate(kimad_plan_t* plan, const double* err_table, uint64_t budget_
 /* kimad_allocate for callers that cannot allocate device memory or hand over a workspace at the point of
  * the call: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * arguments, same kernels, same results as kimad_allocate, but the dynamic programme's tables live in a
- * fixed array inside the library (3.5 MiB per device, held until the process ends) instead of the plan's
+ * fixed array inside the library (4 MiB per device, held until the process ends) instead of the plan's
  * workspace; nothing is allocated or freed, by HIP or otherwise.  The plan supplies sizes, configuration and
  * the candidate sizes K_ij only.  Limits: at most KIMAD_STATIC_MAX_L layers and rows of at most
  * KIMAD_STATIC_MAX_CELLS cost cells (capacity + 1; a cost_units_D of up to 1023 always fits): beyond them
@@ -174,6 +181,12 @@ int kimad_step(kimad_plan_t* plan, uint64_t budget_bytes, double* err_table,
  * exact last-digit pass ran, out[1] = entries that pass recomputed, out[2] = histograms it used,
  * out[3] = layers whose sampled prediction missed and were recounted by a full pass. */
 int kimad_profile_diagnostics(kimad_plan_t* plan, uint32_t* out4, void* stream);
+
+/* DEVICE diagnostics of the last kimad_allocate on the plan (rows that fit LDS only), copied to HOST
+ * (synchronises the stream): out[0] = widest band of cost cells the recurrence visited in a row, out[1] = sum of
+ * the bands' widths over the rows, out[2] = 1 if the bands were the whole rows (no bound could be used),
+ * out[3] = upgrades the upper bound's greedy fill took.  All zero before the first allocation. */
+int kimad_allocate_diagnostics(kimad_plan_t* plan, uint32_t* out4, void* stream);
 
 /* Per-layer state of the last profile / compression, for benchmarks and tests (synchronises the
  * stream).  For each layer larger than 8192 entries, 8 words are written to `out` (HOST):

@@ -11,12 +11,14 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libkimad.so
 
 KIMAD_REUSE_PROFILE = 1
 KIMAD_CFG_CLASSIC_PROFILE = 1
+KIMAD_CFG_FULL_DP = 2
+KIMAD_CFG_BAND_DP = 4
 KIMAD_MAX_J = 64
 
 EXPORTED_SYMBOLS = [
     "kimad_workspace_bytes", "kimad_plan_create", "kimad_plan_destroy", "kimad_plan_grid_sizes",
     "kimad_profile", "kimad_allocate", "kimad_allocate_static", "kimad_compress_ef", "kimad_step",
-    "kimad_profile_diagnostics", "kimad_plan_layer_states", "kimad_plan_set_timing", "kimad_plan_get_timings",
+    "kimad_profile_diagnostics", "kimad_allocate_diagnostics", "kimad_plan_layer_states", "kimad_plan_set_timing", "kimad_plan_get_timings",
     "kimad_server_apply", "kimad_budget_bytes", "kimad_strerror", "kimad_version",
 ]
 
@@ -65,6 +67,7 @@ def lib() -> C.CDLL:
     L.kimad_compress_ef.argtypes = [vp, vp, vp, vp, vp, u64, u32, i32p, vp]
     L.kimad_step.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, u64, i32p, vp]
     L.kimad_profile_diagnostics.argtypes = [vp, C.POINTER(C.c_uint32), vp]
+    L.kimad_allocate_diagnostics.argtypes = [vp, C.POINTER(C.c_uint32), vp]
     L.kimad_plan_layer_states.argtypes = [vp, C.POINTER(C.c_uint32), u32, C.POINTER(C.c_uint32), vp]
     L.kimad_plan_set_timing.argtypes = [vp, C.c_int]
     L.kimad_plan_get_timings.argtypes = [vp, C.c_char_p, u32, C.POINTER(C.c_float), u32, C.POINTER(C.c_uint32)]
@@ -269,6 +272,12 @@ class Plan:
                "kimad_profile_diagnostics")
         return dict(uncertified=int(out[0]), recomputed=int(out[1]), pool_entries=int(out[2]),
                     redo_layers=int(out[3]))
+
+    def allocate_diagnostics(self):
+        out = (C.c_uint32 * 4)()
+        _check(lib().kimad_allocate_diagnostics(C.c_void_p(self.handle), out, C.c_void_p(_stream(None))),
+               "kimad_allocate_diagnostics")
+        return dict(max_band=int(out[0]), sum_bands=int(out[1]), whole_rows=int(out[2]), upgrades=int(out[3]))
 
     def layer_states(self):
         """Per tiled layer: dict(layer, spill_bin, slots_pre, slots_cand, redo, spill_cnt, spill_valid, mode)."""

@@ -322,12 +322,6 @@ struct WaveSpill {
     bool have_blk;
 };
 
-__device__ __forceinline__ void wave_sync_lds() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
 __device__ __forceinline__ void spill_flush(const ProfileBuffers& pb, WaveSpill& ws, uint64_t tmp0) {
     const uint32_t lane = lane_id();
     wave_sync_lds();

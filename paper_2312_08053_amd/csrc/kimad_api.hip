@@ -16,6 +16,7 @@
 #include "k_fused.h"
 #include "k_compress.h"
 #include "k_alloc.h"
+#include "k_alloc_band.h"
 #include "k_server.h"
 
 static_assert(kimad::KIMAD_MAX_J_CONST == KIMAD_MAX_J, "J limit mismatch");
@@ -55,6 +56,7 @@ struct Layout {
     // allocation
     uint64_t ncompact;
     uint64_t row0, row1, choice, dp_flags, dl_wall, dl_w, dl_jj, dl_e, dl_n, dl_bad, rows_g;
+    uint64_t band_lo, band_hi, band_info, live_off, live_e, live_before, live_w, live_jj;
     uint64_t rstride = 0;            // cells per stored DP row (LDS-resident recurrence only)
     uint64_t total = 0;
 };
@@ -254,6 +256,10 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.ncompact = take(16);
     lo.dl_wall = take(4 * LJ); lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
     lo.dl_bad = take(4ull * L);
+    lo.band_lo = take(4ull * (L + 1)); lo.band_hi = take(4ull * (L + 1));
+    lo.band_info = take(64);
+    lo.live_off = take(4ull * (L + 1)); lo.live_e = take(8 * LJ); lo.live_before = take(8 * LJ);
+    lo.live_w = take(4 * LJ); lo.live_jj = take(4 * LJ);
     {
         // a stored row holds a whole number of the forward kernel's 512-thread sweeps (2, 4 or 6 cells per thread)
         const uint64_t cells = std::min<uint64_t>(lo.dp_cells, DP_PAD_WIDE);
@@ -271,6 +277,7 @@ kimad_config_t normalise(const kimad_config_t* cfg) {
     return c;
 }
 
+constexpr uint64_t BAND_AUTO_CELLS = 1537;  // rows from this many cost cells on take the banded recurrence by themselves
 constexpr uint32_t FALLBACK_GRID = 1024;   // workgroups of a pass that usually has nothing to do
 
 __global__ __launch_bounds__(256) void k_zero16(uint4* p, uint64_t n16) {
@@ -426,6 +433,7 @@ struct AllocScratch {
     uint8_t* choice; uint16_t* cprev;    // [L][pitch]
     uint32_t* flags;                     // 16 bytes
     DpLists dl;
+    BandBuffers band;
     double* rows_g;                      // [(L + 1)][rstride]
     uint32_t rstride;
     uint64_t max_cells;                  // longest row (capacity + 1) the tables hold
@@ -434,7 +442,7 @@ struct AllocScratch {
 // Table memory for callers that cannot allocate (kimad_allocate_static): one array per device, inside the
 // loaded code object.  Host code never passes the array's name to a kernel: it is a host-side stand-in,
 // not a device address; the address of each device's copy is looked up once and kept.
-constexpr uint64_t STATIC_SCRATCH_BYTES = 3584ull * 1024ull;
+constexpr uint64_t STATIC_SCRATCH_BYTES = 4096ull * 1024ull;
 static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 
 constexpr int MAX_DEVICES = 64;
@@ -482,6 +490,15 @@ int enqueue_allocate(kimad_plan* p, const AllocScratch& ws, const double* err_ta
         double* rows_g = ws.rows_g;
         const uint32_t rstride = ws.rstride;
         KLAUNCH(p, s, "k_dp_prep", k_dp_prep, dim3(lo.L), dim3(64), ab, dl);
+        double* last_row = rows_g + (size_t)lo.L * rstride;
+        const bool band = (p->cfg.flags & KIMAD_CFG_BAND_DP) || cap + 1 >= BAND_AUTO_CELLS;
+        if (lo.L <= BAND_MAX_L && band && !(p->cfg.flags & KIMAD_CFG_FULL_DP)) {
+            // the recurrence inside the band of cells that Lagrangian bounds leave (same result, a fraction of the cells)
+            KLAUNCH(p, s, "k_dp_bounds", k_dp_bounds, dim3(1), dim3(BOUNDS_THREADS), ab, dl, ws.band);
+            KLAUNCH(p, s, "k_dp_banded", k_dp_banded, dim3(1), dim3(64), ab, ws.band, (const uint32_t*)dl.bad,
+                    (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
+            return KIMAD_OK;
+        }
         // 512 threads: two waves per SIMD leave each thread the registers for two trips in flight
         const uint32_t cpt = (uint32_t)((cap + 1 + 511) / 512);
         if (cpt <= 2) {
@@ -648,6 +665,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     if (hipMemsetAsync(p->ws + lo.state, 0, sizeof(LayerState) * (uint64_t)(lo.B ? lo.B : 1), s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.pool_hist, 0, 4ull * lo.pool_cap * D3_BINS, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.zero2_begin, 0, lo.zero2_end - lo.zero2_begin, s) != hipSuccess ||
+        hipMemsetAsync(p->ws + lo.band_info, 0, 64, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
 
     CompressBuffers& cb = p->cb;
@@ -717,6 +735,11 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     ws.flags = at<uint32_t>(p, lo.dp_flags);
     ws.dl.wall = at<uint32_t>(p, lo.dl_wall); ws.dl.w = at<uint32_t>(p, lo.dl_w); ws.dl.jj = at<uint32_t>(p, lo.dl_jj);
     ws.dl.e = at<double>(p, lo.dl_e); ws.dl.n = at<uint32_t>(p, lo.dl_n); ws.dl.bad = at<uint32_t>(p, lo.dl_bad);
+    ws.band.lo = at<uint32_t>(p, lo.band_lo); ws.band.hi = at<uint32_t>(p, lo.band_hi);
+    ws.band.info = at<uint32_t>(p, lo.band_info);
+    ws.band.live_off = at<uint32_t>(p, lo.live_off); ws.band.live_e = at<double>(p, lo.live_e);
+    ws.band.live_before = at<double>(p, lo.live_before); ws.band.live_w = at<uint32_t>(p, lo.live_w);
+    ws.band.live_jj = at<uint32_t>(p, lo.live_jj);
     ws.rows_g = at<double>(p, lo.rows_g);
     ws.rstride = (uint32_t)lo.rstride;
     ws.max_cells = lo.dp_cells;
@@ -746,6 +769,12 @@ int kimad_allocate_static(kimad_plan_t* p, const double* err_table, uint64_t bud
     ws.dl.jj = reinterpret_cast<uint32_t*>(take(4 * LJ)); ws.dl.e = reinterpret_cast<double*>(take(16 * LJ));
     ws.dl.n = reinterpret_cast<uint32_t*>(take(4ull * KIMAD_STATIC_MAX_L));
     ws.dl.bad = reinterpret_cast<uint32_t*>(take(4ull * KIMAD_STATIC_MAX_L));
+    ws.band.lo = reinterpret_cast<uint32_t*>(take(4ull * (KIMAD_STATIC_MAX_L + 1)));
+    ws.band.hi = reinterpret_cast<uint32_t*>(take(4ull * (KIMAD_STATIC_MAX_L + 1)));
+    ws.band.info = reinterpret_cast<uint32_t*>(take(64));
+    ws.band.live_off = reinterpret_cast<uint32_t*>(take(4ull * (KIMAD_STATIC_MAX_L + 1)));
+    ws.band.live_e = reinterpret_cast<double*>(take(8 * LJ)); ws.band.live_before = reinterpret_cast<double*>(take(8 * LJ));
+    ws.band.live_w = reinterpret_cast<uint32_t*>(take(4 * LJ)); ws.band.live_jj = reinterpret_cast<uint32_t*>(take(4 * LJ));
     ws.rows_g = reinterpret_cast<double*>(take(8ull * (KIMAD_STATIC_MAX_L + 1) * CELLS));
     ws.rstride = (uint32_t)CELLS;
     ws.max_cells = CELLS;
@@ -816,6 +845,21 @@ int kimad_profile_diagnostics(kimad_plan_t* p, uint32_t* out4, void* stream) {
     if (hipStreamSynchronize(s) != hipSuccess) return KIMAD_ERR_HIP;
     return KIMAD_OK;
 }
+
+int kimad_allocate_diagnostics(kimad_plan_t* p, uint32_t* out4, void* stream) {
+    if (!p || !out4) return KIMAD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(out4, p->ws + p->lo.band_info, 16, hipMemcpyDeviceToHost, s) != hipSuccess) return KIMAD_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return KIMAD_ERR_HIP;
+    return KIMAD_OK;
+}
+
+#ifdef KIMAD_STAMPS
+int kimad_debug_band_info(kimad_plan_t* p, uint32_t* out16) {
+    if (hipMemcpy(out16, p->ws + p->lo.band_info, 64, hipMemcpyDeviceToHost) != hipSuccess) return KIMAD_ERR_HIP;
+    return KIMAD_OK;
+}
+#endif
 
 int kimad_plan_set_timing(kimad_plan_t* p, int enable) {
     if (!p) return KIMAD_ERR_INVALID_ARG;

@@ -1,0 +1,221 @@
+"""GPU parity at the sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+* the 124M-element GPT-2-shaped set: every layer's error row, payload and estimator against the oracle,
+  and the allocation for the discretisation factors 1000, 4096 and 0 (exact cost axis) on that table;
+* the 1.3G-element Llama-shaped set, step 0 of its chain: properties that hold at any size on every
+  layer, and the oracle on a sample of nine layers (the oracle sorts 65M elements in about ten seconds;
+  all 218 layers would take minutes);
+* the chain of that configuration (100 consecutive steps, persistent estimator, budgets from the seeded
+  1-10 Gbit/s x 50 ms random walk) on a reduced variant of the same architecture, with a stop after
+  step 50: the estimator is copied to the host and back into fresh buffers and a fresh plan, and the
+  resumed run must continue bit for bit (Algorithm 1, worker lines; Section 3.3, Eq. EF21-2).
+"""
+import numpy as np
+import pytest
+
+import kimad_synth as ks
+from oracle import kimad_oracle as ko
+from tests import gpu_harness as gh
+
+pytestmark = pytest.mark.gpu
+
+
+def _selection_properties(x, ii, h_old, h_new, vals):
+    """What identifies TopK_K(x) with ties to the lower index, without sorting: the payload is ascending
+    and carries x bit for bit, the estimator moved on the support only, nothing dropped is larger than
+    anything kept, and among the entries equal to the smallest kept one the kept ones come first."""
+    assert np.all(ii[1:] > ii[:-1]) and (len(ii) == 0 or ii[-1] < len(x))
+    assert np.array_equal(vals.view(np.uint32), x[ii].view(np.uint32))
+    want = h_old.copy()
+    want[ii] = h_old[ii] + x[ii]
+    assert np.array_equal(h_new.view(np.uint32), want.view(np.uint32))
+    if 0 < len(ii) < len(x):
+        key = ko.magnitude_key(x)
+        kept = np.zeros(len(x), dtype=bool)
+        kept[ii] = True
+        tau = key[ii].min()
+        assert key[~kept].max() <= tau
+        ties_dropped = np.flatnonzero(~kept & (key == tau))
+        if len(ties_dropped):
+            ties_kept = np.flatnonzero(kept & (key == tau))
+            assert ties_kept.max() < ties_dropped.min()
+
+
+@pytest.mark.timeout(900)
+def test_gpt2_full_size_every_layer_against_the_oracle():
+    import torch
+    import paper_2312_08053_amd as kimad
+    work = ks.make_workload("gpt2")
+    g = torch.from_numpy(work.g).cuda()
+    h = torch.from_numpy(work.h).cuda()
+    plan = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes,
+                      D=work.cost_units_D, max_budget_bytes=work.budget_bytes,
+                      capacity_pairs=work.budget_bytes // work.pair_bytes + 1)
+    status = plan.step(work.budget_bytes)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    diag = plan.diagnostics()
+    assert diag["recomputed"] >= diag["uncertified"]
+    Kt = plan.grid_sizes()
+    E_gpu = plan.err_table.cpu().numpy().reshape(work.L, -1)
+    K = plan.K.cpu().numpy().astype(np.uint64)
+    off = plan.offsets.cpu().numpy().astype(np.uint64)
+
+    # allocation: the oracle's DP on the library's table, bit for bit
+    st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, work.budget_bytes, work.pair_bytes, work.cost_units_D)
+    assert st == ko.OK
+    assert np.array_equal(plan.j.cpu().numpy(), j_ref)
+    assert np.array_equal(K, K_ref) and np.array_equal(off, off_ref)
+    assert work.pair_bytes * int(off[-1]) <= work.budget_bytes
+
+    # every layer: error row (1e-5 relative, 0 at K = n), payload and estimator (bit for bit)
+    gL, hL = gh.oracle_layers(work)
+    for i in range(work.L):
+        if i % 20 == 0:
+            print(f"gpt2 full size: oracle row of layer {i}", flush=True)
+        x = ko.operand(gL[i], hL[i])
+        row = ko.topk_error_profile(x, Kt[i])
+        gh.assert_table_close(E_gpu[i:i + 1], row[None, :], Kt[i:i + 1], work.sizes[i:i + 1])
+    gh.check_compress(work, plan, h, K, off, plan.idx, plan.val)
+
+    # the same table with the other cost axes the benchmark reports: D = 4096 (rows of 4094 cells, the wide
+    # shape of the single-workgroup recurrence) and D = 0 (one cell per pair: 622 199 cells, one launch per layer)
+    for D in (4096, 0):
+        print(f"gpt2 full size: allocation with D = {D}", flush=True)
+        st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, work.budget_bytes, work.pair_bytes, D)
+        assert st == ko.OK
+        p2 = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes, D=D,
+                        max_budget_bytes=work.budget_bytes, capacity_pairs=1)
+        j, K2, off2, status2 = p2.allocate(work.budget_bytes, plan.err_table)
+        torch.cuda.synchronize()
+        assert int(status2.item()) == 0
+        assert np.array_equal(j.cpu().numpy(), j_ref), D
+        assert np.array_equal(K2.cpu().numpy().astype(np.uint64), K_ref), D
+        assert np.array_equal(off2.cpu().numpy().astype(np.uint64), off_ref), D
+        p2.close()
+        del p2
+
+
+@pytest.mark.timeout(1200)
+def test_llama_full_size_first_step_of_the_chain():
+    import torch
+    import paper_2312_08053_amd as kimad
+    print("llama full size: generating 1.3e9 values", flush=True)
+    work = ks.make_workload("llama")
+    assert work.L == 218 and work.d == 1_298_761_728
+    budget = ks.budget_from_bandwidth(float(ks.bandwidth_trace(1)[0]))        # 5.5 Gbit/s x 50 ms
+    g = torch.from_numpy(work.g).cuda()
+    h = torch.from_numpy(work.h).cuda()
+    plan = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes,
+                      D=work.cost_units_D, max_budget_bytes=budget, capacity_pairs=budget // work.pair_bytes + 1)
+    print("llama full size: step on the device", flush=True)
+    status = plan.step(budget)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0]
+    Kt = plan.grid_sizes()
+    E_gpu = plan.err_table.cpu().numpy().reshape(work.L, -1)
+    K = plan.K.cpu().numpy().astype(np.uint64)
+    off = plan.offsets.cpu().numpy().astype(np.uint64)
+    st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, budget, work.pair_bytes, work.cost_units_D)
+    assert st == ko.OK
+    assert np.array_equal(plan.j.cpu().numpy(), j_ref)
+    assert np.array_equal(K, K_ref) and np.array_equal(off, off_ref)
+    assert work.pair_bytes * int(off[-1]) <= budget
+
+    # invariants of the table on every layer: non-increasing along the grid, exactly 0 at K = n, never
+    # above the bound of the paper's compressor class, E(K) <= (1 - K/n) ||x||^2 (fp64 norm from numpy)
+    gL, hL = gh.oracle_layers(work)
+    idx = gh.u32(plan.idx)
+    val = plan.val.cpu().numpy()
+    h_new = h.cpu().numpy()
+    for i in range(work.L):
+        if i % 20 == 0:
+            print(f"llama full size: properties of layer {i}", flush=True)
+        x = ko.operand(gL[i], hL[i])
+        n = len(x)
+        row = E_gpu[i]
+        assert np.all(row[1:] <= row[:-1]) and np.all(row >= 0.0)
+        assert np.all(row[Kt[i] == n] == 0.0)
+        norm2 = float(np.dot(x.astype(np.float64), x.astype(np.float64)))
+        assert np.all(row <= (1.0 - Kt[i] / n) * norm2 * (1 + 1e-5))
+        a, b = int(off[i]), int(off[i + 1])
+        assert b - a == int(K[i])
+        _selection_properties(x, idx[a:b].astype(np.int64), hL[i], h_new[work.starts[i]:work.starts[i + 1]], val[a:b])
+
+    # the oracle on nine layers: the embedding (65.5M entries, the largest), the first block's nine kinds
+    # of tensor except two of its four attention matrices, a middle matrix, the last matrix and vector
+    sample = [0, 1, 2, 5, 6, 7, 9, 113, 216, 217]
+    for i in sample:
+        print(f"llama full size: oracle on layer {i}", flush=True)
+        x = ko.operand(gL[i], hL[i])
+        rowref = ko.topk_error_profile(x, Kt[i])
+        gh.assert_table_close(E_gpu[i:i + 1], rowref[None, :], Kt[i:i + 1], work.sizes[i:i + 1])
+    gh.check_compress(work, plan, h, K, off, plan.idx, plan.val, layers=sample)
+
+
+@pytest.mark.timeout(900)
+def test_hundred_step_chain_with_stop_and_resume_on_a_reduced_llama_variant():
+    """The chain of the Llama-shaped configuration on a 2-block variant of the same architecture (hidden 256,
+    2.1M elements, 20 tensors, the norms' vectors sorted whole in LDS and the matrices tiled): 100 steps, a
+    fresh gradient each step with the per-layer scales fixed, the estimator carried on the device, the budget
+    of step k from the seeded 1-10 Gbit/s random walk x 50 ms, scaled by the variant's share of the full
+    model's elements.  Every step is compared with the oracle (table, allocation on that table, payload,
+    estimator).  A second run is stopped after step 50: its estimator goes to the host and back into new
+    buffers and a new plan (nothing of the old plan's workspace survives), and from there on it must produce
+    the first run's payloads and estimator bit for bit."""
+    import torch
+    steps, stop = 100, 50
+    kw = dict(n_layer=2, hidden=256, ffn=704, vocab=2003)
+    w0 = ks.make_workload("llama", step=0, **kw)
+    share = w0.d / ks.WORKLOADS["llama"]["d"]
+    trace = ks.bandwidth_trace(steps)                                  # Gbit/s, seed 0: the configuration's walk
+    assert trace.min() >= 1.0 and trace.max() <= 10.0
+    budgets = [max(8 * w0.L, int(ks.budget_from_bandwidth(float(b)) * share)) for b in trace]
+    g = torch.from_numpy(w0.g).cuda()
+    h = torch.from_numpy(w0.h).cuda()
+    plan = gh.make_plan(w0, g, h, max_budget_bytes=max(budgets))
+    g2 = h2 = plan2 = None
+    h_ref = [x.copy() for x in w0.layer_views(w0.h)]
+    for t in range(steps):
+        if t % 10 == 0:
+            print(f"chain: step {t}", flush=True)
+        wt = ks.make_workload("llama", step=t, **kw)
+        g.copy_(torch.from_numpy(wt.g))
+        status = plan.step(budgets[t])
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [0, 0], (t, status)
+        gL = wt.layer_views(wt.g)
+        E_gpu = plan.err_table.cpu().numpy().reshape(w0.L, -1)
+        E_ref, Kt = ko.profile(gL, h_ref, w0.ratios)
+        gh.assert_table_close(E_gpu, E_ref, Kt, w0.sizes)
+        st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, budgets[t], w0.pair_bytes, w0.cost_units_D)
+        assert st == ko.OK
+        assert np.array_equal(plan.K.cpu().numpy().astype(np.uint64), K_ref), t
+        total = int(off_ref[-1])
+        assert w0.pair_bytes * total <= budgets[t]
+        idx = gh.u32(plan.idx)
+        val = plan.val.cpu().numpy().view(np.uint32)
+        h_now = h.cpu().numpy()
+        for i in range(w0.L):
+            li, lv, lh = ko.compress_ef_layer(gL[i], h_ref[i], int(K_ref[i]))
+            a, b = int(off_ref[i]), int(off_ref[i + 1])
+            assert np.array_equal(idx[a:b], li), (t, i)
+            assert np.array_equal(val[a:b], lv.view(np.uint32)), (t, i)
+            assert np.array_equal(h_now[w0.starts[i]:w0.starts[i + 1]].view(np.uint32), lh.view(np.uint32)), (t, i)
+            h_ref[i] = lh
+        if t >= stop:
+            # the resumed run: same gradient, its own estimator and plan
+            g2.copy_(torch.from_numpy(wt.g))
+            status2 = plan2.step(budgets[t])
+            torch.cuda.synchronize()
+            assert status2.cpu().tolist() == [0, 0], (t, status2)
+            assert torch.equal(plan2.K, plan.K), t
+            assert torch.equal(plan2.idx[:total], plan.idx[:total]), t
+            assert torch.equal(plan2.val[:total].view(torch.int32), plan.val[:total].view(torch.int32)), t
+            assert torch.equal(h2.view(torch.int32), h.view(torch.int32)), t
+        if t == stop - 1:
+            saved = h.cpu().numpy().copy()                              # the checkpoint: the estimator alone
+            g2 = torch.empty_like(g)
+            h2 = torch.from_numpy(saved).cuda()
+            plan2 = gh.make_plan(w0, g2, h2, max_budget_bytes=max(budgets))
+    assert plan2 is not None
