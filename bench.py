@@ -220,8 +220,10 @@ def main() -> int:
             torch.cuda.synchronize()
             return float(np.mean([a.elapsed_time(b) for a, b in ev]))
 
-        t_dec = timed(lambda: kimad.kimad_server_apply(pl, hats, wts, starts_dev, d, None, 0.0))
-        t_all = timed(lambda: kimad.kimad_server_apply(pl, hats, wts, starts_dev, d, xm, 1e-3))
+        sstat = torch.zeros(M, dtype=torch.int32, device="cuda")
+        t_dec = timed(lambda: kimad.kimad_server_apply(pl, hats, wts, starts_dev, d, None, 0.0, status_out=sstat))
+        t_all = timed(lambda: kimad.kimad_server_apply(pl, hats, wts, starts_dev, d, xm, 1e-3, status_out=sstat))
+        assert sstat.cpu().tolist() == [0] * M
         t_step = max(t_all - t_dec, 1e-6)
         step_bytes = 4 * (M + 2) * d
         out["server_step"] = {"workers": M, "decode_ms": round(t_dec, 4), "model_step_ms": round(t_step, 4),

@@ -51,7 +51,12 @@ typedef enum kimad_status {
     KIMAD_ERR_OFFGRID = -8,             /* device status: KIMAD_REUSE_PROFILE given but K is not a grid size */
     KIMAD_ERR_INTERNAL = -9,            /* device status: an internal capacity bound was violated (a bug) */
     KIMAD_ERR_BAD_OFFSETS = -10,        /* device status: offsets/K do not fit capacity_pairs */
-    KIMAD_ERR_STATIC_LIMIT = -11        /* kimad_allocate_static: more layers or longer rows than its fixed tables hold */
+    KIMAD_ERR_STATIC_LIMIT = -11,       /* kimad_allocate_static: more layers or longer rows than its fixed tables hold */
+    KIMAD_ERR_STALE_PROFILE = -12,      /* device status: KIMAD_REUSE_PROFILE, but no kimad_profile has run on this plan
+                                           since the last kimad_compress_ef (which changed h) */
+    KIMAD_ERR_BAD_PAYLOAD = -13,        /* device status of kimad_server_apply: offsets or indices do not fit the layers */
+    KIMAD_ERR_TABLES_TOO_LARGE = -14    /* cost_units_D == 0 without a max_budget_bytes that keeps the allocation's
+                                           tables (L rows of one byte per pair of the budget) within 4 GiB */
 } kimad_status;
 
 /* One layer: DEVICE pointers to n fp32 values each.  g is read-only; h is updated in place by
@@ -64,9 +69,14 @@ typedef struct kimad_layer {
 
 typedef struct kimad_config {
     uint32_t pair_bytes;                /* bytes charged per kept entry; 0 means 8 (u32 index + fp32 value) */
-    uint32_t cost_units_D;              /* Appendix C discretisation factor D applied to the budget; 0 = exact */
+    uint32_t cost_units_D;              /* Appendix C discretisation factor D applied to the budget; 0 = exact
+                                           (one cost cell per pair: set max_budget_bytes, see there) */
     uint64_t max_budget_bytes;          /* largest budget kimad_allocate will see; 0 = uncompressed size.
-                                           Sizes the DP tables when cost_units_D == 0. */
+                                           Sizes the DP tables when cost_units_D == 0: the workspace then grows
+                                           by L * max_budget_bytes / pair_bytes bytes, and a plan whose tables
+                                           would pass 4 GiB is refused with KIMAD_ERR_TABLES_TOO_LARGE (the
+                                           default of 0 does that for models beyond a few million elements:
+                                           give the budget limit, or a factor such as the paper's 1000). */
     uint64_t flags;                     /* KIMAD_CFG_* */
     uint32_t max_workgroups;            /* workgroups (= compute units) the streaming pass of the profile may
                                            occupy; 0 = all of the device.  A smaller number leaves units to
@@ -86,7 +96,12 @@ typedef struct kimad_config {
 
 /* flags of kimad_compress_ef */
 #define KIMAD_REUSE_PROFILE 1u          /* every K[i] is one of layer i's grid sizes and g, h are unchanged
-                                           since the last kimad_profile on this plan: reuse its thresholds */
+                                           since the last kimad_profile on this plan: reuse its thresholds.
+                                           The plan remembers on the device whether a profile is still current: a
+                                           kimad_compress_ef ends that (it changes h), so a second call with this
+                                           flag and no kimad_profile in between is refused through status_out
+                                           (KIMAD_ERR_STALE_PROFILE) and writes nothing.  Changes of g or h by the
+                                           caller are not seen. */
 
 typedef struct kimad_plan kimad_plan_t; /* host object; owns no device memory */
 
@@ -214,18 +229,22 @@ int kimad_plan_layer_states(kimad_plan_t* plan, uint32_t* out, uint32_t max_laye
  *   layer_start  DEVICE uint64[L+1], element offsets of the layers, layer_start[L] = d
  *   d            elements per flat buffer (HOST value of layer_start[L])
  *   x            DEVICE float[d] or NULL (aggregate only)
- * Nothing is allocated; all work is enqueued on `stream`.  Indices are not range-checked against
- * the layer sizes: payloads must come from kimad_compress_ef of plans with the same layer sizes.
+ *   status_out   DEVICE int32[M]: per worker KIMAD_OK, or KIMAD_ERR_BAD_PAYLOAD if its offsets are not a
+ *                non-decreasing sequence from 0 to at most capacity_pairs, or layer_start is not non-decreasing
+ *                up to d (then none of that worker's pairs is applied), or if some pair's index lies outside
+ *                its layer (that pair is skipped, the others applied).  Nothing is ever written out of bounds.
+ * Nothing is allocated; all work is enqueued on `stream`.
  * Returns KIMAD_ERR_INVALID_ARG for null pointers or M out of range. */
 #define KIMAD_MAX_WORKERS 16
 typedef struct kimad_payload {
     const uint32_t* idx;      /* DEVICE */
     const float* val;         /* DEVICE */
     const uint64_t* offsets;  /* DEVICE uint64[L+1] */
+    uint64_t capacity_pairs;  /* entries the idx and val buffers hold */
 } kimad_payload_t;
 int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, const double* weights,
                        uint32_t M, const uint64_t* layer_start, uint32_t L, uint64_t d,
-                       float* x, double gamma, void* stream);
+                       float* x, double gamma, int32_t* status_out, void* stream);
 
 /* Per-kernel timing (tracing aid for benchmarks).  With timing enabled the library records a
  * HIP event on the stream after every kernel it launches.  kimad_plan_get_timings waits for the
@@ -236,6 +255,18 @@ int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, con
 int kimad_plan_set_timing(kimad_plan_t* plan, int enable);
 int kimad_plan_get_timings(kimad_plan_t* plan, char* names, uint32_t names_bytes, float* ms,
                            uint32_t max_entries, uint32_t* count_out);
+
+/* Self-test of the kernels' wave-level building blocks that are written with DPP operands (the 64-lane prefix sum
+ * of the streaming pass, the row-broadcast address and accumulate steps of the allocation's recurrence, the
+ * group maxima of its bounds): one wave runs each on the given per-lane inputs and writes every lane's result, for
+ * a test to compare with host-computed values.  All pointers DEVICE:
+ *   in_u32 uint32[128], in_f64 double[128], out_u32 uint32[64 + 1024], out_f64 double[1024 + 192];
+ *   out_u32[lane]                          = in_u32[0] + ... + in_u32[lane]
+ *   out_u32[64 + (4 k + u) * 64 + lane]    = in_u32[lane] + in_u32[64 + 16 (lane / 16) + 4 k + u]      k, u = 0..3
+ *   out_f64[(4 k + u) * 64 + lane]         = in_f64[lane] + in_f64[64 + 16 (lane / 16) + 4 k + u]
+ *   out_f64[1024 + 64 t + lane]            = max of in_f64 over the lane's aligned group of 2, 4, 8 lanes (t = 0, 1, 2) */
+int kimad_selftest_wave_primitives(const uint32_t* in_u32, const double* in_f64, uint32_t* out_u32, double* out_f64,
+                                   void* stream);
 
 /* Compression budget of one round (Section 3.1, Eq. budget): the bytes that fit into the up-link share
  * of the time budget t at the monitored bandwidth.  The paper's time split t = c/B + T_comp + alpha c/B

@@ -19,7 +19,7 @@ EXPORTED_SYMBOLS = [
     "kimad_workspace_bytes", "kimad_plan_create", "kimad_plan_destroy", "kimad_plan_grid_sizes",
     "kimad_profile", "kimad_allocate", "kimad_allocate_static", "kimad_compress_ef", "kimad_step",
     "kimad_profile_diagnostics", "kimad_allocate_diagnostics", "kimad_plan_layer_states", "kimad_plan_set_timing", "kimad_plan_get_timings",
-    "kimad_server_apply", "kimad_budget_bytes", "kimad_strerror", "kimad_version",
+    "kimad_server_apply", "kimad_selftest_wave_primitives", "kimad_budget_bytes", "kimad_strerror", "kimad_version",
 ]
 
 
@@ -34,7 +34,7 @@ class _Layer(C.Structure):
 
 
 class _Payload(C.Structure):
-    _fields_ = [("idx", C.c_void_p), ("val", C.c_void_p), ("offsets", C.c_void_p)]
+    _fields_ = [("idx", C.c_void_p), ("val", C.c_void_p), ("offsets", C.c_void_p), ("capacity_pairs", C.c_uint64)]
 
 
 class _Config(C.Structure):
@@ -72,7 +72,8 @@ def lib() -> C.CDLL:
     L.kimad_plan_set_timing.argtypes = [vp, C.c_int]
     L.kimad_plan_get_timings.argtypes = [vp, C.c_char_p, u32, C.POINTER(C.c_float), u32, C.POINTER(C.c_uint32)]
     L.kimad_server_apply.argtypes = [C.POINTER(_Payload), C.POINTER(C.c_void_p), C.POINTER(C.c_double), u32, vp, u32, u64,
-                                     vp, C.c_double, vp]
+                                     vp, C.c_double, vp, vp]
+    L.kimad_selftest_wave_primitives.argtypes = [vp, vp, vp, vp, vp]
     L.kimad_strerror.argtypes = [C.c_int]
     L.kimad_strerror.restype = C.c_char_p
     L.kimad_version.restype = C.c_char_p
@@ -183,17 +184,30 @@ def kimad_step(plan: int, budget_bytes: int, err_table, j_out, K_out, offsets_ou
                             C.c_void_p(_ptr(status_out)), C.c_void_p(_stream(stream))), "kimad_step")
 
 
-def kimad_server_apply(payloads, u_hats, weights, layer_start, d: int, x=None, gamma: float = 0.0, stream=None) -> None:
+def kimad_server_apply(payloads, u_hats, weights, layer_start, d: int, x=None, gamma: float = 0.0, stream=None,
+                       status_out=None):
     """payloads: list of (idx, val, offsets) device tensors, one per worker; u_hats: list of flat fp32
     device tensors (updated in place); layer_start: device uint64/int64 tensor [L+1]; x: flat fp32 model
-    or None."""
+    or None; status_out: device int32[M] (allocated here if None).  Returns status_out."""
     M = len(u_hats)
-    pl = (_Payload * M)(*[_Payload(_ptr(i), _ptr(v), _ptr(o)) for (i, v, o) in payloads])
+    def cap(i, v):
+        return 0 if i is None or v is None else min(int(i.numel()), int(v.numel()))
+    pl = (_Payload * M)(*[_Payload(_ptr(i), _ptr(v), _ptr(o), cap(i, v)) for (i, v, o) in payloads])
     uh = (C.c_void_p * M)(*[_ptr(u) for u in u_hats])
     w = (C.c_double * M)(*[float(t) for t in weights])
+    if status_out is None:
+        import torch
+        status_out = torch.empty(M, dtype=torch.int32, device=u_hats[0].device)
     _check(lib().kimad_server_apply(pl, uh, w, M, C.c_void_p(_ptr(layer_start)), int(layer_start.numel()) - 1, int(d),
                                     C.c_void_p(_ptr(x) if x is not None else 0), float(gamma),
-                                    C.c_void_p(_stream(stream))), "kimad_server_apply")
+                                    C.c_void_p(_ptr(status_out)), C.c_void_p(_stream(stream))), "kimad_server_apply")
+    return status_out
+
+
+def kimad_selftest_wave_primitives(in_u32, in_f64, out_u32, out_f64, stream=None) -> None:
+    _check(lib().kimad_selftest_wave_primitives(C.c_void_p(_ptr(in_u32)), C.c_void_p(_ptr(in_f64)), C.c_void_p(_ptr(out_u32)),
+                                                C.c_void_p(_ptr(out_f64)), C.c_void_p(_stream(stream))),
+           "kimad_selftest_wave_primitives")
 
 
 class Plan:

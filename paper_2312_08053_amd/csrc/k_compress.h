@@ -46,6 +46,7 @@ struct CompressBuffers {
     uint32_t* tmp_idx;
     float* tmp_x;
     uint32_t* ncompact;       // layers whose selection needs the streaming compaction pass
+    uint32_t* fresh;          // 1 while the profile's cache describes the current g - h (see ProfileBuffers)
     const LayerState* state;      // fused-profile state (spill range) per big layer
     // outputs
     const uint64_t* K;
@@ -60,11 +61,14 @@ struct CompressBuffers {
 // Per layer: turn K[i] into a selection record using the profile's threshold cache.
 // One workgroup; thread b handles big layer b (looping).
 __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_offgrid, int32_t err_offsets,
-                                                uint32_t use_candidates) {
+                                                int32_t err_stale, uint32_t use_candidates) {
     __shared__ int bad;
     __shared__ uint32_t need_pass;
     const uint32_t tid = threadIdx.x;
-    if (tid == 0) { bad = 0; need_pass = 0u; }
+    // Thresholds may be reused only if a profile wrote them for the g - h that is there now: the compression
+    // itself changes h, so a second call without a new profile in between is refused (status err_stale).
+    const bool stale = use_candidates && *cb.fresh != 1u;
+    if (tid == 0) { bad = stale ? 3 : 0; need_pass = 0u; }
     __syncthreads();
     // validate offsets / K for every layer
     for (uint32_t i = tid; i < cb.L; i += 256) {
@@ -72,7 +76,7 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
         if (K > cb.layers[i].n || off > cb.capacity_pairs || K > cb.capacity_pairs - off) atomicMax(&bad, 1);
     }
     __syncthreads();
-    const bool offsets_bad = bad != 0;
+    const bool offsets_bad = bad == 1;
     __syncthreads();
     for (uint32_t b = tid; b < cb.B; b += 256) {
         SelRec r;
@@ -82,7 +86,7 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
         r.tmp_base = cb.layers[li].tmp0;
         r.h = cb.layers[li].h;
         r.dst = cb.offsets[li];
-        if (!offsets_bad) {
+        if (!offsets_bad && !stale) {
             const uint32_t K = (uint32_t)cb.K[li];
             r.K = K;
             if (K == 0u) {
@@ -127,10 +131,13 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
     if (bad) {
         // refuse the whole call: nothing is written by the later kernels
         for (uint32_t b = tid; b < cb.B; b += 256) { cb.sel[b].mode = SEL_NONE; cb.sel[b].cap = 0; cb.sel[b].K = 0; }
-        if (tid == 0) *cb.status = offsets_bad ? err_offsets : err_offgrid;
+        if (tid == 0) *cb.status = stale ? err_stale : offsets_bad ? err_offsets : err_offgrid;
     } else if (tid == 0) {
         *cb.status = 0;
     }
+    // From here on the cache no longer describes g - h (the estimator is about to change, or a selection from
+    // scratch has overwritten the cache); a refused call that reuses the profile leaves both as they were.
+    if (tid == 0 && (!use_candidates || !bad)) *cb.fresh = 0u;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -35,6 +35,8 @@ struct ProfileBuffers {
     uint32_t* sel_amb;            // entries with an equal prefix
     uint32_t* diag;               // [0] uncertified entries, [1] entries fixed by the exact fallback,
                                   // [2] pool entries handed out
+    uint32_t* fresh;              // 1 while the threshold cache and the candidates describe the current g - h:
+                                  // set by the profile's last kernels, cleared by the compression
     // exact fallback for entries whose bound is not tight: last-digit histograms of their prefix bins
     uint32_t* layer_flag;         // [B] layer has at least one pool entry
     uint32_t pool_cap;            // pool entries the plan holds: min(B * J, POOL_LIMIT)
@@ -489,6 +491,7 @@ __global__ __launch_bounds__(256) void k_scan3p(ProfileBuffers pb, double* err_t
     __shared__ double sumsq[D3_BINS];      // their squares
     const uint32_t tid = threadIdx.x;
     const uint32_t total = min(pb.diag[2], pb.pool_cap);
+    if (blockIdx.x == 0 && tid == 0 && err_table) *pb.fresh = 1u;      // the profile's last kernel on the caller's stream
     for (uint32_t f = blockIdx.x; f < total; f += gridDim.x) {
     __syncthreads();                            // the previous entry's readers are done with the tables
     const uint32_t prefix = pb.pool_prefix[f];
@@ -589,6 +592,7 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_small_profile(ProfileBuffers 
     __shared__ double sd[16];
     const uint32_t li = pb.small_layer[blockIdx.x];
     const LayerDesc L = pb.layers[li];
+    if (blockIdx.x == 0 && threadIdx.x == 0) *pb.fresh = 1u;            // (plans without tiled layers have no other profile kernel)
     const uint32_t P = next_pow2(L.n < 2 ? 2 : L.n);
     load_sorted_small(L, a, P);
     bitonic_sort_lds<SMALL_THREADS>(a, P);

@@ -22,10 +22,30 @@ struct ServerArgs {
 
 // One worker's payload into its estimator: one thread per pair.  The pair's layer is found by
 // bisection in the worker's offsets; indices inside a payload are distinct, so the additions need
-// no atomics.
+// no atomics.  The payload is what a worker sent, not something this library produced: every
+// workgroup first checks the offsets (non-decreasing, starting at 0, the total within the buffers'
+// capacity, the layer starts non-decreasing up to d) and leaves without a write if they are not; a
+// pair whose index lies outside its layer is skipped.  Either way the status word gets err_payload.
 __global__ __launch_bounds__(256) void k_server_decode(const uint32_t* __restrict__ idx, const float* __restrict__ val,
-                                                       const uint64_t* __restrict__ off, float* u_hat,
-                                                       const uint64_t* __restrict__ layer_start, uint32_t L) {
+                                                       const uint64_t* __restrict__ off, uint64_t capacity_pairs,
+                                                       float* u_hat, const uint64_t* __restrict__ layer_start, uint32_t L,
+                                                       uint64_t d, int32_t* status, int32_t err_payload) {
+    __shared__ int bad;
+    if (threadIdx.x == 0) bad = 0;
+    __syncthreads();
+    int mine = 0;
+    for (uint32_t i = threadIdx.x; i <= L; i += 256u) {
+        const uint64_t o = off[i], ls = layer_start[i];
+        if (i == 0 && o != 0) mine = 1;
+        if (i < L && (off[i + 1] < o || layer_start[i + 1] < ls)) mine = 1;
+        if (i == L && (o > capacity_pairs || ls != d)) mine = 1;
+    }
+    if (mine) bad = 1;
+    __syncthreads();
+    if (bad) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) atomicMin(status, err_payload);
+        return;
+    }
     const uint64_t total = off[L];
     const uint64_t stride = (uint64_t)gridDim.x * 256u;
     for (uint64_t p = (uint64_t)blockIdx.x * 256u + threadIdx.x; p < total; p += stride) {
@@ -34,7 +54,10 @@ __global__ __launch_bounds__(256) void k_server_decode(const uint32_t* __restric
             const uint32_t mid = (lo + hi) >> 1;
             if (off[mid] <= p) lo = mid; else hi = mid;
         }
-        float* u = u_hat + layer_start[lo] + idx[p];
+        const uint64_t first = layer_start[lo], n = layer_start[lo + 1] - first;
+        const uint32_t t = idx[p];
+        if ((uint64_t)t >= n) { atomicMin(status, err_payload); continue; }
+        float* u = u_hat + first + t;
         gstore(u, gload(u) + val[p]);
     }
 }

@@ -18,6 +18,7 @@
 #include "k_alloc.h"
 #include "k_alloc_band.h"
 #include "k_server.h"
+#include "k_selftest.h"
 
 static_assert(kimad::KIMAD_MAX_J_CONST == KIMAD_MAX_J, "J limit mismatch");
 
@@ -41,6 +42,7 @@ struct Layout {
     uint64_t layers, ktab, tile_layer, chunk_big, big_layer, small_layer;
     // zeroed before every profile
     uint64_t swg_layer, swg_first, state, lutc;
+    uint64_t fresh = 0;
     uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, shist, ghist, cursor, spill_over, zero1_end;
     uint64_t cprev = 0;
     uint64_t big_tmp0, parts, wg_part0, big_part0, big_nparts, zero1_mid;
@@ -179,6 +181,9 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
         uint64_t pmax = cfg.max_budget_bytes ? cfg.max_budget_bytes / pair : d_all;
         lo.dp_cells = std::min<uint64_t>(pmax, d_all) + 1;
     }
+    // (the winners' table of the allocation is L rows of dp_cells bytes: with the exact cost axis and no
+    // budget limit that is L * d bytes, 18 GB for a 124M-element model: refused rather than asked of the caller)
+    if ((uint64_t)L * align_up(lo.dp_cells) > (4ull << 30)) return KIMAD_ERR_TABLES_TOO_LARGE;
     lo.tmp_cap = tmp_run;                                 // one region of n + REGION_SLACK entries per tiled layer
     // a workgroup of the streaming pass writes its histograms out whole (140 KB a part): on small sets fewer
     // workgroups with at least 16 chunks each do less of that than one per compute unit would
@@ -211,6 +216,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.sq2 = take(8ull * B * SLOT_STRIDE * D2_BINS);
     lo.zero1_mid = off;                                   // the single-pass profile writes the tables above whole
     lo.diag = take(16);
+    lo.fresh = take(16);
     lo.layer_flag = take(4ull * (B ? B : 1));
     lo.shist = take(4ull * B * D1_BINS);
     lo.ghist = take(8ull * D1_BINS);
@@ -283,6 +289,10 @@ constexpr uint32_t FALLBACK_GRID = 1024;   // workgroups of a pass that usually 
 __global__ __launch_bounds__(256) void k_zero16(uint4* p, uint64_t n16) {
     const uint64_t stride = (uint64_t)gridDim.x * 256u;
     for (uint64_t i = (uint64_t)blockIdx.x * 256u + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+__global__ __launch_bounds__(64) void k_fill_i32(int32_t* p, uint32_t n, int32_t v) {
+    for (uint32_t i = threadIdx.x; i < n; i += 64u) p[i] = v;
 }
 
 __global__ __launch_bounds__(256) void k_make_ksel(const uint64_t* K, const kimad::LayerDesc* layers, uint32_t L,
@@ -643,6 +653,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.tgt_above1 = at<uint32_t>(p, lo.tgt_above1); pb.tgt_below = at<double>(p, lo.tgt_below);
     pb.sel_prefix = at<uint32_t>(p, lo.sel_prefix); pb.sel_above = at<uint32_t>(p, lo.sel_above);
     pb.sel_amb = at<uint32_t>(p, lo.sel_amb); pb.diag = at<uint32_t>(p, lo.diag);
+    pb.fresh = at<uint32_t>(p, lo.fresh);
     pb.layer_flag = at<uint32_t>(p, lo.layer_flag);
     pb.pool_prefix = at<uint32_t>(p, lo.pool_prefix); pb.pool_big = at<uint32_t>(p, lo.pool_big);
     pb.pool_t0 = at<uint32_t>(p, lo.pool_t0); pb.pool_cnt = at<uint32_t>(p, lo.pool_cnt);
@@ -666,6 +677,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
         hipMemsetAsync(p->ws + lo.pool_hist, 0, 4ull * lo.pool_cap * D3_BINS, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.zero2_begin, 0, lo.zero2_end - lo.zero2_begin, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.band_info, 0, 64, s) != hipSuccess ||
+        hipMemsetAsync(p->ws + lo.fresh, 0, 16, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
 
     CompressBuffers& cb = p->cb;
@@ -681,6 +693,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     cb.cblk_big = at<uint32_t>(p, lo.cblk_big);
     cb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); cb.tmp_x = at<float>(p, lo.tmp_x);
     cb.ncompact = at<uint32_t>(p, lo.ncompact);
+    cb.fresh = pb.fresh;
     cb.state = pb.state;
     cb.K = nullptr; cb.offsets = nullptr; cb.idx_out = nullptr; cb.val_out = nullptr; cb.capacity_pairs = 0;
     cb.status = nullptr;
@@ -806,7 +819,8 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
     }
     // (the last-digit histograms are zero here: k_resolve clears what it has read)
     KLAUNCH(p, s, "k_lookup", k_lookup, dim3(1), dim3(256), cb, (int32_t)KIMAD_ERR_OFFGRID,
-            (int32_t)KIMAD_ERR_BAD_OFFSETS, (uint32_t)((flags & KIMAD_REUSE_PROFILE) ? 1u : 0u));
+            (int32_t)KIMAD_ERR_BAD_OFFSETS, (int32_t)KIMAD_ERR_STALE_PROFILE,
+            (uint32_t)((flags & KIMAD_REUSE_PROFILE) ? 1u : 0u));
     hipStream_t ss = s;
     if (lo.S) {
         ss = fork_side(p, s);                 // after the lookup: the small layers read its verdict
@@ -923,9 +937,11 @@ int kimad_plan_layer_states(kimad_plan_t* p, uint32_t* out, uint32_t max_layers,
 }
 
 int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, const double* weights, uint32_t M,
-                       const uint64_t* layer_start, uint32_t L, uint64_t d, float* x, double gamma, void* stream) {
+                       const uint64_t* layer_start, uint32_t L, uint64_t d, float* x, double gamma,
+                       int32_t* status_out, void* stream) {
     static_assert(KIMAD_MAX_WORKERS == MAX_WORKERS, "header and kernel constants");
-    if (!payloads || !u_hat || !weights || !layer_start || M == 0 || M > KIMAD_MAX_WORKERS || L == 0 || d == 0)
+    if (!payloads || !u_hat || !weights || !layer_start || M == 0 || M > KIMAD_MAX_WORKERS || L == 0 || d == 0 ||
+        !status_out)
         return KIMAD_ERR_INVALID_ARG;
     ServerArgs a{};
     bool vec_ok = x && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
@@ -936,10 +952,13 @@ int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, con
     }
     a.M = M; a.d = d;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_fill_i32, dim3(1), dim3(64), 0, s, status_out, M, 0);
+    if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP;
     // payload sizes live on the device: a fixed grid strides over whatever the worker sent
     for (uint32_t m = 0; m < M; ++m) {
         hipLaunchKernelGGL(k_server_decode, dim3(1024), dim3(256), 0, s, payloads[m].idx, payloads[m].val,
-                           payloads[m].offsets, u_hat[m], layer_start, L);
+                           payloads[m].offsets, payloads[m].capacity_pairs, u_hat[m], layer_start, L, d,
+                           status_out + m, (int32_t)KIMAD_ERR_BAD_PAYLOAD);
         if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP;
     }
     if (x) {
@@ -950,6 +969,14 @@ int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, con
         if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP;
     }
     return KIMAD_OK;
+}
+
+int kimad_selftest_wave_primitives(const uint32_t* in_u32, const double* in_f64, uint32_t* out_u32, double* out_f64,
+                                   void* stream) {
+    if (!in_u32 || !in_f64 || !out_u32 || !out_f64) return KIMAD_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(k_selftest_wave, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), in_u32, in_f64, out_u32,
+                       out_f64);
+    return hipGetLastError() == hipSuccess ? KIMAD_OK : KIMAD_ERR_HIP;
 }
 
 uint64_t kimad_budget_bytes(double bandwidth_bits_per_s, double t_seconds, double t_comp_seconds, double alpha,
@@ -974,6 +1001,9 @@ const char* kimad_strerror(int status) {
         case KIMAD_ERR_OFFGRID: return "K is not one of the layer's grid sizes";
         case KIMAD_ERR_INTERNAL: return "internal error: candidate region overflow";
         case KIMAD_ERR_BAD_OFFSETS: return "K/offsets do not fit the payload capacity";
+        case KIMAD_ERR_STALE_PROFILE: return "KIMAD_REUSE_PROFILE without a profile of the current g - h";
+        case KIMAD_ERR_BAD_PAYLOAD: return "payload offsets or indices do not fit the layers";
+        case KIMAD_ERR_TABLES_TOO_LARGE: return "exact cost axis without a budget limit: the allocation's tables would exceed 4 GiB";
         case KIMAD_ERR_STATIC_LIMIT: return "too many layers or cost cells for the fixed tables of kimad_allocate_static";
         default: return "unknown status";
     }

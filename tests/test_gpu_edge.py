@@ -207,6 +207,38 @@ def test_device_side_refusals_leave_h_untouched():
     _, _, st = plan.compress_ef(K, off, reuse_profile=True)
     assert int(st.item()) == 0
     gh.check_compress(work, plan, h, Kt[:, 3], off.cpu().numpy(), plan.idx, plan.val)
+    # The compression changed h: the profile's thresholds no longer describe g - h.  A retry that reuses them
+    # (say after a failed send) is refused and changes nothing; Section 3.3's estimator equality would break otherwise.
+    h_after = h.cpu().numpy().copy()
+    plan.idx.zero_()
+    _, _, st = plan.compress_ef(K, off, reuse_profile=True)
+    torch.cuda.synchronize()
+    assert int(st.item()) == -12
+    assert np.array_equal(h.cpu().numpy().view(np.uint32), h_after.view(np.uint32))
+    assert not plan.idx.cpu().numpy().any()
+    # a selection from scratch needs no profile; it too ends the validity of an earlier one
+    plan.profile()
+    _, _, st = plan.compress_ef(K, off, reuse_profile=False)
+    assert int(st.item()) == 0
+    _, _, st = plan.compress_ef(K, off, reuse_profile=True)
+    assert int(st.item()) == -12
+    # and a plan that has never been profiled refuses the reuse as well
+    plan2 = gh.make_plan(work, g, h)
+    _, _, st = plan2.compress_ef(K, off, reuse_profile=True)
+    assert int(st.item()) == -12
+
+
+def test_allocate_refuses_a_budget_beyond_the_plans_tables():
+    import paper_2312_08053_amd as kimad
+    work = ks.make_workload("mlp")                        # exact cost axis: the tables hold max_budget_bytes / 8 cells
+    g, h = gh.to_device(work)
+    plan = gh.make_plan(work, g, h, max_budget_bytes=8 * 1000)
+    plan.profile()
+    with pytest.raises(kimad.KimadError) as e:
+        plan.allocate(8 * 5000)
+    assert e.value.code == -1
+    plan.allocate(8 * 1000)
+    assert int(plan.status[0].item()) == 0
 
 
 def _hash32(a):

@@ -111,3 +111,55 @@ def test_server_apply_refuses_bad_arguments():
         kimad.kimad_server_apply([pl] * 17, [u] * 17, [1.0] * 17, st, 8, None, 0.0)     # too many workers
     with pytest.raises(kimad.KimadError):
         kimad.kimad_server_apply([(None, pl[1], pl[2])], [u], [1.0], st, 8, None, 0.0)  # null pointer
+
+
+def test_payloads_that_do_not_fit_the_layers_are_flagged_and_write_nothing_out_of_bounds():
+    """The server's input comes from workers, not from this library: corrupted offsets or indices must end in a
+    status, never in a write outside the estimator (guard words on both sides stay as they were)."""
+    import torch
+    import paper_2312_08053_amd as kimad
+    sizes = np.array([10, 3, 50], dtype=np.int64)
+    starts = np.concatenate([[0], np.cumsum(sizes)])
+    d = int(starts[-1])
+    st = torch.from_numpy(starts).cuda()
+    guard = 16
+    offsets = np.array([0, 2, 3, 6], dtype=np.int64)
+    idx = np.array([1, 9, 2, 0, 7, 49], dtype=np.uint32)
+    val = np.arange(1, 7, dtype=np.float32)
+
+    def run(off_, idx_, cap_extra=0):
+        buf = torch.full((d + 2 * guard,), 7.0, device="cuda")
+        u = buf[guard:guard + d]
+        u.zero_()
+        i_t = torch.from_numpy(np.concatenate([idx_, np.zeros(cap_extra, np.uint32)]).view(np.int32)).cuda()
+        v_t = torch.from_numpy(np.concatenate([val[:len(idx_)], np.zeros(cap_extra, np.float32)])).cuda()
+        o_t = torch.from_numpy(off_).cuda()
+        status = kimad.kimad_server_apply([(i_t, v_t, o_t)], [u], [1.0], st, d, None, 0.0)
+        torch.cuda.synchronize()
+        b = buf.cpu().numpy()
+        assert np.all(b[:guard] == 7.0) and np.all(b[guard + d:] == 7.0)
+        return int(status.item()), b[guard:guard + d]
+
+    code, u = run(offsets, idx)
+    want = np.zeros(d, np.float32)
+    for i in range(3):
+        for p in range(offsets[i], offsets[i + 1]):
+            want[starts[i] + idx[p]] += val[p]
+    assert code == 0 and np.array_equal(u, want)
+    bad_idx = idx.copy()
+    bad_idx[2] = 3                                        # layer 1 has 3 entries: index 3 is outside it
+    code, u = run(offsets, bad_idx)
+    want2 = want.copy()
+    want2[starts[1] + 2] = 0.0
+    assert code == -13 and np.array_equal(u, want2)       # that pair skipped, the others applied
+    bad_idx[5] = 0xFFFFFFF0
+    code, u = run(offsets, bad_idx)
+    assert code == -13
+    for bad_off in (np.array([0, 4, 3, 6]), np.array([1, 2, 3, 6]), np.array([0, 2, 3, 1 << 40]), np.array([0, 2, 3, 7])):
+        code, u = run(bad_off.astype(np.int64), idx)
+        assert code == -13 and not u.any(), bad_off       # nothing of such a payload is applied
+    # layer starts that do not end at d
+    st_bad = torch.from_numpy(np.array([0, 10, 13, 64], dtype=np.int64)).cuda()
+    u = torch.zeros(d, device="cuda")
+    status = kimad.kimad_server_apply([_dev_payload(offsets, idx, val)], [u], [1.0], st_bad, d, None, 0.0)
+    assert int(status.item()) == -13 and not u.cpu().numpy().any()

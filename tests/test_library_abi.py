@@ -41,6 +41,13 @@ def test_host_side_argument_checks_need_no_gpu():
     with pytest.raises(kimad.KimadError):
         kimad.kimad_workspace_bytes([], 4)
     assert kimad.kimad_strerror(-6).startswith("budget")
+    # the exact cost axis without a budget limit would need L * d bytes of tables: refused above 4 GiB, not asked for
+    gpt2_like = [38_597_376, 786_432] + [2_359_296] * 40
+    with pytest.raises(kimad.KimadError) as e:
+        kimad.kimad_workspace_bytes(gpt2_like, 64)
+    assert e.value.code == -14
+    assert kimad.kimad_workspace_bytes(gpt2_like, 64, D=1000) > 0
+    assert kimad.kimad_workspace_bytes(gpt2_like, 64, D=0, max_budget_bytes=8 * 600_000) > 0
     # the exact-knapsack table grows with the largest budget the plan must serve
     small = kimad.kimad_workspace_bytes([100000] * 4, 8, D=0, max_budget_bytes=8 * 1000)
     large = kimad.kimad_workspace_bytes([100000] * 4, 8, D=0, max_budget_bytes=8 * 100000)
