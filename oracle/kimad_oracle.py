@@ -63,6 +63,17 @@ the design notes of this repository):
       same equation gives c = B (t - T_comp) / (1 + alpha).  B in bits per second, c in bits;
       the byte budget is floor(c / 8); a step with t <= T_comp has no budget.
 
+  R15 Dense fallback (Section 4.2, "Communication adaptivity": the sent size levels off at the
+      uncompressed size).  A layer never costs more than its bare values: K pairs cost
+      min(K * pair_bytes, n * value_bytes) bytes.  A grid point at or beyond the break-even
+      (K * pair_bytes >= n * value_bytes) therefore stands for sending the layer whole: K = n,
+      error 0, charged ceil(n * value_bytes / pair_bytes) pairs.  Optional (`dense_sizes`).
+  R16 Half-precision values (Section 2.2 names quantisation beside sparsification; a 6-byte pair).
+      A kept value v travels as binary16, round to nearest even, saturated to +-65504, NaN kept;
+      worker and server both add the decoded value: h[idx] = fl32(h[idx] + fl32(q16(v))), so the
+      two estimator copies stay equal and what the rounding lost stays in g - h for the next
+      round.  The error table remains that of TopK (the rounding of kept values is not charged).
+
 Pins (tests/test_oracle_*.py): brute force over all subsets / all assignments on
 tiny inputs, closed forms for constant vectors, numpy partition on distinct
 magnitudes, the contraction bound of the paper's compressor class, monotonicity,
@@ -149,15 +160,35 @@ def profile(g_layers: Sequence[np.ndarray], h_layers: Sequence[np.ndarray],
     return E, Kt
 
 
-def compress_ef_layer(g: np.ndarray, h: np.ndarray, K: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+def quantise_f16(v: np.ndarray) -> np.ndarray:
+    """binary16 bit patterns of fp32 values: round to nearest even, saturated to +-65504, NaN kept (reading R16)."""
+    v = np.asarray(v, dtype=np.float32)
+    with np.errstate(invalid="ignore", over="ignore"):
+        clipped = np.clip(v, np.float32(-65504.0), np.float32(65504.0))      # (NaN passes through a clip)
+        return clipped.astype(np.float16).view(np.uint16)
+
+
+def dequantise_f16(bits: np.ndarray) -> np.ndarray:
+    """fp32 values of binary16 bit patterns (exact)."""
+    return np.asarray(bits, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
+def compress_ef_layer(g: np.ndarray, h: np.ndarray, K: int, value_format: str = "f32"):
     """One layer: payload (ascending index, value) of TopK_K(g - h), and the updated estimator.
 
-    h_new[t] = fl32(h[t] + x[t]) on the support, h[t] elsewhere (Section 3.3, Eq. EF21-2).
+    h_new[t] = fl32(h[t] + c[t]) on the support, h[t] elsewhere (Section 3.3, Eq. EF21-2), where c is what the
+    receiver decodes: x itself for fp32 values, fl32(q16(x)) for half-precision values (reading R16; the
+    returned values are then uint16 bit patterns).
     """
     x = operand(g, h)
     idx = np.sort(topk_support(x, int(K))).astype(np.uint32)
     val = x[idx]
     h_new = np.array(h, dtype=np.float32, copy=True)
+    if value_format == "f16":
+        bits = quantise_f16(val)
+        h_new[idx] = np.add(h_new[idx], dequantise_f16(bits), dtype=np.float32)
+        return idx, bits, h_new
+    assert value_format == "f32"
     h_new[idx] = np.add(h_new[idx], val, dtype=np.float32)
     return idx, val, h_new
 
@@ -191,14 +222,31 @@ def cost_units(K_table: np.ndarray, budget_bytes: int, pair_bytes: int, D: int):
     return unit, cap, w
 
 
+def dense_view(E: np.ndarray, K_table: np.ndarray, sizes: Sequence[int], pair_bytes: int, value_bytes: int = 4):
+    """The tables as the allocation sees them with the dense fallback (reading R15): per grid point the error,
+    the pairs charged and the size actually sent.  A point with K * pair_bytes >= n * value_bytes becomes
+    (error 0, ceil(n * value_bytes / pair_bytes) pairs charged, K = n sent)."""
+    E = np.asarray(E, dtype=np.float64)
+    K_table = np.asarray(K_table, dtype=np.int64)
+    n = np.asarray(sizes, dtype=np.int64)[:, None]
+    dense = K_table * int(pair_bytes) >= n * int(value_bytes)
+    dense_pairs = -(-(n * int(value_bytes)) // int(pair_bytes))
+    return (np.where(dense, 0.0, E), np.where(dense, dense_pairs, K_table), np.where(dense, n, K_table))
+
+
 def allocate(E: np.ndarray, K_table: np.ndarray, budget_bytes: int,
-             pair_bytes: int = 8, D: int = 0):
+             pair_bytes: int = 8, D: int = 0, dense_sizes: Sequence[int] = None):
     """Knapsack dynamic programme of Appendix C with readings R5-R8.
 
     Returns (status, j[L], K[L], offsets[L+1]).  On a non-zero status the arrays are empty.
+    `dense_sizes` (the layers' element counts) switches the dense fallback of reading R15 on: the
+    programme then runs on `dense_view` of the tables and K is the size actually sent.
     """
     E = np.asarray(E, dtype=np.float64)
     K_table = np.asarray(K_table, dtype=np.int64)
+    K_sent = K_table
+    if dense_sizes is not None:
+        E, K_table, K_sent = dense_view(E, K_table, dense_sizes, pair_bytes)
     L, J = E.shape
     empty = (np.empty(0, np.int32), np.empty(0, np.uint64), np.empty(0, np.uint64))
     if not np.all(np.isfinite(E)):
@@ -230,7 +278,7 @@ def allocate(E: np.ndarray, K_table: np.ndarray, budget_bytes: int,
     for i in range(L - 1, -1, -1):
         j_out[i] = choice[i, c]
         c -= int(w[i, j_out[i]])
-    K_out = K_table[np.arange(L), j_out].astype(np.uint64)
+    K_out = K_sent[np.arange(L), j_out].astype(np.uint64)
     offsets = np.zeros(L + 1, dtype=np.uint64)
     np.cumsum(K_out, out=offsets[1:])
     return OK, j_out, K_out, offsets
@@ -269,7 +317,8 @@ def server_apply(payloads, u_hats: Sequence[np.ndarray], weights: Sequence[float
         for i in range(L):
             a, b = int(offsets[i]), int(offsets[i + 1])
             where = int(layer_starts[i]) + idx[a:b].astype(np.int64)
-            u[where] = u[where] + val[a:b].astype(np.float32)       # fp32 add; indices of a layer are distinct
+            v = dequantise_f16(val[a:b]) if val.dtype == np.uint16 else val[a:b].astype(np.float32)   # reading R16
+            u[where] = u[where] + v                                  # fp32 add; indices of a layer are distinct
         new_hats.append(u)
     if x_model is None:
         return new_hats, None
@@ -278,6 +327,37 @@ def server_apply(payloads, u_hats: Sequence[np.ndarray], weights: Sequence[float
         acc = acc + np.float64(weights[m]) * new_hats[m].astype(np.float64)
     x_new = (np.asarray(x_model, dtype=np.float32).astype(np.float64) - np.float64(gamma) * acc).astype(np.float32)
     return new_hats, x_new
+
+
+# --------------------------------------------------------------------------- baseline allocators (Section 4.3)
+def uniform_sizes(sizes: Sequence[int], budget_bytes: int, pair_bytes: int = 8) -> np.ndarray:
+    """Kimad without the layer-wise allocation (Section 4.3): one ratio rho = P / d for every layer,
+    K_i = ceil(rho * d_i) clamped to [1, d_i] as for any grid ratio (reading R2); rho is capped at 1."""
+    d = int(sum(int(n) for n in sizes))
+    P = int(budget_bytes) // int(pair_bytes)
+    rho = min(1.0, P / d)
+    return np.array([int(grid_sizes([rho], int(n))[0]) for n in sizes], dtype=np.int64)
+
+
+def whole_model_sizes(g_layers, h_layers, budget_bytes: int, pair_bytes: int = 8) -> np.ndarray:
+    """TopK over the whole model (the paper's "optimal baseline ... with the whole model information"):
+    the P = min(floor(budget / pair_bytes), d) entries of largest magnitude of the concatenation, equal
+    magnitudes by lower position; returned as the number kept in every layer.  Within a layer the kept
+    entries are its own TopK of that size, so its error is `topk_error_profile` at that size."""
+    x = np.concatenate([operand(g, h) for g, h in zip(g_layers, h_layers)])
+    P = min(int(budget_bytes) // int(pair_bytes), x.shape[0])
+    kept = np.zeros(x.shape[0], dtype=bool)
+    kept[magnitude_order(x)[:P]] = True
+    out, pos = [], 0
+    for g in g_layers:
+        out.append(int(kept[pos:pos + len(g)].sum()))
+        pos += len(g)
+    return np.array(out, dtype=np.int64)
+
+
+def errors_at(g_layers, h_layers, K: Sequence[int]) -> np.ndarray:
+    """Per-layer error of TopK at the given sizes (Section 3.2, Eq. norm decomposition), any 0 <= K_i <= d_i."""
+    return np.array([topk_error_profile(operand(g, h), [int(k)])[0] for g, h, k in zip(g_layers, h_layers, K)])
 
 
 def budget_bytes(bandwidth_bits_per_s: float, t: float, t_comp: float, alpha: float = 1.0,
