@@ -81,8 +81,16 @@ typedef struct kimad_config {
     uint32_t max_workgroups;            /* workgroups (= compute units) the streaming pass of the profile may
                                            occupy; 0 = all of the device.  A smaller number leaves units to
                                            other work on the device and changes no result. */
-    uint32_t reserved;                  /* must be 0 */
+    uint32_t value_format;              /* KIMAD_VALUES_F32 (0) or KIMAD_VALUES_F16: how kept values travel */
 } kimad_config_t;
+
+/* Payload values.  F32: the fp32 value x itself.  F16 (Section 2.2 names quantisation beside sparsification):
+ * binary16, round to nearest even, saturated to +-65504, NaN kept; pair_bytes then defaults to 6, val_out holds
+ * uint16 bit patterns, and worker and server both add the decoded value, h[idx] = fl32(h[idx] + fl32(q16(x))):
+ * the two estimator copies stay equal and what the rounding lost stays in g - h for the next round.  The error
+ * table remains that of TopK (the rounding of kept values, below 2^-22 of their energy, is not charged). */
+#define KIMAD_VALUES_F32 0u
+#define KIMAD_VALUES_F16 1u
 
 #define KIMAD_CFG_CLASSIC_PROFILE 1ull  /* profile with two full passes over g, h instead of the sampled
                                            single pass (same results; for comparison and testing) */
@@ -93,6 +101,12 @@ typedef struct kimad_config {
                                            take the band (its cost hardly grows with the row), shorter ones the
                                            whole rows.  Rows that do not fit LDS (more than 4224 cells) and plans
                                            of more than 1024 layers always take whole rows. */
+
+#define KIMAD_CFG_DENSE_FALLBACK 8ull    /* allocation: a layer never costs more than its bare values (4 n bytes).  A grid
+                                           point at or beyond the break-even K * pair_bytes >= 4 n stands for sending
+                                           the layer whole: error 0, K_out = n, charged ceil(4 n / pair_bytes) pairs
+                                           (the levelling off at the uncompressed size in Section 4.2).  offsets_out
+                                           remain the exclusive scan of K_out: size the payload buffers for it. */
 
 /* flags of kimad_compress_ef */
 #define KIMAD_REUSE_PROFILE 1u          /* every K[i] is one of layer i's grid sizes and g, h are unchanged
@@ -182,14 +196,36 @@ int kimad_allocate_static(kimad_plan_t* plan, const double* err_table, uint64_t 
  *   flags    0 (select from scratch: two extra passes over g, h) or KIMAD_REUSE_PROFILE
  *   status_out DEVICE int32[1] */
 int kimad_compress_ef(kimad_plan_t* plan, const uint64_t* K, const uint64_t* offsets,
-                      uint32_t* idx_out, float* val_out, uint64_t capacity_pairs,
-                      uint32_t flags, int32_t* status_out, void* stream);
+                      uint32_t* idx_out, void* val_out /* float[], or uint16[] with KIMAD_VALUES_F16 */,
+                      uint64_t capacity_pairs, uint32_t flags, int32_t* status_out, void* stream);
 
 /* profile -> allocate -> compress_ef(KIMAD_REUSE_PROFILE) on one stream: one worker's step. */
 int kimad_step(kimad_plan_t* plan, uint64_t budget_bytes, double* err_table,
                int32_t* j_out, uint64_t* K_out, uint64_t* offsets_out,
-               uint32_t* idx_out, float* val_out, uint64_t capacity_pairs,
+               uint32_t* idx_out, void* val_out, uint64_t capacity_pairs,
                int32_t* status_out /* DEVICE int32[2]: allocate, compress */, void* stream);
+
+/* Error of TopK at any sizes (Section 3.2, Eq. norm decomposition): err_out[i] = || x_i - TopK_{K[i]}(x_i) ||^2 for
+ * K[i] in 0..n_i (DEVICE uint64[L] in, DEVICE double[L] out), with the accuracy of kimad_profile.  Two passes over
+ * g and h; g and h are not modified.  It overwrites the thresholds of an earlier kimad_profile (a following
+ * KIMAD_REUSE_PROFILE is refused).  This is what prices an allocation that is not on the grid, e.g. the baselines
+ * of the paper's Section 4.3 below. */
+int kimad_error_at(kimad_plan_t* plan, const uint64_t* K, double* err_out, void* stream);
+
+/* Baseline allocators of Section 4.3, HOST arithmetic: "Kimad" without the layer-wise allocation gives every layer
+ * the ratio rho = min(1, P / d), P = floor(budget_bytes / pair_bytes): K_out[i] = min(n_i, max(1, ceil(rho n_i)))
+ * (0 everywhere if P = 0).  *pairs_out (optional) = min(P, d), the size of the whole-model TopK of the same budget.
+ * n, K_out: HOST arrays of L. */
+int kimad_uniform_sizes(const uint64_t* n, uint32_t L, uint64_t budget_bytes, uint32_t pair_bytes, uint64_t* K_out,
+                        uint64_t* pairs_out);
+
+/* Per-layer attribution of a selection made over the whole model (Section 4.3, "the optimal baseline ... with the
+ * whole model information"): idx = the `pairs` ascending positions kept in the flat buffer (the payload of a
+ * one-layer plan over it), layer_start = DEVICE uint64[L+1] element offsets of the layers; counts_out[i] (DEVICE
+ * uint64[L]) = positions inside layer i.  With kimad_error_at on the per-layer plan this gives every layer's share
+ * of the whole-model error. */
+int kimad_payload_layer_counts(const uint32_t* idx, uint64_t pairs, const uint64_t* layer_start, uint32_t L,
+                               uint64_t* counts_out, void* stream);
 
 /* DEVICE diagnostics of the last kimad_profile on the plan, copied to HOST (synchronises the
  * stream): out[0] = table entries whose error bound exceeded the certified tolerance before the
@@ -241,6 +277,8 @@ typedef struct kimad_payload {
     const float* val;         /* DEVICE */
     const uint64_t* offsets;  /* DEVICE uint64[L+1] */
     uint64_t capacity_pairs;  /* entries the idx and val buffers hold */
+    uint32_t value_format;    /* KIMAD_VALUES_F32, or KIMAD_VALUES_F16: val holds uint16 bit patterns */
+    uint32_t pad;             /* 0 */
 } kimad_payload_t;
 int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, const double* weights,
                        uint32_t M, const uint64_t* layer_start, uint32_t L, uint64_t d,

@@ -13,11 +13,15 @@ KIMAD_REUSE_PROFILE = 1
 KIMAD_CFG_CLASSIC_PROFILE = 1
 KIMAD_CFG_FULL_DP = 2
 KIMAD_CFG_BAND_DP = 4
+KIMAD_CFG_DENSE_FALLBACK = 8
+KIMAD_VALUES_F32 = 0
+KIMAD_VALUES_F16 = 1
 KIMAD_MAX_J = 64
 
 EXPORTED_SYMBOLS = [
     "kimad_workspace_bytes", "kimad_plan_create", "kimad_plan_destroy", "kimad_plan_grid_sizes",
     "kimad_profile", "kimad_allocate", "kimad_allocate_static", "kimad_compress_ef", "kimad_step",
+    "kimad_error_at", "kimad_uniform_sizes", "kimad_payload_layer_counts",
     "kimad_profile_diagnostics", "kimad_allocate_diagnostics", "kimad_plan_layer_states", "kimad_plan_set_timing", "kimad_plan_get_timings",
     "kimad_server_apply", "kimad_selftest_wave_primitives", "kimad_budget_bytes", "kimad_strerror", "kimad_version",
 ]
@@ -34,13 +38,14 @@ class _Layer(C.Structure):
 
 
 class _Payload(C.Structure):
-    _fields_ = [("idx", C.c_void_p), ("val", C.c_void_p), ("offsets", C.c_void_p), ("capacity_pairs", C.c_uint64)]
+    _fields_ = [("idx", C.c_void_p), ("val", C.c_void_p), ("offsets", C.c_void_p), ("capacity_pairs", C.c_uint64),
+                ("value_format", C.c_uint32), ("pad", C.c_uint32)]
 
 
 class _Config(C.Structure):
     _fields_ = [("pair_bytes", C.c_uint32), ("cost_units_D", C.c_uint32),
                 ("max_budget_bytes", C.c_uint64), ("flags", C.c_uint64),
-                ("max_workgroups", C.c_uint32), ("reserved", C.c_uint32)]
+                ("max_workgroups", C.c_uint32), ("value_format", C.c_uint32)]
 
 
 _lib = None
@@ -66,6 +71,9 @@ def lib() -> C.CDLL:
     L.kimad_allocate_static.argtypes = [vp, vp, u64, vp, vp, vp, i32p, vp]
     L.kimad_compress_ef.argtypes = [vp, vp, vp, vp, vp, u64, u32, i32p, vp]
     L.kimad_step.argtypes = [vp, u64, vp, vp, vp, vp, vp, vp, u64, i32p, vp]
+    L.kimad_error_at.argtypes = [vp, vp, vp, vp]
+    L.kimad_uniform_sizes.argtypes = [C.POINTER(C.c_uint64), u32, u64, u32, C.POINTER(C.c_uint64), C.POINTER(C.c_uint64)]
+    L.kimad_payload_layer_counts.argtypes = [vp, u64, vp, u32, vp, vp]
     L.kimad_profile_diagnostics.argtypes = [vp, C.POINTER(C.c_uint32), vp]
     L.kimad_allocate_diagnostics.argtypes = [vp, C.POINTER(C.c_uint32), vp]
     L.kimad_plan_layer_states.argtypes = [vp, C.POINTER(C.c_uint32), u32, C.POINTER(C.c_uint32), vp]
@@ -100,8 +108,8 @@ def kimad_version() -> str:
     return lib().kimad_version().decode()
 
 
-def _cfg(pair_bytes=8, D=0, max_budget_bytes=0, cfg_flags=0, max_workgroups=0) -> _Config:
-    return _Config(int(pair_bytes), int(D), int(max_budget_bytes), int(cfg_flags), int(max_workgroups), 0)
+def _cfg(pair_bytes=8, D=0, max_budget_bytes=0, cfg_flags=0, max_workgroups=0, value_format=0) -> _Config:
+    return _Config(int(pair_bytes), int(D), int(max_budget_bytes), int(cfg_flags), int(max_workgroups), int(value_format))
 
 
 def _check(code: int, where: str) -> None:
@@ -121,23 +129,23 @@ def _stream(stream) -> int:
 
 
 def kimad_workspace_bytes(sizes: Sequence[int], J: int, pair_bytes=8, D=0, max_budget_bytes=0,
-                          cfg_flags=0, max_workgroups=0) -> int:
+                          cfg_flags=0, max_workgroups=0, value_format=0) -> int:
     n = (C.c_uint64 * len(sizes))(*[int(s) for s in sizes])
     out = C.c_uint64(0)
-    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups)
+    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups, value_format)
     _check(lib().kimad_workspace_bytes(n, len(sizes), int(J), C.byref(cfg), C.byref(out)), "kimad_workspace_bytes")
     return int(out.value)
 
 
 def kimad_plan_create(g_ptrs: Sequence[int], h_ptrs: Sequence[int], sizes: Sequence[int], ratios: Sequence[float],
                       workspace_ptr: int, workspace_bytes: int, stream=None, pair_bytes=8, D=0,
-                      max_budget_bytes=0, cfg_flags=0, max_workgroups=0) -> int:
+                      max_budget_bytes=0, cfg_flags=0, max_workgroups=0, value_format=0) -> int:
     L = len(sizes)
     layers = (_Layer * L)()
     for i in range(L):
         layers[i].g, layers[i].h, layers[i].n = int(g_ptrs[i]), int(h_ptrs[i]), int(sizes[i])
     r = (C.c_double * len(ratios))(*[float(x) for x in ratios])
-    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups)
+    cfg = _cfg(pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups, value_format)
     plan = C.c_void_p(0)
     _check(lib().kimad_plan_create(layers, L, r, len(ratios), C.byref(cfg), C.c_void_p(int(workspace_ptr)),
                                    int(workspace_bytes), C.c_void_p(_stream(stream)), C.byref(plan)),
@@ -184,6 +192,27 @@ def kimad_step(plan: int, budget_bytes: int, err_table, j_out, K_out, offsets_ou
                             C.c_void_p(_ptr(status_out)), C.c_void_p(_stream(stream))), "kimad_step")
 
 
+def kimad_error_at(plan: int, K, err_out, stream=None) -> None:
+    _check(lib().kimad_error_at(C.c_void_p(plan), C.c_void_p(_ptr(K)), C.c_void_p(_ptr(err_out)),
+                                C.c_void_p(_stream(stream))), "kimad_error_at")
+
+
+def kimad_uniform_sizes(sizes: Sequence[int], budget_bytes: int, pair_bytes: int = 8):
+    """([K_i], pairs of the whole-model TopK of the same budget): host arithmetic of the library."""
+    L = len(sizes)
+    n = (C.c_uint64 * L)(*[int(s) for s in sizes])
+    out = (C.c_uint64 * L)()
+    pairs = C.c_uint64(0)
+    _check(lib().kimad_uniform_sizes(n, L, int(budget_bytes), int(pair_bytes), out, C.byref(pairs)), "kimad_uniform_sizes")
+    return [int(v) for v in out], int(pairs.value)
+
+
+def kimad_payload_layer_counts(idx, pairs: int, layer_start, counts_out, stream=None) -> None:
+    _check(lib().kimad_payload_layer_counts(C.c_void_p(_ptr(idx)), int(pairs), C.c_void_p(_ptr(layer_start)),
+                                            int(layer_start.numel()) - 1, C.c_void_p(_ptr(counts_out)),
+                                            C.c_void_p(_stream(stream))), "kimad_payload_layer_counts")
+
+
 def kimad_server_apply(payloads, u_hats, weights, layer_start, d: int, x=None, gamma: float = 0.0, stream=None,
                        status_out=None):
     """payloads: list of (idx, val, offsets) device tensors, one per worker; u_hats: list of flat fp32
@@ -192,7 +221,10 @@ def kimad_server_apply(payloads, u_hats, weights, layer_start, d: int, x=None, g
     M = len(u_hats)
     def cap(i, v):
         return 0 if i is None or v is None else min(int(i.numel()), int(v.numel()))
-    pl = (_Payload * M)(*[_Payload(_ptr(i), _ptr(v), _ptr(o), cap(i, v)) for (i, v, o) in payloads])
+
+    def fmt(v):                                           # half-precision payloads are torch.float16 tensors
+        return KIMAD_VALUES_F16 if v is not None and v.element_size() == 2 else KIMAD_VALUES_F32
+    pl = (_Payload * M)(*[_Payload(_ptr(i), _ptr(v), _ptr(o), cap(i, v), fmt(v), 0) for (i, v, o) in payloads])
     uh = (C.c_void_p * M)(*[_ptr(u) for u in u_hats])
     w = (C.c_double * M)(*[float(t) for t in weights])
     if status_out is None:
@@ -217,9 +249,9 @@ class Plan:
     ``sizes`` (or lists of per-layer tensors).
     """
 
-    def __init__(self, g, h, sizes: Sequence[int], ratios: Sequence[float], pair_bytes: int = 8, D: int = 0,
+    def __init__(self, g, h, sizes: Sequence[int], ratios: Sequence[float], pair_bytes: int = 0, D: int = 0,
                  max_budget_bytes: int = 0, cfg_flags: int = 0, capacity_pairs: Optional[int] = None,
-                 max_workgroups: int = 0):
+                 max_workgroups: int = 0, value_format: int = 0):
         import torch
         self.torch = torch
         self.sizes = [int(s) for s in sizes]
@@ -236,13 +268,16 @@ class Plan:
             dev = g.device
         self._keep = (g, h)
         self.device = dev
-        nbytes = kimad_workspace_bytes(self.sizes, self.J, pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups)
+        self.value_format = int(value_format)
+        self.pair_bytes = int(pair_bytes) if pair_bytes else (6 if value_format == KIMAD_VALUES_F16 else 8)
+        nbytes = kimad_workspace_bytes(self.sizes, self.J, pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups,
+                                       value_format)
         self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
         base = int(self.workspace.data_ptr())
         self._ws_ptr = (base + 255) // 256 * 256
         self.workspace_bytes = nbytes
         self.handle = kimad_plan_create(g_ptrs, h_ptrs, self.sizes, self.ratios, self._ws_ptr, nbytes,
-                                        None, pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups)
+                                        None, pair_bytes, D, max_budget_bytes, cfg_flags, max_workgroups, value_format)
         d = int(sum(self.sizes))
         self.capacity_pairs = int(capacity_pairs) if capacity_pairs is not None else d
         self.err_table = torch.empty(self.L * self.J, dtype=torch.float64, device=dev)
@@ -251,7 +286,8 @@ class Plan:
         self.offsets = torch.empty(self.L + 1, dtype=torch.int64, device=dev)
         self.status = torch.zeros(2, dtype=torch.int32, device=dev)
         self.idx = torch.empty(self.capacity_pairs, dtype=torch.int32, device=dev)
-        self.val = torch.empty(self.capacity_pairs, dtype=torch.float32, device=dev)
+        self.val = torch.empty(self.capacity_pairs, device=dev,
+                               dtype=torch.float16 if value_format == KIMAD_VALUES_F16 else torch.float32)
 
     def grid_sizes(self) -> np.ndarray:
         out = (C.c_uint64 * (self.L * self.J))()
@@ -279,6 +315,13 @@ class Plan:
         kimad_step(self.handle, budget_bytes, self.err_table, self.j, self.K, self.offsets, self.idx, self.val,
                    self.capacity_pairs, self.status)
         return self.status
+
+    def error_at(self, K, err_out=None):
+        """Per-layer TopK error at the sizes K (device int64[L]); returns a device float64[L]."""
+        if err_out is None:
+            err_out = self.torch.empty(self.L, dtype=self.torch.float64, device=self.device)
+        kimad_error_at(self.handle, K, err_out)
+        return err_out
 
     def diagnostics(self):
         out = (C.c_uint32 * 4)()

@@ -12,7 +12,8 @@ namespace kimad {
 
 struct AllocBuffers {
     const double* E;         // [L][J]
-    const uint32_t* Ktab;    // [L][J]
+    const uint32_t* Ktab;    // [L][J] pairs charged for candidate j (its size, or the dense size where that is cheaper)
+    const uint32_t* Kout;    // [L][J] size sent for candidate j (Ktab itself without the dense fallback)
     uint32_t L, J;
     uint64_t unit;           // cost unit in pairs
     uint32_t cap;            // capacity in units
@@ -32,6 +33,21 @@ constexpr double DP_INF = __builtin_huge_val();
 
 __device__ __forceinline__ uint32_t units_of(uint32_t K, uint64_t unit) {
     return (uint32_t)(((uint64_t)K + unit - 1) / unit);
+}
+
+// Dense fallback: a layer never costs more than its bare values (n * 4 bytes), so a grid point at or beyond the
+// break-even K * pair_bytes >= 4 n stands for sending the layer whole: error 0, K = n, charged
+// ceil(4 n / pair_bytes) pairs (the levelling off at the uncompressed size of the paper's Section 4.2).
+__global__ __launch_bounds__(256) void k_dense_view(const double* E, const uint32_t* Ktab, const LayerDesc* layers, uint32_t L,
+                                                    uint32_t J, uint32_t pair_bytes, double* E_eff, uint32_t* Kcost,
+                                                    uint32_t* Kout) {
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= L * J) return;
+    const uint64_t n = layers[t / J].n, K = Ktab[t];
+    const bool dense = K * pair_bytes >= n * 4ull;
+    E_eff[t] = dense ? 0.0 : E[t];
+    Kcost[t] = dense ? (uint32_t)((n * 4ull + pair_bytes - 1u) / pair_bytes) : (uint32_t)K;
+    Kout[t] = dense ? (uint32_t)n : (uint32_t)K;
 }
 
 // Any Inf/NaN in the table?  Also seeds row 0 of the DP: 0 at cost 0, +inf elsewhere.
@@ -536,7 +552,7 @@ __global__ __launch_bounds__(1024) void k_dp_walk(AllocBuffers ab, const double*
         const uint32_t i = i0b + tid;
         unsigned long long K = 0;
         if (i < ab.L) {
-            K = ab.Ktab[(size_t)i * ab.J + (uint32_t)ab.j_out[i]];
+            K = ab.Kout[(size_t)i * ab.J + (uint32_t)ab.j_out[i]];
             ab.K_out[i] = K;
         }
         unsigned long long tot;
@@ -610,7 +626,7 @@ __global__ __launch_bounds__(1024) void k_dp_final(AllocBuffers ab, const double
         const uint32_t i = i0b + tid;
         unsigned long long K = 0;
         if (i < ab.L) {
-            K = ab.Ktab[(size_t)i * ab.J + (uint32_t)ab.j_out[i]];
+            K = ab.Kout[(size_t)i * ab.J + (uint32_t)ab.j_out[i]];
             ab.K_out[i] = K;
         }
         unsigned long long tot;

@@ -708,7 +708,7 @@ __global__ __launch_bounds__(64) void k_dp_banded(AllocBuffers ab, BandBuffers b
         const uint32_t i = i0 + lane;
         unsigned long long K = 0ull;
         uint32_t j = 0u;
-        if (i < L) { j = s_j[i]; K = ab.Ktab[(size_t)i * J + min(j, J - 1u)]; }
+        if (i < L) { j = s_j[i]; K = ab.Kout[(size_t)i * J + min(j, J - 1u)]; }
         unsigned long long inc = K;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {

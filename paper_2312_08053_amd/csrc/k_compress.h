@@ -11,6 +11,7 @@
 // order and write payload and estimator.
 #pragma once
 #include "common.h"
+#include <hip/hip_fp16.h>
 #include "k_profile.h"   // LDS sort helpers shared with the small-layer profile
 
 namespace kimad {
@@ -52,10 +53,31 @@ struct CompressBuffers {
     const uint64_t* K;
     const uint64_t* offsets;
     uint32_t* idx_out;
-    float* val_out;
+    float* val_out;               // fp32 values, or binary16 bit patterns (uint16) when value_f16 is set
+    uint32_t value_f16;
     uint64_t capacity_pairs;
     int32_t* status;
 };
+
+// A kept value as it travels in half precision: binary16, round to nearest even, saturated to +-65504 (never
+// infinite), NaN kept.  Returns the bit pattern; *decoded gets the fp32 value the receiver will add.
+__device__ __forceinline__ uint16_t value_to_f16(float x, float* decoded) {
+    const float c = x != x ? x : fminf(fmaxf(x, -65504.f), 65504.f);
+    const __half hv = __float2half_rn(c);
+    *decoded = __half2float(hv);
+    return __half_as_ushort(hv);
+}
+
+// Payload slot o gets value x; returns what the estimator must add: x itself, or its half-precision image.
+__device__ __forceinline__ float emit_value(const CompressBuffers& cb, uint64_t o, float x) {
+    if (cb.value_f16) {
+        float dec;
+        reinterpret_cast<uint16_t*>(cb.val_out)[o] = value_to_f16(x, &dec);
+        return dec;
+    }
+    cb.val_out[o] = x;
+    return x;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Per layer: turn K[i] into a selection record using the profile's threshold cache.
@@ -513,8 +535,8 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
         if (keep && pos < room) {
             const uint64_t o = dst + pos;
             cb.idx_out[o] = idx;
-            cb.val_out[o] = x;
-            gstore(h + idx, gload(h + idx) + x);   // the estimator is read here: candidates carry (index, x) only
+            const float add = emit_value(cb, o, x);
+            gstore(h + idx, gload(h + idx) + add);   // the estimator is read here: candidates carry (index, x) only
         }
         out_run += __popc(km);
     };
@@ -584,8 +606,8 @@ __global__ __launch_bounds__(SMALL_THREADS) void k_small_compress(CompressBuffer
             const float g = gload(L.g + idx), hv = gload(L.h + idx);
             const float x = g - hv;
             cb.idx_out[off + pos] = idx;
-            cb.val_out[off + pos] = x;
-            gstore(L.h + idx, hv + x);
+            const float add = emit_value(cb, off + pos, x);
+            gstore(L.h + idx, hv + add);
             ++pos;
         }
     }

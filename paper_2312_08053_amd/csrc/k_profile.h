@@ -138,6 +138,7 @@ __global__ __launch_bounds__(256) void k_scan1(ProfileBuffers pb, const uint32_t
     __shared__ uint32_t su[16];
     __shared__ double sd[16];
     __shared__ uint32_t tbin[MAX_SLOTS];
+    __shared__ double sh_total;              // squares of the whole layer (what K = 0 drops)
     const uint32_t tid = threadIdx.x;
     const uint32_t big = blockIdx.x;
     const uint32_t li = pb.big_layer[big];
@@ -173,6 +174,7 @@ __global__ __launch_bounds__(256) void k_scan1(ProfileBuffers pb, const uint32_t
             above[b] = ctot - run_c;
             run_s += s[k];
         }
+        if (tid == 255u) sh_total = run_s;
     }
     uint8_t* lut = pb.lut1 + (size_t)big * D1_BINS;
     for (uint32_t b = tid; b < D1_BINS; b += 256) lut[b] = (uint8_t)NO_SLOT;
@@ -181,6 +183,7 @@ __global__ __launch_bounds__(256) void k_scan1(ProfileBuffers pb, const uint32_t
     if (tid < J) {
         const uint32_t K = Ktab[(size_t)li * J + tid];
         uint32_t bin = 0xFFFFFFFFu;
+        if (K == 0u) pb.tgt_below[(size_t)li * J + tid] = sh_total;      // nothing kept: everything is dropped
         if (K != 0u && K < L.n) {
             // smallest bin with above[bin] < K (above is non-increasing, above[4095] = 0)
             uint32_t lo = 0, hi = D1_BINS - 1;
@@ -311,7 +314,7 @@ __device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uin
     const uint32_t slot = pb.tgt_slot[t];
     if (slot == NO_SLOT) {                      // K == n (or K == 0): nothing / everything dropped
         if (lane == 0) {
-            if (err_table) err_table[t] = 0.0;
+            if (err_table) err_table[t] = (K == 0u) ? pb.tgt_below[t] : 0.0;
             pb.sel_prefix[t] = 0u;
             pb.sel_above[t] = (K == 0u) ? 0u : L.n;
             pb.sel_amb[t] = 0u;
@@ -484,14 +487,14 @@ __global__ __launch_bounds__(256) void k_hist3p(ProfileBuffers pb, uint32_t ntil
 
 // Exact fallback, scan: one workgroup per pool entry.  With the full key known, the squares of the
 // `unsel` smallest entries of the prefix bin are summed exactly in fp64, smallest first.
-__global__ __launch_bounds__(256) void k_scan3p(ProfileBuffers pb, double* err_table) {
+__global__ __launch_bounds__(256) void k_scan3p(ProfileBuffers pb, double* err_table, uint32_t mark_fresh) {
     __shared__ uint32_t su[16];
     __shared__ double sd[16];
     __shared__ uint32_t cum[D3_BINS];      // entries in lower digits
     __shared__ double sumsq[D3_BINS];      // their squares
     const uint32_t tid = threadIdx.x;
     const uint32_t total = min(pb.diag[2], pb.pool_cap);
-    if (blockIdx.x == 0 && tid == 0 && err_table) *pb.fresh = 1u;      // the profile's last kernel on the caller's stream
+    if (blockIdx.x == 0 && tid == 0 && mark_fresh) *pb.fresh = 1u;     // the grid profile's last kernel on the caller's stream
     for (uint32_t f = blockIdx.x; f < total; f += gridDim.x) {
     __syncthreads();                            // the previous entry's readers are done with the tables
     const uint32_t prefix = pb.pool_prefix[f];
@@ -586,13 +589,13 @@ __device__ __forceinline__ void load_sorted_small(const LayerDesc& L, unsigned l
 constexpr uint32_t SMALL_THREADS = 1024;
 
 __global__ __launch_bounds__(SMALL_THREADS) void k_small_profile(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
-                                                                 double* err_table) {
+                                                                 double* err_table, uint32_t mark_fresh) {
     __shared__ unsigned long long a[SMALL_MAX];       // 64 KB
     __shared__ double loc[SMALL_THREADS];             // per-thread sums, then exclusive suffix sums
     __shared__ double sd[16];
     const uint32_t li = pb.small_layer[blockIdx.x];
     const LayerDesc L = pb.layers[li];
-    if (blockIdx.x == 0 && threadIdx.x == 0) *pb.fresh = 1u;            // (plans without tiled layers have no other profile kernel)
+    if (blockIdx.x == 0 && threadIdx.x == 0 && mark_fresh) *pb.fresh = 1u;   // (plans without tiled layers have no other profile kernel)
     const uint32_t P = next_pow2(L.n < 2 ? 2 : L.n);
     load_sorted_small(L, a, P);
     bitonic_sort_lds<SMALL_THREADS>(a, P);

@@ -4,6 +4,7 @@
 // The decode touches a few percent of the estimators; the model step reads M + 1 dense vectors and
 // writes one: it is the other HBM-bound kernel of the method, 4 (M + 2) bytes per element.
 #pragma once
+#include <hip/hip_fp16.h>
 #include "common.h"
 
 namespace kimad {
@@ -29,7 +30,8 @@ struct ServerArgs {
 __global__ __launch_bounds__(256) void k_server_decode(const uint32_t* __restrict__ idx, const float* __restrict__ val,
                                                        const uint64_t* __restrict__ off, uint64_t capacity_pairs,
                                                        float* u_hat, const uint64_t* __restrict__ layer_start, uint32_t L,
-                                                       uint64_t d, int32_t* status, int32_t err_payload) {
+                                                       uint64_t d, int32_t* status, int32_t err_payload,
+                                                       uint32_t value_f16) {
     __shared__ int bad;
     if (threadIdx.x == 0) bad = 0;
     __syncthreads();
@@ -58,7 +60,9 @@ __global__ __launch_bounds__(256) void k_server_decode(const uint32_t* __restric
         const uint32_t t = idx[p];
         if ((uint64_t)t >= n) { atomicMin(status, err_payload); continue; }
         float* u = u_hat + first + t;
-        gstore(u, gload(u) + val[p]);
+        // half-precision payloads carry binary16 bit patterns: the worker added the decoded value, so does the server
+        const float v = value_f16 ? __half2float(__ushort_as_half(reinterpret_cast<const uint16_t*>(val)[p])) : val[p];
+        gstore(u, gload(u) + v);
     }
 }
 

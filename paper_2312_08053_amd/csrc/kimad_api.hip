@@ -58,6 +58,7 @@ struct Layout {
     // allocation
     uint64_t ncompact;
     uint64_t row0, row1, choice, dp_flags, dl_wall, dl_w, dl_jj, dl_e, dl_n, dl_bad, rows_g;
+    uint64_t dense_E, dense_Kcost, dense_Kout;
     uint64_t band_lo, band_hi, band_info, live_off, live_e, live_before, live_w, live_jj;
     uint64_t rstride = 0;            // cells per stored DP row (LDS-resident recurrence only)
     uint64_t total = 0;
@@ -262,6 +263,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.ncompact = take(16);
     lo.dl_wall = take(4 * LJ); lo.dl_w = take(4 * LJ); lo.dl_jj = take(4 * LJ); lo.dl_e = take(16 * LJ); lo.dl_n = take(4ull * L);
     lo.dl_bad = take(4ull * L);
+    lo.dense_E = take(8 * LJ); lo.dense_Kcost = take(4 * LJ); lo.dense_Kout = take(4 * LJ);
     lo.band_lo = take(4ull * (L + 1)); lo.band_hi = take(4ull * (L + 1));
     lo.band_info = take(64);
     lo.live_off = take(4ull * (L + 1)); lo.live_e = take(8 * LJ); lo.live_before = take(8 * LJ);
@@ -279,7 +281,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
 kimad_config_t normalise(const kimad_config_t* cfg) {
     kimad_config_t c{};
     if (cfg) c = *cfg;
-    if (c.pair_bytes == 0) c.pair_bytes = 8;
+    if (c.pair_bytes == 0) c.pair_bytes = c.value_format == KIMAD_VALUES_F16 ? 6 : 8;
     return c;
 }
 
@@ -293,6 +295,22 @@ __global__ __launch_bounds__(256) void k_zero16(uint4* p, uint64_t n16) {
 
 __global__ __launch_bounds__(64) void k_fill_i32(int32_t* p, uint32_t n, int32_t v) {
     for (uint32_t i = threadIdx.x; i < n; i += 64u) p[i] = v;
+}
+
+// Entries of an ascending index list that fall into each layer's range of the flat buffer: two bisections a layer.
+__global__ __launch_bounds__(256) void k_layer_counts(const uint32_t* __restrict__ idx, uint64_t pairs,
+                                                      const uint64_t* __restrict__ layer_start, uint32_t L, uint64_t* counts) {
+    const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+    if (i >= L) return;
+    auto first_at_or_above = [&](uint64_t pos) {      // number of entries below position pos
+        uint64_t lo = 0, hi = pairs;
+        while (lo < hi) {
+            const uint64_t mid = (lo + hi) >> 1;
+            if ((uint64_t)idx[mid] < pos) lo = mid + 1; else hi = mid;
+        }
+        return lo;
+    };
+    counts[i] = first_at_or_above(layer_start[i + 1]) - first_at_or_above(layer_start[i]);
 }
 
 __global__ __launch_bounds__(256) void k_make_ksel(const uint64_t* K, const kimad::LayerDesc* layers, uint32_t L,
@@ -381,7 +399,9 @@ int zero_range(kimad_plan* p, uint64_t begin, uint64_t end, hipStream_t s) {
 }
 
 // Histogram passes + scans for a target table (the plan's grid, or one K per layer).
-int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, double* err_table, hipStream_t s) {
+// mark_fresh: the targets are the plan's grid, i.e. this is kimad_profile (see ProfileBuffers::fresh).
+int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, double* err_table, hipStream_t s,
+                      uint32_t mark_fresh = 0u) {
     const Layout& lo = p->lo;
     int rc = zero_range(p, lo.zero1_begin, lo.zero1_end, s);
     if (rc) return rc;
@@ -393,7 +413,8 @@ int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, doubl
         if (err_table) {
             // exact last-digit pass for the entries scan 2 could not certify (usually none)
             KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(lo.ntiles), dim3(256), p->pb, lo.ntiles);
-            KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(std::min(lo.pool_cap, POOL_GRID)), dim3(256), p->pb, err_table);
+            KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(std::min(lo.pool_cap, POOL_GRID)), dim3(256), p->pb, err_table,
+                    mark_fresh);
         }
     }
     return KIMAD_OK;
@@ -405,11 +426,14 @@ int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, doubl
 // enqueued on `s`: they then run beside the scans that follow it, which occupy a few dozen
 // workgroups, instead of taking compute units from the persistent grid of the streaming pass.
 // *side gets the stream they were put on (to be joined by the caller).
-int launch_small_profile(kimad_plan* p, double* err_table, hipStream_t s, hipStream_t* side) {
+int launch_small_profile(kimad_plan* p, double* err_table, hipStream_t s, hipStream_t* side,
+                         const uint32_t* ktab_dev = nullptr, uint32_t J = 0) {
     const Layout& lo = p->lo;
     if (!lo.S) return KIMAD_OK;
     *side = fork_side(p, s);
-    KLAUNCH(p, *side, "k_small_profile", k_small_profile, dim3(lo.S), dim3(SMALL_THREADS), p->pb, at<uint32_t>(p, lo.ktab), lo.J, err_table);
+    const uint32_t mark_fresh = ktab_dev ? 0u : 1u;       // other targets than the grid do not make a profile to reuse
+    KLAUNCH(p, *side, "k_small_profile", k_small_profile, dim3(lo.S), dim3(SMALL_THREADS), p->pb,
+            ktab_dev ? ktab_dev : (const uint32_t*)at<uint32_t>(p, lo.ktab), ktab_dev ? J : lo.J, err_table, mark_fresh);
     return KIMAD_OK;
 }
 
@@ -432,7 +456,7 @@ int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, h
             (const uint32_t*)(at<uint32_t>(p, lo.diag) + 3));   // layers marked redo only
     KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(SCAN2_THREADS), p->pb, ktab, lo.J, err_table, CERT_TOL);
     KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(std::min<uint32_t>(lo.ntiles, FALLBACK_GRID)), dim3(256), p->pb, lo.ntiles);
-    KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(std::min(lo.pool_cap, POOL_GRID)), dim3(256), p->pb, err_table);
+    KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(std::min(lo.pool_cap, POOL_GRID)), dim3(256), p->pb, err_table, 1u);
     return KIMAD_OK;
 }
 
@@ -444,6 +468,7 @@ struct AllocScratch {
     uint32_t* flags;                     // 16 bytes
     DpLists dl;
     BandBuffers band;
+    double* dense_E; uint32_t* dense_Kcost; uint32_t* dense_Kout;   // [L][J] each: the tables as the dense fallback sees them
     double* rows_g;                      // [(L + 1)][rstride]
     uint32_t rstride;
     uint64_t max_cells;                  // longest row (capacity + 1) the tables hold
@@ -481,19 +506,31 @@ int enqueue_allocate(kimad_plan* p, const AllocScratch& ws, const double* err_ta
     uint64_t cap = P / unit;
     // Costs above the dearest allocation are unreachable (+inf for ever): cutting the rows there
     // changes no finite cell and so neither the least total nor the smallest cost attaining it.
+    const bool dense = (p->cfg.flags & KIMAD_CFG_DENSE_FALLBACK) != 0;
     uint64_t wmax = 0;
-    for (uint32_t i = 0; i < lo.L; ++i) wmax += ((uint64_t)p->kmax[i] + unit - 1) / unit;
+    for (uint32_t i = 0; i < lo.L; ++i) {
+        uint64_t dearest = p->kmax[i];
+        const uint64_t n = p->hl[i].n, pb = p->cfg.pair_bytes;
+        if (dense && dearest * pb >= n * 4) dearest = (n * 4 + pb - 1) / pb;   // (costs ascend with j up to the break-even, and no grid point costs more than the dense size)
+        wmax += (dearest + unit - 1) / unit;
+    }
     if (cap > wmax) cap = wmax;
     if (cap + 1 > ws.max_cells) return KIMAD_ERR_INVALID_ARG;   // budget beyond what the tables were sized for
 
     AllocBuffers ab;
-    ab.E = err_table; ab.Ktab = at<uint32_t>(p, lo.ktab); ab.L = lo.L; ab.J = lo.J;
+    ab.E = err_table; ab.Ktab = at<uint32_t>(p, lo.ktab); ab.Kout = ab.Ktab; ab.L = lo.L; ab.J = lo.J;
     ab.unit = unit; ab.cap = (uint32_t)cap;
     ab.row0 = ws.row0; ab.row1 = ws.row1;
     ab.choice = ws.choice; ab.cprev = ws.cprev; ab.stride = align_up(cap + 1);   // row pitch: <= align_up(max_cells)
     ab.j_out = j_out; ab.K_out = K_out; ab.offsets_out = offsets_out; ab.status = status_out;
     ab.flags = ws.flags;
     mark(p, s, "begin");
+    if (dense) {
+        KLAUNCH(p, s, "k_dense_view", k_dense_view, dim3((lo.L * lo.J + 255) / 256), dim3(256), err_table, ab.Ktab,
+                (const LayerDesc*)at<LayerDesc>(p, lo.layers), lo.L, lo.J, p->cfg.pair_bytes, ws.dense_E, ws.dense_Kcost,
+                ws.dense_Kout);
+        ab.E = ws.dense_E; ab.Ktab = ws.dense_Kcost; ab.Kout = ws.dense_Kout;
+    }
     const uint32_t cell_blocks = (uint32_t)((cap + 1 + 255) / 256);
     if (cap + 1 <= DP_PAD_WIDE) {
         const DpLists& dl = ws.dl;
@@ -559,7 +596,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
                       kimad_plan_t** plan_out) {
     if (!layers || !ratios || !workspace || !plan_out) return KIMAD_ERR_INVALID_ARG;
     if (L == 0 || L > 65535 || J == 0 || J > KIMAD_MAX_J) return KIMAD_ERR_INVALID_ARG;
-    if (cfg && cfg->reserved) return KIMAD_ERR_INVALID_ARG;
+    if (cfg && cfg->value_format > KIMAD_VALUES_F16) return KIMAD_ERR_INVALID_ARG;
     if (((uintptr_t)workspace) % ALIGN) return KIMAD_ERR_INVALID_ARG;
     for (uint32_t j = 0; j < J; ++j) {
         if (!(ratios[j] > 0.0) || !(ratios[j] <= 1.0)) return KIMAD_ERR_INVALID_ARG;
@@ -696,6 +733,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     cb.fresh = pb.fresh;
     cb.state = pb.state;
     cb.K = nullptr; cb.offsets = nullptr; cb.idx_out = nullptr; cb.val_out = nullptr; cb.capacity_pairs = 0;
+    cb.value_f16 = 0;
     cb.status = nullptr;
     if (lo.S && lo.B) {
         // default priority; without the side stream everything simply runs in order on the caller's stream
@@ -730,7 +768,7 @@ int kimad_profile(kimad_plan_t* p, double* err_table, uint64_t budget_hint_bytes
     int rc;
     if (p->cfg.flags & KIMAD_CFG_CLASSIC_PROFILE) {
         rc = launch_small_profile(p, err_table, s, &ss);
-        if (!rc) rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s);
+        if (!rc) rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s, 1u);
     } else {
         rc = run_fused_profile(p, err_table, budget_hint_bytes / p->cfg.pair_bytes, s, &ss);
     }
@@ -748,6 +786,8 @@ int kimad_allocate(kimad_plan_t* p, const double* err_table, uint64_t budget_byt
     ws.flags = at<uint32_t>(p, lo.dp_flags);
     ws.dl.wall = at<uint32_t>(p, lo.dl_wall); ws.dl.w = at<uint32_t>(p, lo.dl_w); ws.dl.jj = at<uint32_t>(p, lo.dl_jj);
     ws.dl.e = at<double>(p, lo.dl_e); ws.dl.n = at<uint32_t>(p, lo.dl_n); ws.dl.bad = at<uint32_t>(p, lo.dl_bad);
+    ws.dense_E = at<double>(p, lo.dense_E); ws.dense_Kcost = at<uint32_t>(p, lo.dense_Kcost);
+    ws.dense_Kout = at<uint32_t>(p, lo.dense_Kout);
     ws.band.lo = at<uint32_t>(p, lo.band_lo); ws.band.hi = at<uint32_t>(p, lo.band_hi);
     ws.band.info = at<uint32_t>(p, lo.band_info);
     ws.band.live_off = at<uint32_t>(p, lo.live_off); ws.band.live_e = at<double>(p, lo.live_e);
@@ -782,6 +822,8 @@ int kimad_allocate_static(kimad_plan_t* p, const double* err_table, uint64_t bud
     ws.dl.jj = reinterpret_cast<uint32_t*>(take(4 * LJ)); ws.dl.e = reinterpret_cast<double*>(take(16 * LJ));
     ws.dl.n = reinterpret_cast<uint32_t*>(take(4ull * KIMAD_STATIC_MAX_L));
     ws.dl.bad = reinterpret_cast<uint32_t*>(take(4ull * KIMAD_STATIC_MAX_L));
+    ws.dense_E = reinterpret_cast<double*>(take(8 * LJ)); ws.dense_Kcost = reinterpret_cast<uint32_t*>(take(4 * LJ));
+    ws.dense_Kout = reinterpret_cast<uint32_t*>(take(4 * LJ));
     ws.band.lo = reinterpret_cast<uint32_t*>(take(4ull * (KIMAD_STATIC_MAX_L + 1)));
     ws.band.hi = reinterpret_cast<uint32_t*>(take(4ull * (KIMAD_STATIC_MAX_L + 1)));
     ws.band.info = reinterpret_cast<uint32_t*>(take(64));
@@ -798,14 +840,15 @@ int kimad_allocate_static(kimad_plan_t* p, const double* err_table, uint64_t bud
     return rc == KIMAD_ERR_INVALID_ARG ? KIMAD_ERR_STATIC_LIMIT : rc;   // the one argument left to reject: rows too long
 }
 
-int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offsets, uint32_t* idx_out, float* val_out,
+int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offsets, uint32_t* idx_out, void* val_out,
                       uint64_t capacity_pairs, uint32_t flags, int32_t* status_out, void* stream) {
     if (!p || !K || !offsets || !idx_out || !val_out || !status_out) return KIMAD_ERR_INVALID_ARG;
     if (flags & ~KIMAD_REUSE_PROFILE) return KIMAD_ERR_INVALID_ARG;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const Layout& lo = p->lo;
     CompressBuffers cb = p->cb;
-    cb.K = K; cb.offsets = offsets; cb.idx_out = idx_out; cb.val_out = val_out;
+    cb.K = K; cb.offsets = offsets; cb.idx_out = idx_out; cb.val_out = static_cast<float*>(val_out);
+    cb.value_f16 = p->cfg.value_format == KIMAD_VALUES_F16 ? 1u : 0u;
     cb.capacity_pairs = capacity_pairs; cb.status = status_out;
     mark(p, s, "begin");
     if (!(flags & KIMAD_REUSE_PROFILE)) {
@@ -840,7 +883,7 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
 }
 
 int kimad_step(kimad_plan_t* p, uint64_t budget_bytes, double* err_table, int32_t* j_out, uint64_t* K_out,
-               uint64_t* offsets_out, uint32_t* idx_out, float* val_out, uint64_t capacity_pairs, int32_t* status_out,
+               uint64_t* offsets_out, uint32_t* idx_out, void* val_out, uint64_t capacity_pairs, int32_t* status_out,
                void* stream) {
     if (!status_out) return KIMAD_ERR_INVALID_ARG;
     int rc = kimad_profile(p, err_table, budget_bytes, stream);
@@ -947,6 +990,7 @@ int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, con
     bool vec_ok = x && (reinterpret_cast<uintptr_t>(x) % 16 == 0);
     for (uint32_t m = 0; m < M; ++m) {
         if (!payloads[m].idx || !payloads[m].val || !payloads[m].offsets || !u_hat[m]) return KIMAD_ERR_INVALID_ARG;
+        if (payloads[m].value_format > KIMAD_VALUES_F16) return KIMAD_ERR_INVALID_ARG;
         a.u_hat[m] = u_hat[m]; a.w[m] = weights[m];
         vec_ok = vec_ok && (reinterpret_cast<uintptr_t>(u_hat[m]) % 16 == 0);
     }
@@ -958,7 +1002,8 @@ int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, con
     for (uint32_t m = 0; m < M; ++m) {
         hipLaunchKernelGGL(k_server_decode, dim3(1024), dim3(256), 0, s, payloads[m].idx, payloads[m].val,
                            payloads[m].offsets, payloads[m].capacity_pairs, u_hat[m], layer_start, L, d,
-                           status_out + m, (int32_t)KIMAD_ERR_BAD_PAYLOAD);
+                           status_out + m, (int32_t)KIMAD_ERR_BAD_PAYLOAD,
+                           payloads[m].value_format == KIMAD_VALUES_F16 ? 1u : 0u);
         if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP;
     }
     if (x) {
@@ -969,6 +1014,44 @@ int kimad_server_apply(const kimad_payload_t* payloads, float* const* u_hat, con
         if (hipGetLastError() != hipSuccess) return KIMAD_ERR_HIP;
     }
     return KIMAD_OK;
+}
+
+int kimad_error_at(kimad_plan_t* p, const uint64_t* K, double* err_out, void* stream) {
+    if (!p || !K || !err_out) return KIMAD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const Layout& lo = p->lo;
+    mark(p, s, "begin");
+    uint32_t* ksel = at<uint32_t>(p, lo.ksel);
+    KLAUNCH(p, s, "k_make_ksel", k_make_ksel, dim3((lo.L + 255) / 256), dim3(256), K, (const LayerDesc*)p->pb.layers, lo.L, ksel);
+    hipStream_t ss = s;
+    int rc = launch_small_profile(p, err_out, s, &ss, ksel, 1u);
+    if (!rc) rc = run_select_passes(p, ksel, 1, err_out, s, 0u);   // overwrites the grid profile's cache (k_lookup sees it as gone)
+    const int rj = join_side(p, s, ss);
+    return rc ? rc : rj;
+}
+
+int kimad_uniform_sizes(const uint64_t* n, uint32_t L, uint64_t budget_bytes, uint32_t pair_bytes, uint64_t* K_out,
+                        uint64_t* pairs_out) {
+    if (!n || !K_out || L == 0) return KIMAD_ERR_INVALID_ARG;
+    if (pair_bytes == 0) pair_bytes = 8;
+    uint64_t d = 0;
+    for (uint32_t i = 0; i < L; ++i) {
+        if (n[i] == 0 || n[i] > KIMAD_MAX_N) return KIMAD_ERR_INVALID_ARG;
+        d += n[i];
+    }
+    const uint64_t P = budget_bytes / pair_bytes;
+    const double rho = std::min(1.0, (double)P / (double)d);
+    for (uint32_t i = 0; i < L; ++i) K_out[i] = rho > 0.0 ? grid_size_K(rho, n[i]) : 0;
+    if (pairs_out) *pairs_out = std::min(P, d);
+    return KIMAD_OK;
+}
+
+int kimad_payload_layer_counts(const uint32_t* idx, uint64_t pairs, const uint64_t* layer_start, uint32_t L,
+                               uint64_t* counts_out, void* stream) {
+    if (!idx || !layer_start || !counts_out || L == 0) return KIMAD_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(k_layer_counts, dim3((L + 255) / 256), dim3(256), 0, s, idx, pairs, layer_start, L, counts_out);
+    return hipGetLastError() == hipSuccess ? KIMAD_OK : KIMAD_ERR_HIP;
 }
 
 int kimad_selftest_wave_primitives(const uint32_t* in_u32, const double* in_f64, uint32_t* out_u32, double* out_f64,

@@ -1,5 +1,5 @@
-"""The three allocators of the paper's Kimad+ comparison (Section 4.3) through the library, against
-totals assembled from the oracle's pinned functions."""
+"""The three allocators of the paper's Kimad+ comparison (Section 4.3) through the library's C calls, against the
+oracle: sizes bit for bit, every layer's error within 1e-5 relative, and the totals."""
 import numpy as np
 import pytest
 
@@ -10,34 +10,58 @@ from tests import gpu_harness as gh
 pytestmark = pytest.mark.gpu
 
 
+def _close(a, b, rel=1e-5):
+    a, b = np.asarray(a, dtype=np.float64), np.asarray(b, dtype=np.float64)
+    assert np.array_equal(a == 0.0, b == 0.0)
+    assert np.all(np.abs(a - b) <= rel * np.abs(b)), (a, b)
+
+
 @pytest.mark.parametrize("name,kw", [("resnet18", {}), ("gpt2", dict(n_layer=1, vocab=2053))])
 def test_allocator_comparison_matches_the_oracle(name, kw):
     from paper_2312_08053_amd.baselines import allocator_errors
     work = ks.make_workload(name, **kw)
     g, h = gh.to_device(work)
     got = allocator_errors(g, h, work.sizes.tolist(), work.ratios.tolist(), work.budget_bytes,
-                           work.pair_bytes, work.cost_units_D)
+                           work.pair_bytes, work.cost_units_D, per_layer=True)
     gL, hL = gh.oracle_layers(work)
     # Kimad+: the oracle's allocation on the oracle's table
     E, Kt = ko.profile(gL, hL, work.ratios)
     st, j, K, off = ko.allocate(E, Kt, work.budget_bytes, work.pair_bytes, work.cost_units_D)
     assert st == ko.OK and got["kimad_plus"]["status"] == 0
-    want_plus = float(sum(E[i, j[i]] for i in range(work.L)))
+    assert got["kimad_plus"]["layer_pairs"] == [int(k) for k in K]
+    _close(got["kimad_plus"]["layer_errors"], [E[i, j[i]] for i in range(work.L)])
     assert got["kimad_plus"]["pairs"] == int(off[-1])
-    assert abs(got["kimad_plus"]["error"] - want_plus) <= 1e-5 * want_plus
     # uniform ratio: K_i = ceil(rho d_i)
-    P = work.budget_bytes // work.pair_bytes
-    rho = P / work.d
-    Ku = [int(ko.grid_sizes([rho], len(x))[0]) for x in gL]
-    want_uni = float(sum(ko.topk_error_profile(ko.operand(gL[i], hL[i]), [Ku[i]])[0] for i in range(work.L)))
-    assert got["uniform_ratio"]["pairs"] == sum(Ku)
-    assert abs(got["uniform_ratio"]["error"] - want_uni) <= 1e-5 * want_uni
-    # whole model: one TopK over the concatenation
-    xall = ko.operand(work.g, work.h)
-    Kw = int(ko.grid_sizes([rho], work.d)[0])
-    want_whole = float(ko.topk_error_profile(xall, [Kw])[0])
-    assert got["whole_model"]["pairs"] == Kw
-    assert abs(got["whole_model"]["error"] - want_whole) <= 1e-5 * want_whole
-    # what the paper's figure shows: the whole-model TopK is the floor for its own number of pairs
+    Ku = ko.uniform_sizes(work.sizes.tolist(), work.budget_bytes, work.pair_bytes)
+    assert got["uniform_ratio"]["layer_pairs"] == Ku.tolist() and got["uniform_ratio"]["pairs"] == int(Ku.sum())
+    Eu = ko.errors_at(gL, hL, Ku)
+    _close(got["uniform_ratio"]["layer_errors"], Eu)
+    _close(got["uniform_ratio"]["error"], Eu.sum())
+    # whole model: one TopK over the concatenation, attributed to the layers (some may keep nothing)
+    Kw = ko.whole_model_sizes(gL, hL, work.budget_bytes, work.pair_bytes)
+    assert got["whole_model"]["layer_pairs"] == Kw.tolist()
+    assert got["whole_model"]["pairs"] == min(work.budget_bytes // work.pair_bytes, work.d)
+    Ew = ko.errors_at(gL, hL, Kw)
+    _close(got["whole_model"]["layer_errors"], Ew)
+    _close(got["whole_model"]["error"], Ew.sum())
+    # what the paper's figure shows: the whole-model TopK is the floor for its number of pairs
     assert got["whole_model"]["error"] <= got["uniform_ratio"]["error"] * (1 + 1e-9)
+    assert np.array_equal(h.cpu().numpy().view(np.uint32), work.h.view(np.uint32))
+
+
+def test_error_at_any_sizes_including_nothing_and_everything():
+    import torch
+    work = ks.make_workload("gpt2", n_layer=1, vocab=2053, h_factor=0.5)
+    g, h = gh.to_device(work)
+    plan = gh.make_plan(work, g, h)
+    gL, hL = gh.oracle_layers(work)
+    rng = np.random.default_rng(3)
+    sizes = work.sizes.astype(np.int64)
+    for trial in range(3):
+        K = np.array([int(rng.integers(0, n + 1)) for n in sizes], dtype=np.int64)
+        K[rng.integers(0, work.L, size=3)] = 0                      # nothing kept: the whole layer is dropped
+        K[rng.integers(0, work.L, size=2)] = sizes[0]               # clamped to n below
+        K = np.minimum(K, sizes)
+        got = plan.error_at(torch.from_numpy(K).cuda()).cpu().numpy()
+        _close(got, ko.errors_at(gL, hL, K))
     assert np.array_equal(h.cpu().numpy().view(np.uint32), work.h.view(np.uint32))
