@@ -95,6 +95,11 @@ typedef struct kimad_config {
 #define KIMAD_CFG_CLASSIC_PROFILE 1ull  /* profile with two full passes over g, h instead of the sampled
                                            single pass (same results; for comparison and testing) */
 
+#define KIMAD_CFG_SAMPLE_ALWAYS 16ull    /* profile: predict every call from a fresh sampling pass over 1/16 of g, h.  By
+                                           default only a plan's first profile samples; later ones predict from the
+                                           exact histogram the previous one left (gradients of successive rounds are
+                                           distributed alike), which saves the sampling pass.  No result depends on
+                                           the prediction: a layer it misses is recounted by a full pass. */
 #define KIMAD_CFG_FULL_DP 2ull          /* allocation: always run the recurrence over whole rows of cost cells */
 #define KIMAD_CFG_BAND_DP 4ull          /* allocation: always run it inside the band of cells that Lagrangian bounds
                                            leave.  Same results either way; by default rows of 1537 cells or more

@@ -86,11 +86,16 @@ def _fill(sizes: np.ndarray, draw: Callable[[int, int], np.ndarray]) -> np.ndarr
 def _make(name: str, wid: int, shape_list, seed: int, step: int, dist: str, scale_range,
           h_factor: float, ratios: np.ndarray, budget_frac: float, D: int,
           outlier_p: float = 0.0, outlier_mult: float = 1.0,
-          scale_rng_step: Optional[int] = None) -> Workload:
+          scale_rng_step: Optional[int] = None, scales_of_step: Optional[int] = None) -> Workload:
     sizes = _sizes(shape_list)
     L = len(sizes)
     # Scales may be tied to a fixed step so that they persist across a multi-step chain.
-    if scale_rng_step is None:
+    if scales_of_step is not None:
+        # another round of the same model: the per-layer scales of the set drawn for step `scales_of_step` (its
+        # first L draws), fresh values from a stream of their own
+        scale = _log_uniform(np.random.default_rng([seed, wid, scales_of_step]), scale_range[0], scale_range[1], L)
+        rng = np.random.default_rng([seed, wid, step, 1])
+    elif scale_rng_step is None:
         rng = np.random.default_rng([seed, wid, step])
         scale = _log_uniform(rng, scale_range[0], scale_range[1], L)
     else:
@@ -139,6 +144,7 @@ def make_workload(name: str, seed: int = 0, step: int = 0, **kw) -> Workload:
     budget_frac = kw.pop("budget_frac", None)
     D = kw.pop("D", None)
     h_factor = kw.pop("h_factor", None)
+    scales_of_step = kw.pop("scales_of_step", None)       # gpt2 only: a later round with the scales of an earlier set
     if name == "mlp":
         return _make("mlp", 1, _shapes.mlp_shapes(), seed, step, "normal", (-4, -1),
                      0.0 if h_factor is None else h_factor, ratio_grid(-3, 0, 16),
@@ -155,7 +161,7 @@ def make_workload(name: str, seed: int = 0, step: int = 0, **kw) -> Workload:
         return _make("gpt2", 4, _shapes.gpt2_small_shapes(**kw), seed, step, "t2.5", (-5, -2),
                      0.0 if h_factor is None else h_factor, ratio_grid(-5, 0, 64),
                      0.01 if budget_frac is None else budget_frac, 1000 if D is None else D,
-                     outlier_p=1e-3, outlier_mult=100.0)
+                     outlier_p=1e-3, outlier_mult=100.0, scales_of_step=scales_of_step)
     if name == "llama":
         return _make("llama", 5, _shapes.llama_shapes(**kw), seed, step, "t3", (-5, -2),
                      0.0 if h_factor is None else h_factor, ratio_grid(-5, 0, 64),

@@ -14,6 +14,7 @@ KIMAD_CFG_CLASSIC_PROFILE = 1
 KIMAD_CFG_FULL_DP = 2
 KIMAD_CFG_BAND_DP = 4
 KIMAD_CFG_DENSE_FALLBACK = 8
+KIMAD_CFG_SAMPLE_ALWAYS = 16
 KIMAD_VALUES_F32 = 0
 KIMAD_VALUES_F16 = 1
 KIMAD_MAX_J = 64

@@ -144,6 +144,17 @@ __device__ __forceinline__ uint32_t sq_fixed(uint32_t key) {
     uint32_t c = (uint32_t)(sq >> SQ_SHIFT);
     return e == 255u ? (m != 0u ? 1u : 0u) : c;
 }
+// The same square in the units of sq_fixed(), but as the single-pass profile knows it: the low 24
+// bits of the square dropped and replaced by their midpoint.  Every source of a digit-2 table of
+// that profile (the pass itself, the candidate buffer, the recount of a mispredicted layer) uses
+// this form, so the table's bits do not depend on which of them filled a slot.
+__device__ __forceinline__ uint32_t sq_coarse(uint32_t key) {
+    uint32_t e = key >> 23, m = key & 0x7FFFFFu;
+    uint32_t m24 = e ? (m | 0x800000u) : m;
+    uint64_t sq = (uint64_t)m24 * (uint64_t)m24;
+    uint32_t c = ((uint32_t)(sq >> PK_SHIFT) << (PK_SHIFT - SQ_SHIFT)) + (1u << (PK_SHIFT - SQ_SHIFT - 1));
+    return e == 255u ? (m != 0u ? 1u : 0u) : c;
+}
 __device__ __forceinline__ uint64_t sq_exact(uint32_t key) {   // key < 2^19
     return (uint64_t)key * (uint64_t)key;
 }

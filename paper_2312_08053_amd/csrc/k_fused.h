@@ -80,8 +80,15 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void k_sample(ProfileBuffers pb) {
 // ---------------------------------------------------------------------------------------------
 // Prediction: per big layer, the spill bin and the digit-1 bins that get a slot.
 // `budget_pairs` = expected budget of the following allocation in pairs (0 = unknown).
+// `counts` / `gcounts`: per layer and summed digit-1 counts to predict from: the sample of k_sample (scaled to the
+// population through the layer's size), or the exact histogram of the previous profile on this plan (successive
+// gradients of a layer are distributed alike; a layer whose boundary bins moved is recounted like any other
+// misprediction).  `gzero`: 4096 words this launch clears for the totals of the pass that follows.  `fold_zero`:
+// also clear what a profile must find at zero (no separate clearing launch).
 __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
-                                                 unsigned long long budget_pairs) {
+                                                 unsigned long long budget_pairs, const uint32_t* __restrict__ counts,
+                                                 const unsigned long long* __restrict__ gcounts,
+                                                 unsigned long long* gzero, uint32_t fold_zero) {
     __shared__ uint32_t above[D1_BINS];        // sample entries in strictly higher bins
     __shared__ uint32_t bitmap[D1_BINS / 32];
     __shared__ uint32_t su[16];
@@ -94,7 +101,7 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
     // this layer's sample counts are asked for together with the global ones of step (1)
     uint32_t c[16], csum = 0;
     {
-        const uint4* sh4 = reinterpret_cast<const uint4*>(pb.shist + (size_t)big * D1_BINS + tid * 16u);
+        const uint4* sh4 = reinterpret_cast<const uint4*>(counts + (size_t)big * D1_BINS + tid * 16u);
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const uint4 v = sh4[k];
@@ -105,7 +112,7 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
     {
         unsigned long long gc[16], sum = 0;
 #pragma unroll
-        for (int k = 0; k < 16; ++k) { gc[k] = pb.ghist[tid * 16u + k]; sum += gc[k]; }
+        for (int k = 0; k < 16; ++k) { gc[k] = gcounts[tid * 16u + k]; sum += gc[k]; }
         unsigned long long tot;
         const unsigned long long ex = block_exclusive_scan<unsigned long long>(sum, s64, &tot);
         unsigned long long ab = tot - ex - sum;            // entries above this thread's bins
@@ -208,6 +215,14 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
         st.spill_bin = spill_bin; st.nslots_d = ns; st.nslots_t = 0; st.redo = 0;
         st.spill_cnt = 0; st.spill_valid = 0; st.slot_lo = lo_bin; st.pad = 0;
         pb.state[big] = st;
+    }
+    if (big == 0u && gzero)
+        for (uint32_t b = tid; b < D1_BINS; b += 256) gzero[b] = 0ull;
+    if (fold_zero) {
+        for (uint32_t c = tid; c < L.nchunks; c += 256) pb.rec_cnt[L.chunk0 + c] = 0u;    // chunk records start out as "nothing spilled"
+        if (tid == 0) { pb.layer_flag[big] = 0u; pb.cursor[big] = 0u; pb.spill_over[big] = 0u; }
+        if (big == 0u && tid < 4u) pb.diag[tid] = 0u;
+        if (big == 0u && tid == 4u) *pb.fresh = 0u;
     }
 }
 
@@ -586,7 +601,8 @@ __global__ __launch_bounds__(256) void k_reduce_parts(ProfileBuffers pb) {
 //   - its bin already has a slot                          -> nothing
 //   - its bin is in the spilled range                     -> a slot PRE_SLOTS.. filled from the candidates
 //   - neither (prediction missed), or slots run out       -> redo: exact slots, full recount
-__global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J) {
+__global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
+                                                unsigned long long* gacc) {
     __shared__ uint32_t cnt[D1_BINS];
     __shared__ uint32_t above[D1_BINS];
     __shared__ double below[D1_BINS];
@@ -661,6 +677,15 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
         s[k] = sq_to_double(b, ss, cc);
         csum += cc;
         ssum += s[k];
+    }
+    {
+        // the exact histogram stays for the next profile's prediction, with its sum over the layers
+        uint4* hp = reinterpret_cast<uint4*>(pb.hprev + (size_t)big * D1_BINS + tid * 16u);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) hp[k] = make_uint4(c[4 * k], c[4 * k + 1], c[4 * k + 2], c[4 * k + 3]);
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if (c[k]) atomicAdd(&gacc[tid * 16u + k], (unsigned long long)c[k]);
     }
     uint32_t ctot;
     const uint32_t cex = block_exclusive_scan<uint32_t>(csum, su, &ctot);
@@ -794,7 +819,7 @@ __global__ __launch_bounds__(256) void k_hist2c(ProfileBuffers pb) {
             if (slot[t] == NO_SLOT || k0 + (uint32_t)t * SUB >= cnt) continue;
             const uint32_t bin = key[t] >> D1_SHIFT;
             const uint32_t e = slot[t] * D2_BINS + ((key[t] >> D2_SHIFT) & (D2_BINS - 1));
-            const unsigned long long s = bin ? (unsigned long long)sq_fixed(key[t]) : sq_exact(key[t]);
+            const unsigned long long s = bin ? (unsigned long long)sq_coarse(key[t]) : sq_exact(key[t]);
             atomicAdd(&c2[e], 1u);
             if (s) atomicAdd(&s2[e], s);
         }

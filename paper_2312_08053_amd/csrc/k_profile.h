@@ -35,6 +35,9 @@ struct ProfileBuffers {
     uint32_t* sel_amb;            // entries with an equal prefix
     uint32_t* diag;               // [0] uncertified entries, [1] entries fixed by the exact fallback,
                                   // [2] pool entries handed out
+    // exact digit-1 histograms of the last single-pass profile: the prediction of the next one
+    uint32_t* hprev;              // [B][4096]
+    unsigned long long* gprev;    // [2][4096] their sum over the layers, alternating between calls
     uint32_t* fresh;              // 1 while the threshold cache and the candidates describe the current g - h:
                                   // set by the profile's last kernels, cleared by the compression
     // exact fallback for entries whose bound is not tight: last-digit histograms of their prefix bins
@@ -228,8 +231,10 @@ __global__ __launch_bounds__(256) void k_scan1(ProfileBuffers pb, const uint32_t
 // Pass 2: digit-2 histograms (count + squares) of the entries that fall in a boundary bin.
 // Workgroups take tiles in a grid-stride loop.  `gate` (optional) points at a device word that is
 // zero when no layer needs this pass: the single-pass profile launches it as a fallback that
-// normally has nothing to do, with a small grid that leaves after one load.
-__global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb, uint32_t ntiles, const uint32_t* gate) {
+// normally has nothing to do, with a small grid that leaves after one load, and with `coarse` set
+// so that the recount holds the same numbers the pass itself would have put into the slot.
+__global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb, uint32_t ntiles, const uint32_t* gate,
+                                               uint32_t coarse) {
     __shared__ unsigned long long sub[MAX_SLOTS * D2_BINS];   // 64 KB
     __shared__ unsigned long long sub0[D2_BINS];              // exact squares when the slot is bin 0
     __shared__ uint8_t lut[D1_BINS];
@@ -270,7 +275,8 @@ __global__ __launch_bounds__(512) void k_hist2(ProfileBuffers pb, uint32_t ntile
                 if (slot == NO_SLOT) continue;
                 const uint32_t d2 = (key >> D2_SHIFT) & (D2_BINS - 1);
                 if (bin != 0u) {
-                    atomicAdd(&sub[slot * D2_BINS + d2], CNT_ONE | (unsigned long long)sq_fixed(key));
+                    atomicAdd(&sub[slot * D2_BINS + d2],
+                              CNT_ONE | (unsigned long long)(coarse ? sq_coarse(key) : sq_fixed(key)));
                 } else {
                     atomicAdd(&sub[slot * D2_BINS + d2], CNT_ONE);
                     if (key) atomicAdd(&sub0[d2], sq_exact(key));
@@ -305,8 +311,8 @@ __device__ __forceinline__ float prefix_lo(uint32_t prefix) { return __uint_as_f
 // One wave per candidate: every lane holds two digit-2 bins of the candidate's boundary bin.
 // `flagged` and `prefix_out` come back the same in every lane.
 __device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uint32_t* Ktab, uint32_t J,
-                                             double* err_table, double tol, uint32_t big, uint32_t li,
-                                             uint32_t j, bool* flagged, uint32_t* prefix_out) {
+                                             double* err_table, double tol, double widen, uint32_t big,
+                                             uint32_t li, uint32_t j, bool* flagged, uint32_t* prefix_out) {
     const uint32_t lane = lane_id();
     const LayerDesc L = pb.layers[li];
     const size_t t = (size_t)li * J + j;
@@ -370,7 +376,7 @@ __device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uin
     const double base = pb.tgt_below[t] + below2;
     const double E = base + est;
     // single-pass slots hold midpoints of intervals 2^-23 wide (relative): part of the bound
-    if (!pb.state[big].redo) half_gap += E * 1.2e-7;
+    half_gap += E * widen;
     if (lane == 0) {
         if (err_table) err_table[t] = E;
         pb.sel_prefix[t] = prefix;
@@ -388,7 +394,7 @@ __device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uin
 // group gets one pool entry for the exact last-digit pass.
 constexpr uint32_t SCAN2_THREADS = 1024;
 __global__ __launch_bounds__(SCAN2_THREADS) void k_scan2(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
-                                                         double* err_table, double tol) {
+                                                         double* err_table, double tol, double widen) {
     __shared__ uint32_t sh_prefix[KIMAD_MAX_J_CONST];
     __shared__ uint32_t sh_flag[KIMAD_MAX_J_CONST];
     const uint32_t big = blockIdx.x;
@@ -396,7 +402,7 @@ __global__ __launch_bounds__(SCAN2_THREADS) void k_scan2(ProfileBuffers pb, cons
     for (uint32_t jj = threadIdx.x >> 6; jj < KIMAD_MAX_J_CONST; jj += SCAN2_THREADS / 64) {
         bool fl = false;
         uint32_t px = 0xFFFFFFFFu - jj;         // distinct dummy for idle slots and K == n
-        if (jj < J) scan2_target(pb, Ktab, J, err_table, tol, big, li, jj, &fl, &px);
+        if (jj < J) scan2_target(pb, Ktab, J, err_table, tol, widen, big, li, jj, &fl, &px);
         if (lane_id() == 0) { sh_prefix[jj] = px; sh_flag[jj] = fl ? 1u : 0u; }
     }
     __syncthreads();

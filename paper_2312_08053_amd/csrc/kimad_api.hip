@@ -30,6 +30,7 @@ constexpr uint64_t ALIGN = 256;
 // A table entry is accepted from the two histogram levels when its rigorous error bound is
 // below this fraction of the entry; otherwise the exact last-digit pass recomputes it.
 constexpr double CERT_TOL = 4e-6;
+constexpr double SLOT_WIDEN = 1.2e-7;      // half width (relative) of the midpoint form of a single-pass slot's squares
 
 inline uint64_t align_up(uint64_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
@@ -42,7 +43,7 @@ struct Layout {
     uint64_t layers, ktab, tile_layer, chunk_big, big_layer, small_layer;
     // zeroed before every profile
     uint64_t swg_layer, swg_first, state, lutc;
-    uint64_t fresh = 0;
+    uint64_t fresh = 0, hprev = 0, gprev = 0;
     uint64_t zero1_begin, cnt1, sq1, cnt2, sq2, diag, layer_flag, shist, ghist, cursor, spill_over, zero1_end;
     uint64_t cprev = 0;
     uint64_t big_tmp0, parts, wg_part0, big_part0, big_nparts, zero1_mid;
@@ -225,6 +226,8 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.spill_over = take(4ull * (B ? B : 1));
     lo.rec_cnt = take(4ull * (nc ? nc : 1));              // chunk records start out as "nothing spilled"
     lo.zero1_end = off;
+    lo.hprev = take(4ull * B * D1_BINS);
+    lo.gprev = take(2ull * 8ull * D1_BINS);
     lo.pool_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>((uint64_t)B * J, 1), POOL_LIMIT);
     lo.pool_prefix = take(4ull * lo.pool_cap);
     lo.pool_big = take(4ull * lo.pool_cap);
@@ -346,6 +349,10 @@ struct kimad_plan {
     // overlap the short kernels of the tiled path instead of standing in line with them.
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    // The single-pass profile predicts from the exact histogram its previous run on this plan left behind, once
+    // there is one (stream order makes it visible): hist_cur = which of the two total buffers holds it.
+    bool hist_valid = false;
+    uint32_t hist_cur = 0;
     ~kimad_plan() {
         for (hipEvent_t e : ev) (void)hipEventDestroy(e);
         if (ev_fork) (void)hipEventDestroy(ev_fork);
@@ -408,8 +415,8 @@ int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, doubl
     if (lo.B) {
         KLAUNCH(p, s, "k_hist1", k_hist1, dim3(lo.ntiles), dim3(256), p->pb);
         KLAUNCH(p, s, "k_scan1", k_scan1, dim3(lo.B), dim3(256), p->pb, ktab_dev, J);
-        KLAUNCH(p, s, "k_hist2", k_hist2, dim3(lo.ntiles), dim3(512), p->pb, lo.ntiles, (const uint32_t*)nullptr);
-        KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(SCAN2_THREADS), p->pb, ktab_dev, J, err_table, CERT_TOL);
+        KLAUNCH(p, s, "k_hist2", k_hist2, dim3(lo.ntiles), dim3(512), p->pb, lo.ntiles, (const uint32_t*)nullptr, 0u);
+        KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(SCAN2_THREADS), p->pb, ktab_dev, J, err_table, CERT_TOL, 0.0);
         if (err_table) {
             // exact last-digit pass for the entries scan 2 could not certify (usually none)
             KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(lo.ntiles), dim3(256), p->pb, lo.ntiles);
@@ -440,21 +447,38 @@ int launch_small_profile(kimad_plan* p, double* err_table, hipStream_t s, hipStr
 int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, hipStream_t s, hipStream_t* side) {
     const Layout& lo = p->lo;
     const uint32_t* ktab = at<uint32_t>(p, lo.ktab);
-    int rc = zero_range(p, lo.zero1_mid, lo.zero1_end, s);   // the histogram tables are written whole by k_reduce_parts
-    if (rc) return rc;
-    if (!lo.B) return launch_small_profile(p, err_table, s, side);
-    KLAUNCH(p, s, "k_sample", k_sample, dim3(lo.nswg), dim3(SAMPLE_THREADS), p->pb);
-    KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs);
+    if (!lo.B) {
+        int rc0 = zero_range(p, lo.zero1_mid, lo.zero1_end, s);
+        if (rc0) return rc0;
+        return launch_small_profile(p, err_table, s, side);
+    }
+    int rc = KIMAD_OK;
+    unsigned long long* gprev = at<unsigned long long>(p, lo.gprev);
+    unsigned long long* g_last = gprev + (size_t)p->hist_cur * D1_BINS;         // totals of the previous profile
+    unsigned long long* g_next = gprev + (size_t)(p->hist_cur ^ 1u) * D1_BINS;  // where this one's go
+    if (p->hist_valid && !(p->cfg.flags & KIMAD_CFG_SAMPLE_ALWAYS)) {
+        // prediction from the previous profile's exact histogram: no sampling pass, no clearing launch
+        KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs,
+                (const uint32_t*)p->pb.hprev, (const unsigned long long*)g_last, g_next, 1u);
+    } else {
+        rc = zero_range(p, lo.zero1_mid, lo.zero1_end, s);   // the histogram tables are written whole by k_reduce_parts
+        if (rc) return rc;
+        KLAUNCH(p, s, "k_sample", k_sample, dim3(lo.nswg), dim3(SAMPLE_THREADS), p->pb);
+        KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs,
+                (const uint32_t*)p->pb.shist, (const unsigned long long*)p->pb.ghist, g_next, 0u);
+    }
+    p->hist_valid = true;
+    p->hist_cur ^= 1u;
     KLAUNCH(p, s, "k_main", k_main, dim3(p->main_wgs), dim3(FUSED_THREADS), p->pb, p->chunks_per_wg);
     KLAUNCH(p, s, "k_reduce_parts", k_reduce_parts, dim3((LAYER_ENTRIES + REDUCE_ENTRIES - 1) / REDUCE_ENTRIES, lo.B), dim3(256), p->pb);
     rc = launch_small_profile(p, err_table, s, side);
     if (rc) return rc;
-    KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J);
+    KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, g_next);
     KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG), dim3(256), p->pb);
     // fallbacks that normally find nothing to do: small grids
     KLAUNCH(p, s, "k_hist2", k_hist2, dim3(std::min<uint32_t>(lo.ntiles, FALLBACK_GRID)), dim3(512), p->pb, lo.ntiles,
-            (const uint32_t*)(at<uint32_t>(p, lo.diag) + 3));   // layers marked redo only
-    KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(SCAN2_THREADS), p->pb, ktab, lo.J, err_table, CERT_TOL);
+            (const uint32_t*)(at<uint32_t>(p, lo.diag) + 3), 1u);   // layers marked redo only
+    KLAUNCH(p, s, "k_scan2", k_scan2, dim3(lo.B), dim3(SCAN2_THREADS), p->pb, ktab, lo.J, err_table, CERT_TOL, SLOT_WIDEN);
     KLAUNCH(p, s, "k_hist3p", k_hist3p, dim3(std::min<uint32_t>(lo.ntiles, FALLBACK_GRID)), dim3(256), p->pb, lo.ntiles);
     KLAUNCH(p, s, "k_scan3p", k_scan3p, dim3(std::min(lo.pool_cap, POOL_GRID)), dim3(256), p->pb, err_table, 1u);
     return KIMAD_OK;
@@ -691,6 +715,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.sel_prefix = at<uint32_t>(p, lo.sel_prefix); pb.sel_above = at<uint32_t>(p, lo.sel_above);
     pb.sel_amb = at<uint32_t>(p, lo.sel_amb); pb.diag = at<uint32_t>(p, lo.diag);
     pb.fresh = at<uint32_t>(p, lo.fresh);
+    pb.hprev = at<uint32_t>(p, lo.hprev); pb.gprev = at<unsigned long long>(p, lo.gprev);
     pb.layer_flag = at<uint32_t>(p, lo.layer_flag);
     pb.pool_prefix = at<uint32_t>(p, lo.pool_prefix); pb.pool_big = at<uint32_t>(p, lo.pool_big);
     pb.pool_t0 = at<uint32_t>(p, lo.pool_t0); pb.pool_cnt = at<uint32_t>(p, lo.pool_cnt);
@@ -715,6 +740,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
         hipMemsetAsync(p->ws + lo.zero2_begin, 0, lo.zero2_end - lo.zero2_begin, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.band_info, 0, 64, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.fresh, 0, 16, s) != hipSuccess ||
+        hipMemsetAsync(p->ws + lo.gprev, 0, 2ull * 8ull * D1_BINS, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
 
     CompressBuffers& cb = p->cb;

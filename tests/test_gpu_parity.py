@@ -260,3 +260,57 @@ def test_repeated_step_on_the_same_input_is_bit_identical():
             continue
         for a, b, name in zip(first, out, ("E", "K", "idx", "val", "h")):
             assert np.array_equal(a, b), (name, max_wgs)
+
+
+def test_prediction_from_the_previous_rounds_histogram():
+    """From its second profile on, a plan predicts boundary bins and spill range from the exact histogram of the
+    previous profile instead of sampling.  Three rounds with fresh gradients of the same layer scales and a
+    persistent estimator, then a fourth with every layer scaled by 64 (all its boundary bins move by 96): the
+    prediction is then wrong everywhere, which costs time (layers are recounted, or nearly everything lies above
+    the stale spill bin and is kept as a candidate), never correctness.  Every round equals the oracle, and equals,
+    bit for bit and down to the error table, a plan that samples every time: whichever way a digit-2 slot was
+    filled (the pass itself, the candidates, a recount), it holds the same numbers, so no result depends on what
+    the plan predicted, and a resumed run continues the interrupted one exactly."""
+    import torch
+    kw = dict(n_layer=2, vocab=4099)
+    w0 = ks.make_workload("gpt2", **kw)
+    g = torch.from_numpy(w0.g).cuda()
+    h = torch.from_numpy(w0.h).cuda()
+    g2, h2 = g.clone(), h.clone()
+    plan = gh.make_plan(w0, g, h)
+    ref = gh.make_plan(w0, g2, h2, cfg_flags=16)                     # samples on every call
+    h_ref = [x.copy() for x in w0.layer_views(w0.h)]
+    redo = []
+    for t in range(4):
+        wt = w0 if t == 0 else ks.make_workload("gpt2", step=t, scales_of_step=0, **kw)
+        gt = wt.g * np.float32(64.0) if t == 3 else wt.g
+        g.copy_(torch.from_numpy(gt)); g2.copy_(torch.from_numpy(gt))
+        for p_ in (plan, ref):
+            st = p_.step(w0.budget_bytes)
+            torch.cuda.synchronize()
+            assert st.cpu().tolist() == [0, 0], t
+        redo.append((plan.diagnostics()["redo_layers"], ref.diagnostics()["redo_layers"]))
+        total = int(plan.offsets[-1].item())
+        assert torch.equal(plan.err_table.view(torch.int64), ref.err_table.view(torch.int64)), t
+        assert torch.equal(plan.K, ref.K) and torch.equal(plan.idx[:total], ref.idx[:total]), t
+        assert torch.equal(plan.val[:total].view(torch.int32), ref.val[:total].view(torch.int32)), t
+        assert torch.equal(h.view(torch.int32), h2.view(torch.int32)), t
+        gL = [gt[w0.starts[i]:w0.starts[i + 1]] for i in range(w0.L)]
+        E_ref, Kt = ko.profile(gL, h_ref, w0.ratios)
+        E_gpu = plan.err_table.cpu().numpy().reshape(w0.L, -1)
+        gh.assert_table_close(E_gpu, E_ref, Kt, w0.sizes)
+        stt, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, w0.budget_bytes, w0.pair_bytes, w0.cost_units_D)
+        assert stt == ko.OK and np.array_equal(plan.K.cpu().numpy().astype(np.uint64), K_ref)
+        idx = gh.u32(plan.idx)
+        val = plan.val.cpu().numpy().view(np.uint32)
+        h_now = h.cpu().numpy()
+        for i in range(w0.L):
+            li, lv, lh = ko.compress_ef_layer(gL[i], h_ref[i], int(K_ref[i]))
+            a, b = int(off_ref[i]), int(off_ref[i + 1])
+            assert np.array_equal(idx[a:b], li) and np.array_equal(val[a:b], lv.view(np.uint32)), (t, i)
+            assert np.array_equal(h_now[w0.starts[i]:w0.starts[i + 1]].view(np.uint32), lh.view(np.uint32)), (t, i)
+            h_ref[i] = lh
+    spilled = max(st["spill_cnt"] / w0.sizes[st["layer"]] for st in plan.layer_states())
+    print("layers recounted per round (from history, from a sample):", redo, "largest spilled share in round 3:", spilled)
+    assert redo[3][0] > 0 or spilled > 0.5                            # the rescaled round was mispredicted, and absorbed
+    assert redo[1][0] + redo[2][0] <= 2                               # like gradients: the previous histogram serves
