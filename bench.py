@@ -43,6 +43,8 @@ def main() -> int:
                     help="also time the step with tensors below this many elements merged into blocks (Section 6 remark)")
     ap.add_argument("--compare-allocators", action="store_true",
                     help="also report the total error of Kimad+, uniform-ratio Kimad and whole-model TopK (Section 4.3)")
+    ap.add_argument("--single-draw", action="store_true",
+                    help="repeat one gradient draw instead of alternating between two")
     ap.add_argument("--no-overlap", action="store_true",
                     help="skip the measurement of the allocation overlapped with the next round (Section 5 remark)")
     ap.add_argument("--server-workers", type=int, default=4,
@@ -71,6 +73,23 @@ def main() -> int:
     g = torch.from_numpy(work.g).cuda()
     h = torch.from_numpy(work.h).cuda()
     h0 = h.clone()
+    # Successive rounds see different gradients: from its second profile on the plan predicts from the previous
+    # round's histogram, which a repeated input would make a perfect prediction.  The steps alternate between two
+    # draws of the set (same per-layer scales, independent values), copied into g outside the timed intervals.
+    draws = [g.clone()]
+    if not args.single_draw and work.name in ("gpt2", "llama"):
+        kw2 = dict(kw, step=1)
+        if work.name == "gpt2":
+            kw2["scales_of_step"] = 0
+        t0 = time.time()
+        draws.append(torch.from_numpy(ks.make_workload(args.workload, **kw2).g).cuda())
+        t_gen += time.time() - t0
+    nload = [0]
+
+    def load_round():
+        g.copy_(draws[nload[0] % len(draws)])
+        h.copy_(h0)
+        nload[0] += 1
     plan = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes,
                       D=work.cost_units_D, max_budget_bytes=work.budget_bytes,
                       capacity_pairs=work.budget_bytes // work.pair_bytes + 1)
@@ -79,15 +98,18 @@ def main() -> int:
     def one_step():
         plan.step(work.budget_bytes)
 
-    for _ in range(args.warmup):
-        h.copy_(h0)
+    sumKs = []
+    for k in range(max(args.warmup, len(draws))):
+        load_round()
         one_step()
+        if k < len(draws):
+            sumKs.append(int(plan.offsets[-1].item()))
     torch.cuda.synchronize()
     status = plan.status.cpu().tolist()
     if status != [0, 0]:
         print(f"bench.py: step failed with device status {status}", file=sys.stderr)
         return 4
-    sumK = int(plan.offsets[-1].item())
+    sumK = int(round(float(np.mean(sumKs))))
 
     # ---- timed region: K steps, each bracketed by events; h restored between the intervals
     starts = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
@@ -95,7 +117,7 @@ def main() -> int:
     torch.cuda.synchronize()
     w0 = time.perf_counter()
     for k in range(args.steps):
-        h.copy_(h0)
+        load_round()
         starts[k].record(stream)
         one_step()
         ends[k].record(stream)
@@ -109,7 +131,7 @@ def main() -> int:
     def timed_calls(what, reps):
         ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for a, b in ev:
-            h.copy_(h0)
+            load_round()
             if what == "compress":                        # its thresholds come from a profile outside the interval
                 plan.profile(budget_hint_bytes=work.budget_bytes)
             a.record(stream)
@@ -123,7 +145,7 @@ def main() -> int:
         torch.cuda.synchronize()
         return float(np.mean([a.elapsed_time(b) for a, b in ev]))
 
-    h.copy_(h0)
+    load_round()
     plan.profile(budget_hint_bytes=work.budget_bytes)
     plan.allocate(work.budget_bytes)                      # K, offsets stay in the plan's tensors from here on
     torch.cuda.synchronize()
@@ -137,7 +159,7 @@ def main() -> int:
     agg: dict = {}
     order = []
     for k in range(args.steps):
-        h.copy_(h0)
+        load_round()
         one_step()
         for name, t in plan.get_timings():
             if name not in agg:
@@ -186,7 +208,8 @@ def main() -> int:
         "config": {"workload": f"{work.name}-shaped gradient set ({L} tensors, {d} elements)",
                    "ratios": J, "budget_bytes": work.budget_bytes, "cost_units_D": work.cost_units_D,
                    "also_timed_cost_units_D": args.also_D if args.also_D != work.cost_units_D else 0,
-                   "payload_pairs": sumK, "estimator": "zero" if not work.h.any() else "nonzero",
+                   "payload_pairs": sumK, "gradient_draws": len(draws),
+                   "prediction": "previous round's histogram (sampled on a plan's first profile)", "estimator": "zero" if not work.h.any() else "nonzero",
                    "tile_elems": None},
         "wall_ms_per_step": round(wall_ms, 4),
         "min_ms_per_step": round(float(np.min(per_step)), 4),
@@ -230,7 +253,7 @@ def main() -> int:
         o_end = [torch.cuda.Event(enable_timing=True) for _ in range(rounds)]
         for k in range(rounds):
             cur, prev = k % 2, (k + 1) % 2
-            h.copy_(h0)
+            load_round()
             o_start[k].record(stream)
             oplan.profile(errs[cur], budget_hint_bytes=work.budget_bytes)
             ev_prof[cur].record(stream)
@@ -288,14 +311,14 @@ def main() -> int:
         # also_D + 1 cost cells).  Not part of `value`.
         dplan = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes, D=args.also_D,
                            max_budget_bytes=work.budget_bytes, capacity_pairs=work.budget_bytes // work.pair_bytes + 1)
-        for _ in range(max(1, args.warmup)):
-            h.copy_(h0)
+        for _ in range(max(2, args.warmup)):
+            load_round()
             dplan.step(work.budget_bytes)
         torch.cuda.synchronize()
         ds_ = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
         de_ = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
         for k in range(args.steps):
-            h.copy_(h0)
+            load_round()
             ds_[k].record(stream)
             dplan.step(work.budget_bytes)
             de_[k].record(stream)
@@ -313,14 +336,14 @@ def main() -> int:
         bsizes = merge_small(work.sizes.tolist(), args.block_min)
         bplan = kimad.Plan(g, h, bsizes, work.ratios.tolist(), pair_bytes=work.pair_bytes, D=work.cost_units_D,
                            max_budget_bytes=work.budget_bytes, capacity_pairs=work.budget_bytes // work.pair_bytes + 1)
-        for _ in range(max(1, args.warmup)):
-            h.copy_(h0)
+        for _ in range(max(2, args.warmup)):
+            load_round()
             bplan.step(work.budget_bytes)
         torch.cuda.synchronize()
         bs = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
         be = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
         for k in range(args.steps):
-            h.copy_(h0)
+            load_round()
             bs[k].record(stream)
             bplan.step(work.budget_bytes)
             be[k].record(stream)
@@ -333,6 +356,7 @@ def main() -> int:
 
     if args.compare_allocators:
         from paper_2312_08053_amd.baselines import allocator_errors
+        g.copy_(draws[0])
         h.copy_(h0)
         out["allocator_comparison"] = allocator_errors(g, h, work.sizes.tolist(), work.ratios.tolist(), work.budget_bytes,
                                                        work.pair_bytes, work.cost_units_D)

@@ -36,7 +36,9 @@ constexpr uint64_t CNT_ONE = 1ull << 48;      // packed LDS entry: [count:16 | s
 constexpr uint64_t SQ_MASK = CNT_ONE - 1;
 
 // selection modes of a layer in the compaction pass
-enum : uint32_t { SEL_NONE = 0, SEL_PREFIX = 1, SEL_ALL = 2, SEL_CAND = 3 };
+// (SEL_DIRECT: what lies at or above the threshold prefix does not fit the layer's candidate region, or
+// everything is kept: counted, and later written out, straight from g and h.  amb == 0 then means K == n.)
+enum : uint32_t { SEL_NONE = 0, SEL_PREFIX = 1, SEL_ALL = 2, SEL_CAND = 3, SEL_DIRECT = 4 };
 
 struct LayerDesc {
     const float* g;
@@ -51,7 +53,9 @@ struct LayerDesc {
     uint32_t nchunks;
     uint32_t sstride;  // the sampling pre-pass reads one chunk out of every sstride
     uint32_t cblk0;    // first block of 1024 chunks of this layer in the chunk-block list
-    uint64_t tmp0;     // start of this layer's region (n entries) in the candidate buffer
+    uint64_t tmp0;     // start of this layer's region in the candidate buffer
+    uint32_t tmp_cap;  // entries the region holds
+    uint32_t pad;
 };
 
 // Per big layer, state of the fused single-pass profile.
@@ -252,7 +256,12 @@ __device__ __forceinline__ void load_chunk(const LayerDesc& L, uint32_t vbase, Q
 // one per chunk: thousands of waves adding to the same address serialise.  Unused tails of blocks
 // are never referenced: chunk records delimit what is valid.
 constexpr uint32_t SPILL_BLOCK = 512;
-constexpr uint32_t REGION_SLACK = 2048;       // a layer's region holds n + REGION_SLACK entries
+// A layer's region of the candidate buffer holds REGION_PER_CHUNK entries per chunk of the layer plus
+// REGION_SLACK: 5/32 of the layer.  The single-pass profile spills at most about an eighth of a layer into it
+// (each workgroup into the slice that belongs to its chunks), the compaction pass whatever lies at or above a
+// threshold prefix if that fits; whatever does not fit is served from g and h directly.
+constexpr uint32_t REGION_PER_CHUNK = 160;
+constexpr uint32_t REGION_SLACK = 2048;
 struct WaveAlloc { uint32_t base, left; };
 
 __device__ __forceinline__ uint32_t wave_reserve(WaveAlloc& wa, uint32_t total, uint32_t* cursor) {

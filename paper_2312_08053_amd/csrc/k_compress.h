@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
             if (K == 0u) {
                 r.mode = SEL_NONE;
             } else if (K == n) {
-                r.mode = SEL_ALL; r.cap = n + REGION_SLACK; r.above = n;
+                r.mode = SEL_DIRECT; r.above = n;        // everything is kept: no candidates, no threshold
             } else {
                 // the row of grid sizes is read eight entries at a time (a look-up that stops at the
                 // first hit would wait for one load per entry)
@@ -134,19 +134,24 @@ __global__ __launch_bounds__(256) void k_lookup(CompressBuffers cb, int32_t err_
                     r.prefix = cb.sel_prefix[t];
                     r.above = cb.sel_above[t];
                     r.amb = cb.sel_amb[t];
-                    r.cap = n + REGION_SLACK;
+                    r.cap = cb.layers[li].tmp_cap;
                     const LayerState st = cb.state[b];
                     // every entry at or above the threshold prefix already sits in the candidate buffer
                     const bool in_spill = use_candidates && st.spill_valid && st.spill_bin < D1_BINS &&
                                           r.prefix >= (st.spill_bin << D2_BITS);
-                    r.mode = in_spill ? SEL_CAND : SEL_PREFIX;
+                    // The compaction pass writes what lies at or above the threshold prefix into the region; its
+                    // waves reserve space in blocks and leave a block's tail unused when the next chunk does not
+                    // fit (less than the chunk needs, so at most as much again), and every wave its last block
+                    // of a tile.  What would not fit is served from g and h directly.
+                    const uint64_t need = 2ull * ((uint64_t)r.above + r.amb) + 4ull * SPILL_BLOCK * cb.layers[li].ntiles;
+                    r.mode = in_spill ? SEL_CAND : need <= r.cap ? SEL_PREFIX : SEL_DIRECT;
                 }
             }
         }
         cb.sel[b] = r;
         // the classic pass reserves its candidates from zero; the spilled ones keep their records
         if (r.mode != SEL_CAND) cb.cursor[b] = 0u;
-        if (r.mode == SEL_PREFIX || r.mode == SEL_ALL) atomicAdd(&need_pass, 1u);
+        if (r.mode == SEL_PREFIX || r.mode == SEL_DIRECT) atomicAdd(&need_pass, 1u);
     }
     __syncthreads();
     if (tid == 0) *cb.ncompact = bad ? 0u : need_pass;
@@ -206,7 +211,7 @@ __device__ __forceinline__ void compact_tiles(const CompressBuffers& cb, uint32_
                 const uint32_t key = q[u].key[c];
                 if (key == KEY_INVALID) continue;
                 const uint32_t p = key >> D2_SHIFT;
-                const bool all = S.mode == SEL_ALL;
+                const bool all = S.mode == SEL_DIRECT && S.amb == 0u;
                 const bool sure = all || p > S.prefix;
                 const bool amb = !all && p == S.prefix;
                 if (sure || amb) { selm[u] |= 1u << c; ++mine; }
@@ -231,15 +236,17 @@ __device__ __forceinline__ void compact_tiles(const CompressBuffers& cb, uint32_
             for (int d = 32; d > 0; d >>= 1) a += __shfl_xor(a, d, 64);
             total_amb = a;
         }
+        const bool direct = S.mode == SEL_DIRECT;   // counted only: the later kernels read g and h again
         uint32_t start = 0;
-        if (total) start = wave_reserve(wa, total, &cb.cursor[L.big]);
-        // A region of n + REGION_SLACK entries holds every chunk's block; should a reservation still
-        // not fit, drop it, never write out of bounds, and report it.
-        const uint32_t written = start >= S.cap ? 0u : min(total, S.cap - start);
+        if (total && !direct) start = wave_reserve(wa, total, &cb.cursor[L.big]);
+        // k_lookup sends a layer here only if its region holds every chunk's block; should a reservation
+        // still not fit, drop it, never write out of bounds, and report it.
+        const uint32_t written = direct ? total : start >= S.cap ? 0u : min(total, S.cap - start);
         if (written != total && lane == 0) atomicMin(cb.status, err_internal);
         if (lane == 0) { cb.rec_start[chunk] = start; cb.rec_cnt[chunk] = written; cb.rec_amb[chunk] = total_amb; }
         if (total == 0) continue;
         const uint64_t base = S.tmp_base + start;
+        if (!direct) {
 #pragma unroll
         for (int u = 0; u < (int)NQ; ++u) {
             uint32_t pos = rowbase[u];
@@ -254,6 +261,7 @@ __device__ __forceinline__ void compact_tiles(const CompressBuffers& cb, uint32_
                     ++pos;
                 }
             }
+        }
         }
         if (total_amb) {
 #pragma unroll
@@ -364,8 +372,8 @@ __global__ __launch_bounds__(256) void k_resolve(CompressBuffers cb) {
     const SelRec S = cb.sel[b];
     // The histogram is left at zero for the next call, whatever the mode: this kernel is its only reader.
     uint4* h4 = reinterpret_cast<uint4*>(cb.hist3 + (size_t)b * D3_BINS + tid * 16u);
-    if (S.mode != SEL_PREFIX && S.mode != SEL_CAND) {
-        if (tid == 0) { cb.tau[b] = 0u; cb.quota[b] = 0u; }   // SEL_ALL / SEL_NONE: decided by the mode alone
+    if (S.mode != SEL_PREFIX && S.mode != SEL_CAND && !(S.mode == SEL_DIRECT && S.amb != 0u)) {
+        if (tid == 0) { cb.tau[b] = 0u; cb.quota[b] = 0u; }   // everything or nothing: decided by the mode alone
 #pragma unroll
         for (int k = 0; k < 4; ++k) h4[k] = make_uint4(0u, 0u, 0u, 0u);
         return;
@@ -415,6 +423,11 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
     uint32_t cnt = 0, tau = 0, total = 0;
     uint64_t base = 0;
     bool settled = false;
+    // a chunk of a layer that is served from g and h: its 1024 positions take the place of its candidates
+    bool direct = false;
+    const float* gL = nullptr;
+    const float* hL = nullptr;
+    uint32_t vb = 0, mis = 0, nL = 0;
     if (live) {
         // what the chunk index alone addresses goes out together, then the layer's record
         const uint32_t b = chunk_big[chunk];
@@ -432,12 +445,28 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
             base = S.tmp_base + start;
         }
         settled = S.mode == SEL_CAND && cnt == 0u;      // counted by k_hist3c
+        if (S.mode == SEL_DIRECT && amb != 0u) {
+            const LayerDesc L = cb.layers[cb.big_layer[b]];
+            direct = true; cnt = CHUNK; tau = t;
+            gL = L.g; hL = L.h; vb = (chunk - L.chunk0) * CHUNK; mis = L.mis; nL = L.n;
+        }
     }
     uint32_t gt = 0, eq = 0;
-    for (uint32_t k = g.sub; k < cnt; k += SUB) {
-        const uint32_t key = key_of(cb.tmp_x[base + k]);
-        gt += key > tau;
-        eq += key == tau;
+    if (direct) {
+        for (uint32_t k = g.sub; k < CHUNK; k += SUB) {
+            const uint32_t v = vb + k, e = v - mis;
+            if (v >= mis && e < nL) {
+                const uint32_t key = key_of(gload(gL + e) - gload(hL + e));
+                gt += key > tau;
+                eq += key == tau;
+            }
+        }
+    } else {
+        for (uint32_t k = g.sub; k < cnt; k += SUB) {
+            const uint32_t key = key_of(cb.tmp_x[base + k]);
+            gt += key > tau;
+            eq += key == tau;
+        }
     }
 #pragma unroll
     for (int d = SUB / 2; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
@@ -498,6 +527,10 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
     uint64_t src = 0, dst = 0;
     bool filter = false;
     float* h = nullptr;
+    // a chunk of a layer that is served from g and h: its 1024 positions take the place of its candidates
+    bool direct = false;
+    const float* gL = nullptr;
+    uint32_t vb = 0, mis = 0, nL = 0;
     if (chunk < nchunks_total) {
         // everything indexed by the chunk is fetched at once; one more round trip brings the layer's record
         const uint32_t b = chunk_big[chunk];
@@ -520,8 +553,28 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
             src = S.tmp_base + start;
             dst = S.dst;
             room = S.K;                            // payload slots of this layer
+            if (S.mode == SEL_DIRECT) {
+                const LayerDesc L = cb.layers[cb.big_layer[b]];
+                direct = true; cnt = CHUNK; filter = S.amb != 0u;      // amb == 0: every entry is kept
+                gL = L.g; vb = (chunk - L.chunk0) * CHUNK; mis = L.mis; nL = L.n;
+            }
         }
     }
+    // entry k of the chunk: a candidate (index, x), or position k of the chunk itself
+    auto fetch = [&](uint32_t k, uint32_t& idx, float& x) -> bool {
+        if (direct) {
+            const uint32_t v = vb + k, e = v - mis;
+            const bool in = k < cnt && v >= mis && e < nL;
+            const uint32_t at = in ? e : 0u;
+            idx = at;
+            x = gload(gL + at) - gload(h + at);
+            return in;
+        }
+        const bool in = k < cnt;
+        const uint64_t at = in ? src + k : 0ull;
+        idx = cb.tmp_idx[at]; x = cb.tmp_x[at];
+        return in;
+    };
     const uint32_t cmax = wave_max_over_groups(cnt);
     // one round: sixteen candidates of the chunk, in index order
     auto round = [&](bool in, uint32_t idx, float x) {
@@ -545,21 +598,16 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
     constexpr int AHEAD = 4;
     uint32_t pidx[AHEAD];
     float px[AHEAD];
-    // (positions past the chunk's last candidate read entry 0 of the buffer, a valid address, and are dropped)
+    bool pin[AHEAD];
+    // (positions past the chunk's last entry read entry 0 of the buffer or the layer, a valid address, and are dropped)
 #pragma unroll
-    for (int t = 0; t < AHEAD; ++t) {
-        const uint32_t k = (uint32_t)t * SUB + g.sub;
-        const uint64_t at = k < cnt ? src + k : 0ull;
-        pidx[t] = cb.tmp_idx[at]; px[t] = cb.tmp_x[at];
-    }
+    for (int t = 0; t < AHEAD; ++t) pin[t] = fetch((uint32_t)t * SUB + g.sub, pidx[t], px[t]);
 #pragma unroll
     for (int t = 0; t < AHEAD; ++t)
-        if ((uint32_t)t * SUB < cmax) round((uint32_t)t * SUB + g.sub < cnt, pidx[t], px[t]);
+        if ((uint32_t)t * SUB < cmax) round(pin[t], pidx[t], px[t]);
     for (uint32_t k0 = AHEAD * SUB; k0 < cmax; k0 += SUB) {
-        const uint32_t k = k0 + g.sub;
-        const bool in = k < cnt;
         uint32_t idx = 0; float x = 0.f;
-        if (in) { idx = cb.tmp_idx[src + k]; x = cb.tmp_x[src + k]; }
+        const bool in = fetch(k0 + g.sub, idx, x);
         round(in, idx, x);
     }
 }

@@ -318,7 +318,10 @@ __device__ __forceinline__ void main_count(const MainCtx& cx, const float (&x)[N
 // for the next chunk's loads a wait for the store acknowledgements as well, and a returning global
 // atomic per reservation serialises thousands of waves on one address.  So:
 //   * the workgroup owns the slice of the layer's candidate region that corresponds to its chunks
-//     (one entry of space per element: it can never overflow), cut into blocks of 128 entries;
+//     (REGION_PER_CHUNK entries of space per chunk, a quarter more than the largest share of a layer
+//     that k_predict lets spill), cut into blocks of 128 entries; a slice that still runs out marks
+//     the layer's spill as incomplete (spill_over) and the layer is served by the passes that read
+//     g and h instead, like any other misprediction;
 //   * a wave takes blocks from an LDS cursor, fills its current block in an LDS window, and writes
 //     the window out with coalesced stores only when the next chunk does not fit;
 //   * chunk records wait in LDS until that flush.  A chunk's candidates are always contiguous.
@@ -328,8 +331,9 @@ struct WaveSpill {
     uint2* win;           // LDS window of the current block: (index, bits of x)
     uint32_t* pend;       // LDS: PEND x (chunk, start, count)
     uint32_t* lds_cursor; // blocks handed out in this workgroup's slice
-    uint64_t slice0;      // first entry of the slice in the candidate buffer
-    uint32_t slice_rel;   // the same, relative to the layer's region (chunk records are region-relative)
+    uint32_t* over;       // the layer's spill_over flag
+    uint32_t slice_blocks;// blocks the slice holds
+    uint32_t slice_rel;   // first entry of the slice, relative to the layer's region (chunk records are region-relative)
     uint32_t blk;         // region-relative start of the current block (valid if have_blk)
     uint32_t fill;        // entries in the window
     uint32_t flushed;     // of which already written
@@ -358,11 +362,15 @@ __device__ __forceinline__ void spill_flush(const ProfileBuffers& pb, WaveSpill&
     wave_sync_lds();
 }
 
-// take `nb` consecutive blocks of the slice; returns the region-relative entry index of the first
-__device__ __forceinline__ uint32_t spill_take_blocks(WaveSpill& ws, uint32_t nb) {
+// take `nb` consecutive blocks of the slice; returns the region-relative entry index of the first.
+// *ok is false when the slice has no room left for them: nothing may be written then, and the layer
+// is marked.
+__device__ __forceinline__ uint32_t spill_take_blocks(WaveSpill& ws, uint32_t nb, bool* ok) {
     uint32_t b = 0;
     if (lane_id() == 0) b = atomicAdd(ws.lds_cursor, nb);
     b = __builtin_amdgcn_readfirstlane(b);
+    *ok = b + nb <= ws.slice_blocks;            // (the cursor grows by at most 8 blocks per chunk: no wrap)
+    if (!*ok && lane_id() == 0) *ws.over = 1u;
     return ws.slice_rel + b * STAGE;
 }
 
@@ -392,8 +400,10 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
         if (!ws.have_blk || ws.fill + total > STAGE || ws.npend == PEND) {
             spill_flush(pb, ws, L.tmp0);
             if (!ws.have_blk || ws.fill + total > STAGE) {
-                ws.blk = spill_take_blocks(ws, 1u);
-                ws.fill = 0; ws.flushed = 0; ws.have_blk = true;
+                bool ok;
+                ws.blk = spill_take_blocks(ws, 1u, &ok);
+                ws.fill = 0; ws.flushed = 0; ws.have_blk = ok;
+                if (!ok) return;                 // the chunk's record stays "nothing spilled"; the layer is marked
             }
         }
         const uint32_t at = ws.fill;
@@ -425,7 +435,9 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
         // a dense chunk: its own run of blocks, written through the window in rounds
         spill_flush(pb, ws, L.tmp0);
         ws.have_blk = false;
-        const uint32_t start = spill_take_blocks(ws, (total + STAGE - 1) / STAGE);
+        bool ok;
+        const uint32_t start = spill_take_blocks(ws, (total + STAGE - 1) / STAGE, &ok);
+        if (!ok) return;
         const uint64_t base = L.tmp0 + start;
         for (uint32_t r0 = 0; r0 < total; r0 += STAGE) {
 #pragma unroll
@@ -487,7 +499,9 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         WaveSpill ws;
         ws.win = stage + wave * STAGE;
         ws.pend = pend + wave * PEND * 3; ws.lds_cursor = &lds_cursor;
-        ws.slice_rel = (cur - L.chunk0) * CHUNK; ws.slice0 = L.tmp0 + ws.slice_rel;
+        ws.over = pb.spill_over + big;
+        ws.slice_rel = (cur - L.chunk0) * REGION_PER_CHUNK;
+        ws.slice_blocks = (seg_end - cur) * REGION_PER_CHUNK / STAGE;
         ws.blk = 0; ws.fill = 0; ws.flushed = 0; ws.npend = 0; ws.have_blk = false;
 
         // (Fetching the wave's next chunk while the current one is worked on was tried, with the

@@ -397,6 +397,9 @@ __global__ __launch_bounds__(SCAN2_THREADS) void k_scan2(ProfileBuffers pb, cons
                                                          double* err_table, double tol, double widen) {
     __shared__ uint32_t sh_prefix[KIMAD_MAX_J_CONST];
     __shared__ uint32_t sh_flag[KIMAD_MAX_J_CONST];
+    __shared__ uint32_t sh_pool[KIMAD_MAX_J_CONST];     // pool entries this layer has taken
+    __shared__ uint32_t sh_npool;
+    if (threadIdx.x == 0) sh_npool = 0u;
     const uint32_t big = blockIdx.x;
     const uint32_t li = pb.big_layer[big];
     for (uint32_t jj = threadIdx.x >> 6; jj < KIMAD_MAX_J_CONST; jj += SCAN2_THREADS / 64) {
@@ -406,36 +409,43 @@ __global__ __launch_bounds__(SCAN2_THREADS) void k_scan2(ProfileBuffers pb, cons
         if (lane_id() == 0) { sh_prefix[jj] = px; sh_flag[jj] = fl ? 1u : 0u; }
     }
     __syncthreads();
-    if (threadIdx.x >= 64) return;
-    const uint32_t j = threadIdx.x;
-    const bool flagged = sh_flag[j] != 0u;
-    const uint32_t prefix = sh_prefix[j];
-    const uint32_t prev = __shfl_up(prefix, 1, 64);
-    const bool head = j == 0 || prev != prefix;
-    const uint64_t heads = ballot(head), flags = ballot(flagged);
-    if (flags == 0) return;
-    // run of this lane: from its head (highest head bit at or below j) to the lane before the next head
-    const uint64_t below_or_eq = heads & (~0ull >> (63 - j));
-    const uint32_t h0 = 63u - (uint32_t)__clzll((long long)below_or_eq);
-    const uint64_t after = heads & ~((2ull << j) - 1ull);
-    const uint32_t h1 = after ? (uint32_t)__ffsll((long long)after) - 1u : 64u;   // exclusive end
-    const uint64_t run_mask = (h1 >= 64 ? ~0ull : ((1ull << h1) - 1ull)) & ~((1ull << h0) - 1ull);
-    const bool run_flagged = (flags & run_mask) != 0;
-    if (flagged) atomicAdd(&pb.diag[0], 1u);
-    if (head && run_flagged && j < J) {
-        const uint32_t f = atomicAdd(&pb.diag[2], 1u);
-        if (f < pb.pool_cap) {
-            pb.pool_prefix[f] = prefix;
-            pb.pool_big[f] = big;
-            pb.pool_t0[f] = li * J + j;
-            pb.pool_cnt[f] = h1 - h0;
-            pb.layer_flag[big] = 1u;
-        } else {
-            // pool full: no loose value leaves this call
-            for (uint32_t k = h0; k < h1 && k < J; ++k)
-                err_table[(size_t)li * J + k] = __longlong_as_double(0x7FF8000000000000ll);
+    if (threadIdx.x < 64) {
+        const uint32_t j = threadIdx.x;
+        const bool flagged = sh_flag[j] != 0u;
+        const uint32_t prefix = sh_prefix[j];
+        const uint32_t prev = __shfl_up(prefix, 1, 64);
+        const bool head = j == 0 || prev != prefix;
+        const uint64_t heads = ballot(head), flags = ballot(flagged);
+        // run of this lane: from its head (highest head bit at or below j) to the lane before the next head
+        const uint64_t below_or_eq = heads & (~0ull >> (63 - j));
+        const uint32_t h0 = 63u - (uint32_t)__clzll((long long)below_or_eq);
+        const uint64_t after = heads & ~((2ull << j) - 1ull);
+        const uint32_t h1 = after ? (uint32_t)__ffsll((long long)after) - 1u : 64u;   // exclusive end
+        const uint64_t run_mask = (h1 >= 64 ? ~0ull : ((1ull << h1) - 1ull)) & ~((1ull << h0) - 1ull);
+        const bool run_flagged = (flags & run_mask) != 0;
+        if (flagged) atomicAdd(&pb.diag[0], 1u);
+        if (head && run_flagged && j < J) {
+            const uint32_t f = atomicAdd(&pb.diag[2], 1u);
+            if (f < pb.pool_cap) {
+                pb.pool_prefix[f] = prefix;
+                pb.pool_big[f] = big;
+                pb.pool_t0[f] = li * J + j;
+                pb.pool_cnt[f] = h1 - h0;
+                pb.layer_flag[big] = 1u;
+                sh_pool[atomicAdd(&sh_npool, 1u)] = f;
+            } else {
+                // pool full: no loose value leaves this call
+                for (uint32_t k = h0; k < h1 && k < J; ++k)
+                    err_table[(size_t)li * J + k] = __longlong_as_double(0x7FF8000000000000ll);
+            }
         }
     }
+    __syncthreads();
+    // The pool's histograms share their memory with the streaming pass's histogram parts (dead by now): an
+    // entry is cleared here, by the workgroup that takes it, before the exact pass counts into it.
+    static_assert(D3_BINS == 4u * SCAN2_THREADS, "one 16-byte store per thread clears an entry");
+    for (uint32_t k = 0; k < sh_npool; ++k)
+        reinterpret_cast<uint4*>(pb.pool_hist + (size_t)sh_pool[k] * D3_BINS)[threadIdx.x] = make_uint4(0u, 0u, 0u, 0u);
 }
 
 // Exact fallback, pass: last-digit histogram of every pooled prefix bin.  One workgroup per tile;
@@ -513,7 +523,6 @@ __global__ __launch_bounds__(256) void k_scan3p(ProfileBuffers pb, double* err_t
     for (int k = 0; k < 16; ++k) {
         const uint32_t d3 = tid * 16u + k;
         c[k] = h[d3];
-        pb.pool_hist[(size_t)f * D3_BINS + d3] = 0u;       // leave the pool clean for the next call
         const double v = (double)__uint_as_float((prefix << D2_SHIFT) | d3);
         s[k] = (double)c[k] * v * v;
         csum += c[k];

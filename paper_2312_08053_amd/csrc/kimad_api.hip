@@ -72,6 +72,7 @@ struct HostLayer {
     uint32_t sstride, sgroups, swg0, nswg;   // sampling: stride in chunks, sampled groups, workgroups
     uint32_t cblk0, ncblk;                   // blocks of 1024 chunks
     uint64_t tmp0;                           // region start in the candidate buffer
+    uint32_t tmp_cap;                        // entries of the region
 };
 
 uint32_t pick_tile_elems(uint64_t d_big) {
@@ -166,7 +167,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
             h.sgroups = (h.nchunks + h.sstride - 1) / h.sstride;
             h.swg0 = nsw; h.nswg = (h.sgroups + SAMPLE_GROUPS_PER_WG - 1) / SAMPLE_GROUPS_PER_WG;
             nsw += h.nswg;
-            h.tmp0 = tmp_run; tmp_run += n[i] + REGION_SLACK;
+            h.tmp0 = tmp_run; h.tmp_cap = h.nchunks * REGION_PER_CHUNK + REGION_SLACK; tmp_run += h.tmp_cap;
             h.cblk0 = ncblk; h.ncblk = (h.nchunks + CBLOCK - 1) / CBLOCK; ncblk += h.ncblk;
         }
         (*hl)[i] = h;
@@ -186,7 +187,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     // (the winners' table of the allocation is L rows of dp_cells bytes: with the exact cost axis and no
     // budget limit that is L * d bytes, 18 GB for a 124M-element model: refused rather than asked of the caller)
     if ((uint64_t)L * align_up(lo.dp_cells) > (4ull << 30)) return KIMAD_ERR_TABLES_TOO_LARGE;
-    lo.tmp_cap = tmp_run;                                 // one region of n + REGION_SLACK entries per tiled layer
+    lo.tmp_cap = tmp_run;                                 // one region per tiled layer
     // a workgroup of the streaming pass writes its histograms out whole (140 KB a part): on small sets fewer
     // workgroups with at least 16 chunks each do less of that than one per compute unit would
     lo.main_wgs = std::max<uint32_t>(1, std::min<uint32_t>(stream_workgroups(cfg), (lo.nchunks + 15) / 16));
@@ -205,7 +206,11 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.wg_part0 = take(4ull * lo.main_wgs);
     lo.big_part0 = take(4ull * (B ? B : 1));
     lo.big_nparts = take(4ull * (B ? B : 1));
-    lo.parts = take(8ull * PART_STRIDE * (lo.nparts ? lo.nparts : 1));
+    // (the exact pass's pool of last-digit histograms lives in the same memory: the parts are dead once
+    // k_reduce_parts has run, and a pool entry is cleared by the workgroup that takes it)
+    lo.pool_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>((uint64_t)B * J, 1), POOL_LIMIT);
+    lo.parts = take(std::max<uint64_t>(8ull * PART_STRIDE * (lo.nparts ? lo.nparts : 1), 4ull * lo.pool_cap * D3_BINS));
+    lo.pool_hist = lo.parts;
     lo.small_layer = take(4ull * (S ? S : 1));
     lo.swg_layer = take(4ull * (nsw ? nsw : 1));
     lo.swg_first = take(4ull * (nsw ? nsw : 1));
@@ -228,12 +233,10 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.zero1_end = off;
     lo.hprev = take(4ull * B * D1_BINS);
     lo.gprev = take(2ull * 8ull * D1_BINS);
-    lo.pool_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>((uint64_t)B * J, 1), POOL_LIMIT);
     lo.pool_prefix = take(4ull * lo.pool_cap);
     lo.pool_big = take(4ull * lo.pool_cap);
     lo.pool_t0 = take(4ull * lo.pool_cap);
     lo.pool_cnt = take(4ull * lo.pool_cap);
-    lo.pool_hist = take(4ull * lo.pool_cap * D3_BINS);   // zero between calls: cleared by its reader
     lo.tgt_unsel = take(4 * LJ);
     lo.tgt_base = take(8 * LJ);
     lo.lut1 = take(1ull * B * D1_BINS);
@@ -666,7 +669,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
             for (uint32_t t = 0; t < h.ntiles; ++t) tile_layer[h.tile0 + t] = i;
             for (uint32_t c = 0; c < h.nchunks; ++c) chunk_big[h.chunk0 + c] = (uint32_t)h.big;
             d.tile0 = h.tile0; d.ntiles = h.ntiles; d.chunk0 = h.chunk0; d.nchunks = h.nchunks;
-            d.sstride = h.sstride; d.cblk0 = h.cblk0; d.tmp0 = h.tmp0;
+            d.sstride = h.sstride; d.cblk0 = h.cblk0; d.tmp0 = h.tmp0; d.tmp_cap = h.tmp_cap; d.pad = 0;
             for (uint32_t k = 0; k < h.ncblk; ++k) cblk_big[h.cblk0 + k] = (uint32_t)h.big;
             for (uint32_t w = 0; w < h.nswg; ++w) {
                 swg_layer[h.swg0 + w] = i;
@@ -676,7 +679,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
             big_tmp0[h.big] = h.tmp0;
         } else {
             d.tile0 = d.ntiles = d.chunk0 = d.nchunks = 0;
-            d.sstride = 1; d.cblk0 = 0; d.tmp0 = 0;
+            d.sstride = 1; d.cblk0 = 0; d.tmp0 = 0; d.tmp_cap = 0; d.pad = 0;
             small_layer[si++] = i;
         }
         for (uint32_t j = 0; j < J; ++j) p->ktab[(size_t)i * J + j] = grid_size_K(ratios[j], h.n);
@@ -733,10 +736,8 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.tmp_idx = at<uint32_t>(p, lo.tmp_idx); pb.tmp_x = at<float>(p, lo.tmp_x);
     p->main_wgs = lo.main_wgs;
     p->chunks_per_wg = lo.chunks_per_wg;
-    // the pool histograms must start at zero; afterwards k_scan3p clears what it has read.
     // Layer states start as "nothing spilled, nothing cached".
     if (hipMemsetAsync(p->ws + lo.state, 0, sizeof(LayerState) * (uint64_t)(lo.B ? lo.B : 1), s) != hipSuccess ||
-        hipMemsetAsync(p->ws + lo.pool_hist, 0, 4ull * lo.pool_cap * D3_BINS, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.zero2_begin, 0, lo.zero2_end - lo.zero2_begin, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.band_info, 0, 64, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.fresh, 0, 16, s) != hipSuccess ||
@@ -938,6 +939,15 @@ int kimad_allocate_diagnostics(kimad_plan_t* p, uint32_t* out4, void* stream) {
 }
 
 #ifdef KIMAD_STAMPS
+int kimad_debug_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t* cfg, uint64_t* out) {
+    Layout lo;
+    int rc = make_layout(n, L, J, *cfg, lo, nullptr);
+    if (rc) return rc;
+    out[0] = lo.parts; out[1] = lo.small_layer; out[2] = lo.state; out[3] = lo.cnt1; out[4] = lo.rec_cnt; out[5] = lo.hprev;
+    out[6] = lo.pool_prefix; out[7] = lo.sel; out[8] = lo.hist3; out[9] = lo.rec_start; out[10] = lo.tmp_idx;
+    out[11] = lo.tmp_x; out[12] = lo.row0; out[13] = lo.total;
+    return 0;
+}
 int kimad_debug_band_info(kimad_plan_t* p, uint32_t* out16) {
     if (hipMemcpy(out16, p->ws + p->lo.band_info, 64, hipMemcpyDeviceToHost) != hipSuccess) return KIMAD_ERR_HIP;
     return KIMAD_OK;

@@ -89,3 +89,14 @@ def test_product_package_never_imports_the_oracle():
                 for line in open(os.path.join(dirpath, f)):
                     if "oracle" in line:
                         assert "import" not in line and "#include" not in line, (dirpath, f, line)
+
+
+def test_workspace_is_a_quarter_of_the_gradient_buffers_at_most():
+    """The candidate region of a tiled layer holds 5/32 of it, not all of it: a plan's workspace stays below a
+    quarter of the bytes of g and h on the two benchmark shapes (host arithmetic only)."""
+    import kimad_synth.shapes as shapes
+    import paper_2312_08053_amd as kimad
+    for sizes in (shapes.gpt2_small_shapes(), shapes.llama_shapes()):
+        n = [shapes.numel(s) for s in sizes]
+        ws = kimad.kimad_workspace_bytes(n, 64, D=1000)
+        assert ws <= 0.25 * 8 * sum(n), (ws, 8 * sum(n))
