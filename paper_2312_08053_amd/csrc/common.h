@@ -257,10 +257,10 @@ __device__ __forceinline__ void load_chunk(const LayerDesc& L, uint32_t vbase, Q
 // are never referenced: chunk records delimit what is valid.
 constexpr uint32_t SPILL_BLOCK = 512;
 // A layer's region of the candidate buffer holds REGION_PER_CHUNK entries per chunk of the layer plus
-// REGION_SLACK: 5/32 of the layer.  The single-pass profile spills at most about an eighth of a layer into it
+// REGION_SLACK: 21/128 of the layer.  The single-pass profile spills at most an eighth of a layer into it
 // (each workgroup into the slice that belongs to its chunks), the compaction pass whatever lies at or above a
 // threshold prefix if that fits; whatever does not fit is served from g and h directly.
-constexpr uint32_t REGION_PER_CHUNK = 160;
+constexpr uint32_t REGION_PER_CHUNK = 168;        // a multiple of the 8 entries space is handed out in
 constexpr uint32_t REGION_SLACK = 2048;
 struct WaveAlloc { uint32_t base, left; };
 

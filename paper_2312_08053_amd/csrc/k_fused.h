@@ -153,14 +153,18 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
     if (tid == 0) {
         // Spill everything down to the global threshold bin; at least the top 2 % (the sparse upper
         // tail would otherwise need a slot per candidate) and twice the smallest grid size (plus
-        // 3 sigma of the sample count); at most ~12 % of the layer.
+        // 3 sigma of the sample count); at most an eighth of the layer.
         const uint32_t K0 = Ktab[(size_t)li * J];
         const double k0s = 2.0 * (double)K0 / scale;
         uint32_t floor_rank = (uint32_t)fmin((double)ns_total, ceil(k0s + 3.0 * sqrt(k0s) + 2.0));
         floor_rank = max(floor_rank, max(1u, ns_total / 50u));
         uint32_t b = find_bin(floor_rank);
         if (budget_pairs) b = min(b, sh_gbin);
-        const uint32_t bc = find_bin(max(1u, ns_total / 8u));      // never below the top 12.5 %
+        // never more than the top eighth of the layer: the bin that holds the entry of that rank is spilled only
+        // if all of it still lies inside (a layer's candidate region has room for a little more than that share)
+        const uint32_t k8 = max(1u, ns_total / 8u);
+        uint32_t bc = find_bin(k8);
+        if ((bc == 0u ? ns_total : above[bc - 1u]) > k8) ++bc;     // D1_BINS: nothing is spilled
         sh_spill = max(b, bc);
     }
     __syncthreads();
@@ -318,12 +322,13 @@ __device__ __forceinline__ void main_count(const MainCtx& cx, const float (&x)[N
 // for the next chunk's loads a wait for the store acknowledgements as well, and a returning global
 // atomic per reservation serialises thousands of waves on one address.  So:
 //   * the workgroup owns the slice of the layer's candidate region that corresponds to its chunks
-//     (REGION_PER_CHUNK entries of space per chunk, a quarter more than the largest share of a layer
-//     that k_predict lets spill), cut into blocks of 128 entries; a slice that still runs out marks
-//     the layer's spill as incomplete (spill_over) and the layer is served by the passes that read
-//     g and h instead, like any other misprediction;
-//   * a wave takes blocks from an LDS cursor, fills its current block in an LDS window, and writes
-//     the window out with coalesced stores only when the next chunk does not fit;
+//     (REGION_PER_CHUNK entries of space per chunk, a third more than the largest share of a layer
+//     that k_predict lets spill), handed out in units of SPILL_UNIT entries; a slice that still runs
+//     out marks the layer's spill as incomplete (spill_over) and the layer is served by the passes
+//     that read g and h instead, like any other misprediction;
+//   * a wave takes blocks of 128 entries from an LDS cursor, fills its current block in an LDS window,
+//     and writes the window out with coalesced stores only when the next chunk does not fit (a chunk
+//     with more than a block's worth takes exactly what it needs, rounded up to the unit);
 //   * chunk records wait in LDS until that flush.  A chunk's candidates are always contiguous.
 constexpr uint32_t PEND = 16;                   // chunk records a wave holds back
 
@@ -332,7 +337,7 @@ struct WaveSpill {
     uint32_t* pend;       // LDS: PEND x (chunk, start, count)
     uint32_t* lds_cursor; // blocks handed out in this workgroup's slice
     uint32_t* over;       // the layer's spill_over flag
-    uint32_t slice_blocks;// blocks the slice holds
+    uint32_t slice_units; // units of SPILL_UNIT entries the slice holds
     uint32_t slice_rel;   // first entry of the slice, relative to the layer's region (chunk records are region-relative)
     uint32_t blk;         // region-relative start of the current block (valid if have_blk)
     uint32_t fill;        // entries in the window
@@ -362,16 +367,18 @@ __device__ __forceinline__ void spill_flush(const ProfileBuffers& pb, WaveSpill&
     wave_sync_lds();
 }
 
-// take `nb` consecutive blocks of the slice; returns the region-relative entry index of the first.
-// *ok is false when the slice has no room left for them: nothing may be written then, and the layer
-// is marked.
-__device__ __forceinline__ uint32_t spill_take_blocks(WaveSpill& ws, uint32_t nb, bool* ok) {
+// take room for `entries` consecutive entries of the slice; returns the region-relative index of the
+// first.  *ok is false when the slice has no room left for them: nothing may be written then, and the
+// layer is marked.
+constexpr uint32_t SPILL_UNIT = 8;
+__device__ __forceinline__ uint32_t spill_take(WaveSpill& ws, uint32_t entries, bool* ok) {
+    const uint32_t nu = (entries + SPILL_UNIT - 1u) / SPILL_UNIT;
     uint32_t b = 0;
-    if (lane_id() == 0) b = atomicAdd(ws.lds_cursor, nb);
+    if (lane_id() == 0) b = atomicAdd(ws.lds_cursor, nu);
     b = __builtin_amdgcn_readfirstlane(b);
-    *ok = b + nb <= ws.slice_blocks;            // (the cursor grows by at most 8 blocks per chunk: no wrap)
+    *ok = b + nu <= ws.slice_units;             // (the cursor grows by at most 128 units per chunk: no wrap)
     if (!*ok && lane_id() == 0) *ws.over = 1u;
-    return ws.slice_rel + b * STAGE;
+    return ws.slice_rel + b * SPILL_UNIT;
 }
 
 // One chunk of the streaming pass for one wave: histogram updates, ranks of the entries to spill,
@@ -401,7 +408,7 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
             spill_flush(pb, ws, L.tmp0);
             if (!ws.have_blk || ws.fill + total > STAGE) {
                 bool ok;
-                ws.blk = spill_take_blocks(ws, 1u, &ok);
+                ws.blk = spill_take(ws, STAGE, &ok);
                 ws.fill = 0; ws.flushed = 0; ws.have_blk = ok;
                 if (!ok) return;                 // the chunk's record stays "nothing spilled"; the layer is marked
             }
@@ -436,7 +443,7 @@ __device__ __forceinline__ void main_chunk(const ProfileBuffers& pb, const MainC
         spill_flush(pb, ws, L.tmp0);
         ws.have_blk = false;
         bool ok;
-        const uint32_t start = spill_take_blocks(ws, (total + STAGE - 1) / STAGE, &ok);
+        const uint32_t start = spill_take(ws, total, &ok);
         if (!ok) return;
         const uint64_t base = L.tmp0 + start;
         for (uint32_t r0 = 0; r0 < total; r0 += STAGE) {
@@ -501,7 +508,7 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         ws.pend = pend + wave * PEND * 3; ws.lds_cursor = &lds_cursor;
         ws.over = pb.spill_over + big;
         ws.slice_rel = (cur - L.chunk0) * REGION_PER_CHUNK;
-        ws.slice_blocks = (seg_end - cur) * REGION_PER_CHUNK / STAGE;
+        ws.slice_units = (seg_end - cur) * (REGION_PER_CHUNK / SPILL_UNIT);
         ws.blk = 0; ws.fill = 0; ws.flushed = 0; ws.npend = 0; ws.have_blk = false;
 
         // (Fetching the wave's next chunk while the current one is worked on was tried, with the

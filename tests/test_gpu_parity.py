@@ -318,6 +318,6 @@ def test_prediction_from_the_previous_rounds_histogram():
     print("layers recounted per round (from history, from a sample):", redo, "largest share above the spill bin in "
           "round 3:", spilled, "layers whose candidate region overflowed:", overflowed)
     # the rescaled round was mispredicted, and absorbed: nearly everything lay above the stale spill bin, far more
-    # than a layer's candidate region (5/32 of it) holds, so those layers were recounted and compressed from g and h
+    # than a layer's candidate region (about a sixth of it) holds, so those layers were recounted and compressed from g and h
     assert spilled > 0.5 and overflowed > 0 and redo[3][0] >= overflowed
     assert redo[1][0] + redo[2][0] <= 2                               # like gradients: the previous histogram serves

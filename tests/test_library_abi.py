@@ -92,7 +92,7 @@ def test_product_package_never_imports_the_oracle():
 
 
 def test_workspace_is_a_quarter_of_the_gradient_buffers_at_most():
-    """The candidate region of a tiled layer holds 5/32 of it, not all of it: a plan's workspace stays below a
+    """The candidate region of a tiled layer holds about a sixth of it, not all of it: a plan's workspace stays below a
     quarter of the bytes of g and h on the two benchmark shapes (host arithmetic only)."""
     import kimad_synth.shapes as shapes
     import paper_2312_08053_amd as kimad
