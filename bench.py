@@ -267,10 +267,8 @@ def main() -> int:
             # the next round's profile overwrites errs[prev], which round k-1's allocation has long read
         torch.cuda.synchronize()
         oms = float(np.mean([o_start[k].elapsed_time(o_end[k]) for k in range(args.warmup, rounds)]))
-        o_wall = float(o_start[args.warmup].elapsed_time(o_end[rounds - 1])) / args.steps
         out["allocation_overlapped"] = {"what": "sizes from the previous round's table; allocation on a second stream",
                                         "ms_per_round_profile_to_payload": round(oms, 4),
-                                        "ms_per_round_back_to_back": round(o_wall, 4),
                                         "status": ast.cpu().tolist() + oplan.status[1:2].cpu().tolist(),
                                         "gradient_GBs": round(4.0 * d / (oms * 1e-3) / 1e9, 2)}
         del oplan
