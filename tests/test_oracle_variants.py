@@ -148,7 +148,7 @@ def test_uniform_and_whole_model_sizes():
     rng = np.random.default_rng(8)
     sizes = [50, 7, 300, 1]
     gL = [(rng.standard_normal(n) * s).astype(np.float32) for n, s in zip(sizes, (1.0, 100.0, 0.01, 5.0))]
-    hL = [np.zeros(n, np.float32) for n in sizes]
+    hL = [(rng.standard_normal(n) * s).astype(np.float32) for n, s in zip(sizes, (0.5, 300.0, 0.01, 0.0))]
     d = sum(sizes)
     for P in (1, 10, 57, 200, d, d + 50):
         Ku = ko.uniform_sizes(sizes, 8 * P)
@@ -157,7 +157,7 @@ def test_uniform_and_whole_model_sizes():
         Kw = ko.whole_model_sizes(gL, hL, 8 * P)
         assert Kw.sum() == min(P, d) and np.all(Kw <= np.array(sizes))
         # the definition on the concatenation: a magnitude threshold, everything above it kept
-        x = np.concatenate(gL)
+        x = np.concatenate([g - h for g, h in zip(gL, hL)])      # fp32 differences: what is compressed is g - h
         order = np.argsort(-np.abs(x).astype(np.float64), kind="stable")
         kept = np.zeros(d, dtype=bool); kept[order[:min(P, d)]] = True
         pos = 0
@@ -171,5 +171,6 @@ def test_uniform_and_whole_model_sizes():
         if Ku.sum() <= min(P, d):
             assert Ew.sum() <= ko.errors_at(gL, hL, Ku).sum() * (1 + 1e-12)
     full = ko.errors_at(gL, hL, [0, 0, 0, 0])                     # K = 0: everything is dropped
-    for i, g in enumerate(gL):
-        assert abs(full[i] - float(np.dot(g.astype(np.float64), g.astype(np.float64)))) <= 1e-12 * full[i]
+    for i, (g, h) in enumerate(zip(gL, hL)):
+        xi = (g - h).astype(np.float64)
+        assert abs(full[i] - float(np.dot(xi, xi))) <= 1e-12 * full[i]
