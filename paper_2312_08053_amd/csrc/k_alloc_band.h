@@ -477,220 +477,214 @@ __global__ __launch_bounds__(BOUNDS_THREADS) void k_dp_bounds(AllocBuffers ab, D
     if (tid == 0) { bb.info[0] = s_wmax; bb.info[1] = wsum; bb.info[2] = 0u; bb.info[3] = upgrades; }
 }
 
-// The recurrence on the band cells, by one wave: lane t owns cells lo + t, lo + t + 64, ... of the row being
-// written.  Both rows sit in LDS, indexed from their band's first cell.  Only the list records that can
-// connect the bands of the two rows are visited (k_dp_bounds wrote them out, layer after layer); they wait
-// in LDS, a group of layers at a time, and are read as broadcasts, the first four of a layer while the
-// layer before is still being finished.  A single wave executes one instruction every few cycles whatever
-// it does, and the chain of L layers is sequential: the loop is written for few instructions per layer.
+// The recurrence on the band cells, by one workgroup of sixteen waves.  Both rows sit in LDS, indexed from their
+// band's first cell.  Only the list records that can connect the bands of the two rows are visited (k_dp_bounds
+// wrote them out, layer after layer); they wait in LDS, a group of layers at a time.
 //
-// Beside the least total of every cell the kernel keeps its winner (first candidate in list order with a
-// strict "<", then back inside the winner's run while the member before rounds to the same total) and the
-// cell the winner came from.  When the bands are narrow enough these words stay in LDS (a global store inside
-// the loop makes the wave wait for its acknowledgement before the registers it used can be written again: a
-// memory round trip per layer); otherwise they go to the tables in memory, as in the whole-row recurrence.
-// The same wave then finds the least total of the last row at its smallest cost, walks back through the
-// winners and writes j, K and the offsets.
+// The chain of L layers is sequential and a layer is little work (a hundred-odd cells, a few records each), so a
+// layer is spread over the whole workgroup: a group of NP = 1, 2, 4, 8 or 16 neighbouring lanes shares a cell,
+// lane s of the group takes records s, s + NP, ... in ascending order with a strict "<", and the group's minimum of
+// (total, record) in that order, the total first, is formed with DPP moves (no LDS traffic).  That is the candidate
+// the sequential scan of the whole list with a strict "<" would have kept: the first one, in list order, that attains
+// the minimum.  The group's first lane then takes the lowest member of the winner's run whose rounded total is the
+// same, and stores the cell's value, its winner and the cell it came from.  One barrier per layer.
+//
+// When the bands are narrow enough the winners stay in LDS (a global store inside the loop would be waited for
+// before the registers it used can be written again); otherwise they go to the tables in memory, as in the
+// whole-row recurrence.  The least total of the last row at its smallest cost, the walk back through the winners
+// and the outputs j, K and offsets follow in the same launch.
+constexpr uint32_t BANDED_THREADS = 1024;
+static_assert(BANDED_THREADS >= BAND_MAX_L, "the set-up and the outputs give a thread to every layer");
 constexpr uint32_t BAND_LIVE_CAP = 2048;       // live records held in LDS at a time
-constexpr uint32_t BANDED_POOL = 142 * 1024;   // bytes of LDS carved at run time: two rows, live records, winners
+constexpr uint32_t BANDED_POOL = 140 * 1024;   // bytes of LDS carved at run time: two rows, live records, winners
 
-template <bool IN_LDS>
-__device__ __forceinline__ void banded_layers(const AllocBuffers& ab, const BandBuffers& bb, double* row0, double* row1,
-                                              double* l_e, double* l_before, uint32_t* l_w, uint32_t* l_jj, uint32_t live_cap,
-                                              uint32_t* out_w, const uint32_t* s_lo, const uint32_t* s_hi,
-                                              const uint32_t* s_off, const uint32_t* s_wcum) {
-    const uint32_t lane = threadIdx.x;
-    const uint32_t L = ab.L, J = ab.J;
-    auto uni = [](uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
-    uint32_t i = 0;
-    while (i < L) {
-        // a group of layers whose live records fit LDS (at least one layer: a list has at most 64 records)
-        const uint32_t g0 = uni(s_off[i]);
-        uint32_t i1 = i + 1u;
-        while (i1 < L && uni(s_off[i1 + 1u]) - g0 <= live_cap) ++i1;
-        const uint32_t gcount = min(uni(s_off[i1]) - g0, live_cap);
-        for (uint32_t t0 = 0; t0 < gcount; t0 += 256u) {
-            double e[4], b[4];
-            uint32_t w[4], jj[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t t = min(t0 + (uint32_t)u * 64u + lane, gcount - 1u);
-                e[u] = bb.live_e[g0 + t]; b[u] = bb.live_before[g0 + t];
-                w[u] = bb.live_w[g0 + t]; jj[u] = bb.live_jj[g0 + t];
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const uint32_t t = t0 + (uint32_t)u * 64u + lane;
-                if (t < gcount) { l_e[t] = e[u]; l_before[t] = b[u]; l_w[t] = w[u]; l_jj[t] = jj[u]; }
+// (total, record) of another lane of the group; the smaller pair stays
+template <int CTRL>
+__device__ __forceinline__ void take_min_dpp(double& t, uint32_t& k) {
+    const double ot = dpp_f64<CTRL>(t);
+    const uint32_t ok = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)k, CTRL, 0xF, 0xF, false);
+    if (ot < t || (ot == t && ok < k)) { t = ot; k = ok; }
+}
+template <int NP>
+__device__ __forceinline__ void group_min_pair(double& t, uint32_t& k) {
+    if (NP >= 2) take_min_dpp<0xB1>(t, k);       // quad_perm [1,0,3,2]
+    if (NP >= 4) take_min_dpp<0x4E>(t, k);       // quad_perm [2,3,0,1]
+    if (NP >= 8) take_min_dpp<0x141>(t, k);      // row_half_mirror: the other quad of the eight
+    if (NP >= 16) take_min_dpp<0x140>(t, k);     // row_mirror: the other eight of the sixteen
+}
+
+struct BandedLds {
+    double* row0; double* row1;
+    double* l_e; double* l_before; uint32_t* l_w; uint32_t* l_jj;
+    uint32_t* out_w;
+    uint32_t live_cap;
+};
+
+// one layer: NP lanes per cell
+template <int NP, bool IN_LDS>
+__device__ __forceinline__ void banded_layer(const AllocBuffers& ab, const BandedLds& z, uint32_t i, uint32_t base, uint32_t n,
+                                             uint32_t plo, uint32_t pspan, uint32_t clo, uint32_t chi, uint32_t wc) {
+    const uint32_t tid = threadIdx.x, sub = tid % NP, J = ab.J;
+    const double* prow = (i & 1u) ? z.row1 : z.row0;
+    double* crow = (i & 1u) ? z.row0 : z.row1;
+    for (uint32_t c0 = clo; c0 <= chi; c0 += BANDED_THREADS / NP) {
+        const uint32_t c = c0 + tid / NP, cm = c - plo;
+        double best = DP_INF;
+        uint32_t bk = 0xFFu;
+        if (c <= chi) {
+            for (uint32_t k = sub; k < n; k += NP) {
+                const uint32_t src = cm - z.l_w[base + k];      // a cell cheaper than the record wraps far beyond the span
+                if (src <= pspan) {
+                    const double t = prow[src] + z.l_e[base + k];
+                    if (t < best) { best = t; bk = k; }
+                }
             }
         }
-        wave_lds_done();
-        // the first four records of the group's first layer, and its bands: everything a layer needs besides the
-        // previous row is read one layer ahead, so that the row reads are the only LDS round trip on the chain
-        double ne[4];
-        uint32_t nw[4];
-        uint32_t nbase = uni(s_off[i]) - g0, nn = uni(s_off[i + 1u]) - uni(s_off[i]);
-        uint32_t n_plo = s_lo[i], n_phi = s_hi[i], n_clo = s_lo[i + 1u], n_chi = s_hi[i + 1u], n_wc = s_wcum[i];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) { ne[u] = l_e[nbase + u]; nw[u] = l_w[nbase + u]; }
-        for (; i < i1; ++i) {
-            const uint32_t base = nbase, n = nn;
-            double e4[4];
-            uint32_t w4[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) { e4[u] = (uint32_t)u < n ? ne[u] : DP_INF; w4[u] = nw[u]; }
-            const uint32_t plo = uni(n_plo), pspan = uni(n_phi) - plo;
-            const uint32_t clo = uni(n_clo), chi = uni(n_chi);
-            const uint32_t wc = uni(n_wc);
-            if (i + 1u < i1) {                                             // read while this layer is computed
-                nbase = base + n; nn = uni(s_off[i + 2u]) - uni(s_off[i + 1u]);
-                n_plo = n_clo; n_phi = n_chi; n_clo = s_lo[i + 2u]; n_chi = s_hi[i + 2u]; n_wc = s_wcum[i + 1u];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) { ne[u] = l_e[nbase + u]; nw[u] = l_w[nbase + u]; }
-            }
-            const double* prow = (i & 1u) ? row1 : row0;
-            double* crow = (i & 1u) ? row0 : row1;
-            for (uint32_t c0 = clo; c0 <= chi; c0 += 64u) {
-                const uint32_t c = c0 + lane, cm = c - plo;
-                double best = DP_INF, bp = 0.0;                            // least total, and the previous-row value it came from
-                uint32_t bk = 0xFFu;
-                // four records: sources (a cell cheaper than the candidate wraps far beyond the span), row reads, totals
-                auto four = [&](const double (&e)[4], const uint32_t (&w)[4], uint32_t k0) {
-                    uint32_t s[4];
-                    double v[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) { s[u] = cm - w[u]; v[u] = prow[min(s[u], pspan)]; }
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const double t = (s[u] <= pspan ? v[u] : DP_INF) + e[u];   // a trip past the last record adds +inf: never a winner
-                        if (t < best) { best = t; bp = v[u]; bk = k0 + (uint32_t)u; }
-                    }
-                };
-                four(e4, w4, 0u);
-                for (uint32_t k0 = 4u; k0 < n; k0 += 4u) {
-                    double e[4];
-                    uint32_t w[4];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        e[u] = k0 + (uint32_t)u < n ? l_e[base + k0 + u] : DP_INF;
-                        w[u] = l_w[base + k0 + (uint32_t)u];
-                    }
-                    four(e, w, k0);
-                }
-                if (c <= chi) {
-                    uint32_t bj = 0xFFu, from = 0xFFFFu;
-                    if (bk != 0xFFu) {
-                        const uint32_t wj = l_jj[base + bk];
-                        from = c - l_w[base + bk];
-                        bj = wj >> 8;
-                        if (bp + l_before[base + bk] == best) {
-                            const uint32_t jlo = wj & 0xFFu;
-                            uint32_t j = bj - 1u;
-                            while (j > jlo && bp + ab.E[(size_t)i * J + j - 1u] == best) --j;
-                            bj = j;
-                        }
-                    }
-                    crow[c - clo] = best;
-                    if (IN_LDS) {
-                        out_w[wc + (c - clo)] = bj | (from << 16);
-                    } else {
-                        ab.choice[(size_t)i * ab.stride + c] = (uint8_t)bj;
-                        ab.cprev[(size_t)i * ab.stride + c] = (uint16_t)from;
-                    }
+        group_min_pair<NP>(best, bk);
+        if (sub == 0u && c <= chi) {
+            uint32_t bj = 0xFFu, from = 0xFFFFu;
+            if (bk != 0xFFu) {
+                const uint32_t wj = z.l_jj[base + bk];
+                from = c - z.l_w[base + bk];
+                const double bp = prow[from - plo];
+                bj = wj >> 8;
+                if (bp + z.l_before[base + bk] == best) {
+                    const uint32_t jlo = wj & 0xFFu;
+                    uint32_t j = bj - 1u;
+                    while (j > jlo && bp + ab.E[(size_t)i * J + j - 1u] == best) --j;
+                    bj = j;
                 }
             }
-            // (one wave: its LDS instructions run in order, so the next layer's reads see this row; only the
-            // compiler must not move them across)
-            asm volatile("" ::: "memory");
+            crow[c - clo] = best;
+            if (IN_LDS) {
+                z.out_w[wc + (c - clo)] = bj | (from << 16);
+            } else {
+                ab.choice[(size_t)i * ab.stride + c] = (uint8_t)bj;
+                ab.cprev[(size_t)i * ab.stride + c] = (uint16_t)from;
+            }
         }
     }
 }
 
-__global__ __launch_bounds__(64) void k_dp_banded(AllocBuffers ab, BandBuffers bb, const uint32_t* __restrict__ bad,
-                                                  int32_t err_infeasible, int32_t err_nonfinite) {
+template <bool IN_LDS>
+__device__ __forceinline__ void banded_layers(const AllocBuffers& ab, const BandBuffers& bb, const BandedLds& z,
+                                              const uint32_t* s_lo, const uint32_t* s_hi, const uint32_t* s_off,
+                                              const uint32_t* s_wcum) {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t L = ab.L;
+    uint32_t i = 0;
+    while (i < L) {
+        // a group of layers whose live records fit LDS (at least one layer: a list has at most 64 records)
+        const uint32_t g0 = s_off[i];
+        uint32_t i1 = i + 1u;
+        while (i1 < L && s_off[i1 + 1u] - g0 <= z.live_cap) ++i1;
+        const uint32_t gcount = min(s_off[i1] - g0, z.live_cap);
+        for (uint32_t t = tid; t < gcount; t += BANDED_THREADS) {
+            z.l_e[t] = bb.live_e[g0 + t]; z.l_before[t] = bb.live_before[g0 + t];
+            z.l_w[t] = bb.live_w[g0 + t]; z.l_jj[t] = bb.live_jj[g0 + t];
+        }
+        lds_barrier();
+        for (; i < i1; ++i) {
+            const uint32_t base = s_off[i] - g0, n = s_off[i + 1u] - s_off[i];
+            const uint32_t plo = s_lo[i], pspan = s_hi[i] - plo, clo = s_lo[i + 1u], chi = s_hi[i + 1u], wc = s_wcum[i];
+            // lanes per cell: as many as there are records, up to 16 (all of these are the same in every lane)
+            if (n <= 1u) banded_layer<1, IN_LDS>(ab, z, i, base, n, plo, pspan, clo, chi, wc);
+            else if (n <= 2u) banded_layer<2, IN_LDS>(ab, z, i, base, n, plo, pspan, clo, chi, wc);
+            else if (n <= 4u) banded_layer<4, IN_LDS>(ab, z, i, base, n, plo, pspan, clo, chi, wc);
+            else if (n <= 8u) banded_layer<8, IN_LDS>(ab, z, i, base, n, plo, pspan, clo, chi, wc);
+            else banded_layer<16, IN_LDS>(ab, z, i, base, n, plo, pspan, clo, chi, wc);
+            lds_barrier();                       // the next layer reads this row (and the next group overwrites the records)
+        }
+    }
+}
+
+__global__ __launch_bounds__(BANDED_THREADS) void k_dp_banded(AllocBuffers ab, BandBuffers bb, const uint32_t* __restrict__ bad,
+                                                              int32_t err_infeasible, int32_t err_nonfinite) {
     __shared__ __align__(16) unsigned char pool[BANDED_POOL];
     __shared__ uint32_t s_lo[BAND_MAX_L + 1], s_hi[BAND_MAX_L + 1], s_off[BAND_MAX_L + 1], s_wcum[BAND_MAX_L + 1];
     __shared__ uint8_t s_j[BAND_MAX_L];
-    const uint32_t lane = threadIdx.x;
+    __shared__ uint32_t su[16];
+    __shared__ unsigned long long su64[16];
+    __shared__ uint32_t s_wmax, s_bad;
+    __shared__ unsigned long long s_best;        // bits of the least total (non-negative doubles order like their bit patterns)
+    __shared__ uint32_t s_bc;
+    const uint32_t tid = threadIdx.x;
     const uint32_t L = ab.L, J = ab.J, cap = ab.cap;
 #ifdef KIMAD_STAMPS
     const unsigned long long t_begin = __builtin_readcyclecounter();
 #endif
-    uint32_t any_bad = 0u;
-    for (uint32_t i = lane; i < L; i += 64u) any_bad |= bad[i];
-    // bands, live offsets, cumulative widths (one wave: a running sum over chunks of 64 rows)
-    uint32_t carry = 0u, wmax = 1u;
-    for (uint32_t r0 = 0; r0 <= L; r0 += 64u) {
-        const uint32_t r = r0 + lane;
-        uint32_t lo = 0u, hi = 0u, wd = 0u;
-        if (r <= L) {
-            lo = min(bb.lo[r], cap); hi = max(lo, min(bb.hi[r], cap));
-            s_lo[r] = lo; s_hi[r] = hi; s_off[r] = bb.live_off[r];
-            wd = r ? hi - lo + 1u : 0u;                      // row 0 stores nothing
-        }
-        const uint32_t inc = wave_scan_add_u32(wd);
-        // s_wcum[i] = first word of layer i's winners = widths of rows 1..i
-        if (r <= L) s_wcum[r] = carry + inc;                 // widths of rows 1..r: the start of layer r's words (row r + 1)
-        carry += (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
-        wmax = max(wmax, wd);
+    if (tid == 0) { s_wmax = 1u; s_bad = 0u; s_best = ~0ull; s_bc = 0xFFFFFFFFu; }
+    __syncthreads();
+    // bands, live offsets, cumulative widths: rows 0..L (L <= BAND_MAX_L = the workgroup's size; row L by thread 0 again)
+    uint32_t wd = 0u;
+    for (uint32_t r = tid; r <= L; r += BANDED_THREADS) {
+        const uint32_t lo = min(bb.lo[r], cap), hi = max(lo, min(bb.hi[r], cap));
+        s_lo[r] = lo; s_hi[r] = hi; s_off[r] = bb.live_off[r];
     }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) wmax = max(wmax, (uint32_t)__shfl_xor(wmax, d, 64));
-    any_bad = ballot(any_bad != 0u) != 0ull ? 1u : 0u;
-    const uint32_t total_words = carry;
-    wave_lds_done();
+    if (tid < L && bad[tid]) s_bad = 1u;
+    __syncthreads();
+    // s_wcum[i] = first word of layer i's winners = widths of rows 1..i (row 0 stores nothing); thread r - 1 owns row r
+    if (tid < L) wd = s_hi[tid + 1u] - s_lo[tid + 1u] + 1u;
+    if (wd) atomicMax(&s_wmax, wd);
+    uint32_t total_words;
+    const uint32_t before = block_exclusive_scan<uint32_t>(wd, su, &total_words);
+    if (tid < L) s_wcum[tid] = before;
+    __syncthreads();
+    const uint32_t wmax = s_wmax;
+    const bool any_bad = s_bad != 0u;
     // carve the pool
     const uint32_t wr = (wmax + 63u) & ~63u;                                  // cells per row buffer
     const uint32_t total_live = s_off[L];
-    const uint32_t live_cap = min(max(total_live, 64u), BAND_LIVE_CAP);
-    double* row0 = reinterpret_cast<double*>(pool);
-    double* row1 = row0 + wr;
-    double* l_e = row1 + wr;
-    double* l_before = l_e + live_cap + 4u;
-    uint32_t* l_w = reinterpret_cast<uint32_t*>(l_before + live_cap);
-    uint32_t* l_jj = l_w + live_cap + 4u;
-    uint32_t* out_w = l_jj + live_cap;
-    const uint32_t used_bytes = (uint32_t)(reinterpret_cast<unsigned char*>(out_w) - pool);
-    const uint32_t out_cap = (BANDED_POOL - used_bytes) / 4u;                 // (two rows of 4224 cells and 2048 records leave 25 KB)
+    BandedLds z;
+    z.live_cap = min(max(total_live, 64u), BAND_LIVE_CAP);
+    z.row0 = reinterpret_cast<double*>(pool);
+    z.row1 = z.row0 + wr;
+    z.l_e = z.row1 + wr;
+    z.l_before = z.l_e + z.live_cap;
+    z.l_w = reinterpret_cast<uint32_t*>(z.l_before + z.live_cap);
+    z.l_jj = z.l_w + z.live_cap;
+    z.out_w = z.l_jj + z.live_cap;
+    const uint32_t used_bytes = (uint32_t)(reinterpret_cast<unsigned char*>(z.out_w) - pool);
+    const uint32_t out_cap = (BANDED_POOL - used_bytes) / 4u;                 // (two rows of 4224 cells and 2048 records leave 23 KB)
     const bool in_lds = total_words <= out_cap;
-    if (lane == 0) row0[0] = 0.0;
-    if (lane < 4u) { l_e[live_cap + lane] = DP_INF; l_w[live_cap + lane] = 0u; }
-    wave_lds_done();
-    if (in_lds) banded_layers<true>(ab, bb, row0, row1, l_e, l_before, l_w, l_jj, live_cap, out_w, s_lo, s_hi, s_off, s_wcum);
-    else banded_layers<false>(ab, bb, row0, row1, l_e, l_before, l_w, l_jj, live_cap, out_w, s_lo, s_hi, s_off, s_wcum);
+    if (tid == 0) z.row0[0] = 0.0;
+    lds_barrier();
+    if (in_lds) banded_layers<true>(ab, bb, z, s_lo, s_hi, s_off, s_wcum);
+    else banded_layers<false>(ab, bb, z, s_lo, s_hi, s_off, s_wcum);
 #ifdef KIMAD_STAMPS
     const unsigned long long t_layers = __builtin_readcyclecounter();
 #endif
-    // ---- least total of the last row, smallest cost attaining it
+    // ---- least total of the last row, smallest cost attaining it (totals are sums of squares: never negative, so
+    // their bit patterns order like the numbers; +inf stays the largest)
     const uint32_t llo = s_lo[L], lhi = s_hi[L];
-    const double* lrow = (L & 1u) ? row1 : row0;
-    double best = DP_INF;
-    uint32_t bc = 0xFFFFFFFFu;
-    for (uint32_t c = llo + lane; c <= lhi; c += 64u) {
-        const double v = lrow[c - llo];
-        if (v < best) { best = v; bc = c; }                 // ascending cells per lane: keeps the smallest
+    const double* lrow = (L & 1u) ? z.row1 : z.row0;
+    {
+        double best = DP_INF;
+        for (uint32_t c = llo + tid; c <= lhi; c += BANDED_THREADS) best = min_f64(best, lrow[c - llo]);
+        atomicMin(&s_best, (unsigned long long)__double_as_longlong(best));
+        __syncthreads();
+        const double least = __longlong_as_double((long long)s_best);
+        for (uint32_t c = llo + tid; c <= lhi; c += BANDED_THREADS)
+            if (lrow[c - llo] == least) atomicMin(&s_bc, c);
+        __syncthreads();
     }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
-        const double ov = __shfl_xor(best, d, 64);
-        const uint32_t oc = __shfl_xor(bc, d, 64);
-        if (ov < best || (ov == best && oc < bc)) { best = ov; bc = oc; }
-    }
+    const double best = __longlong_as_double((long long)s_best);
+    const uint32_t bc = s_bc;
     int32_t st = 0;
     if (any_bad) st = err_nonfinite;
     else if (!(best < DP_INF)) st = err_infeasible;
-    if (lane == 0) *ab.status = st;
+    if (tid == 0) *ab.status = st;
     if (st != 0) {
-        for (uint32_t i = lane; i < L; i += 64u) { ab.j_out[i] = 0; ab.K_out[i] = 0; }
-        for (uint32_t i = lane; i <= L; i += 64u) ab.offsets_out[i] = 0;
+        for (uint32_t i = tid; i < L; i += BANDED_THREADS) { ab.j_out[i] = 0; ab.K_out[i] = 0; }
+        for (uint32_t i = tid; i <= L; i += BANDED_THREADS) ab.offsets_out[i] = 0;
         return;
     }
-    // ---- back-tracking by one lane, winners into LDS
-    if (lane == 0) {
+    // ---- back-tracking by one thread, winners into LDS
+    if (tid == 0) {
         uint32_t c = bc;
         if (in_lds) {
             for (uint32_t i = L; i-- > 0;) {
-                const uint32_t word = out_w[s_wcum[i] + (c - s_lo[i + 1u])];
+                const uint32_t word = z.out_w[s_wcum[i] + (c - s_lo[i + 1u])];
                 s_j[i] = (uint8_t)word;
                 c = min(word >> 16, cap);
             }
@@ -701,26 +695,19 @@ __global__ __launch_bounds__(64) void k_dp_banded(AllocBuffers ab, BandBuffers b
             }
         }
     }
-    wave_lds_done();
+    __syncthreads();
     // ---- sizes and offsets
-    unsigned long long run = 0ull;
-    for (uint32_t i0 = 0; i0 < L; i0 += 64u) {
-        const uint32_t i = i0 + lane;
+    {
         unsigned long long K = 0ull;
         uint32_t j = 0u;
-        if (i < L) { j = s_j[i]; K = ab.Kout[(size_t)i * J + min(j, J - 1u)]; }
-        unsigned long long inc = K;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const unsigned long long o = __shfl_up(inc, d, 64);
-            if ((int)lane >= d) inc += o;
-        }
-        if (i < L) { ab.j_out[i] = (int32_t)j; ab.K_out[i] = K; ab.offsets_out[i] = run + inc - K; }
-        run += __shfl(inc, 63, 64);
+        if (tid < L) { j = s_j[tid]; K = ab.Kout[(size_t)tid * J + min(j, J - 1u)]; }
+        unsigned long long total;
+        const unsigned long long off = block_exclusive_scan<unsigned long long>(K, su64, &total);
+        if (tid < L) { ab.j_out[tid] = (int32_t)j; ab.K_out[tid] = K; ab.offsets_out[tid] = off; }
+        if (tid == 0) ab.offsets_out[L] = total;
     }
-    if (lane == 0) ab.offsets_out[L] = run;
 #ifdef KIMAD_STAMPS
-    if (lane == 0) {
+    if (tid == 0) {
         bb.info[12] = (uint32_t)(t_layers - t_begin); bb.info[13] = (uint32_t)(__builtin_readcyclecounter() - t_begin);
         bb.info[14] = in_lds ? 1u : 0u; bb.info[15] = total_live;
     }

@@ -569,7 +569,7 @@ int enqueue_allocate(kimad_plan* p, const AllocScratch& ws, const double* err_ta
         if (lo.L <= BAND_MAX_L && band && !(p->cfg.flags & KIMAD_CFG_FULL_DP)) {
             // the recurrence inside the band of cells that Lagrangian bounds leave (same result, a fraction of the cells)
             KLAUNCH(p, s, "k_dp_bounds", k_dp_bounds, dim3(1), dim3(BOUNDS_THREADS), ab, dl, ws.band);
-            KLAUNCH(p, s, "k_dp_banded", k_dp_banded, dim3(1), dim3(64), ab, ws.band, (const uint32_t*)dl.bad,
+            KLAUNCH(p, s, "k_dp_banded", k_dp_banded, dim3(1), dim3(BANDED_THREADS), ab, ws.band, (const uint32_t*)dl.bad,
                     (int32_t)KIMAD_ERR_INFEASIBLE, (int32_t)KIMAD_ERR_NONFINITE);
             return KIMAD_OK;
         }
