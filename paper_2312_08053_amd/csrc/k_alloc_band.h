@@ -161,8 +161,9 @@ __global__ __launch_bounds__(BOUNDS_THREADS) void k_dp_bounds(AllocBuffers ab, D
     __shared__ uint32_t su[16];
     __shared__ double sd[16];
     __shared__ double s_lam[BAND_NLAM], s_btot[BAND_NLAM];
-    __shared__ unsigned long long s_key;
-    __shared__ uint32_t s_sum, s_flag, s_wmax;
+    __shared__ unsigned long long s_key[2];
+    __shared__ uint32_t s_hist[2][64], s_dw[2];
+    __shared__ uint32_t s_flag, s_wmax;
     double* const HE = reinterpret_cast<double*>(pool);                 // vertex errors
     double* const HS = HE + BAND_LCAP;                                  // slope of the edge to the next vertex; 0 where there is none
     uint16_t* const HW = reinterpret_cast<uint16_t*>(HS + BAND_LCAP);   // vertex costs (rows that fit LDS: below 65536)
@@ -182,7 +183,8 @@ __global__ __launch_bounds__(BOUNDS_THREADS) void k_dp_bounds(AllocBuffers ab, D
     const uint32_t my_bad = tid < L ? (dl.bad[tid] | (my_n == 0u ? 1u : 0u)) : 0u;    // or a layer with no affordable candidate
     uint32_t n_tot;
     const uint32_t my_off = block_exclusive_scan<uint32_t>(my_n, su, &n_tot);
-    if (tid == 0) { s_flag = 0u; s_sum = 0u; s_key = 0ull; s_wmax = 0u; }
+    if (tid == 0) { s_flag = 0u; s_key[0] = 0ull; s_key[1] = 0ull; s_wmax = 0u; }
+    if (tid < 128u) s_hist[tid >> 6][tid & 63u] = 0u;
     __syncthreads();
     if (my_bad) s_flag = 1u;
     bool whole = n_tot > BAND_LCAP;
@@ -289,24 +291,50 @@ __global__ __launch_bounds__(BOUNDS_THREADS) void k_dp_bounds(AllocBuffers ab, D
         __syncthreads();
         if (cheapest > cap) whole = true;                                   // nothing fits: the recurrence will say so
         else room = cap - cheapest;
-        hi_b = (unsigned long long)__double_as_longlong(steep);             // at the steepest slope no edge is steeper: it fits
+        // The smallest multiplier (as a bit pattern: non-negative doubles order like their patterns) at which the
+        // edges steeper than it fit the room.  Sixty-four-way search: the patterns between lo_b (does not fit, or 0)
+        // and lo_b + 2^k are cut into 64 buckets, every edge inside adds its cost step to its bucket in LDS, and
+        // every wave finds for itself the lowest bucket boundary at which what lies above fits: six bits of the
+        // pattern per round and two barriers, down to a gap of 2^15 patterns (2^-37 relative: closer breakpoints
+        // make no difference worth a round).
         if (!whole) {
-            // (down to a gap of 2^18 patterns, 2^-34 relative: closer breakpoints make no difference worth a round)
-            for (int step = 0; step < 64 && hi_b - lo_b > (1ull << 18); ++step) {
-                const unsigned long long mid_b = lo_b + (hi_b - lo_b) / 2ull;
-                const double lam = __longlong_as_double((long long)mid_b);
-                uint32_t c = 0u;
+            uint32_t above = 0u;                                             // cost steps of the edges at or beyond lo_b + 2^k
+            uint32_t buf = 0u;
+            for (int k = 63; k > 15; k -= 6) {
+                const int sh = k - 6;                                        // log2 of a bucket's size
 #pragma unroll
-                for (int u = 0; u < (int)BAND_EDGES_PER_THREAD; ++u) c += sl[u] > lam ? dw[u] : 0u;
-                c = wave_scan_add_u32(c);                                   // (DPP adds: lane 63 ends with the wave's total)
-                if (lane == 63u) atomicAdd(&s_sum, c);
+                for (int u = 0; u < (int)BAND_EDGES_PER_THREAD; ++u) {
+                    const unsigned long long bits = (unsigned long long)__double_as_longlong(sl[u]);
+                    // bucket b holds the patterns in (lo_b + b 2^sh, lo_b + (b + 1) 2^sh]
+                    if (dw[u] && bits > lo_b && ((bits - lo_b - 1ull) >> sh) < 64ull)
+                        atomicAdd(&s_hist[buf][(uint32_t)((bits - lo_b - 1ull) >> sh)], dw[u]);
+                }
                 __syncthreads();
-                const bool fits = s_sum <= room;
+                const uint32_t mine = s_hist[buf][lane];
+                s_hist[buf ^ 1u][lane] = 0u;                                 // the other table, for the next round
+                const uint32_t inc = wave_scan_add_u32(mine);                // buckets 0..lane
+                const uint32_t tot = (uint32_t)__builtin_amdgcn_readlane((int)inc, 63);
+                const uint32_t from_here = tot - inc + mine;                 // buckets lane..63
+                // cost at boundary m (edges strictly above lo_b + m 2^sh) = above + buckets m..63
+                const uint64_t fits = ballot(above + from_here <= room);
+                // boundary 64 always fits (the invariant); the lowest fitting boundary of 0..63, if any
+                const uint32_t m = fits ? (uint32_t)__ffsll((long long)fits) - 1u : 64u;
+                const uint32_t keep = m < 64u ? (uint32_t)__builtin_amdgcn_readlane((int)from_here, (int)min(m, 63u)) : 0u;
+                above += keep;
+                hi_b = lo_b + ((unsigned long long)m << sh);
+                if (m > 0u) lo_b += (unsigned long long)(m - 1u) << sh;      // boundary m - 1 does not fit
                 __syncthreads();
-                if (tid == 0) s_sum = 0u;
-                if (fits) hi_b = mid_b; else lo_b = mid_b;
+                buf ^= 1u;
+                if (m == 0u) {
+                    // boundary 0 itself fits: either everything fits (lo_b = 0: the multiplier is 0) or the gap has
+                    // closed onto a pattern that does not fit and its successor that does
+                    break;
+                }
+                // the next round looks inside (boundary m - 1, boundary m], a range of 2^sh patterns
             }
-            __syncthreads();
+            // (a first round that finds even its last boundary too low ends beyond the finite patterns: the steepest
+            // slope itself always fits, nothing being steeper)
+            hi_b = min(hi_b, (unsigned long long)__double_as_longlong(steep));
         }
     }
     if (whole) {
@@ -335,26 +363,30 @@ __global__ __launch_bounds__(BOUNDS_THREADS) void k_dp_bounds(AllocBuffers ab, D
     (void)block_exclusive_scan<uint32_t>(tid < L ? (uint32_t)HW[my_off + s_q[tid]] : 0u, su, &used);
     uint32_t left = cap - used;                                             // used <= cap: lam_star fits
     uint32_t upgrades = 0u;
+    // A round: every layer whose next hull edge fits what is left bids with its slope; the steepest wins (lowest
+    // layer among equals), its owner takes the step and says what it cost.  The bids of consecutive rounds go to two
+    // words in turn, so a round needs two barriers.
     for (uint32_t round = 0; round < BAND_GREEDY && left > 0u; ++round) {
+        const uint32_t buf = round & 1u;
         if (tid < L) {
             const uint32_t q = s_q[tid];
             if (q + 1u < s_hn[tid] && (uint32_t)HW[my_off + q + 1u] - (uint32_t)HW[my_off + q] <= left) {
                 const unsigned long long key = ((unsigned long long)__double_as_longlong(HS[my_off + q]) & ~0x3FFull) | (1023u - tid);
-                atomicMax(&s_key, key);
+                atomicMax(&s_key[buf], key);
             }
         }
         __syncthreads();
-        const unsigned long long best = s_key;
+        const unsigned long long best = s_key[buf];
+        if (best == 0ull) break;                                             // (the same word in every thread)
+        if (tid == 1023u - (uint32_t)(best & 0x3FFull)) {
+            const uint32_t q = s_q[tid];
+            s_dw[buf] = (uint32_t)HW[my_off + q + 1u] - (uint32_t)HW[my_off + q];
+            s_q[tid] = (uint16_t)(q + 1u);
+            s_key[buf ^ 1u] = 0ull;                                          // the next round's word: last read before the previous round's second barrier
+        }
         __syncthreads();
-        if (tid == 0) s_key = 0ull;
-        if (best == 0ull) break;
-        const uint32_t who = 1023u - (uint32_t)(best & 0x3FFull);
-        const uint32_t o = s_off[who], q = s_q[who];
-        left -= (uint32_t)HW[o + q + 1u] - (uint32_t)HW[o + q];
-        __syncthreads();
-        if (tid == 0) s_q[who] = (uint16_t)(q + 1u);
+        left -= s_dw[buf];
         ++upgrades;
-        __syncthreads();
     }
     __syncthreads();
     double ub, abs_tot;

@@ -223,7 +223,11 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
     if (big == 0u && gzero)
         for (uint32_t b = tid; b < D1_BINS; b += 256) gzero[b] = 0ull;
     if (fold_zero) {
-        for (uint32_t c = tid; c < L.nchunks; c += 256) pb.rec_cnt[L.chunk0 + c] = 0u;    // chunk records start out as "nothing spilled"
+        // chunk records start out as "nothing spilled": every workgroup clears an equal share of all layers' records
+        // (a layer's own workgroup clearing them made the largest layer's the last to finish by far)
+        const uint32_t per = (pb.nchunks_total + gridDim.x - 1u) / gridDim.x;
+        const uint32_t c_lo = big * per, c_hi = min(pb.nchunks_total, c_lo + per);
+        for (uint32_t c = c_lo + tid; c < c_hi; c += 256) pb.rec_cnt[c] = 0u;
         if (tid == 0) { pb.layer_flag[big] = 0u; pb.cursor[big] = 0u; pb.spill_over[big] = 0u; }
         if (big == 0u && tid < 4u) pb.diag[tid] = 0u;
         if (big == 0u && tid == 4u) *pb.fresh = 0u;
