@@ -332,20 +332,18 @@ __device__ __forceinline__ void hist3_candidates(const CompressBuffers& cb, uint
     };
     // the first four rounds' loads go out together (positions past the chunk's last candidate read entry 0
     // of the buffer, always a valid address, and are dropped; a chunk without candidates has no valid start)
+    // (and so on, four rounds per memory round trip: a layer that spills an eighth has eight rounds a chunk)
     constexpr int AHEAD = 4;
-    float px[AHEAD];
+    for (uint32_t k0 = 0; k0 < cmax; k0 += AHEAD * SUB) {
+        float px[AHEAD];
 #pragma unroll
-    for (int t = 0; t < AHEAD; ++t) {
-        const uint32_t k = (uint32_t)t * SUB + g.sub;
-        px[t] = cb.tmp_x[k < cnt ? base + k : 0ull];
-    }
+        for (int t = 0; t < AHEAD; ++t) {
+            const uint32_t k = k0 + (uint32_t)t * SUB + g.sub;
+            px[t] = cb.tmp_x[k < cnt ? base + k : 0ull];
+        }
 #pragma unroll
-    for (int t = 0; t < AHEAD; ++t)
-        if ((uint32_t)t * SUB < cmax) round((uint32_t)t * SUB + g.sub < cnt, key_of(px[t]));
-    for (uint32_t k0 = AHEAD * SUB; k0 < cmax; k0 += SUB) {
-        const uint32_t k = k0 + g.sub;
-        const bool in = k < cnt;
-        round(in, in ? key_of(cb.tmp_x[base + k]) : 0u);
+        for (int t = 0; t < AHEAD; ++t)
+            if (k0 + (uint32_t)t * SUB < cmax) round(k0 + (uint32_t)t * SUB + g.sub < cnt, key_of(px[t]));
     }
     // A chunk without an entry in the threshold's prefix bin (nearly all of them) is settled here:
     // every entry above the prefix is above the threshold, none equals it.  The others are counted
@@ -596,19 +594,16 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
     // A chunk rarely holds more than 64 candidates: the loads of the first four rounds go out together,
     // so the wave pays one memory round trip for them instead of four.
     constexpr int AHEAD = 4;
-    uint32_t pidx[AHEAD];
-    float px[AHEAD];
-    bool pin[AHEAD];
     // (positions past the chunk's last entry read entry 0 of the buffer or the layer, a valid address, and are dropped)
+    for (uint32_t k0 = 0; k0 < cmax; k0 += AHEAD * SUB) {
+        uint32_t pidx[AHEAD];
+        float px[AHEAD];
+        bool pin[AHEAD];
 #pragma unroll
-    for (int t = 0; t < AHEAD; ++t) pin[t] = fetch((uint32_t)t * SUB + g.sub, pidx[t], px[t]);
+        for (int t = 0; t < AHEAD; ++t) pin[t] = fetch(k0 + (uint32_t)t * SUB + g.sub, pidx[t], px[t]);
 #pragma unroll
-    for (int t = 0; t < AHEAD; ++t)
-        if ((uint32_t)t * SUB < cmax) round(pin[t], pidx[t], px[t]);
-    for (uint32_t k0 = AHEAD * SUB; k0 < cmax; k0 += SUB) {
-        uint32_t idx = 0; float x = 0.f;
-        const bool in = fetch(k0 + g.sub, idx, x);
-        round(in, idx, x);
+        for (int t = 0; t < AHEAD; ++t)
+            if (k0 + (uint32_t)t * SUB < cmax) round(pin[t], pidx[t], px[t]);
     }
 }
 
