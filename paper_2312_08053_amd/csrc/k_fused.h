@@ -515,11 +515,11 @@ __global__ __launch_bounds__(FUSED_THREADS) void k_main(ProfileBuffers pb, uint3
         ws.slice_units = (seg_end - cur) * (REGION_PER_CHUNK / SPILL_UNIT);
         ws.blk = 0; ws.fill = 0; ws.flushed = 0; ws.npend = 0; ws.have_blk = false;
 
-        // (Fetching the wave's next chunk while the current one is worked on was tried, with the
-        // loads verified to stay in flight across the chunk, at 16, 12 and 8 waves per workgroup: no
-        // gain.  What holds the pass below the speed of a plain read is the stores it issues while it
-        // reads, candidates above all: on this machine stores mixed into a read stream cost about
-        // four times their share of the bandwidth, however they are batched or aligned.)
+        // (Fetching the wave's next chunk while the current one is worked on was tried at 16, 12 and 8
+        // waves per workgroup: no gain.  Measured with one thing removed at a time, the candidate and
+        // record stores cost this pass 4 % and the histogram atomics nothing; a workgroup streams its
+        // share about as fast as a bare loop of the same loads does.  The pass ends with its slowest
+        // workgroup, a tenth behind the average.)
         // Waves take chunks from a counter, not in a fixed rotation: a wave's pace varies with what it
         // finds (spills, flushes, memory), and with fixed shares the segment's end waited for its slowest
         // wave for a good tenth of the pass.  The next chunk is asked for before the current one is
