@@ -124,7 +124,10 @@ typedef struct kimad_config {
 
 typedef struct kimad_plan kimad_plan_t; /* host object; owns no device memory */
 
-/* Bytes of DEVICE workspace a plan over these layer sizes needs.  n: HOST array of L sizes. */
+/* Bytes of DEVICE workspace a plan over these layer sizes needs.  n: HOST array of L sizes.
+ * About a quarter of the bytes of g and h for large models: candidate space for a sixth of every layer above
+ * 8192 entries (8 bytes an entry), histogram tables, chunk records and the allocation's rows (see
+ * kimad_config_t::max_budget_bytes for the latter). */
 int kimad_workspace_bytes(const uint64_t* n, uint32_t L, uint32_t J,
                           const kimad_config_t* cfg, uint64_t* bytes_out);
 
@@ -248,8 +251,9 @@ int kimad_allocate_diagnostics(kimad_plan_t* plan, uint32_t* out4, void* stream)
  * stream).  For each layer larger than 8192 entries, 8 words are written to `out` (HOST):
  * layer index, spill bin (entries at or above this digit-1 bin were kept as candidates; 4096 = none),
  * slots fixed before the pass, slots filled from the candidates, redo flag, candidates kept,
- * candidates valid, selection mode of the last kimad_compress_ef (0 none, 1 read g and h,
- * 2 all entries, 3 from the candidates). */
+ * candidates valid (0 if the layer's candidate space ran out during the pass), selection mode of the last
+ * kimad_compress_ef (0 none, 1 g and h read again into the candidate space, 3 from the profile's candidates,
+ * 4 straight from g and h: everything is kept, or what had to be looked at did not fit the candidate space). */
 int kimad_plan_layer_states(kimad_plan_t* plan, uint32_t* out, uint32_t max_layers, uint32_t* count_out,
                             void* stream);
 
