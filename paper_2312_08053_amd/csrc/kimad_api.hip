@@ -410,10 +410,12 @@ int zero_range(kimad_plan* p, uint64_t begin, uint64_t end, hipStream_t s) {
 
 // Histogram passes + scans for a target table (the plan's grid, or one K per layer).
 // mark_fresh: the targets are the plan's grid, i.e. this is kimad_profile (see ProfileBuffers::fresh).
+// clear: the tables the passes add into (and the profile's "fresh" word) are cleared here; a caller that has
+// already cleared them, before it let other kernels of the same call start on the side stream, passes false.
 int run_select_passes(kimad_plan* p, const uint32_t* ktab_dev, uint32_t J, double* err_table, hipStream_t s,
-                      uint32_t mark_fresh = 0u) {
+                      uint32_t mark_fresh = 0u, bool clear = true) {
     const Layout& lo = p->lo;
-    int rc = zero_range(p, lo.zero1_begin, lo.zero1_end, s);
+    int rc = clear ? zero_range(p, lo.zero1_begin, lo.zero1_end, s) : KIMAD_OK;
     if (rc) return rc;
     if (lo.B) {
         KLAUNCH(p, s, "k_hist1", k_hist1, dim3(lo.ntiles), dim3(256), p->pb);
@@ -794,8 +796,11 @@ int kimad_profile(kimad_plan_t* p, double* err_table, uint64_t budget_hint_bytes
     hipStream_t ss = s;
     int rc;
     if (p->cfg.flags & KIMAD_CFG_CLASSIC_PROFILE) {
-        rc = launch_small_profile(p, err_table, s, &ss);
-        if (!rc) rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s, 1u);
+        // (the clearing comes before the fork: the small layers' kernel on the side stream marks the profile as
+        // fresh, and in a plan without tiled layers nothing marks it again)
+        rc = zero_range(p, lo.zero1_begin, lo.zero1_end, s);
+        if (!rc) rc = launch_small_profile(p, err_table, s, &ss);
+        if (!rc) rc = run_select_passes(p, at<uint32_t>(p, lo.ktab), lo.J, err_table, s, 1u, false);
     } else {
         rc = run_fused_profile(p, err_table, budget_hint_bytes / p->cfg.pair_bytes, s, &ss);
     }

@@ -290,3 +290,18 @@ def test_results_are_reproducible_and_profile_is_pure():
     torch.cuda.synchronize()
     assert torch.equal(a.view(torch.int64), b.view(torch.int64)), "table must be bit-reproducible"
     assert torch.equal(a.view(torch.int64), fresh.view(torch.int64)), "and the same on a new plan"
+
+
+@pytest.mark.parametrize("classic", [False, True])
+def test_profile_of_small_layers_only_can_be_reused(classic):
+    """A plan without a tiled layer: the small layers' kernel, on the side stream, is the only one that marks the
+    profile as fresh, and the clearing at the start of a profile must not overtake it (it did in the two-pass
+    profile: the compression then refused to reuse the thresholds, status STALE_PROFILE)."""
+    rng = np.random.default_rng(161)
+    sizes = [63, 1023, 4096, 5000, 1]
+    gs = [rng.standard_normal(n).astype(np.float32) for n in sizes]
+    hs = [np.zeros(n, np.float32) for n in sizes]
+    hs[1] = (0.5 * rng.standard_normal(1023)).astype(np.float32)
+    w = _work(gs, hs, GRID, budget_frac=0.1, D=50)
+    for _ in range(3):                                    # the race did not lose every time
+        _full_check(w, reuse=True, classic=classic)

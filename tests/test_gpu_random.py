@@ -78,7 +78,8 @@ def random_workload(seed):
     return w, opts
 
 
-@pytest.mark.parametrize("seed", range(16))
+# (seeds 102 to 563: configurations of small layers only, with the two-pass profile and reuse of its thresholds)
+@pytest.mark.parametrize("seed", list(range(24)) + [102, 161, 249, 331, 523, 563])
 def test_random_configuration(seed):
     w, opts = random_workload(seed)
     print(seed, w.sizes.tolist(), w.meta, len(w.ratios), w.budget_bytes, w.cost_units_D, opts, flush=True)
