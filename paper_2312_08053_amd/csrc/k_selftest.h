@@ -15,6 +15,9 @@ namespace kimad {
 // out_f64: [(k4 * 4 + u) * 64 + lane] = in_f64[lane] + in_f64[64 + 16 * (lane / 16) + 4 * k4 + u]
 //          (acc_rec_error4: the accumulator plus the error of lane K + u of the row)
 //          [1024 + t * 64 + lane], t = 0, 1, 2: maximum of in_f64 over the lane's group of 2, 4, 8 lanes (group_max)
+//          [1216 + t * 64 + lane], t = 0..3: the smallest in_f64 of the lane's group of 2, 4, 8, 16 lanes, and
+// out_u32: [1088 + t * 64 + lane]: the smallest in_u32[64 + lane'] & 255 among the lanes of the group that hold it
+//          (group_min_pair: the minimum of (value, record) pairs, the value first)
 __global__ __launch_bounds__(64) void k_selftest_wave(const uint32_t* in_u32, const double* in_f64, uint32_t* out_u32,
                                                       double* out_f64) {
     const uint32_t lane = threadIdx.x;
@@ -41,6 +44,14 @@ __global__ __launch_bounds__(64) void k_selftest_wave(const uint32_t* in_u32, co
     out_f64[1024 + lane] = group_max<2>(acc);
     out_f64[1024 + 64 + lane] = group_max<4>(acc);
     out_f64[1024 + 128 + lane] = group_max<8>(acc);
+    {
+        double v;
+        uint32_t k;
+        v = acc; k = second & 255u; group_min_pair<2>(v, k); out_f64[1216 + lane] = v; out_u32[1088 + lane] = k;
+        v = acc; k = second & 255u; group_min_pair<4>(v, k); out_f64[1216 + 64 + lane] = v; out_u32[1088 + 64 + lane] = k;
+        v = acc; k = second & 255u; group_min_pair<8>(v, k); out_f64[1216 + 128 + lane] = v; out_u32[1088 + 128 + lane] = k;
+        v = acc; k = second & 255u; group_min_pair<16>(v, k); out_f64[1216 + 192 + lane] = v; out_u32[1088 + 192 + lane] = k;
+    }
 }
 
 }  // namespace kimad
