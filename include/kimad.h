@@ -305,8 +305,9 @@ int kimad_plan_get_timings(kimad_plan_t* plan, char* names, uint32_t names_bytes
 
 /* Self-test of the kernels' wave-level building blocks that are written with DPP operands (the 64-lane prefix sum
  * of the streaming pass, the row-broadcast address and accumulate steps of the allocation's recurrence, the
- * group maxima of its bounds and the pair minima of its banded recurrence): one wave runs each on the given per-lane inputs and writes every lane's result, for
- * a test to compare with host-computed values.  All pointers DEVICE:
+ * group maxima of its bounds and the pair minima of its banded recurrence): one wave runs each on the given
+ * per-lane inputs and writes every lane's result, for a test to compare with host-computed values.  All
+ * pointers DEVICE:
  *   in_u32 uint32[128], in_f64 double[128], out_u32 uint32[64 + 1024 + 256], out_f64 double[1024 + 192 + 256];
  *   out_u32[lane]                          = in_u32[0] + ... + in_u32[lane]
  *   out_u32[64 + (4 k + u) * 64 + lane]    = in_u32[lane] + in_u32[64 + 16 (lane / 16) + 4 k + u]      k, u = 0..3
