@@ -23,7 +23,9 @@
  *     default stream): it is enqueued there, except that kernels for layers of at most 8192
  *     entries run on a side stream of the plan between a fork and a join event on the given
  *     stream.  No call waits for the device except kimad_plan_create (synchronous uploads) and
- *     the diagnostics getters.
+ *     the diagnostics getters.  kimad_profile, kimad_allocate, kimad_compress_ef, kimad_step and
+ *     kimad_server_apply may be recorded into a HIP graph by stream capture (per-kernel timing off): tables
+ *     are cleared by kernels, and the recording holds the pointers and the budget of the recorded call.
  *   - Return value: 0 on success, a negative kimad_status otherwise (argument errors are found
  *     on the host before anything is enqueued).  Data-dependent outcomes (infeasible budget,
  *     non-finite table, a K that is not on the grid) are written to a DEVICE status word.

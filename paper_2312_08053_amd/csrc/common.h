@@ -128,9 +128,6 @@ __device__ __forceinline__ uint64_t ballot(bool p) { return __ballot(p); }
 
 // Orders one wave's LDS accesses: what its lanes wrote before is what its lanes read after (the hardware runs a
 // wave's LDS instructions in order; this keeps the compiler from moving them across).
-// The same for a kernel of a single wave that also has global stores in flight: it waits for the wave's LDS
-// operations only (the fences above also wait for the acknowledgement of every global store).
-__device__ __forceinline__ void wave_lds_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 __device__ __forceinline__ void wave_sync_lds() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();

@@ -51,13 +51,6 @@ struct BandBuffers {
     uint32_t* live_jj;     // [L * J] first member | last member << 8
 };
 
-template <typename T>
-__device__ __forceinline__ T wave_sum(T v) {
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) v += __shfl_xor(v, d, 64);
-    return v;
-}
-
 __device__ __forceinline__ double max_f64(double a, double b) {   // neither a signalling NaN (see min_f64)
     double r;
     asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));

@@ -202,7 +202,7 @@ __device__ __forceinline__ void compact_tiles(const CompressBuffers& cb, uint32_
 
         // flags: bit c of sel[u] = candidate, of amb[u] = ambiguous
         uint32_t selm[NQ], ambm[NQ];
-        uint32_t mine = 0, mine_amb = 0;
+        uint32_t mine_amb = 0;
 #pragma unroll
         for (int u = 0; u < (int)NQ; ++u) {
             selm[u] = 0; ambm[u] = 0;
@@ -214,11 +214,11 @@ __device__ __forceinline__ void compact_tiles(const CompressBuffers& cb, uint32_
                 const bool all = S.mode == SEL_DIRECT && S.amb == 0u;
                 const bool sure = all || p > S.prefix;
                 const bool amb = !all && p == S.prefix;
-                if (sure || amb) { selm[u] |= 1u << c; ++mine; }
+                if (sure || amb) selm[u] |= 1u << c;
                 if (amb) { ambm[u] |= 1u << c; ++mine_amb; }
             }
         }
-        // wave totals and the exclusive prefix of `mine` over lanes, per quad row
+        // wave totals and the exclusive prefix of the lanes' counts, per quad row
         uint32_t total = 0, total_amb = 0;
         uint32_t rowbase[NQ];                   // candidates in earlier rows + earlier lanes of this row
 #pragma unroll

@@ -83,12 +83,10 @@ __global__ __launch_bounds__(SAMPLE_THREADS) void k_sample(ProfileBuffers pb) {
 // `counts` / `gcounts`: per layer and summed digit-1 counts to predict from: the sample of k_sample (scaled to the
 // population through the layer's size), or the exact histogram of the previous profile on this plan (successive
 // gradients of a layer are distributed alike; a layer whose boundary bins moved is recounted like any other
-// misprediction).  `gzero`: 4096 words this launch clears for the totals of the pass that follows.  `fold_zero`:
-// also clear what a profile must find at zero (no separate clearing launch).
+// misprediction).  `fold_zero`: also clear what a profile must find at zero (no separate clearing launch).
 __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
                                                  unsigned long long budget_pairs, const uint32_t* __restrict__ counts,
-                                                 const unsigned long long* __restrict__ gcounts,
-                                                 unsigned long long* gzero, uint32_t fold_zero) {
+                                                 const unsigned long long* __restrict__ gcounts, uint32_t fold_zero) {
     __shared__ uint32_t above[D1_BINS];        // sample entries in strictly higher bins
     __shared__ uint32_t bitmap[D1_BINS / 32];
     __shared__ uint32_t su[16];
@@ -220,8 +218,6 @@ __global__ __launch_bounds__(256) void k_predict(ProfileBuffers pb, const uint32
         st.spill_cnt = 0; st.spill_valid = 0; st.slot_lo = lo_bin; st.pad = 0;
         pb.state[big] = st;
     }
-    if (big == 0u && gzero)
-        for (uint32_t b = tid; b < D1_BINS; b += 256) gzero[b] = 0ull;
     if (fold_zero) {
         // chunk records start out as "nothing spilled": every workgroup clears an equal share of all layers' records
         // (a layer's own workgroup clearing them made the largest layer's the last to finish by far)
@@ -567,6 +563,10 @@ __global__ __launch_bounds__(256) void k_reduce_parts(ProfileBuffers pb) {
     __shared__ unsigned long long sh_c[3][REDUCE_ENTRIES], sh_t[3][REDUCE_ENTRIES];
     const uint32_t big = blockIdx.y, lane = threadIdx.x & 63u, w = threadIdx.x >> 6;
     const uint32_t e = blockIdx.x * REDUCE_ENTRIES + 2u * lane;     // and e + 1; `used` is even
+    // The totals over the layers that the prediction of this profile read are done with (that launch has ended), and
+    // the scan that follows this one adds the new ones up: cleared here, between the two.
+    if (blockIdx.x == 0u && big == 0u)
+        for (uint32_t b = threadIdx.x; b < D1_BINS; b += 256u) pb.gprev[b] = 0ull;
     const uint32_t used = D1_BINS + pb.state[big].nslots_d * D2_BINS;
     const uint32_t p0 = pb.big_part0[big], np = pb.big_nparts[big];
     unsigned long long cnt[2] = {0, 0}, t[2] = {0, 0};
@@ -626,8 +626,7 @@ __global__ __launch_bounds__(256) void k_reduce_parts(ProfileBuffers pb) {
 //   - its bin already has a slot                          -> nothing
 //   - its bin is in the spilled range                     -> a slot PRE_SLOTS.. filled from the candidates
 //   - neither (prediction missed), or slots run out       -> redo: exact slots, full recount
-__global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J,
-                                                unsigned long long* gacc) {
+__global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_t* Ktab, uint32_t J) {
     __shared__ uint32_t cnt[D1_BINS];
     __shared__ uint32_t above[D1_BINS];
     __shared__ double below[D1_BINS];
@@ -710,7 +709,7 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
         for (int k = 0; k < 4; ++k) hp[k] = make_uint4(c[4 * k], c[4 * k + 1], c[4 * k + 2], c[4 * k + 3]);
 #pragma unroll
         for (int k = 0; k < 16; ++k)
-            if (c[k]) atomicAdd(&gacc[tid * 16u + k], (unsigned long long)c[k]);
+            if (c[k]) atomicAdd(&pb.gprev[tid * 16u + k], (unsigned long long)c[k]);
     }
     uint32_t ctot;
     const uint32_t cex = block_exclusive_scan<uint32_t>(csum, su, &ctot);

@@ -37,7 +37,7 @@ struct ProfileBuffers {
                                   // [2] pool entries handed out
     // exact digit-1 histograms of the last single-pass profile: the prediction of the next one
     uint32_t* hprev;              // [B][4096]
-    unsigned long long* gprev;    // [2][4096] their sum over the layers, alternating between calls
+    unsigned long long* gprev;    // [4096] their sum over the layers
     uint32_t* fresh;              // 1 while the threshold cache and the candidates describe the current g - h:
                                   // set by the profile's last kernels, cleared by the compression
     // exact fallback for entries whose bound is not tight: last-digit histograms of their prefix bins

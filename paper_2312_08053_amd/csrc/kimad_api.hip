@@ -232,7 +232,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.rec_cnt = take(4ull * (nc ? nc : 1));              // chunk records start out as "nothing spilled"
     lo.zero1_end = off;
     lo.hprev = take(4ull * B * D1_BINS);
-    lo.gprev = take(2ull * 8ull * D1_BINS);
+    lo.gprev = take(8ull * D1_BINS);
     lo.pool_prefix = take(4ull * lo.pool_cap);
     lo.pool_big = take(4ull * lo.pool_cap);
     lo.pool_t0 = take(4ull * lo.pool_cap);
@@ -353,9 +353,8 @@ struct kimad_plan {
     hipStream_t side = nullptr;
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     // The single-pass profile predicts from the exact histogram its previous run on this plan left behind, once
-    // there is one (stream order makes it visible): hist_cur = which of the two total buffers holds it.
+    // there is one (stream order makes it visible).
     bool hist_valid = false;
-    uint32_t hist_cur = 0;
     ~kimad_plan() {
         for (hipEvent_t e : ev) (void)hipEventDestroy(e);
         if (ev_fork) (void)hipEventDestroy(ev_fork);
@@ -458,27 +457,23 @@ int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, h
         return launch_small_profile(p, err_table, s, side);
     }
     int rc = KIMAD_OK;
-    unsigned long long* gprev = at<unsigned long long>(p, lo.gprev);
-    unsigned long long* g_last = gprev + (size_t)p->hist_cur * D1_BINS;         // totals of the previous profile
-    unsigned long long* g_next = gprev + (size_t)(p->hist_cur ^ 1u) * D1_BINS;  // where this one's go
     if (p->hist_valid && !(p->cfg.flags & KIMAD_CFG_SAMPLE_ALWAYS)) {
         // prediction from the previous profile's exact histogram: no sampling pass, no clearing launch
         KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs,
-                (const uint32_t*)p->pb.hprev, (const unsigned long long*)g_last, g_next, 1u);
+                (const uint32_t*)p->pb.hprev, (const unsigned long long*)p->pb.gprev, 1u);
     } else {
         rc = zero_range(p, lo.zero1_mid, lo.zero1_end, s);   // the histogram tables are written whole by k_reduce_parts
         if (rc) return rc;
         KLAUNCH(p, s, "k_sample", k_sample, dim3(lo.nswg), dim3(SAMPLE_THREADS), p->pb);
         KLAUNCH(p, s, "k_predict", k_predict, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, (unsigned long long)budget_pairs,
-                (const uint32_t*)p->pb.shist, (const unsigned long long*)p->pb.ghist, g_next, 0u);
+                (const uint32_t*)p->pb.shist, (const unsigned long long*)p->pb.ghist, 0u);
     }
     p->hist_valid = true;
-    p->hist_cur ^= 1u;
     KLAUNCH(p, s, "k_main", k_main, dim3(p->main_wgs), dim3(FUSED_THREADS), p->pb, p->chunks_per_wg);
     KLAUNCH(p, s, "k_reduce_parts", k_reduce_parts, dim3((LAYER_ENTRIES + REDUCE_ENTRIES - 1) / REDUCE_ENTRIES, lo.B), dim3(256), p->pb);
     rc = launch_small_profile(p, err_table, s, side);
     if (rc) return rc;
-    KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J, g_next);
+    KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J);
     KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG), dim3(256), p->pb);
     // fallbacks that normally find nothing to do: small grids
     KLAUNCH(p, s, "k_hist2", k_hist2, dim3(std::min<uint32_t>(lo.ntiles, FALLBACK_GRID)), dim3(512), p->pb, lo.ntiles,
@@ -566,7 +561,6 @@ int enqueue_allocate(kimad_plan* p, const AllocScratch& ws, const double* err_ta
         double* rows_g = ws.rows_g;
         const uint32_t rstride = ws.rstride;
         KLAUNCH(p, s, "k_dp_prep", k_dp_prep, dim3(lo.L), dim3(64), ab, dl);
-        double* last_row = rows_g + (size_t)lo.L * rstride;
         const bool band = (p->cfg.flags & KIMAD_CFG_BAND_DP) || cap + 1 >= BAND_AUTO_CELLS;
         if (lo.L <= BAND_MAX_L && band && !(p->cfg.flags & KIMAD_CFG_FULL_DP)) {
             // the recurrence inside the band of cells that Lagrangian bounds leave (same result, a fraction of the cells)
@@ -743,7 +737,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
         hipMemsetAsync(p->ws + lo.zero2_begin, 0, lo.zero2_end - lo.zero2_begin, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.band_info, 0, 64, s) != hipSuccess ||
         hipMemsetAsync(p->ws + lo.fresh, 0, 16, s) != hipSuccess ||
-        hipMemsetAsync(p->ws + lo.gprev, 0, 2ull * 8ull * D1_BINS, s) != hipSuccess ||
+        hipMemsetAsync(p->ws + lo.gprev, 0, 8ull * D1_BINS, s) != hipSuccess ||
         hipStreamSynchronize(s) != hipSuccess) { delete p; return KIMAD_ERR_HIP; }
 
     CompressBuffers& cb = p->cb;
