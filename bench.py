@@ -52,7 +52,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one worker on one GPU; --gpus must be 1 "
-              "(the path has no exchange between workers, see DESIGN.md)", file=sys.stderr)
+              "(one worker's step has no exchange between workers: M GPUs run M independent instances)", file=sys.stderr)
         return 2
 
     import numpy as np

@@ -316,7 +316,7 @@ def test_prediction_from_the_previous_rounds_histogram():
     spilled = max(st["spill_cnt"] / w0.sizes[st["layer"]] for st in states)
     overflowed = sum(1 for st in states if not st["spill_valid"])
     print("layers recounted per round (from history, from a sample):", redo, "largest share above the spill bin in "
-          "round 3:", spilled, "layers whose candidate region overflowed:", overflowed)
+          "the last round of the chain:", spilled, "layers whose candidate region overflowed:", overflowed)
     # the rescaled round was mispredicted, and absorbed: nearly everything lay above the stale spill bin, far more
     # than a layer's candidate region (about a sixth of it) holds, so those layers were recounted and compressed from g and h
     assert spilled > 0.5 and overflowed > 0 and redo[3][0] >= overflowed
