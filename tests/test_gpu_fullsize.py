@@ -2,9 +2,9 @@
 
 * the 124M-element GPT-2-shaped set: every layer's error row, payload and estimator against the oracle,
   and the allocation for the discretisation factors 1000, 4096 and 0 (exact cost axis) on that table;
-* the 1.3G-element Llama-shaped set, step 0 of its chain: properties that hold at any size on every
-  layer, and the oracle on a sample of nine layers (the oracle sorts 65M elements in about ten seconds;
-  all 218 layers would take minutes);
+* the 1.3G-element Llama-shaped set, steps 0 to 2 of its chain with the estimator carried over: properties
+  that hold at any size on every layer, and the oracle's own chain on a sample of ten layers (the oracle sorts
+  65M elements in about ten seconds; all 218 layers would take minutes);
 * the chain of that configuration (100 consecutive steps, persistent estimator, budgets from the seeded
   1-10 Gbit/s x 50 ms random walk) on a reduced variant of the same architecture, with a stop after
   step 50: the estimator is copied to the host and back into fresh buffers and a fresh plan, and the
@@ -97,60 +97,87 @@ def test_gpt2_full_size_every_layer_against_the_oracle():
 
 
 @pytest.mark.timeout(1200)
-def test_llama_full_size_first_step_of_the_chain():
+def test_llama_full_size_first_three_steps_of_the_chain():
+    """Steps 0, 1 and 2 of the Llama-shaped configuration at full size: a fresh gradient each step (the per-layer
+    scales fixed), the estimator carried over on the device, the budget of step k from the seeded 1-10 Gbit/s walk.
+    On every layer and every step: the properties that identify TopK and the estimator update, checked with numpy
+    against the estimator as it stood before the step (so, by induction over the steps, the carried estimator is
+    the one the oracle's chain would hold).  On a sample of layers the oracle itself runs its own chain, table row,
+    payload and estimator, from its own carried estimator, and must agree bit for bit."""
     import torch
     import paper_2312_08053_amd as kimad
+    steps = 3
     print("llama full size: generating 1.3e9 values", flush=True)
     work = ks.make_workload("llama")
     assert work.L == 218 and work.d == 1_298_761_728
-    budget = ks.budget_from_bandwidth(float(ks.bandwidth_trace(1)[0]))        # 5.5 Gbit/s x 50 ms
+    trace = ks.bandwidth_trace(steps)
+    assert float(trace[0]) == 5.5                                             # the walk starts at 5.5 Gbit/s (x 50 ms)
+    budgets = [ks.budget_from_bandwidth(float(b)) for b in trace]
     g = torch.from_numpy(work.g).cuda()
     h = torch.from_numpy(work.h).cuda()
     plan = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes,
-                      D=work.cost_units_D, max_budget_bytes=budget, capacity_pairs=budget // work.pair_bytes + 1)
-    print("llama full size: step on the device", flush=True)
-    status = plan.step(budget)
-    torch.cuda.synchronize()
-    assert status.cpu().tolist() == [0, 0]
+                      D=work.cost_units_D, max_budget_bytes=max(budgets),
+                      capacity_pairs=max(budgets) // work.pair_bytes + 1)
     Kt = plan.grid_sizes()
-    E_gpu = plan.err_table.cpu().numpy().reshape(work.L, -1)
-    K = plan.K.cpu().numpy().astype(np.uint64)
-    off = plan.offsets.cpu().numpy().astype(np.uint64)
-    st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, budget, work.pair_bytes, work.cost_units_D)
-    assert st == ko.OK
-    assert np.array_equal(plan.j.cpu().numpy(), j_ref)
-    assert np.array_equal(K, K_ref) and np.array_equal(off, off_ref)
-    assert work.pair_bytes * int(off[-1]) <= budget
-
-    # invariants of the table on every layer: non-increasing along the grid, exactly 0 at K = n, never
-    # above the bound of the paper's compressor class, E(K) <= (1 - K/n) ||x||^2 (fp64 norm from numpy)
-    gL, hL = gh.oracle_layers(work)
-    idx = gh.u32(plan.idx)
-    val = plan.val.cpu().numpy()
-    h_new = h.cpu().numpy()
-    for i in range(work.L):
-        if i % 20 == 0:
-            print(f"llama full size: properties of layer {i}", flush=True)
-        x = ko.operand(gL[i], hL[i])
-        n = len(x)
-        row = E_gpu[i]
-        assert np.all(row[1:] <= row[:-1]) and np.all(row >= 0.0)
-        assert np.all(row[Kt[i] == n] == 0.0)
-        norm2 = float(np.dot(x.astype(np.float64), x.astype(np.float64)))
-        assert np.all(row <= (1.0 - Kt[i] / n) * norm2 * (1 + 1e-5))
-        a, b = int(off[i]), int(off[i + 1])
-        assert b - a == int(K[i])
-        _selection_properties(x, idx[a:b].astype(np.int64), hL[i], h_new[work.starts[i]:work.starts[i + 1]], val[a:b])
-
-    # the oracle on nine layers: the embedding (65.5M entries, the largest), the first block's nine kinds
-    # of tensor except two of its four attention matrices, a middle matrix, the last matrix and vector
+    starts = work.starts
+    # the oracle's own chain on ten layers: the embedding (65.5M entries, the largest), the first block's nine
+    # kinds of tensor except two of its four attention matrices, a middle matrix, the last matrix and vector
     sample = [0, 1, 2, 5, 6, 7, 9, 113, 216, 217]
-    for i in sample:
-        print(f"llama full size: oracle on layer {i}", flush=True)
-        x = ko.operand(gL[i], hL[i])
-        rowref = ko.topk_error_profile(x, Kt[i])
-        gh.assert_table_close(E_gpu[i:i + 1], rowref[None, :], Kt[i:i + 1], work.sizes[i:i + 1])
-    gh.check_compress(work, plan, h, K, off, plan.idx, plan.val, layers=sample)
+    h_ref = {i: work.layer_views(work.h)[i].copy() for i in sample}
+    h_old = work.h                                                            # the estimator before the step, on the host
+    for t in range(steps):
+        if t:
+            print(f"llama full size: generating the gradient of step {t}", flush=True)
+            work = ks.make_workload("llama", step=t)
+            g.copy_(torch.from_numpy(work.g))
+        budget = budgets[t]
+        print(f"llama full size: step {t} on the device, budget {budget} bytes", flush=True)
+        status = plan.step(budget)
+        torch.cuda.synchronize()
+        assert status.cpu().tolist() == [0, 0], t
+        E_gpu = plan.err_table.cpu().numpy().reshape(work.L, -1)
+        K = plan.K.cpu().numpy().astype(np.uint64)
+        off = plan.offsets.cpu().numpy().astype(np.uint64)
+        st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, budget, work.pair_bytes, work.cost_units_D)
+        assert st == ko.OK
+        assert np.array_equal(plan.j.cpu().numpy(), j_ref)
+        assert np.array_equal(K, K_ref) and np.array_equal(off, off_ref)
+        assert work.pair_bytes * int(off[-1]) <= budget
+
+        # invariants of the table on every layer: non-increasing along the grid, exactly 0 at K = n, never
+        # above the bound of the paper's compressor class, E(K) <= (1 - K/n) ||x||^2 (fp64 norm from numpy)
+        gL = work.layer_views(work.g)
+        idx = gh.u32(plan.idx)
+        val = plan.val.cpu().numpy()
+        h_new = h.cpu().numpy()
+        for i in range(work.L):
+            if i % 40 == 0:
+                print(f"llama full size: step {t}, properties of layer {i}", flush=True)
+            h_before = h_old[starts[i]:starts[i + 1]]
+            x = ko.operand(gL[i], h_before)
+            n = len(x)
+            row = E_gpu[i]
+            assert np.all(row[1:] <= row[:-1]) and np.all(row >= 0.0)
+            assert np.all(row[Kt[i] == n] == 0.0)
+            norm2 = float(np.dot(x.astype(np.float64), x.astype(np.float64)))
+            assert np.all(row <= (1.0 - Kt[i] / n) * norm2 * (1 + 1e-5))
+            a, b = int(off[i]), int(off[i + 1])
+            assert b - a == int(K[i])
+            _selection_properties(x, idx[a:b].astype(np.int64), h_before, h_new[starts[i]:starts[i + 1]], val[a:b])
+
+        for i in sample:
+            print(f"llama full size: step {t}, oracle on layer {i}", flush=True)
+            assert np.array_equal(h_old[starts[i]:starts[i + 1]].view(np.uint32), h_ref[i].view(np.uint32))
+            x = ko.operand(gL[i], h_ref[i])
+            rowref = ko.topk_error_profile(x, Kt[i])
+            gh.assert_table_close(E_gpu[i:i + 1], rowref[None, :], Kt[i:i + 1], work.sizes[i:i + 1])
+            li, lv, lh = ko.compress_ef_layer(gL[i], h_ref[i], int(K[i]))
+            a, b = int(off[i]), int(off[i + 1])
+            assert np.array_equal(idx[a:b], li), (t, i)
+            assert np.array_equal(val[a:b].view(np.uint32), lv.view(np.uint32)), (t, i)
+            assert np.array_equal(h_new[starts[i]:starts[i + 1]].view(np.uint32), lh.view(np.uint32)), (t, i)
+            h_ref[i] = lh
+        h_old = h_new
 
 
 @pytest.mark.timeout(900)
