@@ -595,6 +595,7 @@ __global__ __launch_bounds__(256) void k_reduce_parts(ProfileBuffers pb) {
         cnt[0] += sh_c[q][2 * lane]; cnt[1] += sh_c[q][2 * lane + 1];
         t[0] += sh_t[q][2 * lane]; t[1] += sh_t[q][2 * lane + 1];
     }
+    unsigned long long slot_sq = 0;               // this lane's share of the slot's total (blocks beyond the digit-1 bins)
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
         const uint32_t eu = e + (uint32_t)u;
@@ -616,6 +617,23 @@ __global__ __launch_bounds__(256) void k_reduce_parts(ProfileBuffers pb) {
             const size_t o = (size_t)big * SLOT_STRIDE * D2_BINS + (eu - D1_BINS);
             pb.cnt2[o] = (uint32_t)cnt[u];
             reinterpret_cast<unsigned long long*>(pb.sq2)[o] = s2;
+            slot_sq += s2;
+        }
+    }
+    // a workgroup beyond the digit-1 bins holds exactly one slot: its totals, which stand for the slot's bin in the
+    // digit-1 histogram (the pass counts an entry of a slot bin in the slot only), go out with it
+    static_assert(REDUCE_ENTRIES == D2_BINS && D1_BINS % REDUCE_ENTRIES == 0, "one workgroup per slot");
+    if (blockIdx.x >= D1_BINS / REDUCE_ENTRIES) {
+        unsigned long long slot_cnt = cnt[0] + cnt[1];
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) {
+            slot_cnt += __shfl_xor(slot_cnt, d, 64);
+            slot_sq += __shfl_xor(slot_sq, d, 64);
+        }
+        if (lane == 0) {
+            const size_t o = (size_t)big * SLOT_STRIDE + (blockIdx.x - D1_BINS / REDUCE_ENTRIES);
+            pb.slot_cnt[o] = (uint32_t)slot_cnt;
+            pb.slot_sq[o] = slot_sq;
         }
     }
 }
@@ -662,28 +680,13 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
         uint32_t* dst = reinterpret_cast<uint32_t*>(lut);
         for (uint32_t b = tid; b < D1_BINS / 4; b += 256) dst[b] = src[b];
     }
-    if (tid == 0) sh_redo = 0u;
-    __syncthreads();
-
-    // totals of the slots: two threads per slot, 64 digit-2 bins each, every load issued at once
-    static_assert(PRE_SLOTS <= 128, "two threads per slot in a workgroup of 256");
-    {
-        const uint32_t slot = tid >> 1, half = tid & 1u;
-        uint32_t cc = 0;
-        unsigned long long ss = 0;
-        if (slot < st.nslots_d) {
-            const size_t e0 = ((size_t)big * SLOT_STRIDE + slot) * D2_BINS + half * (D2_BINS / 2);
-            const uint4* c4 = reinterpret_cast<const uint4*>(pb.cnt2 + e0);
-            const ulonglong2* s2 = reinterpret_cast<const ulonglong2*>(pb.sq2 + e0);
-#pragma unroll
-            for (int k = 0; k < (int)D2_BINS / 8; ++k) { const uint4 v = c4[k]; cc += v.x + v.y + v.z + v.w; }
-#pragma unroll
-            for (int k = 0; k < (int)D2_BINS / 4; ++k) { const ulonglong2 v = s2[k]; ss += v.x + v.y; }
-        }
-        cc += __shfl_xor(cc, 1, 64);
-        ss += __shfl_xor(ss, 1, 64);
-        if (half == 0u && slot < st.nslots_d) { slot_c[slot] = cc; slot_s[slot] = ss; }
+    // totals of the slots the pass counted (k_reduce_parts summed them)
+    static_assert(PRE_SLOTS <= 256, "one thread per slot");
+    if (tid < st.nslots_d) {
+        slot_c[tid] = pb.slot_cnt[(size_t)big * SLOT_STRIDE + tid];
+        slot_s[tid] = pb.slot_sq[(size_t)big * SLOT_STRIDE + tid];
     }
+    if (tid == 0) sh_redo = 0u;
     __syncthreads();
     uint32_t c[16];
     double s[16];
@@ -707,9 +710,6 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
         uint4* hp = reinterpret_cast<uint4*>(pb.hprev + (size_t)big * D1_BINS + tid * 16u);
 #pragma unroll
         for (int k = 0; k < 4; ++k) hp[k] = make_uint4(c[4 * k], c[4 * k + 1], c[4 * k + 2], c[4 * k + 3]);
-#pragma unroll
-        for (int k = 0; k < 16; ++k)
-            if (c[k]) atomicAdd(&pb.gprev[tid * 16u + k], (unsigned long long)c[k]);
     }
     uint32_t ctot;
     const uint32_t cex = block_exclusive_scan<uint32_t>(csum, su, &ctot);
@@ -729,6 +729,12 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
     }
     for (uint32_t b = tid; b < D1_BINS; b += 256) glutc[b] = (uint8_t)NO_SLOT;
     __syncthreads();
+    // the sum over the layers: neighbouring lanes add to neighbouring bins (a lane adding its own sixteen bins
+    // touched 64 cache lines per instruction, and the additions of all layers queue up on the same lines)
+    for (uint32_t b = tid; b < D1_BINS; b += 256) {
+        const uint32_t cb = cnt[b];
+        if (cb) atomicAdd(&pb.gprev[b], (unsigned long long)cb);
+    }
 
     const uint32_t spill_cnt = st.spill_bin >= D1_BINS ? 0u
                              : (st.spill_bin == 0u ? ctot : above[st.spill_bin - 1u]);

@@ -24,6 +24,8 @@ struct ProfileBuffers {
     // pass 2
     uint32_t* cnt2;               // [B][SLOT_STRIDE][128]
     uint64_t* sq2;                // [B][SLOT_STRIDE][128]
+    uint32_t* slot_cnt;           // [B][SLOT_STRIDE] totals of the slots the single pass counted itself (k_reduce_parts)
+    uint64_t* slot_sq;            // [B][SLOT_STRIDE]
     // per target (layer-major, stride J)
     uint32_t* tgt_slot;           // slot, or NO_SLOT when K == n (nothing dropped)
     uint32_t* tgt_r;              // entries selected inside the boundary bin (1..count)

@@ -50,7 +50,7 @@ struct Layout {
     uint32_t main_wgs = 256, chunks_per_wg = 1, nparts = 0;
     uint64_t pool_prefix, pool_big, pool_t0, pool_cnt, pool_hist, tgt_unsel, tgt_base;
     uint32_t pool_cap = 1;
-    uint64_t lut1, nslots, slot_bin;
+    uint64_t lut1, nslots, slot_bin, slot_cnt, slot_sq;
     uint64_t tgt_slot, tgt_r, tgt_above1, tgt_below, sel_prefix, sel_above, sel_amb;
     // compress
     uint64_t ksel, sel, zero2_begin, hist3, zero2_end, tau, quota, cblk_big;
@@ -241,6 +241,8 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.tgt_base = take(8 * LJ);
     lo.lut1 = take(1ull * B * D1_BINS);
     lo.nslots = take(4ull * (B ? B : 1));
+    lo.slot_cnt = take(4ull * (B ? B : 1) * SLOT_STRIDE);
+    lo.slot_sq = take(8ull * (B ? B : 1) * SLOT_STRIDE);
     lo.slot_bin = take(4ull * B * SLOT_STRIDE);
     lo.tgt_slot = take(4 * LJ);
     lo.tgt_r = take(4 * LJ);
@@ -708,6 +710,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.tile_elems = lo.tile_elems;
     pb.cnt1 = at<uint32_t>(p, lo.cnt1); pb.sq1 = at<uint64_t>(p, lo.sq1);
     pb.lut1 = at<uint8_t>(p, lo.lut1); pb.nslots = at<uint32_t>(p, lo.nslots); pb.slot_bin = at<uint32_t>(p, lo.slot_bin);
+    pb.slot_cnt = at<uint32_t>(p, lo.slot_cnt); pb.slot_sq = at<uint64_t>(p, lo.slot_sq);
     pb.cnt2 = at<uint32_t>(p, lo.cnt2); pb.sq2 = at<uint64_t>(p, lo.sq2);
     pb.tgt_slot = at<uint32_t>(p, lo.tgt_slot); pb.tgt_r = at<uint32_t>(p, lo.tgt_r);
     pb.tgt_above1 = at<uint32_t>(p, lo.tgt_above1); pb.tgt_below = at<double>(p, lo.tgt_below);

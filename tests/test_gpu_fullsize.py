@@ -96,88 +96,112 @@ def test_gpt2_full_size_every_layer_against_the_oracle():
         del p2
 
 
-@pytest.mark.timeout(1200)
-def test_llama_full_size_first_three_steps_of_the_chain():
-    """Steps 0, 1 and 2 of the Llama-shaped configuration at full size: a fresh gradient each step (the per-layer
-    scales fixed), the estimator carried over on the device, the budget of step k from the seeded 1-10 Gbit/s walk.
-    On every layer and every step: the properties that identify TopK and the estimator update, checked with numpy
-    against the estimator as it stood before the step (so, by induction over the steps, the carried estimator is
-    the one the oracle's chain would hold).  On a sample of layers the oracle itself runs its own chain, table row,
-    payload and estimator, from its own carried estimator, and must agree bit for bit."""
+# Steps 0, 1 and 2 of the Llama-shaped configuration at full size: a fresh gradient each step (the per-layer scales
+# fixed), the estimator carried over on the device, the budget of step k from the seeded 1-10 Gbit/s walk.  One test
+# per step (a minute each), sharing the chain's state.  On every layer and every step: the properties that identify
+# TopK and the estimator update, checked with numpy against the estimator as it stood before the step (so, by
+# induction over the steps, the carried estimator is the one the oracle's chain would hold).  On a sample of layers
+# the oracle itself runs its own chain, table row, payload and estimator, from its own carried estimator, and must
+# agree bit for bit.
+_LLAMA_STEPS = 3
+_llama_chain = {}
+
+
+def _llama_chain_step(t):
     import torch
     import paper_2312_08053_amd as kimad
-    steps = 3
-    print("llama full size: generating 1.3e9 values", flush=True)
-    work = ks.make_workload("llama")
-    assert work.L == 218 and work.d == 1_298_761_728
-    trace = ks.bandwidth_trace(steps)
-    assert float(trace[0]) == 5.5                                             # the walk starts at 5.5 Gbit/s (x 50 ms)
-    budgets = [ks.budget_from_bandwidth(float(b)) for b in trace]
-    g = torch.from_numpy(work.g).cuda()
-    h = torch.from_numpy(work.h).cuda()
-    plan = kimad.Plan(g, h, work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes,
-                      D=work.cost_units_D, max_budget_bytes=max(budgets),
-                      capacity_pairs=max(budgets) // work.pair_bytes + 1)
+    c = _llama_chain
+    if t == 0:
+        c.clear()
+        print("llama full size: generating 1.3e9 values", flush=True)
+        work = ks.make_workload("llama")
+        assert work.L == 218 and work.d == 1_298_761_728
+        trace = ks.bandwidth_trace(_LLAMA_STEPS)
+        assert float(trace[0]) == 5.5                                         # the walk starts at 5.5 Gbit/s (x 50 ms)
+        c["budgets"] = [ks.budget_from_bandwidth(float(b)) for b in trace]
+        c["g"] = torch.from_numpy(work.g).cuda()
+        c["h"] = torch.from_numpy(work.h).cuda()
+        c["plan"] = kimad.Plan(c["g"], c["h"], work.sizes.tolist(), work.ratios.tolist(), pair_bytes=work.pair_bytes,
+                               D=work.cost_units_D, max_budget_bytes=max(c["budgets"]),
+                               capacity_pairs=max(c["budgets"]) // work.pair_bytes + 1)
+        # the oracle's own chain on ten layers: the embedding (65.5M entries, the largest), the first block's nine
+        # kinds of tensor except two of its four attention matrices, a middle matrix, the last matrix and vector
+        c["sample"] = [0, 1, 2, 5, 6, 7, 9, 113, 216, 217]
+        c["h_ref"] = {i: work.layer_views(work.h)[i].copy() for i in c["sample"]}
+        c["h_old"] = work.h                                                   # the estimator before the step, on the host
+        c["done"] = 0
+    else:
+        if c.get("done") != t:
+            pytest.skip(f"step {t - 1} of the chain did not complete")
+        print(f"llama full size: generating the gradient of step {t}", flush=True)
+        work = ks.make_workload("llama", step=t)
+        c["g"].copy_(torch.from_numpy(work.g))
+    plan, h, sample, h_ref, h_old = c["plan"], c["h"], c["sample"], c["h_ref"], c["h_old"]
     Kt = plan.grid_sizes()
     starts = work.starts
-    # the oracle's own chain on ten layers: the embedding (65.5M entries, the largest), the first block's nine
-    # kinds of tensor except two of its four attention matrices, a middle matrix, the last matrix and vector
-    sample = [0, 1, 2, 5, 6, 7, 9, 113, 216, 217]
-    h_ref = {i: work.layer_views(work.h)[i].copy() for i in sample}
-    h_old = work.h                                                            # the estimator before the step, on the host
-    for t in range(steps):
-        if t:
-            print(f"llama full size: generating the gradient of step {t}", flush=True)
-            work = ks.make_workload("llama", step=t)
-            g.copy_(torch.from_numpy(work.g))
-        budget = budgets[t]
-        print(f"llama full size: step {t} on the device, budget {budget} bytes", flush=True)
-        status = plan.step(budget)
-        torch.cuda.synchronize()
-        assert status.cpu().tolist() == [0, 0], t
-        E_gpu = plan.err_table.cpu().numpy().reshape(work.L, -1)
-        K = plan.K.cpu().numpy().astype(np.uint64)
-        off = plan.offsets.cpu().numpy().astype(np.uint64)
-        st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, budget, work.pair_bytes, work.cost_units_D)
-        assert st == ko.OK
-        assert np.array_equal(plan.j.cpu().numpy(), j_ref)
-        assert np.array_equal(K, K_ref) and np.array_equal(off, off_ref)
-        assert work.pair_bytes * int(off[-1]) <= budget
+    budget = c["budgets"][t]
+    print(f"llama full size: step {t} on the device, budget {budget} bytes", flush=True)
+    status = plan.step(budget)
+    torch.cuda.synchronize()
+    assert status.cpu().tolist() == [0, 0], t
+    E_gpu = plan.err_table.cpu().numpy().reshape(work.L, -1)
+    K = plan.K.cpu().numpy().astype(np.uint64)
+    off = plan.offsets.cpu().numpy().astype(np.uint64)
+    st, j_ref, K_ref, off_ref = ko.allocate(E_gpu, Kt, budget, work.pair_bytes, work.cost_units_D)
+    assert st == ko.OK
+    assert np.array_equal(plan.j.cpu().numpy(), j_ref)
+    assert np.array_equal(K, K_ref) and np.array_equal(off, off_ref)
+    assert work.pair_bytes * int(off[-1]) <= budget
 
-        # invariants of the table on every layer: non-increasing along the grid, exactly 0 at K = n, never
-        # above the bound of the paper's compressor class, E(K) <= (1 - K/n) ||x||^2 (fp64 norm from numpy)
-        gL = work.layer_views(work.g)
-        idx = gh.u32(plan.idx)
-        val = plan.val.cpu().numpy()
-        h_new = h.cpu().numpy()
-        for i in range(work.L):
-            if i % 40 == 0:
-                print(f"llama full size: step {t}, properties of layer {i}", flush=True)
-            h_before = h_old[starts[i]:starts[i + 1]]
-            x = ko.operand(gL[i], h_before)
-            n = len(x)
-            row = E_gpu[i]
-            assert np.all(row[1:] <= row[:-1]) and np.all(row >= 0.0)
-            assert np.all(row[Kt[i] == n] == 0.0)
-            norm2 = float(np.dot(x.astype(np.float64), x.astype(np.float64)))
-            assert np.all(row <= (1.0 - Kt[i] / n) * norm2 * (1 + 1e-5))
-            a, b = int(off[i]), int(off[i + 1])
-            assert b - a == int(K[i])
-            _selection_properties(x, idx[a:b].astype(np.int64), h_before, h_new[starts[i]:starts[i + 1]], val[a:b])
+    # invariants of the table on every layer: non-increasing along the grid, exactly 0 at K = n, never
+    # above the bound of the paper's compressor class, E(K) <= (1 - K/n) ||x||^2 (fp64 norm from numpy)
+    gL = work.layer_views(work.g)
+    idx = gh.u32(plan.idx)
+    val = plan.val.cpu().numpy()
+    h_new = h.cpu().numpy()
+    for i in range(work.L):
+        if i % 40 == 0:
+            print(f"llama full size: step {t}, properties of layer {i}", flush=True)
+        h_before = h_old[starts[i]:starts[i + 1]]
+        x = ko.operand(gL[i], h_before)
+        n = len(x)
+        row = E_gpu[i]
+        assert np.all(row[1:] <= row[:-1]) and np.all(row >= 0.0)
+        assert np.all(row[Kt[i] == n] == 0.0)
+        norm2 = float(np.dot(x.astype(np.float64), x.astype(np.float64)))
+        assert np.all(row <= (1.0 - Kt[i] / n) * norm2 * (1 + 1e-5))
+        a, b = int(off[i]), int(off[i + 1])
+        assert b - a == int(K[i])
+        _selection_properties(x, idx[a:b].astype(np.int64), h_before, h_new[starts[i]:starts[i + 1]], val[a:b])
 
-        for i in sample:
-            print(f"llama full size: step {t}, oracle on layer {i}", flush=True)
-            assert np.array_equal(h_old[starts[i]:starts[i + 1]].view(np.uint32), h_ref[i].view(np.uint32))
-            x = ko.operand(gL[i], h_ref[i])
-            rowref = ko.topk_error_profile(x, Kt[i])
-            gh.assert_table_close(E_gpu[i:i + 1], rowref[None, :], Kt[i:i + 1], work.sizes[i:i + 1])
-            li, lv, lh = ko.compress_ef_layer(gL[i], h_ref[i], int(K[i]))
-            a, b = int(off[i]), int(off[i + 1])
-            assert np.array_equal(idx[a:b], li), (t, i)
-            assert np.array_equal(val[a:b].view(np.uint32), lv.view(np.uint32)), (t, i)
-            assert np.array_equal(h_new[starts[i]:starts[i + 1]].view(np.uint32), lh.view(np.uint32)), (t, i)
-            h_ref[i] = lh
-        h_old = h_new
+    for i in sample:
+        print(f"llama full size: step {t}, oracle on layer {i}", flush=True)
+        assert np.array_equal(h_old[starts[i]:starts[i + 1]].view(np.uint32), h_ref[i].view(np.uint32))
+        x = ko.operand(gL[i], h_ref[i])
+        rowref = ko.topk_error_profile(x, Kt[i])
+        gh.assert_table_close(E_gpu[i:i + 1], rowref[None, :], Kt[i:i + 1], work.sizes[i:i + 1])
+        li, lv, lh = ko.compress_ef_layer(gL[i], h_ref[i], int(K[i]))
+        a, b = int(off[i]), int(off[i + 1])
+        assert np.array_equal(idx[a:b], li), (t, i)
+        assert np.array_equal(val[a:b].view(np.uint32), lv.view(np.uint32)), (t, i)
+        assert np.array_equal(h_new[starts[i]:starts[i + 1]].view(np.uint32), lh.view(np.uint32)), (t, i)
+        h_ref[i] = lh
+    c["h_old"] = h_new
+    c["done"] = t + 1
+    if t + 1 == _LLAMA_STEPS:
+        plan.close()
+        c.clear()
+        torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("t", list(range(_LLAMA_STEPS)))
+def test_llama_full_size_chain_step(t):
+    try:
+        _llama_chain_step(t)
+    except BaseException:
+        _llama_chain.clear()                      # a failed step ends the chain and frees its buffers
+        raise
 
 
 @pytest.mark.timeout(900)
