@@ -332,14 +332,25 @@ __device__ __forceinline__ T wave_inclusive_scan(T v) {
     return v;
 }
 
+// (32-bit integers take the DPP scan, and the exclusive prefix by subtraction, which is exact for them)
+__device__ __forceinline__ void wave_scan_pair(uint32_t v, uint32_t& inc, uint32_t& exc) {
+    inc = wave_scan_add_u32(v);
+    exc = inc - v;
+}
+template <typename T>
+__device__ __forceinline__ void wave_scan_pair(T v, T& inc, T& exc) {
+    inc = wave_inclusive_scan(v);
+    // exclusive prefix taken from the neighbouring lane: subtracting v back out would cancel
+    // catastrophically for floating-point sums whose terms grow along the scan
+    exc = __shfl_up(inc, 1, 64);
+    if (lane_id() == 0) exc = 0;
+}
+
 template <typename T>
 __device__ __forceinline__ T block_exclusive_scan(T v, T* scratch, T* total) {
     const uint32_t w = threadIdx.x >> 6, nw = blockDim.x >> 6;
-    T inc = wave_inclusive_scan(v);
-    // exclusive prefix taken from the neighbouring lane: subtracting v back out would cancel
-    // catastrophically for floating-point sums whose terms grow along the scan
-    T exc = __shfl_up(inc, 1, 64);
-    if (lane_id() == 0) exc = 0;
+    T inc, exc;
+    wave_scan_pair(v, inc, exc);
     if (lane_id() == 63) scratch[w] = inc;
     __syncthreads();
     T base = 0, tot = 0;

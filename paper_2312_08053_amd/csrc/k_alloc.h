@@ -449,11 +449,14 @@ __global__ __launch_bounds__(256) void k_dp_choice(AllocBuffers ab, DpLists dl, 
 }
 
 constexpr uint32_t DP_STAGE_BYTES = 128u * 1024u;
+constexpr uint32_t DP_WALK_MAX_L = 4224;           // layers whose path cells k_dp_walk keeps in LDS: every layer costs at least one
+                                                   // cell, so a feasible path through rows of at most 4224 cells has no more layers
 
 __global__ __launch_bounds__(1024) void k_dp_walk(AllocBuffers ab, const double* __restrict__ last,
                                                   const uint32_t* __restrict__ bad,
                                                   int32_t err_infeasible, int32_t err_nonfinite) {
     __shared__ __attribute__((aligned(16))) uint8_t stage[DP_STAGE_BYTES];
+    __shared__ uint16_t s_cell[DP_WALK_MAX_L];     // the path's cell per layer (a store to memory in the chain would be waited for)
     __shared__ double sv[16];
     __shared__ unsigned long long sc[16];
     __shared__ unsigned long long cstar;
@@ -486,7 +489,7 @@ __global__ __launch_bounds__(1024) void k_dp_walk(AllocBuffers ab, const double*
             if (sv[w] < best || (sv[w] == best && sc[w] < bc)) { best = sv[w]; bc = sc[w]; }
         int32_t s = 0;
         if (any_bad) s = err_nonfinite;
-        else if (!(best < DP_INF)) s = err_infeasible;
+        else if (!(best < DP_INF) || ab.L > DP_WALK_MAX_L) s = err_infeasible;   // (more layers than cells: no finite total)
         st = s;
         cstar = bc;
         *ab.status = s;
@@ -533,26 +536,23 @@ __global__ __launch_bounds__(1024) void k_dp_walk(AllocBuffers ab, const double*
             const uint16_t* row = srow + (size_t)nrows * pitch;
             for (uint32_t i = hi; i-- > lo_l;) {
                 row -= pitch;
-                ab.j_out[i] = (int32_t)c;                  // the layer's cell for now
+                s_cell[i] = (uint16_t)c;
                 c = min((uint32_t)row[c], ab.cap);         // (a feasible path never meets the 0xFFFF of an empty cell)
             }
             cstar = c;
         }
         hi = lo_l;
     }
-    __threadfence_block();
     __syncthreads();
-    for (uint32_t i = tid; i < ab.L; i += 1024)
-        ab.j_out[i] = (int32_t)ab.choice[(size_t)i * ab.stride + (uint32_t)ab.j_out[i]];
-    __threadfence_block();
-    __syncthreads();
-    // sizes and offsets, in parallel
+    // winners along the path, sizes and offsets, in parallel
     unsigned long long carry = 0;
     for (uint32_t i0b = 0; i0b < ab.L; i0b += 1024) {
         const uint32_t i = i0b + tid;
         unsigned long long K = 0;
         if (i < ab.L) {
-            K = ab.Kout[(size_t)i * ab.J + (uint32_t)ab.j_out[i]];
+            const uint32_t j = ab.choice[(size_t)i * ab.stride + (uint32_t)s_cell[i]];
+            ab.j_out[i] = (int32_t)j;
+            K = ab.Kout[(size_t)i * ab.J + j];
             ab.K_out[i] = K;
         }
         unsigned long long tot;

@@ -488,18 +488,22 @@ __global__ __launch_bounds__(1024) void k_chunk_bases(CompressBuffers cb) {
     const uint32_t kb = blk - L.cblk0;              // this block's number inside the layer
     uint32_t pg = 0, pe = 0;
     {
-        // kb * CBLOCK is a multiple of 1024: every thread takes kb entries, eight loads of each table at a time
+        // kb * CBLOCK is a multiple of 1024: every thread takes kb entries, sixteen loads of each table at a time (the
+        // last block of the largest layer has the most to add up and sets the kernel's duration: few round trips)
         const uint32_t* pgt = cb.c_gt + L.chunk0 + tid;
         const uint32_t* peq = cb.c_eq + L.chunk0 + tid;
-        uint32_t k = 0;
-        for (; k + 4 <= kb; k += 4) {
-            uint32_t a[4], e[4];
+        for (uint32_t k = 0; k < kb; k += 16u) {
+            uint32_t a[16], e[16];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { a[u] = pgt[(size_t)(k + u) * 1024u]; e[u] = peq[(size_t)(k + u) * 1024u]; }
+            for (int u = 0; u < 16; ++u) {
+                const bool in = k + (uint32_t)u < kb;
+                const size_t o = (size_t)(in ? k + (uint32_t)u : 0u) * 1024u;
+                a[u] = pgt[o]; e[u] = peq[o];
+                if (!in) { a[u] = 0u; e[u] = 0u; }
+            }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) { pg += a[u]; pe += e[u]; }
+            for (int u = 0; u < 16; ++u) { pg += a[u]; pe += e[u]; }
         }
-        for (; k < kb; ++k) { pg += pgt[(size_t)k * 1024u]; pe += peq[(size_t)k * 1024u]; }
     }
     uint32_t gt_before, eq_before0;
     (void)block_exclusive_scan<uint32_t>(pg, su, &gt_before);

@@ -312,29 +312,49 @@ __device__ __forceinline__ float prefix_lo(uint32_t prefix) { return __uint_as_f
 
 // One wave per candidate: every lane holds two digit-2 bins of the candidate's boundary bin.
 // `flagged` and `prefix_out` come back the same in every lane.
-__device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uint32_t* Ktab, uint32_t J,
-                                             double* err_table, double tol, double widen, uint32_t big,
-                                             uint32_t li, uint32_t j, bool* flagged, uint32_t* prefix_out) {
+// What a target's loads bring: first what its index addresses, then what its slot addresses.  A wave looks after
+// several targets; it asks for all of one kind together, so that the round trips to memory are two per wave, not
+// two per target.
+struct Scan2Target {
+    uint32_t K, slot, r, above1;
+    double below;
+    uint32_t bin;
+    uint2 c;
+    ulonglong2 q;
+};
+__device__ __forceinline__ void scan2_load_target(const ProfileBuffers& pb, const uint32_t* Ktab, size_t t, Scan2Target& T) {
+    T.K = Ktab[t];
+    T.slot = pb.tgt_slot[t];
+    T.r = pb.tgt_r[t];
+    T.above1 = pb.tgt_above1[t];
+    T.below = pb.tgt_below[t];
+}
+__device__ __forceinline__ void scan2_load_slot(const ProfileBuffers& pb, uint32_t big, Scan2Target& T) {
     const uint32_t lane = lane_id();
-    const LayerDesc L = pb.layers[li];
-    const size_t t = (size_t)li * J + j;
-    const uint32_t K = Ktab[t];
-    const uint32_t slot = pb.tgt_slot[t];
-    if (slot == NO_SLOT) {                      // K == n (or K == 0): nothing / everything dropped
+    T.bin = pb.slot_bin[(size_t)big * SLOT_STRIDE + T.slot];
+    T.c = reinterpret_cast<const uint2*>(pb.cnt2 + ((size_t)big * SLOT_STRIDE + T.slot) * D2_BINS)[lane];
+    T.q = reinterpret_cast<const ulonglong2*>(pb.sq2 + ((size_t)big * SLOT_STRIDE + T.slot) * D2_BINS)[lane];
+}
+__device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const Scan2Target& T, uint32_t n, size_t t,
+                                             double* err_table, double tol, double widen, bool* flagged,
+                                             uint32_t* prefix_out) {
+    const uint32_t lane = lane_id();
+    const uint32_t K = T.K;
+    if (T.slot == NO_SLOT) {                    // K == n (or K == 0): nothing / everything dropped
         if (lane == 0) {
-            if (err_table) err_table[t] = (K == 0u) ? pb.tgt_below[t] : 0.0;
+            if (err_table) err_table[t] = (K == 0u) ? T.below : 0.0;
             pb.sel_prefix[t] = 0u;
-            pb.sel_above[t] = (K == 0u) ? 0u : L.n;
+            pb.sel_above[t] = (K == 0u) ? 0u : n;
             pb.sel_amb[t] = 0u;
             pb.tgt_unsel[t] = 0u;
             pb.tgt_base[t] = 0.0;
         }
         return;
     }
-    const uint32_t bin = pb.slot_bin[(size_t)big * SLOT_STRIDE + slot];
-    const uint32_t r = pb.tgt_r[t];
-    const uint2 c = reinterpret_cast<const uint2*>(pb.cnt2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS)[lane];
-    const ulonglong2 q = reinterpret_cast<const ulonglong2*>(pb.sq2 + ((size_t)big * SLOT_STRIDE + slot) * D2_BINS)[lane];
+    const uint32_t bin = T.bin;
+    const uint32_t r = T.r;
+    const uint2 c = T.c;
+    const ulonglong2 q = T.q;
     // walk digit 2 from the top until r entries are covered: the boundary is the highest bin u > 0
     // with (entries above u) + cnt[u] >= r, or bin 0
     const uint32_t incl = wave_scan_add_u32(c.x + c.y);
@@ -375,14 +395,14 @@ __device__ __forceinline__ void scan2_target(const ProfileBuffers& pb, const uin
             half_gap = 0.5 * (ub - lb);
         }
     }
-    const double base = pb.tgt_below[t] + below2;
+    const double base = T.below + below2;
     const double E = base + est;
     // single-pass slots hold midpoints of intervals 2^-23 wide (relative): part of the bound
     half_gap += E * widen;
     if (lane == 0) {
         if (err_table) err_table[t] = E;
         pb.sel_prefix[t] = prefix;
-        pb.sel_above[t] = pb.tgt_above1[t] + acc;
+        pb.sel_above[t] = T.above1 + acc;
         pb.sel_amb[t] = m;
         pb.tgt_unsel[t] = unsel;
         pb.tgt_base[t] = base;
@@ -404,10 +424,28 @@ __global__ __launch_bounds__(SCAN2_THREADS) void k_scan2(ProfileBuffers pb, cons
     if (threadIdx.x == 0) sh_npool = 0u;
     const uint32_t big = blockIdx.x;
     const uint32_t li = pb.big_layer[big];
-    for (uint32_t jj = threadIdx.x >> 6; jj < KIMAD_MAX_J_CONST; jj += SCAN2_THREADS / 64) {
+    constexpr uint32_t WAVES = SCAN2_THREADS / 64, PER_WAVE = KIMAD_MAX_J_CONST / WAVES;
+    static_assert(PER_WAVE * WAVES == KIMAD_MAX_J_CONST, "every wave looks after the same number of targets");
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t n = pb.layers[li].n;
+    Scan2Target T[PER_WAVE];
+#pragma unroll
+    for (uint32_t u = 0; u < PER_WAVE; ++u) {
+        const uint32_t jj = wave + u * WAVES;
+        T[u].slot = NO_SLOT; T[u].K = 1u; T[u].r = 0u; T[u].above1 = 0u; T[u].below = 0.0;
+        if (jj < J) scan2_load_target(pb, Ktab, (size_t)li * J + jj, T[u]);
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < PER_WAVE; ++u) {
+        T[u].bin = 0u; T[u].c = make_uint2(0u, 0u); T[u].q = make_ulonglong2(0ull, 0ull);
+        if (T[u].slot != NO_SLOT) scan2_load_slot(pb, big, T[u]);
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < PER_WAVE; ++u) {
+        const uint32_t jj = wave + u * WAVES;
         bool fl = false;
         uint32_t px = 0xFFFFFFFFu - jj;         // distinct dummy for idle slots and K == n
-        if (jj < J) scan2_target(pb, Ktab, J, err_table, tol, widen, big, li, jj, &fl, &px);
+        if (jj < J) scan2_target(pb, T[u], n, (size_t)li * J + jj, err_table, tol, widen, &fl, &px);
         if (lane_id() == 0) { sh_prefix[jj] = px; sh_flag[jj] = fl ? 1u : 0u; }
     }
     __syncthreads();

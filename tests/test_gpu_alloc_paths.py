@@ -141,3 +141,19 @@ def test_many_layers_and_many_list_records():
     E = _convex_table(rng, sizes, ratios, -2, 2)
     d = sum(sizes)
     _check(sizes, ratios, E, int(0.05 * 8 * d), 4200, expect_band=False)
+
+
+
+def test_more_layers_than_cost_cells_is_infeasible():
+    """Every layer costs at least one cell: 5000 layers cannot fit rows of 601 cells, whatever the budget's size in
+    bytes (the walk back, which keeps the path's cells in LDS, is never reached)."""
+    rng = np.random.default_rng(23)
+    ratios = [0.05, 0.3, 1.0]
+    sizes = [int(x) for x in rng.integers(100, 3000, size=5000)]
+    E = _convex_table(rng, sizes, ratios, -3, 1)
+    d = sum(sizes)
+    _check(sizes, ratios, E, int(0.25 * 8 * d), 600)
+    # and with as many cells as layers allow it, through rows of 4200 cells
+    sizes = sizes[:4000]
+    E = E[:4000]
+    _check(sizes, ratios, E, int(0.5 * 8 * sum(sizes)), 4200)
