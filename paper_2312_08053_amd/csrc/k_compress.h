@@ -289,11 +289,12 @@ __device__ __forceinline__ void compact_tiles(const CompressBuffers& cb, uint32_
 
 // ---------------------------------------------------------------------------------------------
 // Last-digit histogram of the spilled candidates that share the threshold prefix (layers in
-// SEL_CAND mode).  Sixteen lanes per chunk.
+// SEL_CAND mode).  Eight lanes per chunk.
 __device__ __forceinline__ void hist3_candidates(const CompressBuffers& cb, uint32_t nchunks_total,
                                                  const uint32_t* chunk_big, uint32_t block) {
-    const SubGroup g = sub_group();
-    const uint32_t chunk = block * CHUNKS_PER_WG + threadIdx.x / SUB;
+    constexpr uint32_t S = SUB_COUNT;
+    const SubGroup g = sub_group<S>();
+    const uint32_t chunk = block * (256u / S) + threadIdx.x / S;
     uint32_t cnt = 0, prefix = 0;
     uint64_t base = 0;
     uint32_t* hist3 = cb.hist3;
@@ -310,20 +311,20 @@ __device__ __forceinline__ void hist3_candidates(const CompressBuffers& cb, uint
         prefix = S.prefix;
         hist3 = cb.hist3 + (size_t)b * D3_BINS;
     }
-    const uint32_t cmax = wave_max_over_groups(cnt);
+    const uint32_t cmax = wave_max_over_groups<S>(cnt);
     uint32_t n_above = 0, n_amb = 0;            // of this chunk: threshold prefix exceeded / shared
-    // one round: sixteen candidates of the chunk
+    // one round: one candidate of the chunk per lane of its group
     auto round = [&](bool in, uint32_t key) {
         const bool a = in && (key >> D2_SHIFT) == prefix;
         const bool hi = in && (key >> D2_SHIFT) > prefix;
-        const uint32_t am = ballot_sub(g, a);
-        n_above += __popc(ballot_sub(g, hi));
+        const uint32_t am = ballot_sub<S>(g, a);
+        n_above += __popc(ballot_sub<S>(g, hi));
         n_amb += __popc(am);
         if (am == 0) return;
         // one atomic per group when all its matching lanes hold the same key (zeros, constants)
         const uint32_t first = (uint32_t)__ffs((int)am) - 1u;
         const uint32_t k0v = __shfl(key, g.shift + first, 64);
-        const bool uniform = ballot_sub(g, a && key != k0v) == 0;
+        const bool uniform = ballot_sub<S>(g, a && key != k0v) == 0;
         if (uniform) {
             if (g.sub == first) atomicAdd(&hist3[key & (D3_BINS - 1)], (uint32_t)__popc(am));
         } else if (a) {
@@ -334,16 +335,16 @@ __device__ __forceinline__ void hist3_candidates(const CompressBuffers& cb, uint
     // of the buffer, always a valid address, and are dropped; a chunk without candidates has no valid start)
     // (and so on, four rounds per memory round trip: a layer that spills an eighth has eight rounds a chunk)
     constexpr int AHEAD = 4;
-    for (uint32_t k0 = 0; k0 < cmax; k0 += AHEAD * SUB) {
+    for (uint32_t k0 = 0; k0 < cmax; k0 += AHEAD * S) {
         float px[AHEAD];
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t) {
-            const uint32_t k = k0 + (uint32_t)t * SUB + g.sub;
+            const uint32_t k = k0 + (uint32_t)t * S + g.sub;
             px[t] = cb.tmp_x[k < cnt ? base + k : 0ull];
         }
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t)
-            if (k0 + (uint32_t)t * SUB < cmax) round(k0 + (uint32_t)t * SUB + g.sub < cnt, key_of(px[t]));
+            if (k0 + (uint32_t)t * S < cmax) round(k0 + (uint32_t)t * S + g.sub < cnt, key_of(px[t]));
     }
     // A chunk without an entry in the threshold's prefix bin (nearly all of them) is settled here:
     // every entry above the prefix is above the threshold, none equals it.  The others are counted
@@ -412,11 +413,12 @@ __global__ __launch_bounds__(256) void k_resolve(CompressBuffers cb) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Per chunk: how many candidates lie above tau and how many equal it.  Sixteen lanes per chunk.
+// Per chunk: how many candidates lie above tau and how many equal it.  Eight lanes per chunk.
 __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_t nchunks_total,
                                                      const uint32_t* chunk_big) {
-    const SubGroup g = sub_group();
-    const uint32_t chunk = blockIdx.x * CHUNKS_PER_WG + threadIdx.x / SUB;
+    constexpr uint32_t S = SUB_COUNT;
+    const SubGroup g = sub_group<S>();
+    const uint32_t chunk = blockIdx.x * (256u / S) + threadIdx.x / S;
     const bool live = chunk < nchunks_total;
     uint32_t cnt = 0, tau = 0, total = 0;
     uint64_t base = 0;
@@ -451,7 +453,7 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
     }
     uint32_t gt = 0, eq = 0;
     if (direct) {
-        for (uint32_t k = g.sub; k < CHUNK; k += SUB) {
+        for (uint32_t k = g.sub; k < CHUNK; k += S) {
             const uint32_t v = vb + k, e = v - mis;
             if (v >= mis && e < nL) {
                 const uint32_t key = key_of(gload(gL + e) - gload(hL + e));
@@ -460,14 +462,14 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
             }
         }
     } else {
-        for (uint32_t k = g.sub; k < cnt; k += SUB) {
+        for (uint32_t k = g.sub; k < cnt; k += S) {
             const uint32_t key = key_of(cb.tmp_x[base + k]);
             gt += key > tau;
             eq += key == tau;
         }
     }
 #pragma unroll
-    for (int d = SUB / 2; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
+    for (int d = S / 2; d > 0; d >>= 1) { gt += __shfl_xor(gt, d, 64); eq += __shfl_xor(eq, d, 64); }
     if (cnt == 0) { gt = total; eq = 0; }
     if (live && !settled && g.sub == 0) { cb.c_gt[chunk] = gt; cb.c_eq[chunk] = eq; }
 }

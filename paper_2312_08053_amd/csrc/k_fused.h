@@ -816,10 +816,11 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Digit-2 histograms of the slots PRE_SLOTS.. from the candidate buffer.  Sixteen lanes per chunk.
+// Digit-2 histograms of the slots PRE_SLOTS.. from the candidate buffer.  Eight lanes per chunk.
 __global__ __launch_bounds__(256) void k_hist2c(ProfileBuffers pb) {
-    const SubGroup g = sub_group();
-    const uint32_t chunk = blockIdx.x * CHUNKS_PER_WG + threadIdx.x / SUB;
+    constexpr uint32_t S = SUB_COUNT;
+    const SubGroup g = sub_group<S>();
+    const uint32_t chunk = blockIdx.x * (256u / S) + threadIdx.x / S;
     if (chunk >= pb.nchunks_total) return;
     // what the chunk index alone addresses is fetched together; the layer's state and region follow
     const uint32_t big = pb.chunk_big[chunk];
@@ -837,16 +838,16 @@ __global__ __launch_bounds__(256) void k_hist2c(ProfileBuffers pb) {
     // Four rounds at a time: their keys are loaded together, then their slots.  Positions past the
     // chunk's last candidate read that last candidate again (always a valid address) and are dropped.
     constexpr int AHEAD = 4;
-    for (uint32_t k0 = g.sub; k0 < cnt; k0 += AHEAD * SUB) {
+    for (uint32_t k0 = g.sub; k0 < cnt; k0 += AHEAD * S) {
         uint32_t key[AHEAD], slot[AHEAD];
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t)
-            key[t] = key_of(pb.tmp_x[base + min(k0 + (uint32_t)t * SUB, cnt - 1u)]);
+            key[t] = key_of(pb.tmp_x[base + min(k0 + (uint32_t)t * S, cnt - 1u)]);
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t) slot[t] = (uint32_t)lutc[key[t] >> D1_SHIFT];
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t) {
-            if (slot[t] == NO_SLOT || k0 + (uint32_t)t * SUB >= cnt) continue;
+            if (slot[t] == NO_SLOT || k0 + (uint32_t)t * S >= cnt) continue;
             const uint32_t bin = key[t] >> D1_SHIFT;
             const uint32_t e = slot[t] * D2_BINS + ((key[t] >> D2_SHIFT) & (D2_BINS - 1));
             const unsigned long long s = bin ? (unsigned long long)sq_coarse(key[t]) : sq_exact(key[t]);

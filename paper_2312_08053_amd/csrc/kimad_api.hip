@@ -476,7 +476,7 @@ int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, h
     rc = launch_small_profile(p, err_table, s, side);
     if (rc) return rc;
     KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J);
-    KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG), dim3(256), p->pb);
+    KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + 256u / SUB_COUNT - 1) / (256u / SUB_COUNT)), dim3(256), p->pb);
     // fallbacks that normally find nothing to do: small grids
     KLAUNCH(p, s, "k_hist2", k_hist2, dim3(std::min<uint32_t>(lo.ntiles, FALLBACK_GRID)), dim3(512), p->pb, lo.ntiles,
             (const uint32_t*)(at<uint32_t>(p, lo.diag) + 3), 1u);   // layers marked redo only
@@ -901,10 +901,11 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
     if (lo.B) {
         const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
         const uint32_t cblocks = (lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG;
-        KLAUNCH(p, s, "k_candidates", k_candidates, dim3(cblocks + std::min<uint32_t>(lo.ntiles, 4u * FALLBACK_GRID)), dim3(256), cb,
-                lo.nchunks, chunk_big, cblocks, lo.ntiles, (int32_t)KIMAD_ERR_INTERNAL);
+        const uint32_t nblocks = (lo.nchunks + 256u / SUB_COUNT - 1) / (256u / SUB_COUNT);   // where candidates are only counted
+        KLAUNCH(p, s, "k_candidates", k_candidates, dim3(nblocks + std::min<uint32_t>(lo.ntiles, 4u * FALLBACK_GRID)), dim3(256), cb,
+                lo.nchunks, chunk_big, nblocks, lo.ntiles, (int32_t)KIMAD_ERR_INTERNAL);
         KLAUNCH(p, s, "k_resolve", k_resolve, dim3(lo.B), dim3(256), cb);
-        KLAUNCH(p, s, "k_chunk_count", k_chunk_count, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
+        KLAUNCH(p, s, "k_chunk_count", k_chunk_count, dim3(nblocks), dim3(256), cb, lo.nchunks, chunk_big);
         KLAUNCH(p, s, "k_chunk_bases", k_chunk_bases, dim3(lo.ncblk), dim3(1024), cb);
         KLAUNCH(p, s, "k_finalize", k_finalize, dim3(cblocks), dim3(256), cb, lo.nchunks, chunk_big);
     }
