@@ -580,36 +580,46 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
         return in;
     };
     const uint32_t cmax = wave_max_over_groups(cnt);
-    // one round: sixteen candidates of the chunk, in index order
-    auto round = [&](bool in, uint32_t idx, float x) {
+    // one round: sixteen candidates of the chunk, in index order: which are kept, and where they go
+    auto round = [&](bool in, float x, uint32_t& pos) -> bool {
         const uint32_t key = key_of(x);
         const bool iseq = in && filter && key == tau;
         const uint32_t eqm = ballot_sub(g, iseq);
         const bool keep = in && (!filter || key > tau || (iseq && eq_run + rank_sub(g, eqm) < allow));
         eq_run += __popc(eqm);
         const uint32_t km = ballot_sub(g, keep);
-        const uint32_t pos = out_run + rank_sub(g, km);
-        if (keep && pos < room) {
-            const uint64_t o = dst + pos;
-            cb.idx_out[o] = idx;
-            const float add = emit_value(cb, o, x);
-            gstore(h + idx, gload(h + idx) + add);   // the estimator is read here: candidates carry (index, x) only
-        }
+        pos = out_run + rank_sub(g, km);
         out_run += __popc(km);
+        return keep && pos < room;
     };
     // A chunk rarely holds more than 64 candidates: the loads of the first four rounds go out together,
-    // so the wave pays one memory round trip for them instead of four.
+    // so the wave pays one memory round trip for them instead of four; likewise the estimator entries of what the
+    // four rounds keep are read together, then written (the entries of a chunk are distinct elements).
     constexpr int AHEAD = 4;
     // (positions past the chunk's last entry read entry 0 of the buffer or the layer, a valid address, and are dropped)
     for (uint32_t k0 = 0; k0 < cmax; k0 += AHEAD * SUB) {
-        uint32_t pidx[AHEAD];
-        float px[AHEAD];
-        bool pin[AHEAD];
+        uint32_t pidx[AHEAD], pos[AHEAD];
+        float px[AHEAD], ph[AHEAD];
+        bool pin[AHEAD], keep[AHEAD];
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t) pin[t] = fetch(k0 + (uint32_t)t * SUB + g.sub, pidx[t], px[t]);
 #pragma unroll
-        for (int t = 0; t < AHEAD; ++t)
-            if (k0 + (uint32_t)t * SUB < cmax) round(pin[t], pidx[t], px[t]);
+        for (int t = 0; t < AHEAD; ++t) {
+            keep[t] = false; pos[t] = 0u;
+            if (k0 + (uint32_t)t * SUB < cmax) keep[t] = round(pin[t], px[t], pos[t]);
+        }
+        // the estimator is read here: candidates carry (index, x) only
+#pragma unroll
+        for (int t = 0; t < AHEAD; ++t) ph[t] = keep[t] ? gload(h + pidx[t]) : 0.0f;
+#pragma unroll
+        for (int t = 0; t < AHEAD; ++t) {
+            if (keep[t]) {
+                const uint64_t o = dst + pos[t];
+                cb.idx_out[o] = pidx[t];
+                const float add = emit_value(cb, o, px[t]);
+                gstore(h + pidx[t], ph[t] + add);
+            }
+        }
     }
 }
 
