@@ -259,6 +259,12 @@ constexpr uint32_t SPILL_BLOCK = 512;
 // threshold prefix if that fits; whatever does not fit is served from g and h directly.
 constexpr uint32_t REGION_PER_CHUNK = 168;        // a multiple of the 8 entries space is handed out in
 constexpr uint32_t REGION_SLACK = 2048;
+// The regions of the tiled layers follow one another in the candidate buffer, so a layer's region starts where its
+// first chunk and its number among the tiled layers say: a kernel that walks chunks knows where a chunk's candidates
+// are from what the chunk's index addresses, without reading the layer's record first.
+__host__ __device__ inline uint64_t region_start(uint32_t first_chunk, uint32_t big) {
+    return (uint64_t)first_chunk * REGION_PER_CHUNK + (uint64_t)big * REGION_SLACK;
+}
 struct WaveAlloc { uint32_t base, left; };
 
 __device__ __forceinline__ uint32_t wave_reserve(WaveAlloc& wa, uint32_t total, uint32_t* cursor) {
@@ -281,6 +287,8 @@ __device__ __forceinline__ uint32_t wave_reserve(WaveAlloc& wa, uint32_t total, 
 // wave-wide; these helpers cut out a group's part.
 constexpr uint32_t SUB = 16;                  // lanes per chunk
 constexpr uint32_t SUB_COUNT = 8;             // the same where candidates are only counted
+constexpr uint32_t SUB_HIST = 4;              // and where every candidate is looked at once for a histogram: eight rounds'
+                                              // loads per lane and memory round trip, sixteen chunks to a wave
 constexpr uint32_t CHUNKS_PER_WG = 256 / SUB; // chunks a 256-thread workgroup handles
 struct SubGroup {
     uint32_t sub;   // lane inside the group

@@ -42,6 +42,7 @@ struct CompressBuffers {
     uint32_t* c_eq;               // candidates equal to tau
     uint32_t* o_base;             // first payload slot of the chunk inside the layer
     uint32_t* o_allow;            // ties this chunk may keep
+    const uint32_t* chunk_first;  // chunk -> first chunk of its layer (with the big index: where its region starts)
     const uint32_t* cblk_big;     // block of 1024 chunks -> big index
     // candidate buffer
     uint32_t* tmp_idx;
@@ -56,6 +57,7 @@ struct CompressBuffers {
     float* val_out;               // fp32 values, or binary16 bit patterns (uint16) when value_f16 is set
     uint32_t value_f16;
     uint64_t capacity_pairs;
+    uint64_t tmp_total;           // entries of the candidate buffer (all regions)
     int32_t* status;
 };
 
@@ -289,10 +291,10 @@ __device__ __forceinline__ void compact_tiles(const CompressBuffers& cb, uint32_
 
 // ---------------------------------------------------------------------------------------------
 // Last-digit histogram of the spilled candidates that share the threshold prefix (layers in
-// SEL_CAND mode).  Eight lanes per chunk.
+// SEL_CAND mode).  Four lanes per chunk, eight rounds of candidates per memory round trip.
 __device__ __forceinline__ void hist3_candidates(const CompressBuffers& cb, uint32_t nchunks_total,
                                                  const uint32_t* chunk_big, uint32_t block) {
-    constexpr uint32_t S = SUB_COUNT;
+    constexpr uint32_t S = SUB_HIST;
     const SubGroup g = sub_group<S>();
     const uint32_t chunk = block * (256u / S) + threadIdx.x / S;
     uint32_t cnt = 0, prefix = 0;
@@ -301,13 +303,17 @@ __device__ __forceinline__ void hist3_candidates(const CompressBuffers& cb, uint
     bool is_cand = false;
     if (chunk < nchunks_total) {
         // what the chunk index alone addresses goes out together, then the layer's record
-        const uint32_t b = chunk_big[chunk];
+        const uint32_t b = chunk_big[chunk], first = cb.chunk_first[chunk];
         const uint32_t n_rec = cb.rec_cnt[chunk], start = cb.rec_start[chunk];
-        materialise(b); materialise(n_rec); materialise(start);
+        materialise(b); materialise(first); materialise(n_rec); materialise(start);
+        // where the candidates are follows from the above: they are asked for together with the layer's record
+        // (of a layer in another mode in vain: its chunks count as empty)
+        base = region_start(first, b) + start;
+        // (the compaction half of this launch may be rewriting the records of a layer in another mode: whatever
+        // is read of them, nothing is asked for outside the buffer)
+        cnt = base + n_rec <= cb.tmp_total ? n_rec : 0u;
         const SelRec S = cb.sel[b];
         is_cand = S.mode == SEL_CAND;
-        cnt = is_cand ? n_rec : 0u;
-        base = S.tmp_base + start;
         prefix = S.prefix;
         hist3 = cb.hist3 + (size_t)b * D3_BINS;
     }
@@ -315,6 +321,7 @@ __device__ __forceinline__ void hist3_candidates(const CompressBuffers& cb, uint
     uint32_t n_above = 0, n_amb = 0;            // of this chunk: threshold prefix exceeded / shared
     // one round: one candidate of the chunk per lane of its group
     auto round = [&](bool in, uint32_t key) {
+        in = in && is_cand;
         const bool a = in && (key >> D2_SHIFT) == prefix;
         const bool hi = in && (key >> D2_SHIFT) > prefix;
         const uint32_t am = ballot_sub<S>(g, a);
@@ -331,10 +338,10 @@ __device__ __forceinline__ void hist3_candidates(const CompressBuffers& cb, uint
             atomicAdd(&hist3[key & (D3_BINS - 1)], 1u);
         }
     };
-    // the first four rounds' loads go out together (positions past the chunk's last candidate read entry 0
+    // the first eight rounds' loads go out together (positions past the chunk's last candidate read entry 0
     // of the buffer, always a valid address, and are dropped; a chunk without candidates has no valid start)
-    // (and so on, four rounds per memory round trip: a layer that spills an eighth has eight rounds a chunk)
-    constexpr int AHEAD = 4;
+    // (and so on, eight rounds per memory round trip: a layer that spills an eighth has 32 rounds a chunk)
+    constexpr int AHEAD = 8;
     for (uint32_t k0 = 0; k0 < cmax; k0 += AHEAD * S) {
         float px[AHEAD];
 #pragma unroll
@@ -430,10 +437,10 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
     uint32_t vb = 0, mis = 0, nL = 0;
     if (live) {
         // what the chunk index alone addresses goes out together, then the layer's record
-        const uint32_t b = chunk_big[chunk];
+        const uint32_t b = chunk_big[chunk], first = cb.chunk_first[chunk];
         const uint32_t amb = cb.rec_amb[chunk], start = cb.rec_start[chunk];
         total = cb.rec_cnt[chunk];
-        materialise(b); materialise(amb); materialise(start); materialise(total);
+        materialise(b); materialise(first); materialise(amb); materialise(start); materialise(total);
         const SelRec S = cb.sel[b];
         const uint32_t t = cb.tau[b];
         // Only chunks with entries in the threshold's prefix bin are read again.  Of the others, those
@@ -442,7 +449,7 @@ __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_
         if ((S.mode == SEL_CAND || S.mode == SEL_PREFIX) && amb != 0u) {
             cnt = total;
             tau = t;
-            base = S.tmp_base + start;
+            base = region_start(first, b) + start;
         }
         settled = S.mode == SEL_CAND && cnt == 0u;      // counted by k_hist3c
         if (S.mode == SEL_DIRECT && amb != 0u) {
@@ -537,12 +544,12 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
     uint32_t vb = 0, mis = 0, nL = 0;
     if (chunk < nchunks_total) {
         // everything indexed by the chunk is fetched at once; one more round trip brings the layer's record
-        const uint32_t b = chunk_big[chunk];
+        const uint32_t b = chunk_big[chunk], first = cb.chunk_first[chunk];
         const uint32_t keepn = cb.c_gt[chunk];
         const uint32_t n_rec = cb.rec_cnt[chunk], start = cb.rec_start[chunk], amb = cb.rec_amb[chunk];
         allow = cb.o_allow[chunk];
         out_run = cb.o_base[chunk];
-        materialise(b); materialise(keepn); materialise(n_rec); materialise(start); materialise(amb);
+        materialise(b); materialise(first); materialise(keepn); materialise(n_rec); materialise(start); materialise(amb);
         materialise(allow); materialise(out_run);
         // most chunks keep nothing (the candidates are several times the payload): not read at all
         if (keepn + allow != 0u) {
@@ -554,7 +561,7 @@ __global__ __launch_bounds__(256) void k_finalize(CompressBuffers cb, uint32_t n
             cnt = S.mode != SEL_NONE ? n_rec : 0u;
             h = S.h;
             filter = S.mode == SEL_CAND || (S.mode == SEL_PREFIX && amb != 0u);
-            src = S.tmp_base + start;
+            src = region_start(first, b) + start;
             dst = S.dst;
             room = S.K;                            // payload slots of this layer
             if (S.mode == SEL_DIRECT) {

@@ -816,33 +816,35 @@ __global__ __launch_bounds__(256) void k_scan1x(ProfileBuffers pb, const uint32_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Digit-2 histograms of the slots PRE_SLOTS.. from the candidate buffer.  Eight lanes per chunk.
+// Digit-2 histograms of the slots PRE_SLOTS.. from the candidate buffer.  Four lanes per chunk: the kernel is bound
+// by how many loads its waves keep in flight (eight per lane here), not by their number.
 __global__ __launch_bounds__(256) void k_hist2c(ProfileBuffers pb) {
-    constexpr uint32_t S = SUB_COUNT;
+    constexpr uint32_t S = SUB_HIST;
     const SubGroup g = sub_group<S>();
     const uint32_t chunk = blockIdx.x * (256u / S) + threadIdx.x / S;
     if (chunk >= pb.nchunks_total) return;
-    // what the chunk index alone addresses is fetched together; the layer's state and region follow
+    // what the chunk index alone addresses is fetched together; it says where the chunk's candidates are, so the
+    // layer's state and the first rounds' candidates are asked for together as well
     const uint32_t big = pb.chunk_big[chunk];
+    const uint32_t first = pb.chunk_first[chunk];
     const uint32_t cnt = pb.rec_cnt[chunk];
     const uint32_t start = pb.rec_start[chunk];
-    materialise(big); materialise(cnt); materialise(start);
+    materialise(big); materialise(first); materialise(cnt); materialise(start);
     if (cnt == 0u) return;
+    const uint64_t base = region_start(first, big) + start;
     const LayerState st = pb.state[big];
-    const uint64_t base = pb.big_tmp0[big] + start;
-    materialise((uint32_t)base);
-    if (st.redo || st.nslots_t == 0u) return;
     const uint8_t* lutc = pb.lutc + (size_t)big * D1_BINS;
     uint32_t* c2 = pb.cnt2 + (size_t)big * SLOT_STRIDE * D2_BINS;
     unsigned long long* s2 = reinterpret_cast<unsigned long long*>(pb.sq2) + (size_t)big * SLOT_STRIDE * D2_BINS;
-    // Four rounds at a time: their keys are loaded together, then their slots.  Positions past the
+    // Eight rounds at a time: their keys are loaded together, then their slots.  Positions past the
     // chunk's last candidate read that last candidate again (always a valid address) and are dropped.
-    constexpr int AHEAD = 4;
+    constexpr int AHEAD = 8;
     for (uint32_t k0 = g.sub; k0 < cnt; k0 += AHEAD * S) {
         uint32_t key[AHEAD], slot[AHEAD];
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t)
             key[t] = key_of(pb.tmp_x[base + min(k0 + (uint32_t)t * S, cnt - 1u)]);
+        if (st.redo || st.nslots_t == 0u) return;       // (a layer without such slots: its candidates were asked for in vain)
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t) slot[t] = (uint32_t)lutc[key[t] >> D1_SHIFT];
 #pragma unroll

@@ -61,6 +61,7 @@ struct ProfileBuffers {
     const uint32_t* big_part0;    // [B] first part of each big layer
     const uint32_t* big_nparts;   // [B]
     const uint32_t* chunk_big;    // chunk -> big index
+    const uint32_t* chunk_first;  // chunk -> first chunk of its layer
     uint32_t nchunks_total;
     const uint32_t* swg_layer;    // sampling workgroup -> layer
     const uint32_t* swg_first;    // sampling workgroup -> its first sampled group in that layer

@@ -40,7 +40,7 @@ struct Layout {
     uint32_t tile_elems = 0, ntiles = 0, nchunks = 0, nswg = 0, ncblk = 0;
     uint64_t dp_cells = 0, tmp_cap = 0, sum_kmax = 0;
     // static tables
-    uint64_t layers, ktab, tile_layer, chunk_big, big_layer, small_layer;
+    uint64_t layers, ktab, tile_layer, chunk_big, chunk_first, big_layer, small_layer;
     // zeroed before every profile
     uint64_t swg_layer, swg_first, state, lutc;
     uint64_t fresh = 0, hprev = 0, gprev = 0;
@@ -167,7 +167,8 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
             h.sgroups = (h.nchunks + h.sstride - 1) / h.sstride;
             h.swg0 = nsw; h.nswg = (h.sgroups + SAMPLE_GROUPS_PER_WG - 1) / SAMPLE_GROUPS_PER_WG;
             nsw += h.nswg;
-            h.tmp0 = tmp_run; h.tmp_cap = h.nchunks * REGION_PER_CHUNK + REGION_SLACK; tmp_run += h.tmp_cap;
+            h.tmp0 = region_start(h.chunk0, (uint32_t)h.big); h.tmp_cap = h.nchunks * REGION_PER_CHUNK + REGION_SLACK;
+            tmp_run = h.tmp0 + h.tmp_cap;                 // the regions follow one another: region_start says where
             h.cblk0 = ncblk; h.ncblk = (h.nchunks + CBLOCK - 1) / CBLOCK; ncblk += h.ncblk;
         }
         (*hl)[i] = h;
@@ -201,6 +202,7 @@ int make_layout(const uint64_t* n, uint32_t L, uint32_t J, const kimad_config_t&
     lo.ktab = take(4 * LJ);
     lo.tile_layer = take(4ull * (nt ? nt : 1));
     lo.chunk_big = take(4ull * (nc ? nc : 1));
+    lo.chunk_first = take(4ull * (nc ? nc : 1));
     lo.big_layer = take(4ull * (B ? B : 1));
     lo.big_tmp0 = take(8ull * (B ? B : 1));
     lo.wg_part0 = take(4ull * lo.main_wgs);
@@ -476,7 +478,7 @@ int run_fused_profile(kimad_plan* p, double* err_table, uint64_t budget_pairs, h
     rc = launch_small_profile(p, err_table, s, side);
     if (rc) return rc;
     KLAUNCH(p, s, "k_scan1x", k_scan1x, dim3(lo.B), dim3(256), p->pb, ktab, lo.J);
-    KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + 256u / SUB_COUNT - 1) / (256u / SUB_COUNT)), dim3(256), p->pb);
+    KLAUNCH(p, s, "k_hist2c", k_hist2c, dim3((lo.nchunks + 256u / SUB_HIST - 1) / (256u / SUB_HIST)), dim3(256), p->pb);
     // fallbacks that normally find nothing to do: small grids
     KLAUNCH(p, s, "k_hist2", k_hist2, dim3(std::min<uint32_t>(lo.ntiles, FALLBACK_GRID)), dim3(512), p->pb, lo.ntiles,
             (const uint32_t*)(at<uint32_t>(p, lo.diag) + 3), 1u);   // layers marked redo only
@@ -648,6 +650,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     // host tables
     std::vector<LayerDesc> ld(L);
     std::vector<uint32_t> tile_layer(lo.ntiles ? lo.ntiles : 1), chunk_big(lo.nchunks ? lo.nchunks : 1);
+    std::vector<uint32_t> chunk_first(lo.nchunks ? lo.nchunks : 1);
     std::vector<uint32_t> big_layer(lo.B ? lo.B : 1), small_layer(lo.S ? lo.S : 1);
     std::vector<uint64_t> big_tmp0(lo.B ? lo.B : 1);
     std::vector<uint32_t> swg_layer(lo.nswg ? lo.nswg : 1), swg_first(lo.nswg ? lo.nswg : 1);
@@ -665,7 +668,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
             // Tiles and chunks are reserved for the worst misalignment; positions past the end of
             // the layer load nothing.
             for (uint32_t t = 0; t < h.ntiles; ++t) tile_layer[h.tile0 + t] = i;
-            for (uint32_t c = 0; c < h.nchunks; ++c) chunk_big[h.chunk0 + c] = (uint32_t)h.big;
+            for (uint32_t c = 0; c < h.nchunks; ++c) { chunk_big[h.chunk0 + c] = (uint32_t)h.big; chunk_first[h.chunk0 + c] = h.chunk0; }
             d.tile0 = h.tile0; d.ntiles = h.ntiles; d.chunk0 = h.chunk0; d.nchunks = h.nchunks;
             d.sstride = h.sstride; d.cblk0 = h.cblk0; d.tmp0 = h.tmp0; d.tmp_cap = h.tmp_cap; d.pad = 0;
             for (uint32_t k = 0; k < h.ncblk; ++k) cblk_big[h.cblk0 + k] = (uint32_t)h.big;
@@ -690,6 +693,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     bool ok = up(lo.layers, ld.data(), sizeof(LayerDesc) * L) && up(lo.ktab, p->ktab.data(), 4ull * L * J) &&
               up(lo.tile_layer, tile_layer.data(), 4ull * tile_layer.size()) &&
               up(lo.chunk_big, chunk_big.data(), 4ull * chunk_big.size()) &&
+              up(lo.chunk_first, chunk_first.data(), 4ull * chunk_first.size()) &&
               up(lo.big_layer, big_layer.data(), 4ull * big_layer.size()) &&
               up(lo.big_tmp0, big_tmp0.data(), 8ull * big_tmp0.size()) &&
               up(lo.wg_part0, pt.wg_part0.data(), 4ull * pt.wg_part0.size()) &&
@@ -726,7 +730,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     pb.state = at<LayerState>(p, lo.state); pb.big_tmp0 = at<uint64_t>(p, lo.big_tmp0);
     pb.parts = at<unsigned long long>(p, lo.parts); pb.wg_part0 = at<uint32_t>(p, lo.wg_part0);
     pb.big_part0 = at<uint32_t>(p, lo.big_part0); pb.big_nparts = at<uint32_t>(p, lo.big_nparts);
-    pb.chunk_big = at<uint32_t>(p, lo.chunk_big); pb.nchunks_total = lo.nchunks;
+    pb.chunk_big = at<uint32_t>(p, lo.chunk_big); pb.chunk_first = at<uint32_t>(p, lo.chunk_first); pb.nchunks_total = lo.nchunks;
     pb.swg_layer = at<uint32_t>(p, lo.swg_layer); pb.swg_first = at<uint32_t>(p, lo.swg_first);
     pb.shist = at<uint32_t>(p, lo.shist); pb.ghist = at<unsigned long long>(p, lo.ghist);
     pb.lutc = at<uint8_t>(p, lo.lutc); pb.cursor = at<uint32_t>(p, lo.cursor);
@@ -751,6 +755,7 @@ int kimad_plan_create(const kimad_layer_t* layers, uint32_t L, const double* rat
     cb.sel = at<SelRec>(p, lo.sel); cb.cursor = pb.cursor; cb.hist3 = at<uint32_t>(p, lo.hist3);
     cb.tau = at<uint32_t>(p, lo.tau); cb.quota = at<uint32_t>(p, lo.quota);
     cb.rec_start = at<uint32_t>(p, lo.rec_start); cb.rec_cnt = at<uint32_t>(p, lo.rec_cnt);
+    cb.chunk_first = at<uint32_t>(p, lo.chunk_first); cb.tmp_total = lo.tmp_cap;
     cb.rec_amb = at<uint32_t>(p, lo.rec_amb); cb.c_gt = at<uint32_t>(p, lo.c_gt); cb.c_eq = at<uint32_t>(p, lo.c_eq);
     cb.o_base = at<uint32_t>(p, lo.o_base); cb.o_allow = at<uint32_t>(p, lo.o_allow);
     cb.cblk_big = at<uint32_t>(p, lo.cblk_big);
@@ -902,8 +907,9 @@ int kimad_compress_ef(kimad_plan_t* p, const uint64_t* K, const uint64_t* offset
         const uint32_t* chunk_big = at<uint32_t>(p, lo.chunk_big);
         const uint32_t cblocks = (lo.nchunks + CHUNKS_PER_WG - 1) / CHUNKS_PER_WG;
         const uint32_t nblocks = (lo.nchunks + 256u / SUB_COUNT - 1) / (256u / SUB_COUNT);   // where candidates are only counted
-        KLAUNCH(p, s, "k_candidates", k_candidates, dim3(nblocks + std::min<uint32_t>(lo.ntiles, 4u * FALLBACK_GRID)), dim3(256), cb,
-                lo.nchunks, chunk_big, nblocks, lo.ntiles, (int32_t)KIMAD_ERR_INTERNAL);
+        const uint32_t hblocks = (lo.nchunks + 256u / SUB_HIST - 1) / (256u / SUB_HIST);      // and where they are histogrammed
+        KLAUNCH(p, s, "k_candidates", k_candidates, dim3(hblocks + std::min<uint32_t>(lo.ntiles, 4u * FALLBACK_GRID)), dim3(256), cb,
+                lo.nchunks, chunk_big, hblocks, lo.ntiles, (int32_t)KIMAD_ERR_INTERNAL);
         KLAUNCH(p, s, "k_resolve", k_resolve, dim3(lo.B), dim3(256), cb);
         KLAUNCH(p, s, "k_chunk_count", k_chunk_count, dim3(nblocks), dim3(256), cb, lo.nchunks, chunk_big);
         KLAUNCH(p, s, "k_chunk_bases", k_chunk_bases, dim3(lo.ncblk), dim3(1024), cb);
