@@ -420,7 +420,7 @@ __global__ __launch_bounds__(256) void k_resolve(CompressBuffers cb) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Per chunk: how many candidates lie above tau and how many equal it.  Eight lanes per chunk.
+// Per chunk: how many candidates lie above tau and how many equal it.  Four lanes per chunk.
 __global__ __launch_bounds__(256) void k_chunk_count(CompressBuffers cb, uint32_t nchunks_total,
                                                      const uint32_t* chunk_big) {
     constexpr uint32_t S = SUB_COUNT;
