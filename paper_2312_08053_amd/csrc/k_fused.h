@@ -2,7 +2,8 @@
 //
 // The classic profile (k_profile.h) reads g and h twice: once to find every candidate's boundary
 // bin in digit 1, once to histogram digit 2 inside those bins.  Here a sampling pre-pass over
-// ~1/16 of each layer predicts, per layer,
+// ~1/16 of each layer (a plan's first profile; later ones use the exact digit-1 histogram the previous
+// profile left: successive gradients of a layer are distributed alike) predicts, per layer,
 //   * which digit-1 bins can hold the boundary of a "dense" candidate (K beyond the top few
 //     percent): those bins get digit-2 slots before the pass, and
 //   * a spill bin: every entry at or above it (the top few percent, sized from the budget hint)
